@@ -1,0 +1,386 @@
+"""Pins of the CPU oracle against things other than itself: a hand-evaluated
+example, closed forms, invariants, brute force in pure Python, and torch's CPU
+attention routine as a library special case.  CPU only."""
+
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import citrus_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "eq1_two_key_example.json")
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+# ----------------------------------------------------------------------------
+# hand-evaluated example (Eq. (1), Section 4.1 step 1)
+# ----------------------------------------------------------------------------
+
+def _golden_keys(g):
+    a = 2.0 * math.log(3.0)
+    k = np.zeros((g["kv_heads"], 2, g["head_dim"]))
+    for h, row in enumerate(g["key_first_coord"]):
+        for j, s in enumerate(row):
+            k[h, j, 0] = a if s == "2ln3" else 0.0
+    return k
+
+
+def test_golden_instr_score():
+    g = json.load(open(GOLDEN))
+    k = _golden_keys(g)
+    qi = np.zeros((g["q_heads"], 2, g["head_dim"]))
+    qi[:, :, 0] = np.array(g["instr_query_first_coord"], dtype=float)
+    s = orc.instr_score(qi, k)
+    np.testing.assert_allclose(s, np.array(g["instr_score_expected"]), rtol=0, atol=1e-14)
+    assert abs(s[0].sum() - g["instr_score_mass"]) < 1e-14
+
+
+def test_golden_chunk_attn_and_lm_score():
+    g = json.load(open(GOLDEN))
+    k = _golden_keys(g)
+    v = np.zeros_like(k)
+    v[:, 0, 0] = 1.0
+    v[:, 1, 1] = 1.0
+    q = np.zeros((g["q_heads"], 1, g["head_dim"]))
+    q[:, 0, 0] = np.array(g["chunk_attn"]["query_first_coord"], dtype=float)
+    out, lse, probs = orc.chunk_attn(q, k, v, n_c=1)
+    np.testing.assert_allclose(out[:, 0, :], np.array(g["chunk_attn"]["out_expected"], dtype=float), atol=1e-14)
+    np.testing.assert_allclose(orc.lm_score(q, k, n_c=1), np.array(g["chunk_attn"]["lm_score_expected"]), atol=1e-14)
+    # lse of head 0: log(3 + 1)
+    assert abs(lse[0, 0] - math.log(4.0)) < 1e-14
+
+
+def test_golden_causal_two_token_chunk():
+    g = json.load(open(GOLDEN))
+    k = _golden_keys(g)[:1]
+    v = np.zeros_like(k)
+    v[0, 0, 0] = 1.0
+    v[0, 1, 1] = 1.0
+    q = np.zeros((1, 2, 4))
+    q[0, :, 0] = 1.0
+    out, _, _ = orc.chunk_attn(q, k, v, n_c=0)
+    np.testing.assert_allclose(out[0], np.array(g["causal_two_token_chunk"]["out_expected"], dtype=float), atol=1e-14)
+    np.testing.assert_allclose(orc.lm_score(q, k, n_c=0)[0], g["causal_two_token_chunk"]["lm_score_expected"], atol=1e-14)
+
+
+# ----------------------------------------------------------------------------
+# brute force in pure Python (no numpy arithmetic) on tiny shapes
+# ----------------------------------------------------------------------------
+
+def _py_attention(q, kc, vc, n_c, scale):
+    """Nested-loop causal attention for one (query head, kv head) pair."""
+    c, d = len(q), len(q[0])
+    out, probs = [], []
+    for t in range(c):
+        last = n_c + t
+        logits = [scale * sum(q[t][x] * kc[j][x] for x in range(d)) for j in range(last + 1)]
+        m = max(logits)
+        e = [math.exp(s - m) for s in logits]
+        z = sum(e)
+        p = [x / z for x in e] + [0.0] * (len(kc) - last - 1)
+        probs.append(p)
+        out.append([sum(p[j] * vc[j][x] for j in range(last + 1)) for x in range(d)])
+    return out, probs
+
+
+@pytest.mark.parametrize("hq,hkv,c,n_c,d", [(4, 2, 5, 3, 8), (3, 3, 4, 0, 4), (6, 2, 1, 7, 8)])
+def test_chunk_attn_and_scores_vs_python_loops(hq, hkv, c, n_c, d):
+    r = rng(hq * 100 + c)
+    n = n_c + c
+    q = r.normal(size=(hq, c, d))
+    k = r.normal(size=(hkv, n, d))
+    v = r.normal(size=(hkv, n, d))
+    qi = r.normal(size=(hq, 3, d))
+    out, lse, probs = orc.chunk_attn(q, k, v, n_c)
+    g_size = hq // hkv
+    scale = 1.0 / math.sqrt(d)
+    lm = [[0.0] * n for _ in range(hkv)]
+    ins = [[0.0] * n for _ in range(hkv)]
+    for h in range(hq):
+        g = h // g_size
+        o_py, p_py = _py_attention(q[h].tolist(), k[g].tolist(), v[g].tolist(), n_c, scale)
+        np.testing.assert_allclose(out[h], np.array(o_py), atol=1e-12)
+        for t in range(c):
+            for j in range(n):
+                lm[g][j] += p_py[t][j]
+        # instruction rows: no mask, softmax over all n keys
+        for u in range(3):
+            logits = [scale * sum(qi[h, u, x] * k[g, j, x] for x in range(d)) for j in range(n)]
+            z = sum(math.exp(s) for s in logits)
+            for j in range(n):
+                ins[g][j] += math.exp(logits[j]) / z
+    np.testing.assert_allclose(orc.lm_score(q, k, n_c), np.array(lm), atol=1e-12)
+    np.testing.assert_allclose(orc.instr_score(qi, k), np.array(ins), atol=1e-12)
+
+
+def _py_topk(score, k):
+    """Repeatedly remove the best remaining candidate (highest score, then
+    lowest index)."""
+    n = len(score)
+    if n <= k:
+        return list(range(n))
+    alive = list(range(n))
+    chosen = []
+    for _ in range(k):
+        best = alive[0]
+        for j in alive[1:]:
+            if score[j] > score[best]:
+                best = j
+        alive.remove(best)
+        chosen.append(best)
+    return sorted(chosen)
+
+
+@pytest.mark.parametrize("n,k,levels", [(17, 5, None), (64, 64, None), (40, 39, 3), (33, 1, 2), (50, 20, 4), (9, 30, None)])
+def test_topk_vs_bruteforce(n, k, levels):
+    r = rng(n * 1000 + k)
+    for _ in range(20):
+        s = r.random(n) if levels is None else r.integers(0, levels, n).astype(np.float64)
+        assert orc.topk_select_1d(s, k).tolist() == _py_topk(s.tolist(), k)
+
+
+def test_topk_equals_full_sort_set():
+    r = rng(5)
+    s = r.random(300)
+    idx = orc.topk_select_1d(s, 100)
+    assert set(idx.tolist()) == set(np.argsort(s)[::-1][:100].tolist())
+    assert np.all(np.diff(idx) > 0)
+
+
+def test_topk_per_layer_sums_heads():
+    s = np.array([[0.9, 0.1, 0.5, 0.0], [0.0, 0.2, 0.6, 0.3]])
+    # per head: top-2 are {0,2} and {2,3}; layer-wise sums are .9 .3 1.1 .3 -> {0,2}
+    np.testing.assert_array_equal(orc.topk_select(s, 2), [[0, 2], [2, 3]])
+    np.testing.assert_array_equal(orc.topk_select(s, 2, orc.SELECT_PER_LAYER), [[0, 2]])
+    # layer-wise tie between positions 1 and 3 (sum .3 each): the lower index wins
+    np.testing.assert_array_equal(orc.topk_select(s, 3, orc.SELECT_PER_LAYER), [[0, 1, 2]])
+
+
+# ----------------------------------------------------------------------------
+# invariants and closed forms
+# ----------------------------------------------------------------------------
+
+def test_softmax_rows_sum_to_one_and_mass():
+    r = rng(11)
+    hq, hkv, c, n_c, d, n_i = 8, 2, 16, 24, 16, 5
+    q = r.normal(size=(hq, c, d)) * 3
+    k = r.normal(size=(hkv, n_c + c, d)) * 3
+    v = r.normal(size=(hkv, n_c + c, d))
+    qi = r.normal(size=(hq, n_i, d)) * 3
+    _, _, probs = orc.chunk_attn(q, k, v, n_c)
+    np.testing.assert_allclose(probs.sum(axis=-1), 1.0, atol=1e-12)
+    # masked entries are exactly zero
+    for t in range(c):
+        assert np.all(probs[:, t, n_c + t + 1:] == 0.0)
+    g_size = hq // hkv
+    np.testing.assert_allclose(orc.instr_score(qi, k).sum(axis=1), n_i * g_size, atol=1e-11)
+    np.testing.assert_allclose(orc.lm_score(q, k, n_c).sum(axis=1), c * g_size, atol=1e-11)
+
+
+def test_zero_instruction_queries_give_uniform_scores():
+    r = rng(3)
+    k = r.normal(size=(2, 37, 8))
+    s = orc.instr_score(np.zeros((4, 6, 8)), k)
+    np.testing.assert_allclose(s, 6 * 2 / 37.0, atol=1e-13)
+
+
+def test_identical_keys_give_equal_scores_and_lowest_indices():
+    r = rng(4)
+    key = r.normal(size=(8,))
+    k = np.broadcast_to(key, (2, 50, 8)).copy()
+    qi = r.normal(size=(4, 6, 8))
+    s = orc.instr_score(qi, k)
+    np.testing.assert_allclose(s, 6 * 2 / 50.0, atol=1e-13)
+    # all-equal scores (exactly equal by construction here): lowest indices win
+    np.testing.assert_array_equal(orc.topk_select(np.full((2, 50), 0.24), 7), np.tile(np.arange(7), (2, 1)))
+
+
+def test_dominant_key_takes_all_mass():
+    r = rng(6)
+    d = 8
+    k = r.normal(size=(1, 20, d)) * 0.01
+    k[0, 13] = 100.0
+    qi = np.abs(r.normal(size=(2, 4, d))) + 0.5
+    s = orc.instr_score(qi, k)
+    assert abs(s[0, 13] - 8.0) < 1e-9 and s[0].sum() == pytest.approx(8.0)
+
+
+def test_instr_score_permutation_equivariance_and_head_grouping():
+    r = rng(8)
+    hq, hkv, n, d = 6, 3, 29, 8
+    k = r.normal(size=(hkv, n, d))
+    qi = r.normal(size=(hq, 4, d))
+    perm = r.permutation(n)
+    np.testing.assert_allclose(orc.instr_score(qi, k[:, perm]), orc.instr_score(qi, k)[:, perm], atol=1e-13)
+    # contiguous grouping: zeroing heads 0,1 (group 0) makes only KV head 0 uniform
+    qz = qi.copy()
+    qz[0:2] = 0.0
+    s = orc.instr_score(qz, k)
+    np.testing.assert_allclose(s[0], 4 * 2 / n, atol=1e-13)
+    assert np.std(s[1]) > 1e-3 and np.std(s[2]) > 1e-3
+
+
+def test_tova_special_case_single_token_chunk():
+    """A chunk of one token with one query head per KV head: the chunk score
+    is that token's attention row (TOVA as CSE with l_s = 1, Section 5.2)."""
+    r = rng(9)
+    d, n_c = 16, 30
+    q = r.normal(size=(2, 1, d))
+    k = r.normal(size=(2, n_c + 1, d))
+    s = orc.lm_score(q, k, n_c)
+    for h in range(2):
+        row = torch.softmax(torch.from_numpy(q[h, 0] @ k[h].T / math.sqrt(d)), dim=0).numpy()
+        np.testing.assert_allclose(s[h], row, atol=1e-13)
+
+
+def test_custom_scale_is_used():
+    r = rng(10)
+    q = r.normal(size=(1, 2, 4)); k = r.normal(size=(1, 5, 4)); v = r.normal(size=(1, 5, 4))
+    o1, _, _ = orc.chunk_attn(q, k, v, 3, scale=0.5)      # 1/sqrt(4)
+    o2, _, _ = orc.chunk_attn(q, k, v, 3)
+    o3, _, _ = orc.chunk_attn(q, k, v, 3, scale=0.25)
+    np.testing.assert_allclose(o1, o2, atol=1e-15)
+    assert np.max(np.abs(o1 - o3)) > 1e-3
+
+
+# ----------------------------------------------------------------------------
+# library special case: torch's CPU attention
+# ----------------------------------------------------------------------------
+
+def _sdpa(q, k, v, mask=None, causal=False, group=1):
+    tq = torch.from_numpy(q)[None]
+    tk = torch.from_numpy(np.repeat(k, group, axis=0))[None]
+    tv = torch.from_numpy(np.repeat(v, group, axis=0))[None]
+    m = None if mask is None else torch.from_numpy(mask)
+    return torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=m, is_causal=causal)[0].numpy()
+
+
+def _doc(seed, hq, hkv, t, d, n_i, chunk):
+    r = rng(seed)
+    n_chunks = (t + chunk - 1) // chunk
+    return (r.normal(size=(hq, t, d)), r.normal(size=(hkv, t, d)), r.normal(size=(hkv, t, d)),
+            [r.normal(size=(hq, n_i, d)) for _ in range(n_chunks)])
+
+
+def test_chunk_attn_vs_torch_sdpa():
+    hq, hkv, t, d = 4, 2, 24, 8
+    q, k, v, _ = _doc(21, hq, hkv, t, d, 2, 8)
+    np.testing.assert_allclose(orc.full_causal_attention(q, k, v), _sdpa(q, k, v, causal=True, group=2), atol=1e-12)
+
+
+@pytest.mark.parametrize("mode", [orc.CACHE_INSTR, orc.CACHE_SHARED, orc.CACHE_DUAL])
+def test_budget_at_least_document_is_full_attention(mode):
+    hq, hkv, t, d, chunk = 4, 2, 45, 8, 8          # ragged last chunk of 5
+    q, k, v, qi = _doc(22, hq, hkv, t, d, 3, chunk)
+    res = orc.process_document(q, k, v, qi, chunk, budget=64, cache_mode=mode, budget_lm=64)
+    out = np.concatenate([tr.out for tr in res.trace], axis=1)
+    np.testing.assert_allclose(out, _sdpa(q, k, v, causal=True, group=2), atol=1e-12)
+    assert res.k_cache.shape[1] == t
+    np.testing.assert_array_equal(res.positions, np.tile(np.arange(t), (hkv, 1)))
+    np.testing.assert_array_equal(res.k_cache, k)
+
+
+def test_sliding_window_replay_matches_banded_attention():
+    """Forcing 'keep the most recent k candidates' turns the loop into
+    sliding-window attention, which torch computes with a band mask: pins the
+    cache/chunk concatenation, n_c bookkeeping and the gather."""
+    hq, hkv, t, d, chunk, budget = 2, 1, 40, 8, 6, 9
+    q, k, v, qi = _doc(23, hq, hkv, t, d, 2, chunk)
+    n_chunks = (t + chunk - 1) // chunk
+    forced, n_c = [], 0
+    for i in range(n_chunks):
+        c = min(chunk, t - i * chunk)
+        n = n_c + c
+        keep = min(budget, n)
+        forced.append(np.arange(n - keep, n)[None, :])
+        n_c = keep
+    res = orc.process_document(q, k, v, qi, chunk, budget, forced_idx=forced)
+    out = np.concatenate([tr.out for tr in res.trace], axis=1)
+    # row t (chunk i starting at lo) sees positions max(0, lo - budget) .. t
+    mask = np.zeros((t, t), dtype=bool)
+    for row in range(t):
+        lo = (row // chunk) * chunk
+        mask[row, max(0, lo - budget):row + 1] = True
+    np.testing.assert_allclose(out, _sdpa(q, k, v, mask=mask, group=2), atol=1e-12)
+    np.testing.assert_array_equal(res.positions[0], np.arange(t - budget, t))
+    np.testing.assert_array_equal(res.v_cache[0], v[0, t - budget:])
+
+
+def test_process_document_invariants_and_cache_contents():
+    hq, hkv, t, d, chunk, budget = 4, 2, 70, 8, 16, 24
+    q, k, v, qi = _doc(24, hq, hkv, t, d, 3, chunk)
+    res = orc.process_document(q, k, v, qi, chunk, budget)
+    tokens = 0
+    for i, tr in enumerate(res.trace):
+        assert tr.n_c == min(budget, tokens)
+        c = min(chunk, t - i * chunk)
+        tokens += c
+        assert tr.idx.shape == (hkv, min(budget, tr.n_c + c))
+        assert np.all(np.diff(tr.idx, axis=1) > 0)
+        np.testing.assert_allclose(tr.score.sum(axis=1), 3 * 2, atol=1e-11)
+    assert res.positions.shape == (hkv, budget)
+    assert np.all(np.diff(res.positions, axis=1) > 0)
+    for g in range(hkv):
+        np.testing.assert_array_equal(res.k_cache[g], k[g, res.positions[g]])
+        np.testing.assert_array_equal(res.v_cache[g], v[g, res.positions[g]])
+    # the two single-cache modes are the same computation
+    res2 = orc.process_document(q, k, v, qi, chunk, budget, cache_mode=orc.CACHE_SHARED)
+    np.testing.assert_array_equal(res.positions, res2.positions)
+    # layer-wise selection: every KV head keeps the same positions
+    res3 = orc.process_document(q, k, v, qi, chunk, budget, select_mode=orc.SELECT_PER_LAYER)
+    np.testing.assert_array_equal(res3.positions[0], res3.positions[1])
+    assert res3.trace[-1].idx.shape[0] == 1
+
+
+def test_dual_mode_threads_are_separate():
+    """Chunk attention reads the LM cache, the instruction score reads the
+    instruction cache: force the LM cache to a sliding window and the
+    instruction cache to 'oldest positions' and check each against torch."""
+    hq, hkv, t, d, chunk, budget = 2, 1, 30, 8, 5, 7
+    q, k, v, qi = _doc(25, hq, hkv, t, d, 2, chunk)
+    n_chunks = t // chunk
+    f_lm, f_in, n_c = [], [], 0
+    for i in range(n_chunks):
+        n = n_c + chunk
+        keep = min(budget, n)
+        f_lm.append(np.arange(n - keep, n)[None, :])
+        f_in.append(np.arange(keep)[None, :])
+        n_c = keep
+    res = orc.process_document(q, k, v, qi, chunk, budget, cache_mode=orc.CACHE_DUAL, budget_lm=budget,
+                               forced_idx=f_in, forced_idx_lm=f_lm)
+    out = np.concatenate([tr.out for tr in res.trace], axis=1)
+    mask = np.zeros((t, t), dtype=bool)
+    for row in range(t):
+        lo = (row // chunk) * chunk
+        mask[row, max(0, lo - budget):row + 1] = True
+    np.testing.assert_allclose(out, _sdpa(q, k, v, mask=mask, group=2), atol=1e-12)
+    np.testing.assert_array_equal(res.positions[0], np.arange(budget))
+    np.testing.assert_array_equal(res.positions_lm[0], np.arange(t - budget, t))
+    # last step's instruction score: softmax over [positions 0..6 ; last chunk]
+    cand = np.concatenate([np.arange(budget), np.arange(t - chunk, t)])
+    logits = torch.from_numpy(qi[n_chunks - 1] @ k[0, cand].T / math.sqrt(d))
+    expect = torch.softmax(logits, dim=-1).sum(dim=(0, 1)).numpy()
+    np.testing.assert_allclose(res.trace[-1].score[0], expect, atol=1e-12)
+    # LM score of the last step sums the causal probabilities over [window ; chunk]
+    np.testing.assert_allclose(res.trace[-1].score_lm.sum(), chunk * hq, atol=1e-11)
+
+
+def test_kv_compact_is_a_bit_copy_and_broadcasts():
+    r = rng(30)
+    k = r.normal(size=(3, 10, 4)).astype(np.float32)
+    v = r.normal(size=(3, 10, 4)).astype(np.float32)
+    idx = np.array([[1, 4, 9]])
+    kn, vn = orc.kv_compact(k, v, idx)
+    assert kn.dtype == np.float32
+    for g in range(3):
+        np.testing.assert_array_equal(kn[g], k[g, [1, 4, 9]])
+        np.testing.assert_array_equal(vn[g], v[g, [1, 4, 9]])
+    kn, _ = orc.kv_compact(k, v, np.tile(np.arange(10), (3, 1)))
+    np.testing.assert_array_equal(kn, k)
