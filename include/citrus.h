@@ -1,0 +1,264 @@
+/*
+ * citrus.h - C ABI of the CItruS chunk-eviction hot path for AMD MI355X (gfx950).
+ *
+ * CItruS = Chunked Instruction-aware State Eviction (arXiv 2406.12018).  A long
+ * document is read chunk by chunk against a bounded key/value cache; after each
+ * chunk the cache is cut back to its budget k by keeping the states with the
+ * highest attention-based importance.  This library implements the per-chunk,
+ * per-layer step of that procedure for all (document, layer, head) units at
+ * once:
+ *
+ *   citrus_chunk_attn       the chunk's queries attend causally over
+ *                           [retained cache ; chunk]            (Section 4.1, step 1)
+ *   citrus_instr_score      the instruction's queries attend over the same
+ *                           keys; softmax weights are summed per key
+ *                                                               (Eq. (1) with s = I, Section 4.2)
+ *   citrus_topk_select      keep the k highest scores           (Eq. (2)-(3), (4)-(5))
+ *   citrus_kv_compact       gather the kept K/V rows into the new cache
+ *                                                               (Eq. (3), (5))
+ *   citrus_process_document the chunk loop around those four    (Section 4.1 "Overall
+ *                                                               process", Section 4.3)
+ *
+ * General rules, valid for every entry point
+ * ------------------------------------------
+ * Memory.  Every pointer is a DEVICE pointer unless its comment says "host".
+ *   The caller owns all buffers, including the workspace; the library allocates
+ *   and frees no device memory and keeps no mutable global state.
+ * Tensors.  A citrus_tensor is a base pointer plus ELEMENT strides for the
+ *   document (b), layer (l), head (h) and sequence (s) axes; the head_dim axis is
+ *   contiguous (stride 1).  Rows (one head_dim vector) must start on a 16-byte
+ *   boundary, i.e. ptr is 16-byte aligned and every stride is a multiple of
+ *   8 (bf16) or 4 (f32) elements.  Element type is citrus_config.dtype.
+ *   bf16 is the 16-bit brain-float, stored as its raw bits.
+ * Heads.  Query head h reads KV head h / G with G = q_heads / kv_heads
+ *   (contiguous groups).
+ * Candidates.  The keys a step works on are the concatenation
+ *   [cache rows 0..cache_len-1 ; chunk rows 0..chunk_len-1]; n = cache_len +
+ *   chunk_len.  Candidate index j < cache_len is cache row j, otherwise chunk
+ *   row j - cache_len.
+ * Streams.  hip_stream is a hipStream_t (NULL = the default stream).  Calls
+ *   only enqueue work and return; results are valid once the stream has been
+ *   synchronised by the caller.  No call synchronises the device.
+ * Errors.  Every entry point returns a citrus_status.  Arguments are validated
+ *   on the host before anything is launched; on a validation error nothing is
+ *   launched and outputs are untouched.  A failed launch maps to
+ *   CITRUS_ERR_DEVICE.  Nothing throws or aborts across this boundary.
+ * Determinism.  No floating-point atomics are used anywhere: the same inputs
+ *   give bit-identical outputs from run to run.
+ * Concurrency.  Calls that share a workspace or an output buffer must be
+ *   ordered on one stream (or by the caller); otherwise calls are independent.
+ */
+#ifndef CITRUS_H
+#define CITRUS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CITRUS_ABI_VERSION 1
+
+typedef enum {
+  CITRUS_OK = 0,
+  CITRUS_ERR_NULL = 1,        /* a required pointer is NULL                          */
+  CITRUS_ERR_SHAPE = 2,       /* sizes/strides inconsistent or out of range          */
+  CITRUS_ERR_UNSUPPORTED = 3, /* dtype / head_dim / mode not implemented             */
+  CITRUS_ERR_WORKSPACE = 4,   /* workspace NULL or smaller than citrus_workspace_bytes */
+  CITRUS_ERR_DEVICE = 5,      /* the HIP runtime reported an error at launch         */
+  CITRUS_ERR_PROVIDER = 6     /* the chunk provider returned a negative value        */
+} citrus_status;
+
+typedef enum { CITRUS_F32 = 0, CITRUS_BF16 = 1 } citrus_dtype;
+
+/* Cache designs of Section 4.2.  INSTR and SHARED run the same kernel sequence
+ * on one cache that the chunk attends over and the instruction scores (with
+ * layer-independent synthetic inputs there is no separate language-modelling
+ * cache to differ from); DUAL keeps a language-modelling cache, scored by the
+ * chunk's own attention (Eq. (1) with s = chunk), next to the instruction cache. */
+typedef enum { CITRUS_CACHE_INSTR = 0, CITRUS_CACHE_SHARED = 1, CITRUS_CACHE_DUAL = 2 } citrus_cache_mode;
+
+/* PER_KV_HEAD: one index set per (document, layer, KV head).
+ * PER_LAYER:   scores of all KV heads are added first and one index set is used
+ *              by the whole layer (the layer-wise eviction of Section 4.1).     */
+typedef enum { CITRUS_SELECT_PER_KV_HEAD = 0, CITRUS_SELECT_PER_LAYER = 1 } citrus_select_mode;
+
+/* Plain data, passed by pointer, read during the call only. */
+typedef struct {
+  int32_t batch;          /* B  documents                                    >= 1 */
+  int32_t layers;         /* L                                               >= 1 */
+  int32_t q_heads;        /* Hq, a multiple of kv_heads                          */
+  int32_t kv_heads;       /* Hkv                                             >= 1 */
+  int32_t head_dim;       /* d: 64 or 128                                        */
+  int32_t chunk_len;      /* l_s: maximum chunk length c                     >= 1 */
+  int32_t budget;         /* k: states kept in the (instruction) cache       >= 1 */
+  int32_t budget_lm;      /* DUAL: budget of the language-modelling cache; else ignored */
+  int32_t instr_len;      /* n_i: instruction tokens                         >= 1 */
+  int32_t cache_capacity; /* rows per head of every cache buffer, >= max(budget, budget_lm) */
+  int32_t dtype;          /* citrus_dtype                                        */
+  int32_t cache_mode;     /* citrus_cache_mode                                   */
+  int32_t select_mode;    /* citrus_select_mode                                  */
+  float softmax_scale;    /* 0 -> 1/sqrt(head_dim), the scaling of Eq. (1)       */
+} citrus_config;
+
+typedef struct {
+  void* ptr;
+  int64_t stride_b, stride_l, stride_h, stride_s; /* in elements */
+} citrus_tensor;
+
+/* Bytes of workspace that is enough for any entry point under this
+ * configuration (0 if cfg is NULL or invalid). */
+size_t citrus_workspace_bytes(const citrus_config* cfg);
+
+/* Static, NUL-terminated description of a status code (host pointer). */
+const char* citrus_status_string(int32_t status);
+
+int32_t citrus_abi_version(void);
+
+/*
+ * Chunk attention (Section 4.1, step 1: "encode the current text chunk given
+ * the cache"; softmax and 1/sqrt(d_k) scaling as written inside Eq. (1)).
+ *
+ *   out[b,l,h,t,:] = sum_j softmax_j( scale * q[b,l,h,t,:] . Kcat[b,l,h/G,j,:] ) * Vcat[b,l,h/G,j,:]
+ *   over candidates j <= cache_len + t (the whole cache and the causal prefix
+ *   of the chunk).
+ *
+ * q, out      [B, L, Hq, chunk_len, d]
+ * k_cache, v_cache [B, L, Hkv, >= cache_len, d]   (ptr may be NULL iff cache_len == 0)
+ * k_chunk, v_chunk [B, L, Hkv, chunk_len, d]
+ * cache_len   0 .. cfg->cache_capacity;  chunk_len 1 .. cfg->chunk_len
+ * lse         optional, dense [B, L, Hq, chunk_len] f32: log-sum-exp of each
+ *             row's scaled logits over the candidates it sees
+ * lm_score    optional, dense [B, L, Hkv, n] f32: chunk-scored importance,
+ *             lm_score[b,l,g,j] = sum over heads h of group g and chunk rows t
+ *             of the attention probability p[h,t,j] (0 where masked); Eq. (1)
+ *             with s = the chunk, as a sum (divide by chunk_len*G for the mean).
+ *             Needs lse: if lse is NULL the workspace is used for it.
+ * Compute: bf16 inputs, f32 accumulation, probabilities rounded to bf16 before
+ * the P.V product, bf16 output; f32 mode computes in f32 throughout.
+ */
+int32_t citrus_chunk_attn(const citrus_config* cfg, citrus_tensor q, citrus_tensor k_cache, citrus_tensor v_cache,
+                          int32_t cache_len, citrus_tensor k_chunk, citrus_tensor v_chunk, int32_t chunk_len,
+                          citrus_tensor out, float* lse, float* lm_score, void* workspace, size_t workspace_bytes,
+                          void* hip_stream);
+
+/*
+ * Instruction-aware importance (Eq. (1) with the instruction I in the role of
+ * the chunk: Imp(I, c^I) / Imp(I, c) of Section 4.2), as a sum:
+ *
+ *   score[b,l,g,j] = sum_{h in group g} sum_{u < instr_len}
+ *                    softmax_j( scale * q_instr[b,l,h,u,:] . Kcat[b,l,g,j,:] )
+ *
+ * with the softmax over all n candidates, no mask.  Each row of score sums to
+ * instr_len * G; Imp = score / (instr_len * G).
+ *
+ * q_instr [B, L, Hq, instr_len, d];  K segments as in citrus_chunk_attn.
+ * score   dense [B, L, Hkv, n] f32.
+ * workspace: >= citrus_workspace_bytes(cfg).
+ */
+int32_t citrus_instr_score(const citrus_config* cfg, citrus_tensor q_instr, citrus_tensor k_cache, int32_t cache_len,
+                           citrus_tensor k_chunk, int32_t chunk_len, float* score, void* workspace,
+                           size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Selection (Eq. (2)-(3)): the positions of the min(k, n) highest scores.
+ * Equal scores: the lower position wins.  Output positions are ascending, so
+ * kept states stay in their original order.  n <= k keeps everything
+ * (0..n-1), as the first chunk does in the paper.
+ *
+ * score dense [B, L, Hkv, n] f32 (finite values).
+ * idx   dense int32, row pitch k:  [B, L, Hkv, k] (PER_KV_HEAD) or [B, L, 1, k]
+ *       (PER_LAYER, scores added over Hkv in head order first).  Entries
+ *       min(k,n).. of a row are left untouched.
+ * n >= 1, k >= 1.  No workspace needed (arguments kept for symmetry; may be NULL/0).
+ */
+int32_t citrus_topk_select(const citrus_config* cfg, const float* score, int32_t n, int32_t k, int32_t* idx,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Compaction (Eq. (3), (5): the evicted cache holds exactly the selected
+ * states):  k_new[b,l,g,r,:] = Kcat[b,l,g, idx[b,l,g',r], :], same for V, for
+ * r < m, where g' = g (PER_KV_HEAD) or 0 (PER_LAYER).  Bit copies.
+ *
+ * idx   dense int32 with row pitch idx_pitch (>= m), values in [0, n).
+ * m     rows to write per head, 1 .. cfg->cache_capacity.
+ * k_new, v_new [B, L, Hkv, >= m, d]; must not overlap any source.
+ */
+int32_t citrus_kv_compact(const citrus_config* cfg, citrus_tensor k_cache, citrus_tensor v_cache, int32_t cache_len,
+                          citrus_tensor k_chunk, citrus_tensor v_chunk, int32_t chunk_len, const int32_t* idx,
+                          int32_t idx_pitch, int32_t m, citrus_tensor k_new, citrus_tensor v_new, void* hip_stream);
+
+/* One chunk's tensors, filled in by the provider. */
+typedef struct {
+  citrus_tensor q;       /* [B, L, Hq,  chunk_len, d]                         */
+  citrus_tensor k, v;    /* [B, L, Hkv, chunk_len, d]                         */
+  citrus_tensor q_instr; /* [B, L, Hq,  instr_len, d] instruction queries for this step */
+  citrus_tensor out;     /* [B, L, Hq,  chunk_len, d] where to write the attention output */
+  int32_t chunk_len;     /* 1 .. cfg->chunk_len (the last chunk may be short)  */
+} citrus_chunk_io;
+
+/* Host callback.  Must fill *io for chunk `chunk_index` (buffers valid on
+ * hip_stream until the stream has passed this step) and return 0; return 1
+ * for "no more chunks", a negative value to abort. */
+typedef int32_t (*citrus_chunk_provider)(void* user, int32_t chunk_index, void* hip_stream, citrus_chunk_io* io);
+
+/* A ready-made provider for documents that are resident in device memory:
+ * pass citrus_resident_provider as `next` and a (host) pointer to this struct
+ * as `user`.  Chunk i covers document positions i*chunk_len .. min(doc_len,
+ * (i+1)*chunk_len)-1. */
+typedef struct {
+  citrus_tensor q;       /* [B, L, Hq,  doc_len, d]                            */
+  citrus_tensor k, v;    /* [B, L, Hkv, doc_len, d]                            */
+  citrus_tensor out;     /* [B, L, Hq,  doc_len, d]                            */
+  citrus_tensor q_instr; /* [B, L, Hq,  instr_len, d] for chunk 0 ...          */
+  int64_t q_instr_stride_chunk; /* ... plus this many elements per chunk (0 = same queries every chunk) */
+  int32_t doc_len;
+  int32_t chunk_len;     /* must equal cfg->chunk_len                          */
+  int32_t dtype;         /* citrus_dtype of the tensors (must equal cfg->dtype) */
+} citrus_resident_doc;
+int32_t citrus_resident_provider(void* user, int32_t chunk_index, void* hip_stream, citrus_chunk_io* io);
+
+/*
+ * The chunk loop (Section 4.1 "Overall process", Section 4.3).  For chunk
+ * index i = first_chunk, first_chunk+1, ... until `max_chunks` steps are done
+ * or the provider returns 1:
+ *   INSTR / SHARED:  chunk_attn over [cache ; chunk] -> io.out;
+ *                    instr_score over the same keys; topk_select(budget);
+ *                    kv_compact into the other buffer of the ping-pong pair.
+ *   DUAL:            chunk_attn (+ chunk-scored importance) over
+ *                    [LM cache ; chunk], topk_select(budget_lm), kv_compact of
+ *                    the LM pair; then instr_score / topk_select(budget) /
+ *                    kv_compact on the instruction pair.
+ * An empty cache (length 0) is the start of a document: the first chunk enters
+ * whole if it fits the budget.
+ *
+ * k_cache[2], v_cache[2]        ping-pong buffers [B, L, Hkv, cache_capacity, d]
+ *                               of the instruction (or only) cache
+ * k_cache_lm[2], v_cache_lm[2]  DUAL only (else may be NULL pointers)
+ * cache_len, cache_len_lm       host, in/out: valid rows on entry / on return
+ *                               (cache_len_lm may be NULL unless DUAL)
+ * buffer_index, buffer_index_lm host, in/out: which buffer of the pair is
+ *                               current (0/1) on entry / on return.  Passing
+ *                               the values a previous call returned, with the
+ *                               same buffers, resumes a document bit-exactly.
+ * idx_history     optional dense int32 [steps, B, L, Hsel, budget]: the
+ *                 selection of every step done by this call (step 0 = chunk
+ *                 first_chunk); Hsel = Hkv or 1 (PER_LAYER)
+ * idx_history_lm  same for the LM cache with pitch budget_lm (DUAL)
+ * chunks_done     host, optional: number of steps performed
+ * No host/device synchronisation happens inside the loop.
+ */
+int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider next, void* user,
+                                int32_t first_chunk, int32_t max_chunks,
+                                const citrus_tensor* k_cache, const citrus_tensor* v_cache,
+                                const citrus_tensor* k_cache_lm, const citrus_tensor* v_cache_lm,
+                                int32_t* cache_len, int32_t* cache_len_lm,
+                                int32_t* buffer_index, int32_t* buffer_index_lm,
+                                int32_t* idx_history, int32_t* idx_history_lm, int32_t* chunks_done,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CITRUS_H */

@@ -1,0 +1,8 @@
+"""MI355X-native CItruS chunk-eviction hot path: HIP kernels behind a C ABI
+(include/citrus.h) and this thin ctypes binding."""
+
+from .binding import (  # noqa: F401
+    BF16, F32, CACHE_DUAL, CACHE_INSTR, CACHE_SHARED, SELECT_PER_KV_HEAD, SELECT_PER_LAYER,
+    CitrusError, Config, DocumentState, abi_version, alloc_workspace, citrus_chunk_attn, citrus_instr_score,
+    citrus_kv_compact, citrus_process_document, citrus_topk_select, resident_doc, status_string, workspace_bytes,
+)

@@ -1,0 +1,319 @@
+"""ctypes binding of libcitrus.so (the C ABI in include/citrus.h).
+
+Argument marshalling only: every step of the hot path runs in the HIP kernels
+behind the C entry points of the same names.  torch is used for device memory
+and for the current HIP stream, nothing else.  There is no CPU fallback: if the
+library is missing or an entry point fails, an exception is raised.
+"""
+
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Callable, Optional, Sequence
+
+import torch
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libcitrus.so")
+
+F32, BF16 = 0, 1
+CACHE_INSTR, CACHE_SHARED, CACHE_DUAL = 0, 1, 2
+SELECT_PER_KV_HEAD, SELECT_PER_LAYER = 0, 1
+
+OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE, ERR_PROVIDER = range(7)
+
+EXPORTS = (
+    "citrus_abi_version", "citrus_status_string", "citrus_workspace_bytes", "citrus_chunk_attn",
+    "citrus_instr_score", "citrus_topk_select", "citrus_kv_compact", "citrus_resident_provider",
+    "citrus_process_document",
+)
+
+
+class CitrusError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = _lib().citrus_status_string(status).decode() if _LIB is not None else "?"
+        super().__init__(f"{where}: status {status} ({msg})")
+
+
+class CConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "batch", "layers", "q_heads", "kv_heads", "head_dim", "chunk_len", "budget", "budget_lm", "instr_len",
+        "cache_capacity", "dtype", "cache_mode", "select_mode")] + [("softmax_scale", C.c_float)]
+
+
+class CTensor(C.Structure):
+    _fields_ = [("ptr", C.c_void_p), ("stride_b", C.c_int64), ("stride_l", C.c_int64), ("stride_h", C.c_int64),
+                ("stride_s", C.c_int64)]
+
+
+class CChunkIO(C.Structure):
+    _fields_ = [("q", CTensor), ("k", CTensor), ("v", CTensor), ("q_instr", CTensor), ("out", CTensor),
+                ("chunk_len", C.c_int32)]
+
+
+class CResidentDoc(C.Structure):
+    _fields_ = [("q", CTensor), ("k", CTensor), ("v", CTensor), ("out", CTensor), ("q_instr", CTensor),
+                ("q_instr_stride_chunk", C.c_int64), ("doc_len", C.c_int32), ("chunk_len", C.c_int32),
+                ("dtype", C.c_int32)]
+
+
+PROVIDER = C.CFUNCTYPE(C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(CChunkIO))
+
+_LIB = None
+
+
+def _lib():
+    """Load libcitrus.so (built in-tree by paper_2406_12018_amd.build)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -m paper_2406_12018_amd.build); "
+                           "there is no fallback path")
+    lib = C.CDLL(LIB_PATH)
+    P, I, V, S = C.POINTER, C.c_int32, C.c_void_p, C.c_size_t
+    lib.citrus_abi_version.restype = I
+    lib.citrus_status_string.restype = C.c_char_p
+    lib.citrus_status_string.argtypes = [I]
+    lib.citrus_workspace_bytes.restype = S
+    lib.citrus_workspace_bytes.argtypes = [P(CConfig)]
+    lib.citrus_chunk_attn.restype = I
+    lib.citrus_chunk_attn.argtypes = [P(CConfig), CTensor, CTensor, CTensor, I, CTensor, CTensor, I, CTensor, V, V, V, S, V]
+    lib.citrus_instr_score.restype = I
+    lib.citrus_instr_score.argtypes = [P(CConfig), CTensor, CTensor, I, CTensor, I, V, V, S, V]
+    lib.citrus_topk_select.restype = I
+    lib.citrus_topk_select.argtypes = [P(CConfig), V, I, I, V, V, S, V]
+    lib.citrus_kv_compact.restype = I
+    lib.citrus_kv_compact.argtypes = [P(CConfig), CTensor, CTensor, I, CTensor, CTensor, I, V, I, I, CTensor, CTensor, V]
+    lib.citrus_resident_provider.restype = I
+    lib.citrus_resident_provider.argtypes = [V, I, V, P(CChunkIO)]
+    lib.citrus_process_document.restype = I
+    lib.citrus_process_document.argtypes = [P(CConfig), V, V, I, I, P(CTensor), P(CTensor), P(CTensor), P(CTensor),
+                                            P(I), P(I), P(I), P(I), V, V, P(I), V, S, V]
+    _LIB = lib
+    return lib
+
+
+@dataclass
+class Config:
+    batch: int
+    layers: int
+    q_heads: int
+    kv_heads: int
+    head_dim: int
+    chunk_len: int
+    budget: int
+    instr_len: int
+    dtype: int = BF16
+    cache_mode: int = CACHE_INSTR
+    select_mode: int = SELECT_PER_KV_HEAD
+    budget_lm: int = 0
+    cache_capacity: int = 0          # 0 -> max(budget, budget_lm)
+    softmax_scale: float = 0.0
+
+    def __post_init__(self):
+        if self.cache_capacity == 0:
+            self.cache_capacity = max(self.budget, self.budget_lm)
+
+    def c(self) -> CConfig:
+        return CConfig(self.batch, self.layers, self.q_heads, self.kv_heads, self.head_dim, self.chunk_len,
+                       self.budget, self.budget_lm, self.instr_len, self.cache_capacity, self.dtype,
+                       self.cache_mode, self.select_mode, self.softmax_scale)
+
+    @property
+    def torch_dtype(self) -> torch.dtype:
+        return torch.float32 if self.dtype == F32 else torch.bfloat16
+
+    @property
+    def sel_heads(self) -> int:
+        return 1 if self.select_mode == SELECT_PER_LAYER else self.kv_heads
+
+    @staticmethod
+    def from_workload(w, **overrides) -> "Config":
+        kw = dict(batch=w.batch, layers=w.layers, q_heads=w.q_heads, kv_heads=w.kv_heads, head_dim=w.head_dim,
+                  chunk_len=w.chunk_len, budget=w.budget, instr_len=w.instr_len,
+                  dtype=F32 if w.dtype == "f32" else BF16, cache_mode=w.cache_mode, select_mode=w.select_mode,
+                  budget_lm=w.budget_lm)
+        kw.update(overrides)
+        return Config(**kw)
+
+
+def tensor(t: Optional[torch.Tensor]) -> CTensor:
+    """[B, L, H, S, d] torch tensor (d contiguous) -> citrus_tensor."""
+    if t is None:
+        return CTensor(None, 0, 0, 0, 0)
+    if t.dim() != 5 or t.stride(4) != 1:
+        raise ValueError("expected a [B, L, H, S, d] tensor with contiguous last axis")
+    return CTensor(t.data_ptr(), t.stride(0), t.stride(1), t.stride(2), t.stride(3))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _check(status: int, where: str):
+    if status != OK:
+        raise CitrusError(status, where)
+
+
+def abi_version() -> int:
+    return _lib().citrus_abi_version()
+
+
+def status_string(status: int) -> str:
+    return _lib().citrus_status_string(status).decode()
+
+
+def workspace_bytes(cfg: Config) -> int:
+    cc = cfg.c()
+    return int(_lib().citrus_workspace_bytes(C.byref(cc)))
+
+
+def alloc_workspace(cfg: Config, device="cuda") -> torch.Tensor:
+    n = workspace_bytes(cfg)
+    if n == 0:
+        raise CitrusError(ERR_SHAPE, "citrus_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def citrus_chunk_attn(cfg: Config, q, k_cache, v_cache, cache_len: int, k_chunk, v_chunk, out=None, lse=None,
+                      lm_score=None, workspace=None, stream=None, chunk_len: Optional[int] = None):
+    chunk_len = q.shape[3] if chunk_len is None else chunk_len
+    if out is None:
+        out = torch.empty_like(q)
+    cc = cfg.c()
+    st = _lib().citrus_chunk_attn(C.byref(cc), tensor(q), tensor(k_cache), tensor(v_cache), cache_len,
+                                  tensor(k_chunk), tensor(v_chunk), chunk_len, tensor(out), _ptr(lse),
+                                  _ptr(lm_score), _ptr(workspace), 0 if workspace is None else workspace.numel(),
+                                  _stream(stream))
+    _check(st, "citrus_chunk_attn")
+    return out
+
+
+def citrus_instr_score(cfg: Config, q_instr, k_cache, cache_len: int, k_chunk, score=None, workspace=None,
+                       stream=None, chunk_len: Optional[int] = None):
+    chunk_len = k_chunk.shape[3] if chunk_len is None else chunk_len
+    if score is None:
+        score = torch.empty((cfg.batch, cfg.layers, cfg.kv_heads, cache_len + chunk_len), dtype=torch.float32,
+                            device=q_instr.device)
+    cc = cfg.c()
+    st = _lib().citrus_instr_score(C.byref(cc), tensor(q_instr), tensor(k_cache), cache_len, tensor(k_chunk),
+                                   chunk_len, _ptr(score), _ptr(workspace),
+                                   0 if workspace is None else workspace.numel(), _stream(stream))
+    _check(st, "citrus_instr_score")
+    return score
+
+
+def citrus_topk_select(cfg: Config, score, k: int, idx=None, stream=None, n: Optional[int] = None):
+    n = score.shape[-1] if n is None else n
+    if idx is None:
+        idx = torch.full((cfg.batch, cfg.layers, cfg.sel_heads, k), -1, dtype=torch.int32, device=score.device)
+    cc = cfg.c()
+    st = _lib().citrus_topk_select(C.byref(cc), _ptr(score), n, k, _ptr(idx), None, 0, _stream(stream))
+    _check(st, "citrus_topk_select")
+    return idx
+
+
+def citrus_kv_compact(cfg: Config, k_cache, v_cache, cache_len: int, k_chunk, v_chunk, idx, m: int, k_new, v_new,
+                      stream=None, chunk_len: Optional[int] = None, idx_pitch: Optional[int] = None):
+    chunk_len = k_chunk.shape[3] if chunk_len is None else chunk_len
+    idx_pitch = idx.shape[-1] if idx_pitch is None else idx_pitch
+    cc = cfg.c()
+    st = _lib().citrus_kv_compact(C.byref(cc), tensor(k_cache), tensor(v_cache), cache_len, tensor(k_chunk),
+                                  tensor(v_chunk), chunk_len, _ptr(idx), idx_pitch, m, tensor(k_new), tensor(v_new),
+                                  _stream(stream))
+    _check(st, "citrus_kv_compact")
+    return k_new, v_new
+
+
+@dataclass
+class DocumentState:
+    """Ping-pong cache buffers and the host-side bookkeeping of the chunk loop."""
+    k_cache: Sequence[torch.Tensor]
+    v_cache: Sequence[torch.Tensor]
+    cache_len: int = 0
+    buffer_index: int = 0
+    k_cache_lm: Optional[Sequence[torch.Tensor]] = None
+    v_cache_lm: Optional[Sequence[torch.Tensor]] = None
+    cache_len_lm: int = 0
+    buffer_index_lm: int = 0
+
+    @staticmethod
+    def allocate(cfg: Config, device="cuda") -> "DocumentState":
+        shape = (cfg.batch, cfg.layers, cfg.kv_heads, cfg.cache_capacity, cfg.head_dim)
+        mk = lambda: [torch.zeros(shape, dtype=cfg.torch_dtype, device=device) for _ in range(2)]
+        st = DocumentState(mk(), mk())
+        if cfg.cache_mode == CACHE_DUAL:
+            st.k_cache_lm, st.v_cache_lm = mk(), mk()
+        return st
+
+    def current(self):
+        return (self.k_cache[self.buffer_index][:, :, :, :self.cache_len],
+                self.v_cache[self.buffer_index][:, :, :, :self.cache_len])
+
+    def current_lm(self):
+        return (self.k_cache_lm[self.buffer_index_lm][:, :, :, :self.cache_len_lm],
+                self.v_cache_lm[self.buffer_index_lm][:, :, :, :self.cache_len_lm])
+
+
+def resident_doc(cfg: Config, q, k, v, q_instr, out, doc_len: Optional[int] = None) -> CResidentDoc:
+    """q [B,L,Hq,T,d], k/v [B,L,Hkv,T,d], out like q, q_instr [n_chunks,B,L,Hq,n_i,d] or [B,L,Hq,n_i,d]."""
+    if q_instr.dim() == 6:
+        qi0, stride_chunk = q_instr[0], q_instr.stride(0)
+    else:
+        qi0, stride_chunk = q_instr, 0
+    return CResidentDoc(tensor(q), tensor(k), tensor(v), tensor(out), tensor(qi0), stride_chunk,
+                        q.shape[3] if doc_len is None else doc_len, cfg.chunk_len, cfg.dtype)
+
+
+def citrus_process_document(cfg: Config, state: DocumentState, workspace, *, doc: Optional[CResidentDoc] = None,
+                            provider: Optional[Callable] = None, first_chunk: int = 0, max_chunks: int = -1,
+                            idx_history=None, idx_history_lm=None, stream=None) -> int:
+    """Run the chunk loop.  Either ``doc`` (a resident document, served by the
+    library's own provider) or ``provider`` (a Python callable
+    ``(chunk_index, io: CChunkIO) -> 0 | 1 | negative``) supplies the chunks.
+    Updates ``state`` in place and returns the number of chunks processed."""
+    lib = _lib()
+    if (doc is None) == (provider is None):
+        raise ValueError("give exactly one of doc / provider")
+    if doc is not None:
+        fn = C.cast(lib.citrus_resident_provider, C.c_void_p)
+        user = C.cast(C.pointer(doc), C.c_void_p)
+        keep = doc
+    else:
+        def _cb(_user, index, _stream_ptr, io_ptr):
+            try:
+                return int(provider(index, io_ptr.contents))
+            except Exception:  # never let an exception cross the C boundary
+                return -1
+        keep = PROVIDER(_cb)
+        fn = C.cast(keep, C.c_void_p)
+        user = None
+    arr = lambda ts: (CTensor * 2)(tensor(ts[0]), tensor(ts[1]))
+    kc, vc = arr(state.k_cache), arr(state.v_cache)
+    dual = state.k_cache_lm is not None
+    kl = arr(state.k_cache_lm) if dual else None
+    vl = arr(state.v_cache_lm) if dual else None
+    n_c, n_c_lm = C.c_int32(state.cache_len), C.c_int32(state.cache_len_lm)
+    cur, cur_lm = C.c_int32(state.buffer_index), C.c_int32(state.buffer_index_lm)
+    done = C.c_int32(0)
+    cc = cfg.c()
+    st = lib.citrus_process_document(C.byref(cc), fn, user, first_chunk, max_chunks, kc, vc, kl, vl,
+                                     C.byref(n_c), C.byref(n_c_lm), C.byref(cur), C.byref(cur_lm),
+                                     _ptr(idx_history), _ptr(idx_history_lm), C.byref(done), _ptr(workspace),
+                                     0 if workspace is None else workspace.numel(), _stream(stream))
+    del keep
+    state.cache_len, state.buffer_index = n_c.value, cur.value
+    if dual:
+        state.cache_len_lm, state.buffer_index_lm = n_c_lm.value, cur_lm.value
+    _check(st, "citrus_process_document")
+    return done.value

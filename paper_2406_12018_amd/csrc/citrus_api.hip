@@ -1,0 +1,371 @@
+// Host side of the C ABI declared in include/citrus.h: argument validation,
+// kernel dispatch, and the chunk loop of the paper's "Overall process"
+// (Section 4.1, Section 4.3).  No device memory is allocated here and no call
+// synchronises with the device.
+#include <math.h>
+#include <string.h>
+
+#include "citrus_internal.h"
+
+using namespace citrus;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+int elem_bytes(int dtype) { return dtype == CITRUS_F32 ? 4 : 2; }
+
+citrus_status check_config(const citrus_config* c) {
+  if (c == nullptr) return CITRUS_ERR_NULL;
+  if (c->batch < 1 || c->layers < 1 || c->q_heads < 1 || c->kv_heads < 1) return CITRUS_ERR_SHAPE;
+  if (c->q_heads % c->kv_heads != 0) return CITRUS_ERR_SHAPE;
+  if (c->chunk_len < 1 || c->budget < 1 || c->instr_len < 1) return CITRUS_ERR_SHAPE;
+  if (static_cast<int64_t>(c->batch) * c->layers > 65535 || c->q_heads > 65535) return CITRUS_ERR_SHAPE;
+  if (c->cache_mode != CITRUS_CACHE_INSTR && c->cache_mode != CITRUS_CACHE_SHARED &&
+      c->cache_mode != CITRUS_CACHE_DUAL)
+    return CITRUS_ERR_UNSUPPORTED;
+  if (c->select_mode != CITRUS_SELECT_PER_KV_HEAD && c->select_mode != CITRUS_SELECT_PER_LAYER)
+    return CITRUS_ERR_UNSUPPORTED;
+  if (c->dtype != CITRUS_F32 && c->dtype != CITRUS_BF16) return CITRUS_ERR_UNSUPPORTED;
+  if (c->head_dim != 64 && c->head_dim != 128) return CITRUS_ERR_UNSUPPORTED;
+  if (c->cache_mode == CITRUS_CACHE_DUAL && c->budget_lm < 1) return CITRUS_ERR_SHAPE;
+  const int need = c->cache_mode == CITRUS_CACHE_DUAL && c->budget_lm > c->budget ? c->budget_lm : c->budget;
+  if (c->cache_capacity < need) return CITRUS_ERR_SHAPE;
+  if (!(c->softmax_scale >= 0.0f) || isinf(c->softmax_scale)) return CITRUS_ERR_SHAPE;
+  return CITRUS_OK;
+}
+
+Dims dims_of(const citrus_config* c) {
+  Dims d;
+  d.B = c->batch; d.L = c->layers; d.Hq = c->q_heads; d.Hkv = c->kv_heads; d.G = c->q_heads / c->kv_heads;
+  d.D = c->head_dim;
+  d.scale = c->softmax_scale > 0.0f ? c->softmax_scale : 1.0f / sqrtf(static_cast<float>(c->head_dim));
+  return d;
+}
+
+// 16-byte row alignment: pointer and every stride.
+citrus_status check_tensor(const citrus_tensor& t, int dtype, bool may_be_null) {
+  if (t.ptr == nullptr) return may_be_null ? CITRUS_OK : CITRUS_ERR_NULL;
+  const int64_t q = 16 / elem_bytes(dtype);
+  if (reinterpret_cast<uintptr_t>(t.ptr) % 16 != 0) return CITRUS_ERR_SHAPE;
+  if (t.stride_b % q || t.stride_l % q || t.stride_h % q || t.stride_s % q) return CITRUS_ERR_SHAPE;
+  if (t.stride_s <= 0) return CITRUS_ERR_SHAPE;
+  return CITRUS_OK;
+}
+
+#define CITRUS_TRY(expr)                         \
+  do {                                           \
+    const citrus_status st__ = (expr);           \
+    if (st__ != CITRUS_OK) return st__;          \
+  } while (0)
+
+citrus_status check_lengths(const citrus_config* c, int cache_len, int chunk_len) {
+  if (cache_len < 0 || cache_len > c->cache_capacity) return CITRUS_ERR_SHAPE;
+  if (chunk_len < 1 || chunk_len > c->chunk_len) return CITRUS_ERR_SHAPE;
+  return CITRUS_OK;
+}
+
+// Workspace layout (all blocks kAlign-aligned).
+struct Workspace {
+  size_t lse_chunk, lse_instr, score, score_lm, idx, idx_lm, total;
+};
+
+Workspace workspace_layout(const citrus_config* c) {
+  Workspace w;
+  const size_t units_q = static_cast<size_t>(c->batch) * c->layers * c->q_heads;
+  const size_t units_kv = static_cast<size_t>(c->batch) * c->layers * c->kv_heads;
+  const size_t n_max = static_cast<size_t>(c->cache_capacity) + c->chunk_len;
+  const bool dual = c->cache_mode == CITRUS_CACHE_DUAL;
+  size_t off = 0;
+  w.lse_chunk = off; off += align_up(units_q * c->chunk_len * sizeof(float));
+  w.lse_instr = off; off += align_up(units_q * c->instr_len * sizeof(float));
+  w.score = off;     off += align_up(units_kv * n_max * sizeof(float));
+  w.score_lm = off;  off += dual ? align_up(units_kv * n_max * sizeof(float)) : 0;
+  w.idx = off;       off += align_up(units_kv * c->budget * sizeof(int32_t));
+  w.idx_lm = off;    off += dual ? align_up(units_kv * c->budget_lm * sizeof(int32_t)) : 0;
+  w.total = off;
+  return w;
+}
+
+citrus_status check_workspace(const citrus_config* c, const void* ws, size_t bytes) {
+  if (ws == nullptr || bytes < workspace_layout(c).total) return CITRUS_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(ws) % 16 != 0) return CITRUS_ERR_WORKSPACE;
+  return CITRUS_OK;
+}
+
+// ---- dispatch: MFMA kernels where they apply, generic kernels otherwise ----
+
+hipError_t run_attn(const citrus_config* c, const Dims& dm, View q, int rows, Segments ks, Segments vs, int causal,
+                    View out, float* lse, hipStream_t st) {
+  if (mfma_path_supported(c->dtype, dm)) return launch_attn_mfma(dm, q, rows, ks, vs, causal, out, lse, st);
+  return launch_attn_generic(c->dtype, dm, q, rows, ks, vs, causal, out, lse, st);
+}
+
+hipError_t run_colsum(const citrus_config* c, const Dims& dm, View q, int rows, Segments ks, int causal,
+                      const float* lse, float* score, hipStream_t st) {
+  if (mfma_path_supported(c->dtype, dm)) return launch_colsum_mfma(dm, q, rows, ks, causal, lse, score, st);
+  return launch_colsum_generic(c->dtype, dm, q, rows, ks, causal, lse, score, st);
+}
+
+// Unchecked bodies shared by the public entry points and the chunk loop.
+
+citrus_status do_chunk_attn(const citrus_config* c, const Dims& dm, const citrus_tensor& q, Segments ks, Segments vs,
+                            const citrus_tensor& out, float* lse, float* lm_score, hipStream_t st) {
+  CITRUS_TRY(hip_status(run_attn(c, dm, make_view(q), ks.c, ks, vs, /*causal=*/1, make_view(out), lse, st)));
+  if (lm_score != nullptr)
+    CITRUS_TRY(hip_status(run_colsum(c, dm, make_view(q), ks.c, ks, /*causal=*/1, lse, lm_score, st)));
+  return CITRUS_OK;
+}
+
+citrus_status do_instr_score(const citrus_config* c, const Dims& dm, const citrus_tensor& q_instr, Segments ks,
+                             float* lse_ws, float* score, hipStream_t st) {
+  View none{nullptr, 0, 0, 0, 0};
+  // pass 1: row normalisers (log-sum-exp over all n candidates, no mask)
+  CITRUS_TRY(hip_status(run_attn(c, dm, make_view(q_instr), c->instr_len, ks, ks, /*causal=*/0, none, lse_ws, st)));
+  // pass 2: probabilities summed down the rows of each KV group
+  CITRUS_TRY(hip_status(run_colsum(c, dm, make_view(q_instr), c->instr_len, ks, /*causal=*/0, lse_ws, score, st)));
+  return CITRUS_OK;
+}
+
+int sel_heads(const citrus_config* c) { return c->select_mode == CITRUS_SELECT_PER_LAYER ? 1 : c->kv_heads; }
+
+citrus_status do_topk(const citrus_config* c, const float* score, int n, int k, int32_t* idx, hipStream_t st) {
+  const bool per_layer = c->select_mode == CITRUS_SELECT_PER_LAYER;
+  const int units = c->batch * c->layers * (per_layer ? 1 : c->kv_heads);
+  return hip_status(launch_topk(score, units, per_layer ? c->kv_heads : 1, n, k, idx, st));
+}
+
+citrus_status do_compact(const citrus_config* c, const Dims& dm, Segments ks, Segments vs, const int32_t* idx,
+                         int idx_pitch, int m, const citrus_tensor& k_new, const citrus_tensor& v_new,
+                         hipStream_t st) {
+  return hip_status(launch_compact(elem_bytes(c->dtype), dm, ks, vs, idx, idx_pitch, sel_heads(c), m,
+                                   make_view(k_new), make_view(v_new), st));
+}
+
+Segments segments(const citrus_tensor& cache, int cache_len, const citrus_tensor& chunk, int chunk_len) {
+  Segments s;
+  s.cache = make_view(cache);
+  s.chunk = make_view(chunk);
+  s.n_c = cache_len;
+  s.c = chunk_len;
+  if (cache_len == 0) s.cache = s.chunk;  // never dereferenced, but keep it a valid pointer
+  return s;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t citrus_abi_version(void) { return CITRUS_ABI_VERSION; }
+
+const char* citrus_status_string(int32_t status) {
+  switch (status) {
+    case CITRUS_OK: return "ok";
+    case CITRUS_ERR_NULL: return "a required pointer is NULL";
+    case CITRUS_ERR_SHAPE: return "sizes or strides are inconsistent or out of range";
+    case CITRUS_ERR_UNSUPPORTED: return "dtype, head_dim or mode not supported";
+    case CITRUS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case CITRUS_ERR_DEVICE: return "HIP runtime error at kernel launch";
+    case CITRUS_ERR_PROVIDER: return "chunk provider reported an error";
+    default: return "unknown status";
+  }
+}
+
+size_t citrus_workspace_bytes(const citrus_config* cfg) {
+  if (check_config(cfg) != CITRUS_OK) return 0;
+  return workspace_layout(cfg).total;
+}
+
+int32_t citrus_chunk_attn(const citrus_config* cfg, citrus_tensor q, citrus_tensor k_cache, citrus_tensor v_cache,
+                          int32_t cache_len, citrus_tensor k_chunk, citrus_tensor v_chunk, int32_t chunk_len,
+                          citrus_tensor out, float* lse, float* lm_score, void* workspace, size_t workspace_bytes,
+                          void* hip_stream) {
+  CITRUS_TRY(check_config(cfg));
+  CITRUS_TRY(check_lengths(cfg, cache_len, chunk_len));
+  CITRUS_TRY(check_tensor(q, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(out, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(k_chunk, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(v_chunk, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(k_cache, cfg->dtype, cache_len == 0));
+  CITRUS_TRY(check_tensor(v_cache, cfg->dtype, cache_len == 0));
+  if (lm_score != nullptr && lse == nullptr) {
+    CITRUS_TRY(check_workspace(cfg, workspace, workspace_bytes));
+    lse = reinterpret_cast<float*>(static_cast<char*>(workspace) + workspace_layout(cfg).lse_chunk);
+  }
+  const Dims dm = dims_of(cfg);
+  return do_chunk_attn(cfg, dm, q, segments(k_cache, cache_len, k_chunk, chunk_len),
+                       segments(v_cache, cache_len, v_chunk, chunk_len), out, lse, lm_score,
+                       static_cast<hipStream_t>(hip_stream));
+}
+
+int32_t citrus_instr_score(const citrus_config* cfg, citrus_tensor q_instr, citrus_tensor k_cache, int32_t cache_len,
+                           citrus_tensor k_chunk, int32_t chunk_len, float* score, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+  CITRUS_TRY(check_config(cfg));
+  CITRUS_TRY(check_lengths(cfg, cache_len, chunk_len));
+  if (score == nullptr) return CITRUS_ERR_NULL;
+  CITRUS_TRY(check_tensor(q_instr, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(k_chunk, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(k_cache, cfg->dtype, cache_len == 0));
+  CITRUS_TRY(check_workspace(cfg, workspace, workspace_bytes));
+  const Dims dm = dims_of(cfg);
+  float* lse_ws = reinterpret_cast<float*>(static_cast<char*>(workspace) + workspace_layout(cfg).lse_instr);
+  return do_instr_score(cfg, dm, q_instr, segments(k_cache, cache_len, k_chunk, chunk_len), lse_ws, score,
+                        static_cast<hipStream_t>(hip_stream));
+}
+
+int32_t citrus_topk_select(const citrus_config* cfg, const float* score, int32_t n, int32_t k, int32_t* idx,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  CITRUS_TRY(check_config(cfg));
+  if (score == nullptr || idx == nullptr) return CITRUS_ERR_NULL;
+  if (n < 1 || k < 1) return CITRUS_ERR_SHAPE;
+  return do_topk(cfg, score, n, k, idx, static_cast<hipStream_t>(hip_stream));
+}
+
+int32_t citrus_kv_compact(const citrus_config* cfg, citrus_tensor k_cache, citrus_tensor v_cache, int32_t cache_len,
+                          citrus_tensor k_chunk, citrus_tensor v_chunk, int32_t chunk_len, const int32_t* idx,
+                          int32_t idx_pitch, int32_t m, citrus_tensor k_new, citrus_tensor v_new, void* hip_stream) {
+  CITRUS_TRY(check_config(cfg));
+  CITRUS_TRY(check_lengths(cfg, cache_len, chunk_len));
+  if (idx == nullptr) return CITRUS_ERR_NULL;
+  if (m < 1 || m > cfg->cache_capacity || idx_pitch < m) return CITRUS_ERR_SHAPE;
+  CITRUS_TRY(check_tensor(k_chunk, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(v_chunk, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(k_cache, cfg->dtype, cache_len == 0));
+  CITRUS_TRY(check_tensor(v_cache, cfg->dtype, cache_len == 0));
+  CITRUS_TRY(check_tensor(k_new, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(v_new, cfg->dtype, false));
+  if (k_new.ptr == k_cache.ptr || v_new.ptr == v_cache.ptr || k_new.ptr == k_chunk.ptr || v_new.ptr == v_chunk.ptr)
+    return CITRUS_ERR_SHAPE;
+  const Dims dm = dims_of(cfg);
+  return do_compact(cfg, dm, segments(k_cache, cache_len, k_chunk, chunk_len),
+                    segments(v_cache, cache_len, v_chunk, chunk_len), idx, idx_pitch, m, k_new, v_new,
+                    static_cast<hipStream_t>(hip_stream));
+}
+
+int32_t citrus_resident_provider(void* user, int32_t chunk_index, void* hip_stream, citrus_chunk_io* io) {
+  (void)hip_stream;
+  if (user == nullptr || io == nullptr || chunk_index < 0) return -1;
+  const citrus_resident_doc* d = static_cast<const citrus_resident_doc*>(user);
+  if (d->chunk_len < 1 || d->doc_len < 0) return -1;
+  const int64_t lo = static_cast<int64_t>(chunk_index) * d->chunk_len;
+  if (lo >= d->doc_len) return 1;
+  const int64_t hi = lo + d->chunk_len < d->doc_len ? lo + d->chunk_len : d->doc_len;
+  if (d->dtype != CITRUS_F32 && d->dtype != CITRUS_BF16) return -1;
+  const int esize = elem_bytes(d->dtype);
+  auto advance = [](citrus_tensor t, int64_t rows, int esz) {
+    t.ptr = static_cast<char*>(t.ptr) + rows * t.stride_s * esz;
+    return t;
+  };
+  io->q = advance(d->q, lo, esize);
+  io->k = advance(d->k, lo, esize);
+  io->v = advance(d->v, lo, esize);
+  io->out = advance(d->out, lo, esize);
+  io->q_instr = d->q_instr;
+  io->q_instr.ptr = static_cast<char*>(d->q_instr.ptr) + static_cast<int64_t>(chunk_index) * d->q_instr_stride_chunk * esize;
+  io->chunk_len = static_cast<int32_t>(hi - lo);
+  return 0;
+}
+
+int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider next, void* user,
+                                int32_t first_chunk, int32_t max_chunks, const citrus_tensor* k_cache,
+                                const citrus_tensor* v_cache, const citrus_tensor* k_cache_lm,
+                                const citrus_tensor* v_cache_lm, int32_t* cache_len, int32_t* cache_len_lm,
+                                int32_t* buffer_index, int32_t* buffer_index_lm, int32_t* idx_history,
+                                int32_t* idx_history_lm, int32_t* chunks_done, void* workspace,
+                                size_t workspace_bytes, void* hip_stream) {
+  CITRUS_TRY(check_config(cfg));
+  if (next == nullptr || k_cache == nullptr || v_cache == nullptr || cache_len == nullptr || buffer_index == nullptr)
+    return CITRUS_ERR_NULL;
+  const bool dual = cfg->cache_mode == CITRUS_CACHE_DUAL;
+  if (dual && (k_cache_lm == nullptr || v_cache_lm == nullptr || cache_len_lm == nullptr || buffer_index_lm == nullptr))
+    return CITRUS_ERR_NULL;
+  if (first_chunk < 0) return CITRUS_ERR_SHAPE;
+  for (int i = 0; i < 2; ++i) {
+    CITRUS_TRY(check_tensor(k_cache[i], cfg->dtype, false));
+    CITRUS_TRY(check_tensor(v_cache[i], cfg->dtype, false));
+    if (dual) {
+      CITRUS_TRY(check_tensor(k_cache_lm[i], cfg->dtype, false));
+      CITRUS_TRY(check_tensor(v_cache_lm[i], cfg->dtype, false));
+    }
+  }
+  if (k_cache[0].ptr == k_cache[1].ptr || v_cache[0].ptr == v_cache[1].ptr) return CITRUS_ERR_SHAPE;
+  if (*cache_len < 0 || *cache_len > cfg->budget || (*buffer_index != 0 && *buffer_index != 1)) return CITRUS_ERR_SHAPE;
+  if (dual && (*cache_len_lm < 0 || *cache_len_lm > cfg->budget_lm || (*buffer_index_lm != 0 && *buffer_index_lm != 1)))
+    return CITRUS_ERR_SHAPE;
+  CITRUS_TRY(check_workspace(cfg, workspace, workspace_bytes));
+
+  const Dims dm = dims_of(cfg);
+  const Workspace wl = workspace_layout(cfg);
+  char* ws = static_cast<char*>(workspace);
+  float* lse_chunk = reinterpret_cast<float*>(ws + wl.lse_chunk);
+  float* lse_instr = reinterpret_cast<float*>(ws + wl.lse_instr);
+  float* score = reinterpret_cast<float*>(ws + wl.score);
+  float* score_lm = reinterpret_cast<float*>(ws + wl.score_lm);
+  int32_t* idx_ws = reinterpret_cast<int32_t*>(ws + wl.idx);
+  int32_t* idx_lm_ws = reinterpret_cast<int32_t*>(ws + wl.idx_lm);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const size_t units_sel = static_cast<size_t>(cfg->batch) * cfg->layers * sel_heads(cfg);
+
+  int n_c = *cache_len, cur = *buffer_index;
+  int n_c_lm = dual ? *cache_len_lm : 0, cur_lm = dual ? *buffer_index_lm : 0;
+  int done = 0;
+  citrus_status status = CITRUS_OK;
+  for (; max_chunks < 0 || done < max_chunks; ++done) {
+    citrus_chunk_io io;
+    memset(&io, 0, sizeof(io));
+    const int32_t rc = next(user, first_chunk + done, hip_stream, &io);
+    if (rc == 1) break;
+    if (rc != 0) { status = CITRUS_ERR_PROVIDER; break; }
+    const int c = io.chunk_len;
+    if (c < 1 || c > cfg->chunk_len) { status = CITRUS_ERR_SHAPE; break; }
+    if ((status = check_tensor(io.q, cfg->dtype, false)) != CITRUS_OK) break;
+    if ((status = check_tensor(io.k, cfg->dtype, false)) != CITRUS_OK) break;
+    if ((status = check_tensor(io.v, cfg->dtype, false)) != CITRUS_OK) break;
+    if ((status = check_tensor(io.q_instr, cfg->dtype, false)) != CITRUS_OK) break;
+    if ((status = check_tensor(io.out, cfg->dtype, false)) != CITRUS_OK) break;
+
+    // instruction (or only) cache: candidates [cache ; chunk]
+    const Segments ks = segments(k_cache[cur], n_c, io.k, c), vs = segments(v_cache[cur], n_c, io.v, c);
+    const int n = n_c + c;
+    const int m = n < cfg->budget ? n : cfg->budget;
+
+    if (dual) {
+      // language-modelling thread: the chunk attends over [LM cache ; chunk] and scores it itself
+      const Segments kl = segments(k_cache_lm[cur_lm], n_c_lm, io.k, c), vl = segments(v_cache_lm[cur_lm], n_c_lm, io.v, c);
+      const int n_lm = n_c_lm + c;
+      const int m_lm = n_lm < cfg->budget_lm ? n_lm : cfg->budget_lm;
+      int32_t* idx_lm = idx_history_lm ? idx_history_lm + static_cast<size_t>(done) * units_sel * cfg->budget_lm : idx_lm_ws;
+      if ((status = do_chunk_attn(cfg, dm, io.q, kl, vl, io.out, lse_chunk, score_lm, st)) != CITRUS_OK) break;
+      if ((status = do_topk(cfg, score_lm, n_lm, cfg->budget_lm, idx_lm, st)) != CITRUS_OK) break;
+      if ((status = do_compact(cfg, dm, kl, vl, idx_lm, cfg->budget_lm, m_lm, k_cache_lm[cur_lm ^ 1],
+                               v_cache_lm[cur_lm ^ 1], st)) != CITRUS_OK)
+        break;
+      cur_lm ^= 1;
+      n_c_lm = m_lm;
+    } else {
+      if ((status = do_chunk_attn(cfg, dm, io.q, ks, vs, io.out, nullptr, nullptr, st)) != CITRUS_OK) break;
+    }
+
+    int32_t* idx = idx_history ? idx_history + static_cast<size_t>(done) * units_sel * cfg->budget : idx_ws;
+    if ((status = do_instr_score(cfg, dm, io.q_instr, ks, lse_instr, score, st)) != CITRUS_OK) break;
+    if ((status = do_topk(cfg, score, n, cfg->budget, idx, st)) != CITRUS_OK) break;
+    if ((status = do_compact(cfg, dm, ks, vs, idx, cfg->budget, m, k_cache[cur ^ 1], v_cache[cur ^ 1], st)) != CITRUS_OK)
+      break;
+    cur ^= 1;
+    n_c = m;
+  }
+  *cache_len = n_c;
+  *buffer_index = cur;
+  if (dual) {
+    *cache_len_lm = n_c_lm;
+    *buffer_index_lm = cur_lm;
+  }
+  if (chunks_done != nullptr) *chunks_done = done;
+  return status;
+}
+
+}  // extern "C"

@@ -1,0 +1,58 @@
+// Internal declarations shared by the translation units of libcitrus.so.
+// Not part of the public ABI (see include/citrus.h for that).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "citrus.h"
+
+namespace citrus {
+
+// A strided [B, L, H, S, d] view in element units; d is contiguous.
+struct View {
+  const void* ptr;
+  int64_t sb, sl, sh, ss;
+};
+
+inline View make_view(const citrus_tensor& t) { return View{t.ptr, t.stride_b, t.stride_l, t.stride_h, t.stride_s}; }
+
+// Problem sizes every kernel launcher receives.
+struct Dims {
+  int B, L, Hq, Hkv, G, D;
+  float scale;  // softmax scale (already resolved, never 0)
+};
+
+// The candidate keys/values of a step: cache rows then chunk rows.
+struct Segments {
+  View cache;   // [B, L, Hkv, >= n_c, d]
+  View chunk;   // [B, L, Hkv, c, d]
+  int n_c;      // valid cache rows
+  int c;        // chunk rows
+};
+
+inline citrus_status hip_status(hipError_t e) { return e == hipSuccess ? CITRUS_OK : CITRUS_ERR_DEVICE; }
+
+// ---- generic VALU kernels (f32 and bf16 element types), attn_generic.hip ----
+// rows: number of query rows per head; causal != 0 -> row t sees candidates j <= n_c + t.
+// out may be NULL (log-sum-exp only); lse may be NULL.
+hipError_t launch_attn_generic(int dtype, const Dims& dm, View q, int rows, Segments kseg, Segments vseg, int causal,
+                               View out, float* lse, hipStream_t st);
+// score[b,l,g,j] = sum_{h in g} sum_{t<rows} exp(scale*q.k - lse[b,l,h,t]) (0 where masked)
+hipError_t launch_colsum_generic(int dtype, const Dims& dm, View q, int rows, Segments kseg, int causal,
+                                 const float* lse, float* score, hipStream_t st);
+
+// ---- bf16 MFMA kernels (head_dim 128), attn_mfma.hip ----
+bool mfma_path_supported(int dtype, const Dims& dm);
+hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments kseg, Segments vseg, int causal, View out,
+                            float* lse, hipStream_t st);
+hipError_t launch_colsum_mfma(const Dims& dm, View q, int rows, Segments kseg, int causal, const float* lse,
+                              float* score, hipStream_t st);
+
+// ---- selection and compaction, select_compact.hip ----
+// units = B*L*Hsel; score rows are [units*(per_layer?Hkv:1)] x n.
+hipError_t launch_topk(const float* score, int units, int heads_to_sum, int n, int k, int32_t* idx, hipStream_t st);
+hipError_t launch_compact(int elem_bytes, const Dims& dm, Segments kseg, Segments vseg, const int32_t* idx,
+                          int idx_pitch, int idx_heads, int m, View k_new, View v_new, hipStream_t st);
+
+}  // namespace citrus

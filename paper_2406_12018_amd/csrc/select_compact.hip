@@ -1,0 +1,177 @@
+// Selection (Eq. (2)-(3): keep the k highest importance scores) and compaction
+// (Eq. (3), (5): the evicted cache holds exactly the selected states).
+#include "citrus_internal.h"
+
+namespace citrus {
+namespace {
+
+constexpr int kSelThreads = 256;
+constexpr int kSelWaves = kSelThreads / 64;
+
+// Order-preserving map float -> uint32 (larger float <=> larger key).  -0 is
+// folded onto +0 first so that equal values get equal keys.
+__device__ inline uint32_t order_key(float f) {
+  f += 0.0f;
+  const uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// The value a selection unit ranks for candidate j: one head's score, or the
+// sum over the layer's KV heads taken in head order (layer-wise eviction).
+__device__ inline float unit_score(const float* base, int heads_to_sum, int n, int j) {
+  float s = base[j];
+  for (int g = 1; g < heads_to_sum; ++g) s += base[static_cast<int64_t>(g) * n + j];
+  return s;
+}
+
+// One workgroup per selection unit.  A radix select over the 32-bit order keys
+// (4 passes of 8 bits, integer LDS histograms) finds the k-th largest key T;
+// then one ordered pass emits, in ascending position, every candidate with
+// key > T and the first (k - count(key > T)) candidates with key == T.  The
+// result is exactly the top-k under (score descending, position ascending).
+__global__ __launch_bounds__(kSelThreads) void topk_kernel(const float* score, int heads_to_sum, int n, int k,
+                                                          int32_t* idx) {
+  __shared__ int hist[256];
+  __shared__ uint32_t s_prefix;
+  __shared__ int s_need;
+  __shared__ int wave_tot[2][kSelWaves];
+  const int unit = blockIdx.x, tid = threadIdx.x;
+  const float* base = score + static_cast<int64_t>(unit) * heads_to_sum * n;
+  int32_t* out = idx + static_cast<int64_t>(unit) * k;
+
+  if (n <= k) {  // nothing to evict: keep every candidate
+    for (int j = tid; j < n; j += kSelThreads) out[j] = j;
+    return;
+  }
+
+  uint32_t prefix = 0;  // bits of T fixed so far (high bits)
+  int need = k;         // rank of T among the keys that match the prefix
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    hist[tid] = 0;  // kSelThreads == 256 bins
+    __syncthreads();
+    const uint32_t hi_mask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
+    for (int j = tid; j < n; j += kSelThreads) {
+      const uint32_t key = order_key(unit_score(base, heads_to_sum, n, j));
+      if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 0xff], 1);
+    }
+    __syncthreads();
+    if (tid == 0) {
+      int cum = 0, bin = 255;
+      for (; bin > 0; --bin) {
+        if (cum + hist[bin] >= need) break;
+        cum += hist[bin];
+      }
+      s_prefix = prefix | (static_cast<uint32_t>(bin) << shift);
+      s_need = need - cum;
+    }
+    __syncthreads();
+    prefix = s_prefix;
+    need = s_need;
+    __syncthreads();
+  }
+  const uint32_t thr = prefix;  // key of the k-th best candidate
+  // `need` = how many candidates with key == thr are kept (lowest positions first)
+
+  const int lane = tid % 64, w = tid / 64;
+  int kept_before = 0, eq_before = 0;
+  for (int j0 = 0; j0 < n; j0 += kSelThreads) {
+    const int j = j0 + tid;
+    uint32_t key = 0;
+    bool in = j < n;
+    if (in) key = order_key(unit_score(base, heads_to_sum, n, j));
+    const bool gt = in && key > thr, eq = in && key == thr;
+    const uint64_t eq_ballot = __ballot(eq);
+    const uint64_t below = (1ull << lane) - 1ull;
+    if (lane == 0) wave_tot[0][w] = __popcll(eq_ballot);
+    __syncthreads();
+    int eq_rank = eq_before + __popcll(eq_ballot & below);
+    int eq_total = 0;
+    for (int x = 0; x < kSelWaves; ++x) {
+      if (x < w) eq_rank += wave_tot[0][x];
+      eq_total += wave_tot[0][x];
+    }
+    const bool keep = gt || (eq && eq_rank < need);
+    const uint64_t keep_ballot = __ballot(keep);
+    if (lane == 0) wave_tot[1][w] = __popcll(keep_ballot);
+    __syncthreads();
+    int pos = kept_before + __popcll(keep_ballot & below);
+    int keep_total = 0;
+    for (int x = 0; x < kSelWaves; ++x) {
+      if (x < w) pos += wave_tot[1][x];
+      keep_total += wave_tot[1][x];
+    }
+    if (keep) out[pos] = j;
+    kept_before += keep_total;
+    eq_before += eq_total;
+    __syncthreads();
+  }
+}
+
+// Row gather: every thread moves 16 bytes of a K row and 16 bytes of a V row.
+template <int ROW_BYTES>
+__global__ __launch_bounds__(256) void compact_kernel(Dims dm, Segments ks, Segments vs, int elem_bytes,
+                                                      const int32_t* idx, int idx_pitch, int idx_heads, int m,
+                                                      View k_new, View v_new) {
+  constexpr int kLanesPerRow = ROW_BYTES / 16;
+  constexpr int kRowsPerBlock = 256 / kLanesPerRow;
+  const int g = blockIdx.y, b = blockIdx.z / dm.L, l = blockIdx.z % dm.L;
+  const int r = blockIdx.x * kRowsPerBlock + threadIdx.x / kLanesPerRow;
+  const int seg = threadIdx.x % kLanesPerRow;
+  if (r >= m) return;
+  const int gi = idx_heads == 1 ? 0 : g;
+  int j = idx[(static_cast<int64_t>(blockIdx.z) * idx_heads + gi) * idx_pitch + r];
+  j = max(0, min(j, ks.n_c + ks.c - 1));  // a bad index must never become an out-of-bounds read
+  const int64_t unit_cache_k = b * ks.cache.sb + l * ks.cache.sl + g * ks.cache.sh;
+  const int64_t unit_chunk_k = b * ks.chunk.sb + l * ks.chunk.sl + g * ks.chunk.sh;
+  const int64_t unit_cache_v = b * vs.cache.sb + l * vs.cache.sl + g * vs.cache.sh;
+  const int64_t unit_chunk_v = b * vs.chunk.sb + l * vs.chunk.sl + g * vs.chunk.sh;
+  const char* ksrc;
+  const char* vsrc;
+  if (j < ks.n_c) {
+    ksrc = static_cast<const char*>(ks.cache.ptr) + (unit_cache_k + static_cast<int64_t>(j) * ks.cache.ss) * elem_bytes;
+    vsrc = static_cast<const char*>(vs.cache.ptr) + (unit_cache_v + static_cast<int64_t>(j) * vs.cache.ss) * elem_bytes;
+  } else {
+    const int jc = j - ks.n_c;
+    ksrc = static_cast<const char*>(ks.chunk.ptr) + (unit_chunk_k + static_cast<int64_t>(jc) * ks.chunk.ss) * elem_bytes;
+    vsrc = static_cast<const char*>(vs.chunk.ptr) + (unit_chunk_v + static_cast<int64_t>(jc) * vs.chunk.ss) * elem_bytes;
+  }
+  char* kdst = static_cast<char*>(const_cast<void*>(k_new.ptr)) +
+               (b * k_new.sb + l * k_new.sl + g * k_new.sh + static_cast<int64_t>(r) * k_new.ss) * elem_bytes;
+  char* vdst = static_cast<char*>(const_cast<void*>(v_new.ptr)) +
+               (b * v_new.sb + l * v_new.sl + g * v_new.sh + static_cast<int64_t>(r) * v_new.ss) * elem_bytes;
+  const uint4 kv = reinterpret_cast<const uint4*>(ksrc)[seg];
+  const uint4 vv = reinterpret_cast<const uint4*>(vsrc)[seg];
+  reinterpret_cast<uint4*>(kdst)[seg] = kv;
+  reinterpret_cast<uint4*>(vdst)[seg] = vv;
+}
+
+template <int ROW_BYTES>
+hipError_t compact_launch(int elem_bytes, const Dims& dm, Segments ks, Segments vs, const int32_t* idx,
+                          int idx_pitch, int idx_heads, int m, View k_new, View v_new, hipStream_t st) {
+  constexpr int kRowsPerBlock = 256 / (ROW_BYTES / 16);
+  dim3 grid((m + kRowsPerBlock - 1) / kRowsPerBlock, dm.Hkv, dm.B * dm.L);
+  hipLaunchKernelGGL((compact_kernel<ROW_BYTES>), grid, dim3(256), 0, st, dm, ks, vs, elem_bytes, idx, idx_pitch,
+                     idx_heads, m, k_new, v_new);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_topk(const float* score, int units, int heads_to_sum, int n, int k, int32_t* idx, hipStream_t st) {
+  hipLaunchKernelGGL(topk_kernel, dim3(units), dim3(kSelThreads), 0, st, score, heads_to_sum, n, k, idx);
+  return hipGetLastError();
+}
+
+hipError_t launch_compact(int elem_bytes, const Dims& dm, Segments ks, Segments vs, const int32_t* idx,
+                          int idx_pitch, int idx_heads, int m, View k_new, View v_new, hipStream_t st) {
+  const int row_bytes = dm.D * elem_bytes;
+  switch (row_bytes) {
+    case 128: return compact_launch<128>(elem_bytes, dm, ks, vs, idx, idx_pitch, idx_heads, m, k_new, v_new, st);
+    case 256: return compact_launch<256>(elem_bytes, dm, ks, vs, idx, idx_pitch, idx_heads, m, k_new, v_new, st);
+    case 512: return compact_launch<512>(elem_bytes, dm, ks, vs, idx, idx_pitch, idx_heads, m, k_new, v_new, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace citrus

@@ -1,0 +1,107 @@
+"""Shared helpers of the GPU parity tests: tolerances, conversions, the
+selection band rule, and a step-by-step driver of the four entry points."""
+
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import citrus_oracle as orc
+
+TOL = {"f32": (1e-5, 1e-5), "bf16": (2e-2, 1e-2)}   # (atol, rtol): |gpu - ref| <= atol + rtol*|ref|
+
+
+def np64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def bits(t: torch.Tensor) -> np.ndarray:
+    """Raw bit pattern of a tensor (bf16 -> int16, f32 -> int32) on the host."""
+    t = t.detach().to("cpu").contiguous()
+    return t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32).numpy()
+
+
+def assert_close(gpu, ref, dtype: str, what: str = ""):
+    atol, rtol = TOL[dtype]
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert gpu.shape == ref.shape, (what, gpu.shape, ref.shape)
+    err = np.abs(gpu - ref)
+    bound = atol + rtol * np.abs(ref)
+    bad = err > bound
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} outside tolerance, max err {err.max():.3e}"
+    assert np.isfinite(gpu).all(), what
+
+
+def check_selection(gpu_idx, gpu_score, ref_score, k: int, dtype: str, what: str = ""):
+    """The two selection checks for one score vector.
+
+    1. Exact: the GPU's indices are exactly the top-k (lower index wins ties,
+       ascending output) of the GPU's OWN f32 score vector.
+    2. Band rule: against the oracle's selection on the oracle's scores, the
+       sets may differ only at positions whose oracle score lies within the
+       tolerance of the oracle's k-th best score.
+    Returns the fraction of positions inside the band.
+    """
+    gpu_idx = np.asarray(gpu_idx)
+    n = ref_score.shape[0]
+    m = min(k, n)
+    own = orc.topk_select_1d(np.asarray(gpu_score, dtype=np.float32), k)
+    np.testing.assert_array_equal(gpu_idx[:m], own, err_msg=f"{what}: not the exact top-k of its own scores")
+    ref_idx = orc.topk_select_1d(ref_score, k)
+    if n <= k:
+        np.testing.assert_array_equal(gpu_idx[:m], ref_idx)
+        return 0.0
+    atol, rtol = TOL[dtype]
+    boundary = np.sort(ref_score)[::-1][k - 1]
+    band = np.abs(ref_score - boundary) <= atol + rtol * abs(boundary)
+    diff = np.setxor1d(gpu_idx[:m], ref_idx)
+    assert band[diff].all(), f"{what}: selection differs outside the tolerance band at {diff[~band[diff]][:8]}"
+    return float(band.mean())
+
+
+class StepwiseRun:
+    """Drives chunk_attn / instr_score / topk_select / kv_compact one chunk at
+    a time through the binding, keeping every intermediate for comparison."""
+
+    def __init__(self, api, cfg, device="cuda"):
+        self.api, self.cfg = api, cfg
+        self.state = api.DocumentState.allocate(cfg, device)
+        self.ws = api.alloc_workspace(cfg, device)
+        self.steps = []
+
+    def step(self, q, k, v, q_instr):
+        api, cfg, st = self.api, self.cfg, self.state
+        dual = cfg.cache_mode == api.CACHE_DUAL
+        c = q.shape[3]
+        rec = {"n_c": st.cache_len}
+        kc, vc = st.k_cache[st.buffer_index], st.v_cache[st.buffer_index]
+        n = st.cache_len + c
+        if dual:
+            kl, vl = st.k_cache_lm[st.buffer_index_lm], st.v_cache_lm[st.buffer_index_lm]
+            n_lm = st.cache_len_lm + c
+            lm_score = torch.empty((cfg.batch, cfg.layers, cfg.kv_heads, n_lm), dtype=torch.float32, device=q.device)
+            lse = torch.empty((cfg.batch, cfg.layers, cfg.q_heads, c), dtype=torch.float32, device=q.device)
+            out = api.citrus_chunk_attn(cfg, q, kl, vl, st.cache_len_lm, k, v, lse=lse, lm_score=lm_score,
+                                        workspace=self.ws)
+            idx_lm = api.citrus_topk_select(cfg, lm_score, cfg.budget_lm)
+            m_lm = min(cfg.budget_lm, n_lm)
+            api.citrus_kv_compact(cfg, kl, vl, st.cache_len_lm, k, v, idx_lm, m_lm,
+                                  st.k_cache_lm[st.buffer_index_lm ^ 1], st.v_cache_lm[st.buffer_index_lm ^ 1])
+            rec.update(n_c_lm=st.cache_len_lm, score_lm=lm_score, idx_lm=idx_lm, m_lm=m_lm, lse=lse)
+            st.buffer_index_lm ^= 1
+            st.cache_len_lm = m_lm
+        else:
+            lse = torch.empty((cfg.batch, cfg.layers, cfg.q_heads, c), dtype=torch.float32, device=q.device)
+            out = api.citrus_chunk_attn(cfg, q, kc, vc, st.cache_len, k, v, lse=lse)
+            rec["lse"] = lse
+        score = api.citrus_instr_score(cfg, q_instr, kc, st.cache_len, k, workspace=self.ws)
+        idx = api.citrus_topk_select(cfg, score, cfg.budget)
+        m = min(cfg.budget, n)
+        api.citrus_kv_compact(cfg, kc, vc, st.cache_len, k, v, idx, m, st.k_cache[st.buffer_index ^ 1],
+                              st.v_cache[st.buffer_index ^ 1])
+        st.buffer_index ^= 1
+        st.cache_len = m
+        rec.update(out=out, score=score, idx=idx, m=m)
+        self.steps.append(rec)
+        return rec

@@ -1,0 +1,153 @@
+"""The C-ABI library loads, exports every symbol the header declares, and turns
+bad arguments into error codes on the host without touching a device.  CPU only."""
+
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2406_12018_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "citrus.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(citrus_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B._lib()
+    names = declared_symbols()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert B.abi_version() == 1
+
+
+def test_struct_layouts_match_the_header():
+    assert C.sizeof(B.CConfig) == 14 * 4
+    assert C.sizeof(B.CTensor) == 5 * 8
+    assert C.sizeof(B.CChunkIO) == 5 * 40 + 8
+    assert C.sizeof(B.CResidentDoc) == 5 * 40 + 8 + 16
+
+
+def cfg(**kw):
+    base = dict(batch=1, layers=1, q_heads=4, kv_heads=2, head_dim=64, chunk_len=32, budget=64, instr_len=8, dtype=B.F32)
+    base.update(kw)
+    return B.Config(**base)
+
+
+def test_status_strings():
+    for s in range(7):
+        assert B.status_string(s) not in ("", "unknown status")
+    assert B.status_string(99) == "unknown status"
+
+
+@pytest.mark.parametrize("kw,ok", [
+    ({}, True), ({"q_heads": 3}, False), ({"head_dim": 96}, False), ({"budget": 0}, False), ({"dtype": 7}, False),
+    ({"cache_mode": B.CACHE_DUAL}, False), ({"cache_mode": B.CACHE_DUAL, "budget_lm": 16}, True),
+    ({"cache_capacity": 8}, False), ({"softmax_scale": -1.0}, False), ({"select_mode": 5}, False),
+    ({"batch": 70000}, False),
+])
+def test_workspace_bytes_validates_config(kw, ok):
+    assert (B.workspace_bytes(cfg(**kw)) > 0) == ok
+
+
+def fake(ptr=0x1000, s=64):
+    return B.CTensor(ptr, s * 1024, s * 512, s * 128, s)
+
+
+def test_entry_points_reject_bad_arguments_before_any_launch():
+    lib = B._lib()
+    c = cfg().c()
+    null = B.CTensor(None, 0, 0, 0, 0)
+    ws = C.c_void_p(0x10000)
+    big = 1 << 30
+    # NULL config
+    assert lib.citrus_chunk_attn(None, fake(), fake(), fake(), 0, fake(), fake(), 8, fake(), None, None, None, 0, None) == B.ERR_NULL
+    # NULL q
+    assert lib.citrus_chunk_attn(C.byref(c), null, fake(), fake(), 0, fake(), fake(), 8, fake(), None, None, None, 0, None) == B.ERR_NULL
+    # NULL cache with cache_len > 0
+    assert lib.citrus_chunk_attn(C.byref(c), fake(), null, null, 4, fake(), fake(), 8, fake(), None, None, None, 0, None) == B.ERR_NULL
+    # chunk_len out of range, cache_len above capacity
+    assert lib.citrus_chunk_attn(C.byref(c), fake(), fake(), fake(), 0, fake(), fake(), 33, fake(), None, None, None, 0, None) == B.ERR_SHAPE
+    assert lib.citrus_chunk_attn(C.byref(c), fake(), fake(), fake(), 65, fake(), fake(), 8, fake(), None, None, None, 0, None) == B.ERR_SHAPE
+    # misaligned pointer / stride
+    assert lib.citrus_chunk_attn(C.byref(c), fake(0x1004), fake(), fake(), 0, fake(), fake(), 8, fake(), None, None, None, 0, None) == B.ERR_SHAPE
+    assert lib.citrus_chunk_attn(C.byref(c), fake(s=66), fake(), fake(), 0, fake(), fake(), 8, fake(), None, None, None, 0, None) == B.ERR_SHAPE
+    # lm_score without lse needs a workspace
+    assert lib.citrus_chunk_attn(C.byref(c), fake(), fake(), fake(), 0, fake(), fake(), 8, fake(), None, C.c_void_p(0x2000), None, 0, None) == B.ERR_WORKSPACE
+    # instr_score: NULL score, missing / short workspace
+    assert lib.citrus_instr_score(C.byref(c), fake(), fake(), 0, fake(), 8, None, ws, big, None) == B.ERR_NULL
+    assert lib.citrus_instr_score(C.byref(c), fake(), fake(), 0, fake(), 8, C.c_void_p(0x2000), None, 0, None) == B.ERR_WORKSPACE
+    assert lib.citrus_instr_score(C.byref(c), fake(), fake(), 0, fake(), 8, C.c_void_p(0x2000), ws, 16, None) == B.ERR_WORKSPACE
+    # topk: NULLs, n/k < 1
+    assert lib.citrus_topk_select(C.byref(c), None, 8, 4, C.c_void_p(0x2000), None, 0, None) == B.ERR_NULL
+    assert lib.citrus_topk_select(C.byref(c), C.c_void_p(0x2000), 0, 4, C.c_void_p(0x3000), None, 0, None) == B.ERR_SHAPE
+    assert lib.citrus_topk_select(C.byref(c), C.c_void_p(0x2000), 8, 0, C.c_void_p(0x3000), None, 0, None) == B.ERR_SHAPE
+    # compact: NULL idx, m out of range, pitch < m, destination aliasing a source
+    assert lib.citrus_kv_compact(C.byref(c), fake(), fake(), 4, fake(), fake(), 8, None, 8, 8, fake(0x9000), fake(0xA000), None) == B.ERR_NULL
+    assert lib.citrus_kv_compact(C.byref(c), fake(), fake(), 4, fake(), fake(), 8, C.c_void_p(0x2000), 8, 0, fake(0x9000), fake(0xA000), None) == B.ERR_SHAPE
+    assert lib.citrus_kv_compact(C.byref(c), fake(), fake(), 4, fake(), fake(), 8, C.c_void_p(0x2000), 4, 8, fake(0x9000), fake(0xA000), None) == B.ERR_SHAPE
+    assert lib.citrus_kv_compact(C.byref(c), fake(), fake(), 4, fake(), fake(), 8, C.c_void_p(0x2000), 8, 8, fake(), fake(0xA000), None) == B.ERR_SHAPE
+    # unsupported head_dim
+    bad = cfg(head_dim=96).c()
+    assert lib.citrus_topk_select(C.byref(bad), C.c_void_p(0x2000), 8, 4, C.c_void_p(0x3000), None, 0, None) == B.ERR_UNSUPPORTED
+
+
+def test_process_document_validation_and_provider_protocol():
+    lib = B._lib()
+    c = cfg().c()
+    two = (B.CTensor * 2)(fake(0x10000), fake(0x20000))
+    two_v = (B.CTensor * 2)(fake(0x30000), fake(0x40000))
+    same = (B.CTensor * 2)(fake(0x10000), fake(0x10000))
+    n_c, cur, done = C.c_int32(0), C.c_int32(0), C.c_int32(-1)
+    ws, big = C.c_void_p(0x100000), 1 << 30
+    calls = []
+
+    def provider(_u, i, _s, _io):
+        calls.append(i)
+        return 1          # "no more chunks" before anything would be launched
+
+    cb = B.PROVIDER(provider)
+    fn = C.cast(cb, C.c_void_p)
+    run = lambda **o: lib.citrus_process_document(
+        o.get("cfg", C.byref(c)), o.get("fn", fn), None, o.get("first", 3), -1, o.get("k", two), two_v, None, None,
+        C.byref(o.get("n_c", n_c)), None, C.byref(cur), None, None, None, C.byref(done), o.get("ws", ws),
+        o.get("ws_bytes", big), None)
+    assert run() == B.OK and calls == [3] and done.value == 0
+    assert run(fn=None) == B.ERR_NULL
+    assert run(k=same) == B.ERR_SHAPE
+    assert run(n_c=C.c_int32(65)) == B.ERR_SHAPE
+    assert run(first=-1) == B.ERR_SHAPE
+    assert run(ws=None) == B.ERR_WORKSPACE
+    assert run(ws_bytes=100) == B.ERR_WORKSPACE
+    # a provider that aborts
+    cb2 = B.PROVIDER(lambda _u, i, _s, _io: -5)
+    assert run(fn=C.cast(cb2, C.c_void_p)) == B.ERR_PROVIDER
+    # a provider that hands over an invalid chunk length: rejected before any launch
+    def bad_len(_u, i, _s, io):
+        io.contents.chunk_len = 1000
+        return 0
+    cb3 = B.PROVIDER(bad_len)
+    assert run(fn=C.cast(cb3, C.c_void_p)) == B.ERR_SHAPE
+    # DUAL needs the LM buffers
+    d = cfg(cache_mode=B.CACHE_DUAL, budget_lm=32).c()
+    assert run(cfg=C.byref(d)) == B.ERR_NULL
+
+
+def test_resident_provider_slices_the_document():
+    lib = B._lib()
+    doc = B.CResidentDoc(fake(0x100000), fake(0x200000), fake(0x300000), fake(0x400000), fake(0x500000),
+                         4096, 70, 32, B.BF16)
+    io = B.CChunkIO()
+    assert lib.citrus_resident_provider(C.byref(doc), 0, None, C.byref(io)) == 0 and io.chunk_len == 32
+    assert io.q.ptr == 0x100000 and io.q_instr.ptr == 0x500000
+    assert lib.citrus_resident_provider(C.byref(doc), 2, None, C.byref(io)) == 0 and io.chunk_len == 6
+    assert io.k.ptr == 0x200000 + 64 * 64 * 2 and io.out.ptr == 0x400000 + 64 * 64 * 2
+    assert io.q_instr.ptr == 0x500000 + 2 * 4096 * 2
+    assert lib.citrus_resident_provider(C.byref(doc), 3, None, C.byref(io)) == 1
+    assert lib.citrus_resident_provider(None, 0, None, C.byref(io)) < 0
