@@ -1,0 +1,426 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, entry point
+by entry point and over whole documents.  Needs an MI355X."""
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2406_12018_amd as api
+from oracle import citrus_oracle as orc
+from workloads import WORKLOADS, make_chunk, make_document, peaked, scaled_down
+from workloads.synth import Workload
+
+from helpers import TOL, StepwiseRun, assert_close, bits, check_selection, np64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def rand(shape, dtype, seed, scale=1.0):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    return (torch.randn(shape, generator=g, dtype=torch.float32) * scale).to(dtype).to(DEV)
+
+
+def make_cfg(dtype, B=1, L=2, Hq=4, Hkv=2, d=64, c=32, k=64, n_i=8, **kw):
+    return api.Config(batch=B, layers=L, q_heads=Hq, kv_heads=Hkv, head_dim=d, chunk_len=c, budget=k, instr_len=n_i,
+                      dtype=api.F32 if dtype == "f32" else api.BF16, **kw)
+
+
+def tdt(dtype):
+    return torch.float32 if dtype == "f32" else torch.bfloat16
+
+
+# ----------------------------------------------------------------------------
+# compaction: bit-exact
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128), ("bf16", 64), ("f32", 128)])
+@pytest.mark.parametrize("per_layer", [False, True])
+def test_kv_compact_bit_exact(dtype, d, per_layer):
+    B, L, Hkv, n_c, c, m = 2, 3, 2, 37, 21, 29
+    cfg = make_cfg(dtype, B=B, L=L, Hkv=Hkv, d=d, c=32, k=64,
+                   select_mode=api.SELECT_PER_LAYER if per_layer else api.SELECT_PER_KV_HEAD)
+    say(f"compact {dtype} d={d} per_layer={per_layer}")
+    # strided sources: cache has capacity 64, chunk is a slice of a longer document tensor
+    kc, vc = rand((B, L, Hkv, 64, d), tdt(dtype), 1), rand((B, L, Hkv, 64, d), tdt(dtype), 2)
+    kdoc, vdoc = rand((B, L, Hkv, 100, d), tdt(dtype), 3), rand((B, L, Hkv, 100, d), tdt(dtype), 4)
+    kch, vch = kdoc[:, :, :, 40:40 + c], vdoc[:, :, :, 40:40 + c]
+    hs = 1 if per_layer else Hkv
+    r = np.random.default_rng(5)
+    idx_np = np.stack([np.sort(r.choice(n_c + c, m, replace=False)) for _ in range(B * L * hs)]).reshape(B, L, hs, m)
+    idx = torch.full((B, L, hs, 40), -7, dtype=torch.int32, device=DEV)
+    idx[..., :m] = torch.from_numpy(idx_np).to(DEV)
+    kn = torch.full((B, L, Hkv, 64, d), 9.0, dtype=tdt(dtype), device=DEV)
+    vn = torch.full_like(kn, 9.0)
+    api.citrus_kv_compact(cfg, kc, vc, n_c, kch, vch, idx, m, kn, vn)
+    torch.cuda.synchronize()
+    for b in range(B):
+        for l in range(L):
+            kcat = np.concatenate([bits(kc[b, l, :, :n_c]), bits(kch[b, l])], axis=1)
+            vcat = np.concatenate([bits(vc[b, l, :, :n_c]), bits(vch[b, l])], axis=1)
+            k_ref, v_ref = orc.kv_compact(kcat, vcat, idx_np[b, l])
+            np.testing.assert_array_equal(bits(kn[b, l, :, :m]), k_ref)
+            np.testing.assert_array_equal(bits(vn[b, l, :, :m]), v_ref)
+    # rows beyond m are untouched
+    assert (kn[:, :, :, m:] == 9.0).all() and (vn[:, :, :, m:] == 9.0).all()
+
+
+def test_kv_compact_identity():
+    cfg = make_cfg("bf16", d=128, c=16, k=64)
+    kc, vc = rand((1, 2, 2, 64, 128), torch.bfloat16, 1), rand((1, 2, 2, 64, 128), torch.bfloat16, 2)
+    kch, vch = rand((1, 2, 2, 16, 128), torch.bfloat16, 3), rand((1, 2, 2, 16, 128), torch.bfloat16, 4)
+    idx = torch.arange(56, dtype=torch.int32, device=DEV).expand(1, 2, 2, 56).contiguous()
+    kn, vn = torch.zeros_like(kc), torch.zeros_like(vc)
+    api.citrus_kv_compact(cfg, kc, vc, 40, kch, vch, idx, 56, kn, vn)
+    assert torch.equal(kn[:, :, :, :40], kc[:, :, :, :40]) and torch.equal(kn[:, :, :, 40:56], kch)
+    assert torch.equal(vn[:, :, :, :40], vc[:, :, :, :40]) and torch.equal(vn[:, :, :, 40:56], vch)
+
+
+# ----------------------------------------------------------------------------
+# selection: exact
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,k,levels", [(96, 64, None), (1280, 768, None), (1280, 768, 7), (6144, 4096, None),
+                                        (2048, 1024, 2), (300, 300, None), (5, 64, None), (1, 1, None),
+                                        (1000, 1, None), (1000, 999, 3), (257, 128, None)])
+@pytest.mark.parametrize("per_layer", [False, True])
+def test_topk_select_exact(n, k, levels, per_layer):
+    B, L, Hkv = 2, 2, 4
+    cfg = make_cfg("f32", B=B, L=L, Hq=4, Hkv=Hkv, k=k,
+                   select_mode=api.SELECT_PER_LAYER if per_layer else api.SELECT_PER_KV_HEAD)
+    say(f"topk n={n} k={k} levels={levels} per_layer={per_layer}")
+    r = np.random.default_rng(n * 7 + k)
+    s = r.random((B, L, Hkv, n)).astype(np.float32) if levels is None else \
+        (r.integers(0, levels, (B, L, Hkv, n)) * 0.125 - 0.25).astype(np.float32)
+    idx = api.citrus_topk_select(cfg, torch.from_numpy(s).to(DEV), k).cpu().numpy()
+    m = min(n, k)
+    for b in range(B):
+        for l in range(L):
+            if per_layer:
+                layer = s[b, l, 0].copy()
+                for g in range(1, Hkv):
+                    layer = (layer + s[b, l, g]).astype(np.float32)   # same f32 order as the kernel
+                np.testing.assert_array_equal(idx[b, l, 0, :m], orc.topk_select_1d(layer, k))
+            else:
+                ref = orc.topk_select(s[b, l], k)
+                np.testing.assert_array_equal(idx[b, l, :, :m], ref)
+    assert (idx[..., m:] == -1).all()
+
+
+def test_topk_all_equal_scores_keep_lowest_indices():
+    cfg = make_cfg("f32", B=1, L=1, Hq=2, Hkv=2, k=100)
+    s = torch.full((1, 1, 2, 333), 0.2, device=DEV)
+    idx = api.citrus_topk_select(cfg, s, 100).cpu().numpy()
+    np.testing.assert_array_equal(idx[0, 0], np.tile(np.arange(100), (2, 1)))
+
+
+# ----------------------------------------------------------------------------
+# instruction score and chunk attention
+# ----------------------------------------------------------------------------
+
+SHAPES = [
+    # dtype, B, L, Hq, Hkv, d,  c,  n_c, n_i, qk_scale
+    ("f32", 1, 1, 4, 1, 64, 32, 64, 8, 1.0 / 8),
+    ("f32", 2, 2, 4, 2, 64, 19, 45, 5, 1.0),
+    ("f32", 1, 2, 2, 2, 128, 32, 0, 3, 0.5),
+    ("bf16", 1, 2, 8, 2, 128, 96, 160, 24, 0.09),
+    ("bf16", 1, 1, 32, 8, 128, 512, 768, 64, 0.09),
+    ("bf16", 2, 1, 4, 4, 128, 70, 131, 33, 1.0),
+    ("bf16", 1, 1, 16, 2, 128, 130, 0, 64, 1.0),
+    ("bf16", 1, 2, 4, 2, 64, 50, 77, 9, 0.5),
+    ("bf16", 1, 1, 2, 1, 128, 1, 300, 1, 1.0),
+]
+
+
+def step_inputs(dtype, B, L, Hq, Hkv, d, c, n_c, n_i, s, seed=0):
+    t = tdt(dtype)
+    cap = max(n_c, 1) + 3
+    return dict(q=rand((B, L, Hq, c, d), t, seed + 1, s), qi=rand((B, L, Hq, n_i, d), t, seed + 2, s),
+                kc=rand((B, L, Hkv, cap, d), t, seed + 3, s), vc=rand((B, L, Hkv, cap, d), t, seed + 4),
+                k=rand((B, L, Hkv, c, d), t, seed + 5, s), v=rand((B, L, Hkv, c, d), t, seed + 6))
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "-".join(str(x) for x in s[:9]))
+def test_instr_score_parity(shape):
+    dtype, B, L, Hq, Hkv, d, c, n_c, n_i, s = shape
+    say(f"instr_score {shape}")
+    x = step_inputs(*shape)
+    cfg = make_cfg(dtype, B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, c=c, k=max(n_c, 1) + 3, n_i=n_i)
+    ws = api.alloc_workspace(cfg)
+    score = api.citrus_instr_score(cfg, x["qi"], x["kc"], n_c, x["k"], workspace=ws)
+    torch.cuda.synchronize()
+    got = np64(score)
+    for b in range(B):
+        for l in range(L):
+            kcat = np.concatenate([np64(x["kc"][b, l, :, :n_c]), np64(x["k"][b, l])], axis=1)
+            ref = orc.instr_score(np64(x["qi"][b, l]), kcat)
+            assert_close(got[b, l], ref, dtype, f"score b{b} l{l}")
+    # total mass = instruction rows x heads per KV head
+    np.testing.assert_allclose(got.sum(-1), n_i * (Hq // Hkv), rtol=2e-3 if dtype == "bf16" else 1e-5)
+    # run-to-run bit identical
+    again = api.citrus_instr_score(cfg, x["qi"], x["kc"], n_c, x["k"], workspace=ws)
+    assert torch.equal(score, again)
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "-".join(str(x) for x in s[:9]))
+def test_chunk_attn_parity(shape):
+    dtype, B, L, Hq, Hkv, d, c, n_c, n_i, s = shape
+    say(f"chunk_attn {shape}")
+    x = step_inputs(*shape, seed=100)
+    cfg = make_cfg(dtype, B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, c=c, k=max(n_c, 1) + 3, n_i=n_i)
+    ws = api.alloc_workspace(cfg)
+    lse = torch.empty((B, L, Hq, c), dtype=torch.float32, device=DEV)
+    lm = torch.empty((B, L, Hkv, n_c + c), dtype=torch.float32, device=DEV)
+    kc = x["kc"] if n_c > 0 else None
+    vc = x["vc"] if n_c > 0 else None
+    out = api.citrus_chunk_attn(cfg, x["q"], kc, vc, n_c, x["k"], x["v"], lse=lse, lm_score=lm, workspace=ws)
+    torch.cuda.synchronize()
+    for b in range(B):
+        for l in range(L):
+            kcat = np.concatenate([np64(x["kc"][b, l, :, :n_c]), np64(x["k"][b, l])], axis=1)
+            vcat = np.concatenate([np64(x["vc"][b, l, :, :n_c]), np64(x["v"][b, l])], axis=1)
+            o_ref, lse_ref, _ = orc.chunk_attn(np64(x["q"][b, l]), kcat, vcat, n_c)
+            assert_close(np64(out[b, l]), o_ref, dtype, f"out b{b} l{l}")
+            assert_close(np64(lse[b, l]), lse_ref, dtype, f"lse b{b} l{l}")
+            assert_close(np64(lm[b, l]), orc.lm_score(np64(x["q"][b, l]), kcat, n_c), dtype, f"lm_score b{b} l{l}")
+    # lm_score without a caller lse goes through the workspace and gives the same bits
+    lm2 = torch.empty_like(lm)
+    out2 = api.citrus_chunk_attn(cfg, x["q"], kc, vc, n_c, x["k"], x["v"], lm_score=lm2, workspace=ws)
+    assert torch.equal(out, out2) and torch.equal(lm, lm2)
+
+
+def test_chunk_attn_strided_views_and_short_chunk():
+    """Chunk tensors that are slices of document tensors; chunk shorter than cfg.chunk_len."""
+    dtype, B, L, Hq, Hkv, d = "bf16", 1, 2, 8, 2, 128
+    cfg = make_cfg(dtype, B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, c=64, k=128, n_i=8)
+    qd, kd, vd = (rand((B, L, h, 200, d), torch.bfloat16, s) for h, s in ((Hq, 1), (Hkv, 2), (Hkv, 3)))
+    kc, vc = rand((B, L, Hkv, 128, d), torch.bfloat16, 4), rand((B, L, Hkv, 128, d), torch.bfloat16, 5)
+    outd = torch.zeros_like(qd)
+    lo, hi = 150, 187
+    api.citrus_chunk_attn(cfg, qd[:, :, :, lo:hi], kc, vc, 100, kd[:, :, :, lo:hi], vd[:, :, :, lo:hi],
+                          out=outd[:, :, :, lo:hi])
+    torch.cuda.synchronize()
+    assert (outd[:, :, :, :lo] == 0).all() and (outd[:, :, :, hi:] == 0).all()
+    for l in range(L):
+        kcat = np.concatenate([np64(kc[0, l, :, :100]), np64(kd[0, l, :, lo:hi])], axis=1)
+        vcat = np.concatenate([np64(vc[0, l, :, :100]), np64(vd[0, l, :, lo:hi])], axis=1)
+        o_ref, _, _ = orc.chunk_attn(np64(qd[0, l, :, lo:hi]), kcat, vcat, 100)
+        assert_close(np64(outd[0, l, :, lo:hi]), o_ref, dtype, f"strided out l{l}")
+
+
+def test_custom_softmax_scale():
+    cfg = make_cfg("f32", B=1, L=1, Hq=2, Hkv=1, d=64, c=16, k=32, n_i=4, softmax_scale=0.3)
+    x = step_inputs("f32", 1, 1, 2, 1, 64, 16, 20, 4, 1.0)
+    out = api.citrus_chunk_attn(cfg, x["q"], x["kc"], x["vc"], 20, x["k"], x["v"])
+    kcat = np.concatenate([np64(x["kc"][0, 0, :, :20]), np64(x["k"][0, 0])], axis=1)
+    vcat = np.concatenate([np64(x["vc"][0, 0, :, :20]), np64(x["v"][0, 0])], axis=1)
+    o_ref, _, _ = orc.chunk_attn(np64(x["q"][0, 0]), kcat, vcat, 20, scale=0.3)
+    assert_close(np64(out[0, 0]), o_ref, "f32", "scaled out")
+
+
+# ----------------------------------------------------------------------------
+# whole documents: step-by-step, teacher-forced against the oracle
+# ----------------------------------------------------------------------------
+
+def run_document_stepwise(w: Workload, sample_units=None, check_every=1):
+    """Run the four entry points chunk by chunk; at every checked step replay
+    the GPU's selections in the oracle (so one near-tie cannot change later
+    steps) and compare outputs, scores, selections and the compacted cache."""
+    cfg = api.Config.from_workload(w)
+    doc = make_document(w, DEV)
+    run = StepwiseRun(api, cfg, DEV)
+    dual = w.cache_mode == api.CACHE_DUAL
+    units = sample_units or [(b, l) for b in range(w.batch) for l in range(w.layers)]
+    hs = cfg.sel_heads
+    # oracle-side state per unit: document positions held by each cache row
+    pos = {u: np.zeros((w.kv_heads, 0), dtype=np.int64) for u in units}
+    pos_lm = {u: np.zeros((w.kv_heads, 0), dtype=np.int64) for u in units}
+    host = {name: t.cpu() for name, t in doc.items()}
+    band_fracs = []
+    for i in range(w.n_chunks):
+        lo, hi = w.chunk_bounds(i)
+        rec = run.step(doc["q"][:, :, :, lo:hi], doc["k"][:, :, :, lo:hi], doc["v"][:, :, :, lo:hi], doc["q_instr"][i])
+        torch.cuda.synchronize()
+        c = hi - lo
+        chunk_pos = np.broadcast_to(np.arange(lo, hi), (w.kv_heads, c))
+        for (b, l) in units:
+            kd, vd = np64(host["k"][b, l]), np64(host["v"][b, l])
+            qd = np64(host["q"][b, l, :, lo:hi])
+            qi = np64(host["q_instr"][i, b, l])
+            # the cache the GPU should hold = document rows at the replayed positions
+            cand = np.concatenate([pos[(b, l)], chunk_pos], axis=1)
+            kcat = np.stack([kd[g, cand[g]] for g in range(w.kv_heads)])
+            vcat = np.stack([vd[g, cand[g]] for g in range(w.kv_heads)])
+            n_c = pos[(b, l)].shape[1]
+            assert n_c == rec["n_c"]
+            idx = rec["idx"][b, l].cpu().numpy()[:, :rec["m"]]
+            check = (i % check_every == 0) or i == w.n_chunks - 1
+            if dual:
+                cand_lm = np.concatenate([pos_lm[(b, l)], chunk_pos], axis=1)
+                kcat_lm = np.stack([kd[g, cand_lm[g]] for g in range(w.kv_heads)])
+                vcat_lm = np.stack([vd[g, cand_lm[g]] for g in range(w.kv_heads)])
+                n_c_lm = pos_lm[(b, l)].shape[1]
+                idx_lm = rec["idx_lm"][b, l].cpu().numpy()[:, :rec["m_lm"]]
+                if check:
+                    o_ref, lse_ref, _ = orc.chunk_attn(qd, kcat_lm, vcat_lm, n_c_lm)
+                    s_lm_ref = orc.lm_score(qd, kcat_lm, n_c_lm)
+                    assert_close(np64(rec["score_lm"][b, l]), s_lm_ref, w.dtype, f"lm_score step {i} unit {(b, l)}")
+                    for g in range(hs):
+                        ref_vec = s_lm_ref.sum(0) if hs == 1 else s_lm_ref[g]
+                        gpu_vec = layer_sum_f32(rec["score_lm"][b, l]) if hs == 1 else rec["score_lm"][b, l, g].cpu().numpy()
+                        band_fracs.append(check_selection(idx_lm[g], gpu_vec, ref_vec, w.budget_lm, w.dtype,
+                                                          f"lm select step {i}"))
+                pos_lm[(b, l)] = np.stack([cand_lm[g][idx_lm[g % hs]] for g in range(w.kv_heads)])
+            elif check:
+                o_ref, lse_ref, _ = orc.chunk_attn(qd, kcat, vcat, n_c)
+            if check:
+                assert_close(np64(rec["out"][b, l]), o_ref, w.dtype, f"out step {i} unit {(b, l)}")
+                assert_close(np64(rec["lse"][b, l]), lse_ref, w.dtype, f"lse step {i} unit {(b, l)}")
+                s_ref = orc.instr_score(qi, kcat)
+                assert_close(np64(rec["score"][b, l]), s_ref, w.dtype, f"score step {i} unit {(b, l)}")
+                for g in range(hs):
+                    ref_vec = s_ref.sum(0) if hs == 1 else s_ref[g]
+                    gpu_vec = layer_sum_f32(rec["score"][b, l]) if hs == 1 else rec["score"][b, l, g].cpu().numpy()
+                    band_fracs.append(check_selection(idx[g], gpu_vec, ref_vec, w.budget, w.dtype, f"select step {i}"))
+            pos[(b, l)] = np.stack([cand[g][idx[g % hs]] for g in range(w.kv_heads)])
+            if check:
+                # compaction bit-exact: cache row r holds document row pos[r]
+                st = run.state
+                kc_gpu, vc_gpu = st.current()
+                for g in range(w.kv_heads):
+                    p = torch.from_numpy(pos[(b, l)][g])
+                    np.testing.assert_array_equal(bits(kc_gpu[b, l, g]), bits(host["k"][b, l, g][p]))
+                    np.testing.assert_array_equal(bits(vc_gpu[b, l, g]), bits(host["v"][b, l, g][p]))
+                if dual:
+                    kl_gpu, vl_gpu = st.current_lm()
+                    for g in range(w.kv_heads):
+                        p = torch.from_numpy(pos_lm[(b, l)][g])
+                        np.testing.assert_array_equal(bits(kl_gpu[b, l, g]), bits(host["k"][b, l, g][p]))
+                        np.testing.assert_array_equal(bits(vl_gpu[b, l, g]), bits(host["v"][b, l, g][p]))
+    say(f"{w.name}: mean in-band fraction of the selection band rule = {np.mean(band_fracs):.3f}")
+    return run, doc
+
+
+def layer_sum_f32(score_blg: torch.Tensor) -> np.ndarray:
+    s = score_blg.cpu().numpy()
+    acc = s[0].copy()
+    for g in range(1, s.shape[0]):
+        acc = (acc + s[g]).astype(np.float32)
+    return acc
+
+
+DOC_CASES = {
+    "cfg1": WORKLOADS["cfg1_tiny_f32"],
+    "cfg1_peaked": peaked(WORKLOADS["cfg1_tiny_f32"]),
+    "cfg1_ragged": scaled_down(WORKLOADS["cfg1_tiny_f32"], doc_len=499, layers=2, kv_heads=2, batch=2),
+    "cfg1_per_layer": scaled_down(peaked(WORKLOADS["cfg1_tiny_f32"]), layers=2, kv_heads=2, doc_len=200,
+                                  select_mode=api.SELECT_PER_LAYER),
+    "cfg1_dual": scaled_down(peaked(WORKLOADS["cfg1_tiny_f32"]), doc_len=256, cache_mode=api.CACHE_DUAL, budget_lm=48),
+    "cfg1_chunk_gt_budget": scaled_down(WORKLOADS["cfg1_tiny_f32"], doc_len=300, chunk_len=80, budget=50),
+    "cfg2_small": scaled_down(WORKLOADS["cfg2_mistral7b"], layers=2, doc_len=2560),
+    "cfg2_small_peaked": scaled_down(peaked(WORKLOADS["cfg2_mistral7b"]), layers=1, doc_len=2000),
+    "cfg3_small_shared_mha": scaled_down(WORKLOADS["cfg3_llama2_7b_shared"], batch=2, layers=1, q_heads=4, kv_heads=4,
+                                         doc_len=2100, chunk_len=256, budget=384, instr_len=32),
+    "cfg4_small_dual": scaled_down(peaked(WORKLOADS["cfg4_dual"]), batch=2, layers=1, q_heads=8, kv_heads=2,
+                                   doc_len=1536, chunk_len=256, budget=320, budget_lm=384),
+    "cfg5_small_g8": scaled_down(WORKLOADS["cfg5_large"], batch=1, layers=1, q_heads=16, kv_heads=2, doc_len=2048,
+                                 chunk_len=512, budget=640, instr_len=96),
+}
+
+
+@pytest.mark.parametrize("case", list(DOC_CASES), ids=list(DOC_CASES))
+def test_document_stepwise_teacher_forced(case):
+    say(f"document {case}")
+    run_document_stepwise(DOC_CASES[case])
+
+
+# ----------------------------------------------------------------------------
+# the chunk loop entry point
+# ----------------------------------------------------------------------------
+
+def run_process_document(w, doc, split_at=None, use_python_provider=False):
+    cfg = api.Config.from_workload(w)
+    state = api.DocumentState.allocate(cfg, DEV)
+    ws = api.alloc_workspace(cfg, DEV)
+    out = torch.zeros_like(doc["q"])
+    hist = torch.full((w.n_chunks, w.batch, w.layers, cfg.sel_heads, w.budget), -1, dtype=torch.int32, device=DEV)
+    hist_lm = None
+    if w.cache_mode == api.CACHE_DUAL:
+        hist_lm = torch.full((w.n_chunks, w.batch, w.layers, cfg.sel_heads, w.budget_lm), -1, dtype=torch.int32, device=DEV)
+    rd = api.resident_doc(cfg, doc["q"], doc["k"], doc["v"], doc["q_instr"], out)
+    if use_python_provider:
+        def provider(i, io):
+            lo, hi = w.chunk_bounds(i)
+            if lo >= w.doc_len:
+                return 1
+            io.q = api.binding.tensor(doc["q"][:, :, :, lo:hi])
+            io.k = api.binding.tensor(doc["k"][:, :, :, lo:hi])
+            io.v = api.binding.tensor(doc["v"][:, :, :, lo:hi])
+            io.out = api.binding.tensor(out[:, :, :, lo:hi])
+            io.q_instr = api.binding.tensor(doc["q_instr"][i])
+            io.chunk_len = hi - lo
+            return 0
+        done = api.citrus_process_document(cfg, state, ws, provider=provider, idx_history=hist, idx_history_lm=hist_lm)
+    elif split_at is None:
+        done = api.citrus_process_document(cfg, state, ws, doc=rd, idx_history=hist, idx_history_lm=hist_lm)
+    else:
+        d1 = api.citrus_process_document(cfg, state, ws, doc=rd, max_chunks=split_at, idx_history=hist,
+                                         idx_history_lm=hist_lm)
+        torch.cuda.synchronize()
+        d2 = api.citrus_process_document(cfg, state, ws, doc=rd, first_chunk=split_at, idx_history=hist[split_at:],
+                                         idx_history_lm=None if hist_lm is None else hist_lm[split_at:])
+        done = d1 + d2
+    torch.cuda.synchronize()
+    assert done == w.n_chunks
+    return state, out, hist, hist_lm
+
+
+@pytest.mark.parametrize("case", ["cfg1", "cfg1_ragged", "cfg1_dual", "cfg2_small", "cfg4_small_dual"])
+def test_process_document_equals_stepwise_and_resumes(case):
+    w = DOC_CASES[case]
+    say(f"process_document {case}")
+    cfg = api.Config.from_workload(w)
+    doc = make_document(w, DEV)
+    # stepwise reference run on the GPU (itself checked against the oracle above)
+    run = StepwiseRun(api, cfg, DEV)
+    outs = []
+    for i in range(w.n_chunks):
+        lo, hi = w.chunk_bounds(i)
+        outs.append(run.step(doc["q"][:, :, :, lo:hi], doc["k"][:, :, :, lo:hi], doc["v"][:, :, :, lo:hi],
+                             doc["q_instr"][i])["out"])
+    torch.cuda.synchronize()
+    out_step = torch.cat(outs, dim=3)
+    state, out, hist, hist_lm = run_process_document(w, doc)
+    assert torch.equal(out, out_step)
+    assert state.cache_len == run.state.cache_len == min(w.budget, w.doc_len)
+    for a, b in zip(state.current(), run.state.current()):
+        assert torch.equal(a, b)
+    for i, rec in enumerate(run.steps):
+        assert torch.equal(hist[i][..., :rec["m"]], rec["idx"][..., :rec["m"]])
+        if hist_lm is not None:
+            assert torch.equal(hist_lm[i][..., :rec["m_lm"]], rec["idx_lm"][..., :rec["m_lm"]])
+    if hist_lm is not None:
+        for a, b in zip(state.current_lm(), run.state.current_lm()):
+            assert torch.equal(a, b)
+    # resume: two calls give the same bits as one; so does a second full run and a Python provider
+    for kw in (dict(split_at=max(1, w.n_chunks // 3)), dict(), dict(use_python_provider=True)):
+        state2, out2, hist2, _ = run_process_document(w, doc, **kw)
+        assert torch.equal(out2, out) and torch.equal(hist2, hist), kw
+        for a, b in zip(state2.current(), state.current()):
+            assert torch.equal(a, b)
+
+
+def test_budget_at_least_document_is_full_causal_attention():
+    w = scaled_down(WORKLOADS["cfg2_mistral7b"], layers=1, q_heads=8, kv_heads=2, doc_len=700, chunk_len=128,
+                    budget=1024, instr_len=16)
+    doc = make_document(w, DEV)
+    state, out, hist, _ = run_process_document(w, doc)
+    assert state.cache_len == 700
+    kc, vc = state.current()
+    assert torch.equal(kc, doc["k"]) and torch.equal(vc, doc["v"])
+    ref = orc.full_causal_attention(np64(doc["q"][0, 0]), np64(doc["k"][0, 0]), np64(doc["v"][0, 0]))
+    assert_close(np64(out[0, 0]), ref, "bf16", "full causal")
