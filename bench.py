@@ -1,0 +1,210 @@
+#!/usr/bin/env python3
+"""Benchmark of the CItruS chunk-eviction hot path on one MI355X.
+
+One step = one whole document through citrus_process_document (chunk
+attention, instruction score, top-k selection, K/V compaction for every chunk,
+all layers and heads).  Inputs are synthetic, seeded, and resident in HBM before
+the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+"""
+
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per chunk-attention launch measured offline with rocprofv3 --pmc
+# (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see
+# profiles/.  None until a measurement for that workload exists.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+class HipEvents:
+    """A flat array of hipEvent_t created through the HIP runtime (timing enabled)."""
+
+    def __init__(self, count: int):
+        self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [C.c_void_p]
+        self.arr = (C.c_void_p * count)()
+        for i in range(count):
+            ev = C.c_void_p()
+            rc = self.hip.hipEventCreate(C.byref(ev))
+            if rc != 0:
+                raise RuntimeError(f"hipEventCreate failed: {rc}")
+            self.arr[i] = ev
+
+    def elapsed_ms(self, i: int, j: int) -> float:
+        ms = C.c_float()
+        rc = self.hip.hipEventElapsedTime(C.byref(ms), self.arr[i], self.arr[j])
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return ms.value
+
+    def destroy(self):
+        for ev in self.arr:
+            self.hip.hipEventDestroy(ev)
+
+
+def attn_flops_per_launch(w, i: int, budget: int) -> float:
+    """Algorithmic (causal-masked) flops of chunk i's attention launch:
+    4 * d * Hq * B * L * sum_t (n_c + t + 1)."""
+    lo, hi = w.chunk_bounds(i)
+    c = hi - lo
+    n_c = w.cache_len_before(i, budget)
+    return 4.0 * w.head_dim * w.q_heads * w.batch * w.layers * (c * n_c + c * (c + 1) / 2.0)
+
+
+def cpu_baseline(w, target_seconds: float = 15.0):
+    """The CPU oracle, as it stands, timed on steady-state chunk steps of one
+    (document, layer) unit of the same workload; scaled to the metric's unit."""
+    import numpy as np
+    import torch
+    from oracle import citrus_oracle as orc
+    from workloads import make_chunk
+
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    f64 = lambda t: t.to(torch.float64).numpy()
+    first = min(w.n_chunks - 1, (w.budget + w.chunk_len - 1) // w.chunk_len)   # first steady-state chunk
+    n_c = w.cache_len_before(first)
+    rng = np.random.default_rng(0)
+    ch = make_chunk(w, first, "cpu", b=[0], l=[0])
+    # a steady-state cache: budget rows with the workload's plain value distribution
+    kc = f64((torch.from_numpy(rng.standard_normal((w.kv_heads, n_c, w.head_dim))) * w.head_dim ** -0.5).to(w.torch_dtype))
+    vc = f64((torch.from_numpy(rng.standard_normal((w.kv_heads, n_c, w.head_dim))) * w.head_dim ** -0.5).to(w.torch_dtype))
+    q, k, v, qi = (f64(ch[x][0, 0]) for x in ("q", "k", "v", "q_instr"))
+    steps, t0 = 0, time.perf_counter()
+    while True:
+        k_cat = np.concatenate([kc, k], axis=1)
+        v_cat = np.concatenate([vc, v], axis=1)
+        orc.chunk_attn(q, k_cat, v_cat, n_c)
+        s = orc.instr_score(qi, k_cat)
+        idx = orc.topk_select(s, w.budget)
+        kc, vc = orc.kv_compact(k_cat, v_cat, idx)
+        steps += 1
+        dt = time.perf_counter() - t0
+        if dt > target_seconds or steps >= 64:
+            break
+    per_unit_step = dt / steps                       # seconds per (document, layer) chunk step
+    tok_s = w.chunk_len / (per_unit_step * w.batch * w.layers)
+    return {"value": tok_s, "unit": "document tokens/s per layer-stack", "cores": threads, "kind": "oracle",
+            "sample": f"{steps} steady-state chunk steps (cache {n_c} + chunk {w.chunk_len}) of one (document, layer) "
+                      f"unit, {dt:.1f} s, scaled by batch*layers={w.batch * w.layers}; numpy float64, BLAS threads={threads}"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg2_mistral7b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2406_12018_amd as api
+    from workloads import WORKLOADS, make_document
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = WORKLOADS[args.workload]
+    cfg = api.Config.from_workload(w)
+    dual = w.cache_mode == api.CACHE_DUAL
+
+    doc = make_document(w, dev)
+    out = torch.empty_like(doc["q"])
+    state = api.DocumentState.allocate(cfg, dev)
+    ws = api.alloc_workspace(cfg, dev)
+    rd = api.resident_doc(cfg, doc["q"], doc["k"], doc["v"], doc["q_instr"], out)
+    torch.cuda.synchronize()
+
+    E = api.binding.EVENTS_PER_STEP
+    events = HipEvents(args.steps * w.n_chunks * E)
+
+    def one_document(ev_offset=None):
+        state.cache_len = state.cache_len_lm = 0
+        state.buffer_index = state.buffer_index_lm = 0
+        pe = None
+        if ev_offset is not None:
+            pe = C.cast(C.byref(events.arr, ev_offset * C.sizeof(C.c_void_p)), C.c_void_p)
+        done = api.citrus_process_document(cfg, state, ws, doc=rd, phase_events=pe)
+        assert done == w.n_chunks
+
+    for _ in range(args.warmup):
+        one_document()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        one_document(s * w.n_chunks * E)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens = w.batch * w.doc_len
+    value = tokens / (ms_per_step * 1e-3)
+
+    # per-phase device time from the events recorded inside the timed region
+    names = {1: "chunk_attn", 2: "lm_score", 3: "lm_select", 4: "lm_compact", 5: "instr_score", 6: "select", 7: "compact"}
+    phase_ms = {v: 0.0 for v in names.values()}
+    attn_ms, attn_fl = [], []
+    for s in range(args.steps):
+        for i in range(w.n_chunks):
+            base = (s * w.n_chunks + i) * E
+            for p, name in names.items():
+                if not dual and p in (2, 3, 4):
+                    continue
+                phase_ms[name] += events.elapsed_ms(base + p - 1, base + p)
+            attn_ms.append(events.elapsed_ms(base, base + 1))
+            attn_fl.append(attn_flops_per_launch(w, i, w.budget_lm if dual else w.budget))
+    events.destroy()
+    phase_ms = {k: round(v / args.steps, 4) for k, v in phase_ms.items() if dual or not k.startswith("lm_")}
+    avg_ms = sum(attn_ms) / len(attn_ms)
+    avg_fl = sum(attn_fl) / len(attn_fl)
+    achieved = avg_fl / (avg_ms * 1e-3) / 1e12
+    traffic = MEASURED_TRAFFIC_BYTES.get(w.name)
+
+    result = {
+        "metric": "document tokens/sec per layer-stack + % HBM/MFMA peak, Mistral-7B shape",
+        "value": round(value, 1), "unit": "document tokens/s per layer-stack",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "layers": w.layers, "q_heads": w.q_heads,
+                   "kv_heads": w.kv_heads, "head_dim": w.head_dim, "doc_len": w.doc_len, "chunk_len": w.chunk_len,
+                   "budget": w.budget, "instr_len": w.instr_len,
+                   "cache_mode": ["instr", "shared", "dual"][w.cache_mode], "select": "per_kv_head"},
+        "roofline": {"kernel": "attn_mfma_kernel (chunk attention)", "bound": "mfma",
+                     "achieved": round(achieved, 2), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": traffic,
+                     "avg_launch_ms": round(avg_ms, 5), "algorithmic_flops_per_launch": avg_fl},
+        "phase_ms_per_step": phase_ms,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -59,6 +59,7 @@ extern "C" {
 #endif
 
 #define CITRUS_ABI_VERSION 1
+#define CITRUS_EVENTS_PER_STEP 8
 
 typedef enum {
   CITRUS_OK = 0,
@@ -247,6 +248,14 @@ int32_t citrus_resident_provider(void* user, int32_t chunk_index, void* hip_stre
  *                 first_chunk); Hsel = Hkv or 1 (PER_LAYER)
  * idx_history_lm  same for the LM cache with pitch budget_lm (DUAL)
  * chunks_done     host, optional: number of steps performed
+ * phase_events    host, optional: array of hipEvent_t handles created by the
+ *                 caller (with timing enabled), CITRUS_EVENTS_PER_STEP per step.
+ *                 Step s records event [s*CITRUS_EVENTS_PER_STEP + p] on
+ *                 hip_stream at these points: p=0 step start, 1 after chunk
+ *                 attention, 2 after the chunk-scored importance, 3 after the
+ *                 LM selection, 4 after the LM compaction (2..4 coincide with 1
+ *                 unless DUAL), 5 after the instruction score, 6 after the
+ *                 selection, 7 after the compaction.  For per-phase timing only.
  * No host/device synchronisation happens inside the loop.
  */
 int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider next, void* user,
@@ -256,6 +265,7 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
                                 int32_t* cache_len, int32_t* cache_len_lm,
                                 int32_t* buffer_index, int32_t* buffer_index_lm,
                                 int32_t* idx_history, int32_t* idx_history_lm, int32_t* chunks_done,
+                                void* const* phase_events,
                                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
 #ifdef __cplusplus

@@ -22,6 +22,8 @@ F32, BF16 = 0, 1
 CACHE_INSTR, CACHE_SHARED, CACHE_DUAL = 0, 1, 2
 SELECT_PER_KV_HEAD, SELECT_PER_LAYER = 0, 1
 
+EVENTS_PER_STEP = 8
+
 OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE, ERR_PROVIDER = range(7)
 
 EXPORTS = (
@@ -92,7 +94,7 @@ def _lib():
     lib.citrus_resident_provider.argtypes = [V, I, V, P(CChunkIO)]
     lib.citrus_process_document.restype = I
     lib.citrus_process_document.argtypes = [P(CConfig), V, V, I, I, P(CTensor), P(CTensor), P(CTensor), P(CTensor),
-                                            P(I), P(I), P(I), P(I), V, V, P(I), V, S, V]
+                                            P(I), P(I), P(I), P(I), V, V, P(I), V, V, S, V]
     _LIB = lib
     return lib
 
@@ -277,11 +279,13 @@ def resident_doc(cfg: Config, q, k, v, q_instr, out, doc_len: Optional[int] = No
 
 def citrus_process_document(cfg: Config, state: DocumentState, workspace, *, doc: Optional[CResidentDoc] = None,
                             provider: Optional[Callable] = None, first_chunk: int = 0, max_chunks: int = -1,
-                            idx_history=None, idx_history_lm=None, stream=None) -> int:
+                            idx_history=None, idx_history_lm=None, phase_events=None, stream=None) -> int:
     """Run the chunk loop.  Either ``doc`` (a resident document, served by the
     library's own provider) or ``provider`` (a Python callable
     ``(chunk_index, io: CChunkIO) -> 0 | 1 | negative``) supplies the chunks.
-    Updates ``state`` in place and returns the number of chunks processed."""
+    ``phase_events`` is an optional ctypes array of hipEvent_t handles
+    (EVENTS_PER_STEP per step).  Updates ``state`` in place and returns the
+    number of chunks processed."""
     lib = _lib()
     if (doc is None) == (provider is None):
         raise ValueError("give exactly one of doc / provider")
@@ -309,7 +313,7 @@ def citrus_process_document(cfg: Config, state: DocumentState, workspace, *, doc
     cc = cfg.c()
     st = lib.citrus_process_document(C.byref(cc), fn, user, first_chunk, max_chunks, kc, vc, kl, vl,
                                      C.byref(n_c), C.byref(n_c_lm), C.byref(cur), C.byref(cur_lm),
-                                     _ptr(idx_history), _ptr(idx_history_lm), C.byref(done), _ptr(workspace),
+                                     _ptr(idx_history), _ptr(idx_history_lm), C.byref(done), phase_events, _ptr(workspace),
                                      0 if workspace is None else workspace.numel(), _stream(stream))
     del keep
     state.cache_len, state.buffer_index = n_c.value, cur.value

@@ -1,7 +1,396 @@
-// placeholder until the MFMA kernels land
+// bf16 MFMA kernels for head_dim 128 on gfx950 (CDNA4).
+//
+//  attn_mfma_kernel    flash-style chunk attention (Section 4.1 step 1; softmax
+//                      with the 1/sqrt(d_k) scaling of Eq. (1)): online softmax
+//                      over 64-key tiles staged in LDS, S^T = K.Q^T and
+//                      O^T = V^T.P^T on v_mfma_f32_32x32x16_bf16.  Without a
+//                      value/output tensor it only produces the row
+//                      log-sum-exp (first pass of the instruction score).
+//  colsum_mfma_kernel  summed form of Eq. (1): probabilities exp(s - lse)
+//                      added down the query rows of a KV group, per key.
+//
+// Layout facts used throughout (wave64, v_mfma_f32_32x32x16_bf16):
+//   A operand: lane l holds row (l % 32), contraction slots 8*(l / 32) .. +7
+//   B operand: lane l holds column (l % 32), the same contraction slots
+//   C/D:       lane l, register i holds column (l % 32),
+//              row 8*(i / 4) + 4*(l / 32) + (i % 4)
+// Computing S^T (keys x queries) puts one query per lane, so softmax row
+// reductions are in-lane plus one exchange with lane l ^ 32, and the S^T
+// accumulators are directly the B operand (P^T) of the second product.
 #include "citrus_internal.h"
+
 namespace citrus {
-bool mfma_path_supported(int, const Dims&) { return false; }
-hipError_t launch_attn_mfma(const Dims&, View, int, Segments, Segments, int, View, float*, hipStream_t) { return hipErrorNotSupported; }
-hipError_t launch_colsum_mfma(const Dims&, View, int, Segments, int, const float*, float*, hipStream_t) { return hipErrorNotSupported; }
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+
+constexpr int D = 128;
+constexpr int kThreads = 256;
+constexpr int kWaves = 4;
+constexpr int kRowsPerWave = 64;  // two 32-query column tiles per wave
+constexpr int kTileN = 64;        // keys per LDS tile
+constexpr int kPitch = D + 8;     // LDS row pitch in bf16 (272 B): conflict-free 16-byte column reads
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+union Pack8 {
+  bf16x8 v;
+  uint4 u;
+  uint32_t w[4];
+};
+
+__device__ inline uint32_t pack_bf16x2(float lo, float hi) {
+  f32x2 f = {lo, hi};
+  bf16x2 b = __builtin_convertvector(f, bf16x2);  // round to nearest even
+  return __builtin_bit_cast(uint32_t, b);
 }
+
+__device__ inline const uint16_t* unit_ptr(const View& v, int b, int l, int h) {
+  return static_cast<const uint16_t*>(v.ptr) + (b * v.sb + l * v.sl + h * v.sh);
+}
+
+// How the four waves of a block split (head, 64-row tile) tasks inside one KV group.
+struct TaskShape {
+  int heads_per_block;  // 4, 2 or 1 query heads of the group
+  int tiles_per_block;  // 4 / heads_per_block row tiles of 64
+};
+__host__ __device__ inline TaskShape task_shape(int G) {
+  const int hpb = (G % 4 == 0) ? 4 : ((G % 2 == 0) ? 2 : 1);
+  return TaskShape{hpb, kWaves / hpb};
+}
+
+template <bool HAS_PV>
+__global__ __launch_bounds__(kThreads) void attn_mfma_kernel(Dims dm, View q, int rows, Segments ks, Segments vs,
+                                                            int causal, View out, float* lse) {
+  __shared__ __attribute__((aligned(16))) uint16_t k_s[kTileN * kPitch];
+  __shared__ __attribute__((aligned(16))) uint16_t v_s[HAS_PV ? kTileN * kPitch : 8];
+
+  const int tid = threadIdx.x, lane = tid % 64, w = tid / 64;
+  const int col = lane % 32, grp = lane / 32;
+  const TaskShape ts = task_shape(dm.G);
+  const int head_groups = dm.G / ts.heads_per_block;
+  const int g = blockIdx.y, b = blockIdx.z / dm.L, l = blockIdx.z % dm.L;
+  const int hg = blockIdx.x % head_groups, rb = blockIdx.x / head_groups;
+  const int h = g * dm.G + hg * ts.heads_per_block + (w % ts.heads_per_block);
+  const int row0 = (rb * ts.tiles_per_block + w / ts.heads_per_block) * kRowsPerWave;
+  const int n = ks.n_c + ks.c;
+
+  // last candidate any row of this block / this wave can see
+  const int blk_row_last = min(rows, (rb + 1) * ts.tiles_per_block * kRowsPerWave) - 1;
+  const int blk_limit = causal ? ks.n_c + blk_row_last : n - 1;
+  const int num_tiles = blk_limit / kTileN + 1;
+  const bool wave_active = row0 < rows;
+  const int wave_row_last = min(rows, row0 + kRowsPerWave) - 1;
+  const int wave_limit_max = causal ? ks.n_c + wave_row_last : n - 1;  // beyond it the wave sees nothing
+  const int wave_limit_min = causal ? ks.n_c + row0 : n - 1;           // up to it every row sees everything
+
+  // ---- Q^T operand, kept in registers: q_op[qt][kk] = Q[row0 + 32 qt + col][16 kk + 8 grp ..+7] ----
+  bf16x8 q_op[2][8];
+  int t_lane[2];
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) {
+    t_lane[qt] = min(row0 + 32 * qt + col, rows - 1);
+    const uint16_t* qp = unit_ptr(q, b, l, h) + static_cast<int64_t>(max(t_lane[qt], 0)) * q.ss + 8 * grp;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      Pack8 p;
+      p.u = *reinterpret_cast<const uint4*>(qp + 16 * kk);
+      q_op[qt][kk] = p.v;
+    }
+  }
+  int limit_lane[2];
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) limit_lane[qt] = causal ? ks.n_c + t_lane[qt] : n - 1;
+
+  // ---- global -> register -> LDS staging of one 64-key tile ----
+  const uint16_t* k_cache_u = unit_ptr(ks.cache, b, l, g);
+  const uint16_t* k_chunk_u = unit_ptr(ks.chunk, b, l, g);
+  const uint16_t* v_cache_u = HAS_PV ? unit_ptr(vs.cache, b, l, g) : nullptr;
+  const uint16_t* v_chunk_u = HAS_PV ? unit_ptr(vs.chunk, b, l, g) : nullptr;
+  uint4 k_st[4], v_st[4];
+  const int st_row = tid / 16, st_seg = tid % 16;  // piece p = tid + 256 i -> row st_row + 16 i
+  auto fetch_tile = [&](int j0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int j = j0 + st_row + 16 * i;
+      uint4 kz = {0u, 0u, 0u, 0u}, vz = {0u, 0u, 0u, 0u};
+      if (j < n) {
+        const bool in_cache = j < ks.n_c;
+        const uint16_t* kp = in_cache ? k_cache_u + static_cast<int64_t>(j) * ks.cache.ss
+                                      : k_chunk_u + static_cast<int64_t>(j - ks.n_c) * ks.chunk.ss;
+        kz = *reinterpret_cast<const uint4*>(kp + 8 * st_seg);
+        if (HAS_PV) {
+          const uint16_t* vp = in_cache ? v_cache_u + static_cast<int64_t>(j) * vs.cache.ss
+                                        : v_chunk_u + static_cast<int64_t>(j - ks.n_c) * vs.chunk.ss;
+          vz = *reinterpret_cast<const uint4*>(vp + 8 * st_seg);
+        }
+      }
+      k_st[i] = kz;
+      v_st[i] = vz;
+    }
+  };
+  auto stage_tile = [&]() {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int off = (st_row + 16 * i) * kPitch + 8 * st_seg;
+      *reinterpret_cast<uint4*>(&k_s[off]) = k_st[i];
+      if (HAS_PV) *reinterpret_cast<uint4*>(&v_s[off]) = v_st[i];
+    }
+  };
+
+  // ---- running softmax state: one query per lane and column tile ----
+  const float c2 = dm.scale * kLog2e;  // logits are kept in the log2 domain
+  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+  f32x16 o_acc[4][2];  // [d residue r][qt]: row c' of tile r is head_dim index 4 c' + r
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o_acc[r][qt][i] = 0.f;
+
+  fetch_tile(0);
+  stage_tile();
+  __syncthreads();
+
+  for (int jt = 0; jt < num_tiles; ++jt) {
+    const int j0 = jt * kTileN;
+    if (jt + 1 < num_tiles) fetch_tile(j0 + kTileN);  // in flight while this tile is computed
+
+    if (wave_active && j0 <= wave_limit_max) {
+      // S^T = K . Q^T for 64 keys x 64 queries
+      f32x16 s_acc[2][2];
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) s_acc[mt][qt][i] = 0.f;
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+          Pack8 a;
+          a.u = *reinterpret_cast<const uint4*>(&k_s[(32 * mt + col) * kPitch + 16 * kk + 8 * grp]);
+#pragma unroll
+          for (int qt = 0; qt < 2; ++qt)
+            s_acc[mt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, q_op[qt][kk], s_acc[mt][qt], 0, 0, 0);
+        }
+      }
+
+      const bool need_mask = j0 + kTileN - 1 > wave_limit_min;
+      uint32_t p_pk[2][2][8];  // [mt][qt][pair]: bf16 probabilities, pairs of consecutive registers
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) {
+        if (need_mask) {
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int j = j0 + 32 * mt + 8 * (i / 4) + 4 * grp + (i % 4);
+              if (j > limit_lane[qt]) s_acc[mt][qt][i] = -INFINITY;
+            }
+        }
+        float mx = s_acc[0][qt][0];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s_acc[mt][qt][i]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run[qt], mx * c2);
+        if (__any(m_new > m_run[qt])) {  // wave-uniform: skip the rescale when no row's maximum moved
+          const float alpha = exp2f(m_run[qt] - m_new);
+          l_run[qt] *= alpha;
+          if (HAS_PV) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+              for (int i = 0; i < 16; ++i) o_acc[r][qt][i] *= alpha;
+          }
+          m_run[qt] = m_new;
+        }
+        float psum = 0.f;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+          float p[16];
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            p[i] = exp2f(fmaf(s_acc[mt][qt][i], c2, -m_run[qt]));
+            psum += p[i];
+          }
+          if (HAS_PV) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) p_pk[mt][qt][i] = pack_bf16x2(p[2 * i], p[2 * i + 1]);
+          }
+        }
+        l_run[qt] += psum;
+      }
+
+      if (HAS_PV) {
+        // O^T += V^T . P^T ; contraction step (mt, half) covers keys 32 mt + 16 half .. +15 in the
+        // slot order the S^T accumulators already have: slot i of lane group grp is key
+        // 8 (i / 4) + 4 grp + (i % 4) of the step.
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+          for (int half = 0; half < 2; ++half) {
+            uint2 vw[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+              const int key = 32 * mt + 16 * half + 8 * (i / 4) + 4 * grp + (i % 4);
+              vw[i] = *reinterpret_cast<const uint2*>(&v_s[key * kPitch + 4 * col]);
+            }
+            Pack8 pb[2];
+#pragma unroll
+            for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+              for (int x = 0; x < 4; ++x) pb[qt].w[x] = p_pk[mt][qt][4 * half + x];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              Pack8 a;
+#pragma unroll
+              for (int x = 0; x < 4; ++x) {
+                const uint32_t wa = (r < 2) ? vw[2 * x].x : vw[2 * x].y;
+                const uint32_t wb = (r < 2) ? vw[2 * x + 1].x : vw[2 * x + 1].y;
+                a.w[x] = __builtin_amdgcn_perm(wb, wa, (r & 1) ? 0x07060302u : 0x05040100u);
+              }
+#pragma unroll
+              for (int qt = 0; qt < 2; ++qt)
+                o_acc[r][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, pb[qt].v, o_acc[r][qt], 0, 0, 0);
+            }
+          }
+        }
+      }
+    }
+
+    __syncthreads();  // every wave is done reading this tile
+    if (jt + 1 < num_tiles) stage_tile();
+    __syncthreads();
+  }
+
+  if (!wave_active) return;
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) {
+    const float l_tot = l_run[qt] + __shfl_xor(l_run[qt], 32, 64);
+    const int t = row0 + 32 * qt + col;
+    if (t >= rows) continue;
+    if (lse != nullptr && grp == 0)
+      lse[(static_cast<int64_t>(blockIdx.z) * dm.Hq + h) * rows + t] = (m_run[qt] + log2f(l_tot)) * kLn2;
+    if (HAS_PV) {
+      const float inv = 1.f / l_tot;
+      uint16_t* op = const_cast<uint16_t*>(unit_ptr(out, b, l, h)) + static_cast<int64_t>(t) * out.ss;
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        // registers 4 i4 .. 4 i4 + 3 are rows c' = 8 i4 + 4 grp + 0..3, i.e. head_dim 32 i4 + 16 grp + 0..15
+        uint32_t wds[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int i = 4 * i4 + e;
+          wds[2 * e] = pack_bf16x2(o_acc[0][qt][i] * inv, o_acc[1][qt][i] * inv);
+          wds[2 * e + 1] = pack_bf16x2(o_acc[2][qt][i] * inv, o_acc[3][qt][i] * inv);
+        }
+        uint4* dst = reinterpret_cast<uint4*>(op + 32 * i4 + 16 * grp);
+        dst[0] = make_uint4(wds[0], wds[1], wds[2], wds[3]);
+        dst[1] = make_uint4(wds[4], wds[5], wds[6], wds[7]);
+      }
+    }
+  }
+}
+
+// One wave per 32 candidate keys: the keys stay in registers as the A operand,
+// the query rows of the KV group stream by as B operands.  Per-lane partial
+// sums are reduced across the 32 query lanes once at the end (fixed order).
+__global__ __launch_bounds__(kThreads) void colsum_mfma_kernel(Dims dm, View q, int rows, Segments ks, int causal,
+                                                              const float* lse, float* score) {
+  const int tid = threadIdx.x, lane = tid % 64, w = tid / 64;
+  const int col = lane % 32, grp = lane / 32;
+  const int g = blockIdx.y, b = blockIdx.z / dm.L, l = blockIdx.z % dm.L;
+  const int n = ks.n_c + ks.c;
+  const int j0 = (blockIdx.x * kWaves + w) * 32;
+  if (j0 >= n) return;  // no block-level synchronisation below
+
+  bf16x8 k_op[8];
+  {
+    const int j = min(j0 + col, n - 1);
+    const uint16_t* kp = (j < ks.n_c ? unit_ptr(ks.cache, b, l, g) + static_cast<int64_t>(j) * ks.cache.ss
+                                     : unit_ptr(ks.chunk, b, l, g) + static_cast<int64_t>(j - ks.n_c) * ks.chunk.ss) +
+                         8 * grp;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      Pack8 p;
+      p.u = *reinterpret_cast<const uint4*>(kp + 16 * kk);
+      k_op[kk] = p.v;
+    }
+  }
+  const float c2 = dm.scale * kLog2e;
+  float part[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) part[i] = 0.f;
+
+  // rows before t_first see none of this wave's keys (causal, chunk keys only)
+  const int t_first = (causal && j0 > ks.n_c) ? ((j0 - ks.n_c) / 32) * 32 : 0;
+  for (int hh = 0; hh < dm.G; ++hh) {
+    const int h = g * dm.G + hh;
+    const uint16_t* q_u = unit_ptr(q, b, l, h);
+    const float* lse_h = lse + (static_cast<int64_t>(blockIdx.z) * dm.Hq + h) * rows;
+    for (int t0 = t_first; t0 < rows; t0 += 32) {
+      const int t = t0 + col;
+      const int tc = min(t, rows - 1);
+      const uint16_t* qp = q_u + static_cast<int64_t>(tc) * q.ss + 8 * grp;
+      const float lse2 = lse_h[tc] * kLog2e;
+      f32x16 s;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[i] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        Pack8 p;
+        p.u = *reinterpret_cast<const uint4*>(qp + 16 * kk);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_op[kk], p.v, s, 0, 0, 0);
+      }
+      const int limit = (t < rows) ? (causal ? ks.n_c + t : n - 1) : -1;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int j = j0 + 8 * (i / 4) + 4 * grp + (i % 4);
+        const float p = exp2f(fmaf(s[i], c2, -lse2));
+        part[i] += (j <= limit) ? p : 0.f;
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    float v = part[i];
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    const int j = j0 + 8 * (i / 4) + 4 * grp + (i % 4);
+    if (col == 0 && j < n) score[(static_cast<int64_t>(blockIdx.z) * dm.Hkv + g) * n + j] = v;
+  }
+}
+
+}  // namespace
+
+bool mfma_path_supported(int dtype, const Dims& dm) { return dtype == CITRUS_BF16 && dm.D == D; }
+
+hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments ks, Segments vs, int causal, View out,
+                            float* lse, hipStream_t st) {
+  const TaskShape ts = task_shape(dm.G);
+  const int rows_per_block = ts.tiles_per_block * kRowsPerWave;
+  dim3 grid(((rows + rows_per_block - 1) / rows_per_block) * (dm.G / ts.heads_per_block), dm.Hkv, dm.B * dm.L);
+  if (out.ptr != nullptr)
+    hipLaunchKernelGGL((attn_mfma_kernel<true>), grid, dim3(kThreads), 0, st, dm, q, rows, ks, vs, causal, out, lse);
+  else
+    hipLaunchKernelGGL((attn_mfma_kernel<false>), grid, dim3(kThreads), 0, st, dm, q, rows, ks, vs, causal, out, lse);
+  return hipGetLastError();
+}
+
+hipError_t launch_colsum_mfma(const Dims& dm, View q, int rows, Segments ks, int causal, const float* lse,
+                              float* score, hipStream_t st) {
+  const int n = ks.n_c + ks.c;
+  dim3 grid((n + 32 * kWaves - 1) / (32 * kWaves), dm.Hkv, dm.B * dm.L);
+  hipLaunchKernelGGL(colsum_mfma_kernel, grid, dim3(kThreads), 0, st, dm, q, rows, ks, causal, lse, score);
+  return hipGetLastError();
+}
+
+}  // namespace citrus

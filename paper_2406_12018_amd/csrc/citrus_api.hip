@@ -275,8 +275,8 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
                                 const citrus_tensor* v_cache, const citrus_tensor* k_cache_lm,
                                 const citrus_tensor* v_cache_lm, int32_t* cache_len, int32_t* cache_len_lm,
                                 int32_t* buffer_index, int32_t* buffer_index_lm, int32_t* idx_history,
-                                int32_t* idx_history_lm, int32_t* chunks_done, void* workspace,
-                                size_t workspace_bytes, void* hip_stream) {
+                                int32_t* idx_history_lm, int32_t* chunks_done, void* const* phase_events,
+                                void* workspace, size_t workspace_bytes, void* hip_stream) {
   CITRUS_TRY(check_config(cfg));
   if (next == nullptr || k_cache == nullptr || v_cache == nullptr || cache_len == nullptr || buffer_index == nullptr)
     return CITRUS_ERR_NULL;
@@ -314,6 +314,10 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
   int n_c_lm = dual ? *cache_len_lm : 0, cur_lm = dual ? *buffer_index_lm : 0;
   int done = 0;
   citrus_status status = CITRUS_OK;
+  auto mark = [&](int step, int phase) {
+    if (phase_events != nullptr)
+      (void)hipEventRecord(static_cast<hipEvent_t>(phase_events[step * CITRUS_EVENTS_PER_STEP + phase]), st);
+  };
   for (; max_chunks < 0 || done < max_chunks; ++done) {
     citrus_chunk_io io;
     memset(&io, 0, sizeof(io));
@@ -333,28 +337,40 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
     const int n = n_c + c;
     const int m = n < cfg->budget ? n : cfg->budget;
 
+    mark(done, 0);
     if (dual) {
       // language-modelling thread: the chunk attends over [LM cache ; chunk] and scores it itself
       const Segments kl = segments(k_cache_lm[cur_lm], n_c_lm, io.k, c), vl = segments(v_cache_lm[cur_lm], n_c_lm, io.v, c);
       const int n_lm = n_c_lm + c;
       const int m_lm = n_lm < cfg->budget_lm ? n_lm : cfg->budget_lm;
       int32_t* idx_lm = idx_history_lm ? idx_history_lm + static_cast<size_t>(done) * units_sel * cfg->budget_lm : idx_lm_ws;
-      if ((status = do_chunk_attn(cfg, dm, io.q, kl, vl, io.out, lse_chunk, score_lm, st)) != CITRUS_OK) break;
+      if ((status = do_chunk_attn(cfg, dm, io.q, kl, vl, io.out, lse_chunk, nullptr, st)) != CITRUS_OK) break;
+      mark(done, 1);
+      if ((status = hip_status(run_colsum(cfg, dm, make_view(io.q), c, kl, /*causal=*/1, lse_chunk, score_lm, st))) !=
+          CITRUS_OK)
+        break;
+      mark(done, 2);
       if ((status = do_topk(cfg, score_lm, n_lm, cfg->budget_lm, idx_lm, st)) != CITRUS_OK) break;
+      mark(done, 3);
       if ((status = do_compact(cfg, dm, kl, vl, idx_lm, cfg->budget_lm, m_lm, k_cache_lm[cur_lm ^ 1],
                                v_cache_lm[cur_lm ^ 1], st)) != CITRUS_OK)
         break;
+      mark(done, 4);
       cur_lm ^= 1;
       n_c_lm = m_lm;
     } else {
       if ((status = do_chunk_attn(cfg, dm, io.q, ks, vs, io.out, nullptr, nullptr, st)) != CITRUS_OK) break;
+      for (int p = 1; p <= 4; ++p) mark(done, p);
     }
 
     int32_t* idx = idx_history ? idx_history + static_cast<size_t>(done) * units_sel * cfg->budget : idx_ws;
     if ((status = do_instr_score(cfg, dm, io.q_instr, ks, lse_instr, score, st)) != CITRUS_OK) break;
+    mark(done, 5);
     if ((status = do_topk(cfg, score, n, cfg->budget, idx, st)) != CITRUS_OK) break;
+    mark(done, 6);
     if ((status = do_compact(cfg, dm, ks, vs, idx, cfg->budget, m, k_cache[cur ^ 1], v_cache[cur ^ 1], st)) != CITRUS_OK)
       break;
+    mark(done, 7);
     cur ^= 1;
     n_c = m;
   }

@@ -116,7 +116,7 @@ def test_process_document_validation_and_provider_protocol():
     fn = C.cast(cb, C.c_void_p)
     run = lambda **o: lib.citrus_process_document(
         o.get("cfg", C.byref(c)), o.get("fn", fn), None, o.get("first", 3), -1, o.get("k", two), two_v, None, None,
-        C.byref(o.get("n_c", n_c)), None, C.byref(cur), None, None, None, C.byref(done), o.get("ws", ws),
+        C.byref(o.get("n_c", n_c)), None, C.byref(cur), None, None, None, C.byref(done), None, o.get("ws", ws),
         o.get("ws_bytes", big), None)
     assert run() == B.OK and calls == [3] and done.value == 0
     assert run(fn=None) == B.ERR_NULL
