@@ -19,6 +19,9 @@ SOURCES = ["citrus_api.hip", "attn_generic.hip", "attn_mfma.hip", "select_compac
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # keep MFMA accumulators in VGPRs: the softmax rescale touches them with vector ALU ops, and
+    # AGPR-resident accumulators cost a copy per register and per loop iteration
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
     "-Wall", "-Wno-unused-function",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]

@@ -32,6 +32,7 @@ constexpr int kThreads = 256;
 constexpr int kWaves = 4;
 constexpr int kRowsPerWave = 64;  // two 32-query column tiles per wave
 constexpr int kTileN = 64;        // keys per LDS tile
+constexpr int kXcds = 8;
 constexpr int kPitch = D + 8;     // LDS row pitch in bf16 (272 B): conflict-free 16-byte column reads
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -65,15 +66,26 @@ __host__ __device__ inline TaskShape task_shape(int G) {
 template <bool HAS_PV>
 __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(Dims dm, View q, int rows, Segments ks, Segments vs,
                                                             int causal, View out, float* lse) {
-  __shared__ __attribute__((aligned(16))) uint16_t k_s[kTileN * kPitch];
-  __shared__ __attribute__((aligned(16))) uint16_t v_s[HAS_PV ? kTileN * kPitch : 8];
+  __shared__ __attribute__((aligned(16))) uint16_t k_s[2 * kTileN * kPitch];  // double-buffered tiles
+  __shared__ __attribute__((aligned(16))) uint16_t v_s[HAS_PV ? 2 * kTileN * kPitch : 8];
 
   const int tid = threadIdx.x, lane = tid % 64, w = tid / 64;
   const int col = lane % 32, grp = lane / 32;
   const TaskShape ts = task_shape(dm.G);
   const int head_groups = dm.G / ts.heads_per_block;
-  const int g = blockIdx.y, b = blockIdx.z / dm.L, l = blockIdx.z % dm.L;
-  const int hg = blockIdx.x % head_groups, rb = blockIdx.x / head_groups;
+  const int rows_per_block = ts.tiles_per_block * kRowsPerWave;
+  const int row_blocks = (rows + rows_per_block - 1) / rows_per_block;
+  // Workgroups are handed to the 8 XCDs round-robin by their linear id.  Remap so that the
+  // workgroups of one (document, layer, KV head), which read the same K/V, land on ONE XCD and
+  // share its L2; within a unit the row blocks with the longest causal range come first.
+  int logical = blockIdx.x;
+  const int total = gridDim.x;
+  if (total % kXcds == 0) logical = (blockIdx.x % kXcds) * (total / kXcds) + blockIdx.x / kXcds;
+  const int rb = row_blocks - 1 - logical % row_blocks;
+  const int hg = (logical / row_blocks) % head_groups;
+  const int g = (logical / (row_blocks * head_groups)) % dm.Hkv;
+  const int bl = logical / (row_blocks * head_groups * dm.Hkv);
+  const int b = bl / dm.L, l = bl % dm.L;
   const int h = g * dm.G + hg * ts.heads_per_block + (w % ts.heads_per_block);
   const int row0 = (rb * ts.tiles_per_block + w / ts.heads_per_block) * kRowsPerWave;
   const int n = ks.n_c + ks.c;
@@ -112,30 +124,35 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(Dims dm, View q, in
   const uint16_t* v_chunk_u = HAS_PV ? unit_ptr(vs.chunk, b, l, g) : nullptr;
   uint4 k_st[4], v_st[4];
   const int st_row = tid / 16, st_seg = tid % 16;  // piece p = tid + 256 i -> row st_row + 16 i
+  // Both candidate addresses are formed unconditionally and one is selected, so the strides
+  // stay in scalar registers.
+  const int64_t k_ss_cache = ks.cache.ss, k_ss_chunk = ks.chunk.ss;
+  const int64_t v_ss_cache = vs.cache.ss, v_ss_chunk = vs.chunk.ss;
+  const int n_c = ks.n_c;
   auto fetch_tile = [&](int j0) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int j = j0 + st_row + 16 * i;
       uint4 kz = {0u, 0u, 0u, 0u}, vz = {0u, 0u, 0u, 0u};
       if (j < n) {
-        const bool in_cache = j < ks.n_c;
-        const uint16_t* kp = in_cache ? k_cache_u + static_cast<int64_t>(j) * ks.cache.ss
-                                      : k_chunk_u + static_cast<int64_t>(j - ks.n_c) * ks.chunk.ss;
-        kz = *reinterpret_cast<const uint4*>(kp + 8 * st_seg);
+        const bool in_cache = j < n_c;
+        const uint16_t* kp_cache = k_cache_u + j * k_ss_cache;
+        const uint16_t* kp_chunk = k_chunk_u + (j - n_c) * k_ss_chunk;
+        kz = *reinterpret_cast<const uint4*>((in_cache ? kp_cache : kp_chunk) + 8 * st_seg);
         if (HAS_PV) {
-          const uint16_t* vp = in_cache ? v_cache_u + static_cast<int64_t>(j) * vs.cache.ss
-                                        : v_chunk_u + static_cast<int64_t>(j - ks.n_c) * vs.chunk.ss;
-          vz = *reinterpret_cast<const uint4*>(vp + 8 * st_seg);
+          const uint16_t* vp_cache = v_cache_u + j * v_ss_cache;
+          const uint16_t* vp_chunk = v_chunk_u + (j - n_c) * v_ss_chunk;
+          vz = *reinterpret_cast<const uint4*>((in_cache ? vp_cache : vp_chunk) + 8 * st_seg);
         }
       }
       k_st[i] = kz;
       v_st[i] = vz;
     }
   };
-  auto stage_tile = [&]() {
+  auto stage_tile = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int off = (st_row + 16 * i) * kPitch + 8 * st_seg;
+      const int off = buf * kTileN * kPitch + (st_row + 16 * i) * kPitch + 8 * st_seg;
       *reinterpret_cast<uint4*>(&k_s[off]) = k_st[i];
       if (HAS_PV) *reinterpret_cast<uint4*>(&v_s[off]) = v_st[i];
     }
@@ -153,101 +170,91 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(Dims dm, View q, in
       for (int i = 0; i < 16; ++i) o_acc[r][qt][i] = 0.f;
 
   fetch_tile(0);
-  stage_tile();
+  stage_tile(0);
   __syncthreads();
 
   for (int jt = 0; jt < num_tiles; ++jt) {
     const int j0 = jt * kTileN;
+    const uint16_t* k_t = k_s + (jt & 1) * kTileN * kPitch;
+    const uint16_t* v_t = v_s + (HAS_PV ? (jt & 1) * kTileN * kPitch : 0);
     if (jt + 1 < num_tiles) fetch_tile(j0 + kTileN);  // in flight while this tile is computed
 
     if (wave_active && j0 <= wave_limit_max) {
-      // S^T = K . Q^T for 64 keys x 64 queries
-      f32x16 s_acc[2][2];
+      const bool need_mask = j0 + kTileN - 1 > wave_limit_min;
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
+      for (int mt = 0; mt < 2; ++mt) {  // two sub-steps of 32 keys
+        // S^T = K . Q^T for 32 keys x 64 queries
+        f32x16 s_acc[2];
 #pragma unroll
         for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) s_acc[mt][qt][i] = 0.f;
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
+          for (int i = 0; i < 16; ++i) s_acc[qt][i] = 0.f;
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
           Pack8 a;
-          a.u = *reinterpret_cast<const uint4*>(&k_s[(32 * mt + col) * kPitch + 16 * kk + 8 * grp]);
+          a.u = *reinterpret_cast<const uint4*>(&k_t[(32 * mt + col) * kPitch + 16 * kk + 8 * grp]);
 #pragma unroll
           for (int qt = 0; qt < 2; ++qt)
-            s_acc[mt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, q_op[qt][kk], s_acc[mt][qt], 0, 0, 0);
+            s_acc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, q_op[qt][kk], s_acc[qt], 0, 0, 0);
         }
-      }
 
-      const bool need_mask = j0 + kTileN - 1 > wave_limit_min;
-      uint32_t p_pk[2][2][8];  // [mt][qt][pair]: bf16 probabilities, pairs of consecutive registers
+        uint32_t p_pk[2][8];  // [qt][pair]: bf16 probabilities, pairs of consecutive registers
 #pragma unroll
-      for (int qt = 0; qt < 2; ++qt) {
-        if (need_mask) {
-#pragma unroll
-          for (int mt = 0; mt < 2; ++mt)
+        for (int qt = 0; qt < 2; ++qt) {
+          if (need_mask) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
               const int j = j0 + 32 * mt + 8 * (i / 4) + 4 * grp + (i % 4);
-              if (j > limit_lane[qt]) s_acc[mt][qt][i] = -INFINITY;
+              if (j > limit_lane[qt]) s_acc[qt][i] = -INFINITY;
             }
-        }
-        float mx = s_acc[0][qt][0];
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s_acc[mt][qt][i]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run[qt], mx * c2);
-        if (__any(m_new > m_run[qt])) {  // wave-uniform: skip the rescale when no row's maximum moved
-          const float alpha = exp2f(m_run[qt] - m_new);
-          l_run[qt] *= alpha;
-          if (HAS_PV) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-              for (int i = 0; i < 16; ++i) o_acc[r][qt][i] *= alpha;
           }
-          m_run[qt] = m_new;
-        }
-        float psum = 0.f;
+          float mx = s_acc[qt][0];
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
+          for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s_acc[qt][i]);
+          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+          const float m_new = fmaxf(m_run[qt], mx * c2);
+          if (__any(m_new > m_run[qt])) {  // wave-uniform: skip the rescale when no row's maximum moved
+            const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
+            l_run[qt] *= alpha;
+            if (HAS_PV) {
+#pragma unroll
+              for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o_acc[r][qt][i] *= alpha;
+            }
+            m_run[qt] = m_new;
+          }
           float p[16];
+          float psum = 0.f;
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
-            p[i] = exp2f(fmaf(s_acc[mt][qt][i], c2, -m_run[qt]));
+            p[i] = __builtin_amdgcn_exp2f(fmaf(s_acc[qt][i], c2, -m_run[qt]));
             psum += p[i];
           }
+          l_run[qt] += psum;
           if (HAS_PV) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) p_pk[mt][qt][i] = pack_bf16x2(p[2 * i], p[2 * i + 1]);
+            for (int i = 0; i < 8; ++i) p_pk[qt][i] = pack_bf16x2(p[2 * i], p[2 * i + 1]);
           }
         }
-        l_run[qt] += psum;
-      }
 
-      if (HAS_PV) {
-        // O^T += V^T . P^T ; contraction step (mt, half) covers keys 32 mt + 16 half .. +15 in the
-        // slot order the S^T accumulators already have: slot i of lane group grp is key
-        // 8 (i / 4) + 4 grp + (i % 4) of the step.
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
+        if (HAS_PV) {
+          // O^T += V^T . P^T ; contraction step `half` covers keys 32 mt + 16 half .. +15 in the slot
+          // order the S^T accumulators already have: slot i of lane group grp is key
+          // 8 (i / 4) + 4 grp + (i % 4) of the step.
 #pragma unroll
           for (int half = 0; half < 2; ++half) {
             uint2 vw[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
               const int key = 32 * mt + 16 * half + 8 * (i / 4) + 4 * grp + (i % 4);
-              vw[i] = *reinterpret_cast<const uint2*>(&v_s[key * kPitch + 4 * col]);
+              vw[i] = *reinterpret_cast<const uint2*>(&v_t[key * kPitch + 4 * col]);
             }
             Pack8 pb[2];
 #pragma unroll
             for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
-              for (int x = 0; x < 4; ++x) pb[qt].w[x] = p_pk[mt][qt][4 * half + x];
+              for (int x = 0; x < 4; ++x) pb[qt].w[x] = p_pk[qt][4 * half + x];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
               Pack8 a;
@@ -266,8 +273,9 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(Dims dm, View q, in
       }
     }
 
-    __syncthreads();  // every wave is done reading this tile
-    if (jt + 1 < num_tiles) stage_tile();
+    // The other buffer was last read one iteration ago and every wave has passed the barrier
+    // that ended that iteration, so it can be overwritten now.
+    if (jt + 1 < num_tiles) stage_tile((jt + 1) & 1);
     __syncthreads();
   }
 
@@ -278,7 +286,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(Dims dm, View q, in
     const int t = row0 + 32 * qt + col;
     if (t >= rows) continue;
     if (lse != nullptr && grp == 0)
-      lse[(static_cast<int64_t>(blockIdx.z) * dm.Hq + h) * rows + t] = (m_run[qt] + log2f(l_tot)) * kLn2;
+      lse[(static_cast<int64_t>(bl) * dm.Hq + h) * rows + t] = (m_run[qt] + log2f(l_tot)) * kLn2;
     if (HAS_PV) {
       const float inv = 1.f / l_tot;
       uint16_t* op = const_cast<uint16_t*>(unit_ptr(out, b, l, h)) + static_cast<int64_t>(t) * out.ss;
@@ -377,7 +385,7 @@ hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments ks, Segme
                             float* lse, hipStream_t st) {
   const TaskShape ts = task_shape(dm.G);
   const int rows_per_block = ts.tiles_per_block * kRowsPerWave;
-  dim3 grid(((rows + rows_per_block - 1) / rows_per_block) * (dm.G / ts.heads_per_block), dm.Hkv, dm.B * dm.L);
+  dim3 grid(((rows + rows_per_block - 1) / rows_per_block) * (dm.G / ts.heads_per_block) * dm.Hkv * dm.B * dm.L);
   if (out.ptr != nullptr)
     hipLaunchKernelGGL((attn_mfma_kernel<true>), grid, dim3(kThreads), 0, st, dm, q, rows, ks, vs, causal, out, lse);
   else
