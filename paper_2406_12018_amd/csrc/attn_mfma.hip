@@ -26,14 +26,16 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) short i16x4;
 
 constexpr int D = 128;
-constexpr int kThreads = 256;
-constexpr int kWaves = 4;
-constexpr int kRowsPerWave = 64;  // two 32-query column tiles per wave
-constexpr int kTileN = 64;        // keys per LDS tile
+constexpr int kWaves = 8;               // two waves per SIMD: one wave's softmax overlaps the other's MFMAs
+constexpr int kThreads = kWaves * 64;
+constexpr int kRowsPerWave = 32;        // one 32-query column tile per wave
+constexpr int kTileN = 64;              // keys per LDS tile
 constexpr int kXcds = 8;
-constexpr int kPitch = D + 8;     // LDS row pitch in bf16 (272 B): conflict-free 16-byte column reads
+constexpr int kPitchK = D + 8;          // LDS row pitch of K in bf16 (272 B): conflict-free 16-byte column reads
+constexpr int kPitchV = D + 16;         // LDS row pitch of V in bf16 (288 B): conflict-free transpose reads
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -41,6 +43,7 @@ union Pack8 {
   bf16x8 v;
   uint4 u;
   uint32_t w[4];
+  i16x4 h[2];
 };
 
 __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
@@ -53,21 +56,30 @@ __device__ inline const uint16_t* unit_ptr(const View& v, int b, int l, int h) {
   return static_cast<const uint16_t*>(v.ptr) + (b * v.sb + l * v.sl + h * v.sh);
 }
 
-// How the four waves of a block split (head, 64-row tile) tasks inside one KV group.
+// LDS transpose read (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane s passes the
+// address of 4 consecutive bf16 and lane i receives element (i % 4) of lanes i/4, 4 + i/4,
+// 8 + i/4, 12 + i/4.  With lane s pointing at &V[key(s / 4)][d0 + 4 (s % 4)], lane i gets
+// V[key(0..3)][d0 + i]: four keys of one head_dim column, i.e. half of an MFMA A operand of V^T.
+__device__ inline i16x4 lds_read_tr16(const uint16_t* p) {
+  typedef i16x4 __attribute__((address_space(3))) * lds_ptr;
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+}
+
+// How the waves of a block split (head, 32-row tile) tasks inside one KV group.
 struct TaskShape {
-  int heads_per_block;  // 4, 2 or 1 query heads of the group
-  int tiles_per_block;  // 4 / heads_per_block row tiles of 64
+  int heads_per_block;  // 8, 4, 2 or 1 query heads of the group
+  int tiles_per_block;  // kWaves / heads_per_block row tiles of 32
 };
 __host__ __device__ inline TaskShape task_shape(int G) {
-  const int hpb = (G % 4 == 0) ? 4 : ((G % 2 == 0) ? 2 : 1);
+  const int hpb = (G % 8 == 0) ? 8 : (G % 4 == 0) ? 4 : ((G % 2 == 0) ? 2 : 1);
   return TaskShape{hpb, kWaves / hpb};
 }
 
 template <bool HAS_PV>
 __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(Dims dm, View q, int rows, Segments ks, Segments vs,
                                                             int causal, View out, float* lse) {
-  __shared__ __attribute__((aligned(16))) uint16_t k_s[2 * kTileN * kPitch];  // double-buffered tiles
-  __shared__ __attribute__((aligned(16))) uint16_t v_s[HAS_PV ? 2 * kTileN * kPitch : 8];
+  __shared__ __attribute__((aligned(16))) uint16_t k_s[2 * kTileN * kPitchK];  // double-buffered tiles
+  __shared__ __attribute__((aligned(16))) uint16_t v_s[HAS_PV ? 2 * kTileN * kPitchV : 8];
 
   const int tid = threadIdx.x, lane = tid % 64, w = tid / 64;
   const int col = lane % 32, grp = lane / 32;
@@ -88,186 +100,182 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(Dims dm, View q, in
   const int b = bl / dm.L, l = bl % dm.L;
   const int h = g * dm.G + hg * ts.heads_per_block + (w % ts.heads_per_block);
   const int row0 = (rb * ts.tiles_per_block + w / ts.heads_per_block) * kRowsPerWave;
-  const int n = ks.n_c + ks.c;
+  const int n_c = ks.n_c;
+  const int n = n_c + ks.c;
 
   // last candidate any row of this block / this wave can see
-  const int blk_row_last = min(rows, (rb + 1) * ts.tiles_per_block * kRowsPerWave) - 1;
-  const int blk_limit = causal ? ks.n_c + blk_row_last : n - 1;
+  const int blk_row_last = min(rows, (rb + 1) * rows_per_block) - 1;
+  const int blk_limit = causal ? n_c + blk_row_last : n - 1;
   const int num_tiles = blk_limit / kTileN + 1;
   const bool wave_active = row0 < rows;
   const int wave_row_last = min(rows, row0 + kRowsPerWave) - 1;
-  const int wave_limit_max = causal ? ks.n_c + wave_row_last : n - 1;  // beyond it the wave sees nothing
-  const int wave_limit_min = causal ? ks.n_c + row0 : n - 1;           // up to it every row sees everything
+  const int wave_limit_max = causal ? n_c + wave_row_last : n - 1;  // beyond it the wave sees nothing
+  const int wave_limit_min = causal ? n_c + row0 : n - 1;           // up to it every row sees everything
 
-  // ---- Q^T operand, kept in registers: q_op[qt][kk] = Q[row0 + 32 qt + col][16 kk + 8 grp ..+7] ----
-  bf16x8 q_op[2][8];
-  int t_lane[2];
-#pragma unroll
-  for (int qt = 0; qt < 2; ++qt) {
-    t_lane[qt] = min(row0 + 32 * qt + col, rows - 1);
-    const uint16_t* qp = unit_ptr(q, b, l, h) + static_cast<int64_t>(max(t_lane[qt], 0)) * q.ss + 8 * grp;
+  // ---- Q^T operand, kept in registers: q_op[kk] = Q[row0 + col][16 kk + 8 grp ..+7] ----
+  bf16x8 q_op[8];
+  const int t_lane = max(min(row0 + col, rows - 1), 0);
+  {
+    const uint16_t* qp = unit_ptr(q, b, l, h) + static_cast<int64_t>(t_lane) * q.ss + 8 * grp;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
       Pack8 p;
       p.u = *reinterpret_cast<const uint4*>(qp + 16 * kk);
-      q_op[qt][kk] = p.v;
+      q_op[kk] = p.v;
     }
   }
-  int limit_lane[2];
-#pragma unroll
-  for (int qt = 0; qt < 2; ++qt) limit_lane[qt] = causal ? ks.n_c + t_lane[qt] : n - 1;
+  const int limit_lane = causal ? n_c + t_lane : n - 1;
 
-  // ---- global -> register -> LDS staging of one 64-key tile ----
+  // ---- global -> register -> LDS staging of one 64-key tile (two K and two V pieces per thread) ----
+  // Rows past the last candidate re-read the last row (finite values; their logits are masked).
+  // Both candidate addresses are formed and one is selected, so the strides stay scalar.
   const uint16_t* k_cache_u = unit_ptr(ks.cache, b, l, g);
   const uint16_t* k_chunk_u = unit_ptr(ks.chunk, b, l, g);
   const uint16_t* v_cache_u = HAS_PV ? unit_ptr(vs.cache, b, l, g) : nullptr;
   const uint16_t* v_chunk_u = HAS_PV ? unit_ptr(vs.chunk, b, l, g) : nullptr;
-  uint4 k_st[4], v_st[4];
-  const int st_row = tid / 16, st_seg = tid % 16;  // piece p = tid + 256 i -> row st_row + 16 i
-  // Both candidate addresses are formed unconditionally and one is selected, so the strides
-  // stay in scalar registers.
   const int64_t k_ss_cache = ks.cache.ss, k_ss_chunk = ks.chunk.ss;
   const int64_t v_ss_cache = vs.cache.ss, v_ss_chunk = vs.chunk.ss;
-  const int n_c = ks.n_c;
-  auto fetch_tile = [&](int j0) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int j = j0 + st_row + 16 * i;
-      uint4 kz = {0u, 0u, 0u, 0u}, vz = {0u, 0u, 0u, 0u};
-      if (j < n) {
-        const bool in_cache = j < n_c;
-        const uint16_t* kp_cache = k_cache_u + j * k_ss_cache;
-        const uint16_t* kp_chunk = k_chunk_u + (j - n_c) * k_ss_chunk;
-        kz = *reinterpret_cast<const uint4*>((in_cache ? kp_cache : kp_chunk) + 8 * st_seg);
-        if (HAS_PV) {
-          const uint16_t* vp_cache = v_cache_u + j * v_ss_cache;
-          const uint16_t* vp_chunk = v_chunk_u + (j - n_c) * v_ss_chunk;
-          vz = *reinterpret_cast<const uint4*>((in_cache ? vp_cache : vp_chunk) + 8 * st_seg);
-        }
-      }
-      k_st[i] = kz;
-      v_st[i] = vz;
-    }
+  const int st_row = tid / 16, st_seg = tid % 16;  // piece i covers tile row st_row + 32 i
+  auto k_row_ptr = [&](int j) {
+    const uint16_t* pc = k_cache_u + j * k_ss_cache;
+    const uint16_t* pk = k_chunk_u + (j - n_c) * k_ss_chunk;
+    return reinterpret_cast<const uint4*>((j < n_c ? pc : pk) + 8 * st_seg);
   };
-  auto stage_tile = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int off = buf * kTileN * kPitch + (st_row + 16 * i) * kPitch + 8 * st_seg;
-      *reinterpret_cast<uint4*>(&k_s[off]) = k_st[i];
-      if (HAS_PV) *reinterpret_cast<uint4*>(&v_s[off]) = v_st[i];
-    }
+  auto v_row_ptr = [&](int j) {
+    const uint16_t* pc = v_cache_u + j * v_ss_cache;
+    const uint16_t* pk = v_chunk_u + (j - n_c) * v_ss_chunk;
+    return reinterpret_cast<const uint4*>((j < n_c ? pc : pk) + 8 * st_seg);
   };
+  uint4 k_st0, k_st1, v_st0 = {0u, 0u, 0u, 0u}, v_st1 = {0u, 0u, 0u, 0u};  // named, so they stay in registers
+#define CITRUS_FETCH_TILE(j0_)                                  \
+  do {                                                          \
+    const int ja_ = min((j0_) + st_row, n - 1);                 \
+    const int jb_ = min((j0_) + st_row + 32, n - 1);            \
+    k_st0 = *k_row_ptr(ja_);                                    \
+    k_st1 = *k_row_ptr(jb_);                                    \
+    if (HAS_PV) {                                               \
+      v_st0 = *v_row_ptr(ja_);                                  \
+      v_st1 = *v_row_ptr(jb_);                                  \
+    }                                                           \
+  } while (0)
+#define CITRUS_STAGE_TILE(buf_)                                                                          \
+  do {                                                                                                   \
+    uint16_t* kd_ = &k_s[(buf_) * kTileN * kPitchK + st_row * kPitchK + 8 * st_seg];                     \
+    *reinterpret_cast<uint4*>(kd_) = k_st0;                                                              \
+    *reinterpret_cast<uint4*>(kd_ + 32 * kPitchK) = k_st1;                                               \
+    if (HAS_PV) {                                                                                        \
+      uint16_t* vd_ = &v_s[(buf_) * kTileN * kPitchV + st_row * kPitchV + 8 * st_seg];                   \
+      *reinterpret_cast<uint4*>(vd_) = v_st0;                                                            \
+      *reinterpret_cast<uint4*>(vd_ + 32 * kPitchV) = v_st1;                                             \
+    }                                                                                                    \
+  } while (0)
 
-  // ---- running softmax state: one query per lane and column tile ----
+  // per-lane LDS offsets (elements)
+  const int k_lane_off = col * kPitchK + 8 * grp;  // A operand of S^T: key row `col`, contraction slots 8 grp..
+  // V^T operand through transpose reads.  The 16-lane group q16 = lane / 16 serves MFMA rows
+  // 16 (q16 % 2) .. +15 for contraction lane group q16 / 2; output row c' of tile r is head_dim
+  // 16 r + (c' % 16) + 64 (c' / 16), which keeps the two groups of a half-wave 128 B apart in LDS.
+  const int s16 = lane % 16, q16 = lane / 16;
+  const int v_lane_off = (4 * (q16 / 2) + s16 / 4) * kPitchV + 64 * (q16 % 2) + 4 * (s16 % 4);
+
+  // ---- running softmax state: one query per lane ----
   const float c2 = dm.scale * kLog2e;  // logits are kept in the log2 domain
-  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
-  f32x16 o_acc[4][2];  // [d residue r][qt]: row c' of tile r is head_dim index 4 c' + r
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x16 o_acc[4];
 #pragma unroll
   for (int r = 0; r < 4; ++r)
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o_acc[r][qt][i] = 0.f;
+    for (int i = 0; i < 16; ++i) o_acc[r][i] = 0.f;
 
-  fetch_tile(0);
-  stage_tile(0);
+  CITRUS_FETCH_TILE(0);
+  CITRUS_STAGE_TILE(0);
   __syncthreads();
 
   for (int jt = 0; jt < num_tiles; ++jt) {
     const int j0 = jt * kTileN;
-    const uint16_t* k_t = k_s + (jt & 1) * kTileN * kPitch;
-    const uint16_t* v_t = v_s + (HAS_PV ? (jt & 1) * kTileN * kPitch : 0);
-    if (jt + 1 < num_tiles) fetch_tile(j0 + kTileN);  // in flight while this tile is computed
+    const uint16_t* k_t = k_s + (jt & 1) * kTileN * kPitchK + k_lane_off;
+    const uint16_t* v_t = v_s + (HAS_PV ? (jt & 1) * kTileN * kPitchV + v_lane_off : 0);
+    if (jt + 1 < num_tiles) CITRUS_FETCH_TILE(j0 + kTileN);  // in flight while this tile is computed
 
     if (wave_active && j0 <= wave_limit_max) {
-      const bool need_mask = j0 + kTileN - 1 > wave_limit_min;
+      // S^T = K . Q^T for 64 keys x 32 queries
+      f32x16 s_acc[2];
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {  // two sub-steps of 32 keys
-        // S^T = K . Q^T for 32 keys x 64 queries
-        f32x16 s_acc[2];
+      for (int mt = 0; mt < 2; ++mt) {
+        Pack8 a[8];
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt)
+        for (int kk = 0; kk < 8; ++kk) a[kk].u = *reinterpret_cast<const uint4*>(k_t + 32 * mt * kPitchK + 16 * kk);
 #pragma unroll
-          for (int i = 0; i < 16; ++i) s_acc[qt][i] = 0.f;
+        for (int i = 0; i < 16; ++i) s_acc[mt][i] = 0.f;
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-          Pack8 a;
-          a.u = *reinterpret_cast<const uint4*>(&k_t[(32 * mt + col) * kPitch + 16 * kk + 8 * grp]);
-#pragma unroll
-          for (int qt = 0; qt < 2; ++qt)
-            s_acc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, q_op[qt][kk], s_acc[qt], 0, 0, 0);
-        }
+        for (int kk = 0; kk < 8; ++kk)
+          s_acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk].v, q_op[kk], s_acc[mt], 0, 0, 0);
+      }
 
-        uint32_t p_pk[2][8];  // [qt][pair]: bf16 probabilities, pairs of consecutive registers
+      if (j0 + kTileN - 1 > wave_limit_min) {  // wave-uniform: only tiles that touch the causal edge / the tail
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-          if (need_mask) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const int j = j0 + 32 * mt + 8 * (i / 4) + 4 * grp + (i % 4);
-              if (j > limit_lane[qt]) s_acc[qt][i] = -INFINITY;
-            }
-          }
-          float mx = s_acc[qt][0];
-#pragma unroll
-          for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s_acc[qt][i]);
-          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-          const float m_new = fmaxf(m_run[qt], mx * c2);
-          if (__any(m_new > m_run[qt])) {  // wave-uniform: skip the rescale when no row's maximum moved
-            const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
-            l_run[qt] *= alpha;
-            if (HAS_PV) {
-#pragma unroll
-              for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) o_acc[r][qt][i] *= alpha;
-            }
-            m_run[qt] = m_new;
-          }
-          float p[16];
-          float psum = 0.f;
+        for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
-            p[i] = __builtin_amdgcn_exp2f(fmaf(s_acc[qt][i], c2, -m_run[qt]));
-            psum += p[i];
+            const int j = j0 + 32 * mt + 8 * (i / 4) + 4 * grp + (i % 4);
+            if (j > limit_lane) s_acc[mt][i] = -INFINITY;
           }
-          l_run[qt] += psum;
-          if (HAS_PV) {
+      }
+      float mx = s_acc[0][0];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) p_pk[qt][i] = pack_bf16x2(p[2 * i], p[2 * i + 1]);
-          }
-        }
-
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s_acc[mt][i]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run, mx * c2);
+      if (__any(m_new > m_run)) {  // wave-uniform: skip the rescale when no row's maximum moved
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        l_run *= alpha;
         if (HAS_PV) {
-          // O^T += V^T . P^T ; contraction step `half` covers keys 32 mt + 16 half .. +15 in the slot
-          // order the S^T accumulators already have: slot i of lane group grp is key
-          // 8 (i / 4) + 4 grp + (i % 4) of the step.
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o_acc[r][i] *= alpha;
+        }
+        m_run = m_new;
+      }
+      uint32_t p_pk[2][8];  // [mt][pair]: bf16 probabilities, pairs of consecutive registers
+      float psum = 0.f;
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) {
+        float p[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          p[i] = __builtin_amdgcn_exp2f(fmaf(s_acc[mt][i], c2, -m_run));
+          psum += p[i];
+        }
+        if (HAS_PV) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) p_pk[mt][i] = pack_bf16x2(p[2 * i], p[2 * i + 1]);
+        }
+      }
+      l_run += psum;
+
+      if (HAS_PV) {
+        // O^T += V^T . P^T ; contraction step (mt, half) covers keys 32 mt + 16 half .. +15 in the slot
+        // order the S^T accumulators already have: slot i of lane group grp is key
+        // 8 (i / 4) + 4 grp + (i % 4) of the step, so slots 0..3 / 4..7 are two transpose reads.
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
 #pragma unroll
           for (int half = 0; half < 2; ++half) {
-            uint2 vw[8];
+            Pack8 a[4];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-              const int key = 32 * mt + 16 * half + 8 * (i / 4) + 4 * grp + (i % 4);
-              vw[i] = *reinterpret_cast<const uint2*>(&v_t[key * kPitch + 4 * col]);
-            }
-            Pack8 pb[2];
+            for (int r = 0; r < 4; ++r)
 #pragma unroll
-            for (int qt = 0; qt < 2; ++qt)
+              for (int rd = 0; rd < 2; ++rd)
+                a[r].h[rd] = lds_read_tr16(v_t + (32 * mt + 16 * half + 8 * rd) * kPitchV + 16 * r);
+            Pack8 pb;
 #pragma unroll
-              for (int x = 0; x < 4; ++x) pb[qt].w[x] = p_pk[qt][4 * half + x];
+            for (int x = 0; x < 4; ++x) pb.w[x] = p_pk[mt][4 * half + x];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              Pack8 a;
-#pragma unroll
-              for (int x = 0; x < 4; ++x) {
-                const uint32_t wa = (r < 2) ? vw[2 * x].x : vw[2 * x].y;
-                const uint32_t wb = (r < 2) ? vw[2 * x + 1].x : vw[2 * x + 1].y;
-                a.w[x] = __builtin_amdgcn_perm(wb, wa, (r & 1) ? 0x07060302u : 0x05040100u);
-              }
-#pragma unroll
-              for (int qt = 0; qt < 2; ++qt)
-                o_acc[r][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, pb[qt].v, o_acc[r][qt], 0, 0, 0);
-            }
+            for (int r = 0; r < 4; ++r)
+              o_acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[r].v, pb.v, o_acc[r], 0, 0, 0);
           }
         }
       }
@@ -275,49 +283,45 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(Dims dm, View q, in
 
     // The other buffer was last read one iteration ago and every wave has passed the barrier
     // that ended that iteration, so it can be overwritten now.
-    if (jt + 1 < num_tiles) stage_tile((jt + 1) & 1);
+    if (jt + 1 < num_tiles) CITRUS_STAGE_TILE((jt + 1) & 1);
     __syncthreads();
   }
 
   if (!wave_active) return;
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const int t = row0 + col;
+  if (t >= rows) return;
+  if (lse != nullptr && grp == 0)
+    lse[(static_cast<int64_t>(bl) * dm.Hq + h) * rows + t] = (m_run + log2f(l_tot)) * kLn2;
+  if (HAS_PV) {
+    const float inv = 1.f / l_tot;
+    uint16_t* op = const_cast<uint16_t*>(unit_ptr(out, b, l, h)) + static_cast<int64_t>(t) * out.ss;
 #pragma unroll
-  for (int qt = 0; qt < 2; ++qt) {
-    const float l_tot = l_run[qt] + __shfl_xor(l_run[qt], 32, 64);
-    const int t = row0 + 32 * qt + col;
-    if (t >= rows) continue;
-    if (lse != nullptr && grp == 0)
-      lse[(static_cast<int64_t>(bl) * dm.Hq + h) * rows + t] = (m_run[qt] + log2f(l_tot)) * kLn2;
-    if (HAS_PV) {
-      const float inv = 1.f / l_tot;
-      uint16_t* op = const_cast<uint16_t*>(unit_ptr(out, b, l, h)) + static_cast<int64_t>(t) * out.ss;
+    for (int r = 0; r < 4; ++r)
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
-        // registers 4 i4 .. 4 i4 + 3 are rows c' = 8 i4 + 4 grp + 0..3, i.e. head_dim 32 i4 + 16 grp + 0..15
-        uint32_t wds[8];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int i = 4 * i4 + e;
-          wds[2 * e] = pack_bf16x2(o_acc[0][qt][i] * inv, o_acc[1][qt][i] * inv);
-          wds[2 * e + 1] = pack_bf16x2(o_acc[2][qt][i] * inv, o_acc[3][qt][i] * inv);
-        }
-        uint4* dst = reinterpret_cast<uint4*>(op + 32 * i4 + 16 * grp);
-        dst[0] = make_uint4(wds[0], wds[1], wds[2], wds[3]);
-        dst[1] = make_uint4(wds[4], wds[5], wds[6], wds[7]);
+        // registers 4 i4 .. +3 are rows c' = 8 i4 + 4 grp + 0..3 -> head_dim 16 r + (c' % 16) + 64 (c' / 16)
+        const int c0 = 8 * i4 + 4 * grp;
+        const int d0 = 16 * r + (c0 % 16) + 64 * (c0 / 16);
+        uint2 wds;
+        wds.x = pack_bf16x2(o_acc[r][4 * i4] * inv, o_acc[r][4 * i4 + 1] * inv);
+        wds.y = pack_bf16x2(o_acc[r][4 * i4 + 2] * inv, o_acc[r][4 * i4 + 3] * inv);
+        *reinterpret_cast<uint2*>(op + d0) = wds;
       }
-    }
   }
 }
 
 // One wave per 32 candidate keys: the keys stay in registers as the A operand,
 // the query rows of the KV group stream by as B operands.  Per-lane partial
 // sums are reduced across the 32 query lanes once at the end (fixed order).
-__global__ __launch_bounds__(kThreads) void colsum_mfma_kernel(Dims dm, View q, int rows, Segments ks, int causal,
+constexpr int kColsumWaves = 4;
+__global__ __launch_bounds__(kColsumWaves * 64) void colsum_mfma_kernel(Dims dm, View q, int rows, Segments ks, int causal,
                                                               const float* lse, float* score) {
   const int tid = threadIdx.x, lane = tid % 64, w = tid / 64;
   const int col = lane % 32, grp = lane / 32;
   const int g = blockIdx.y, b = blockIdx.z / dm.L, l = blockIdx.z % dm.L;
   const int n = ks.n_c + ks.c;
-  const int j0 = (blockIdx.x * kWaves + w) * 32;
+  const int j0 = (blockIdx.x * kColsumWaves + w) * 32;
   if (j0 >= n) return;  // no block-level synchronisation below
 
   bf16x8 k_op[8];
@@ -396,8 +400,8 @@ hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments ks, Segme
 hipError_t launch_colsum_mfma(const Dims& dm, View q, int rows, Segments ks, int causal, const float* lse,
                               float* score, hipStream_t st) {
   const int n = ks.n_c + ks.c;
-  dim3 grid((n + 32 * kWaves - 1) / (32 * kWaves), dm.Hkv, dm.B * dm.L);
-  hipLaunchKernelGGL(colsum_mfma_kernel, grid, dim3(kThreads), 0, st, dm, q, rows, ks, causal, lse, score);
+  dim3 grid((n + 32 * kColsumWaves - 1) / (32 * kColsumWaves), dm.Hkv, dm.B * dm.L);
+  hipLaunchKernelGGL(colsum_mfma_kernel, grid, dim3(kColsumWaves * 64), 0, st, dm, q, rows, ks, causal, lse, score);
   return hipGetLastError();
 }
 
