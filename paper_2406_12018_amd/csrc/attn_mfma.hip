@@ -29,7 +29,7 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) short i16x4;
 
 constexpr int D = 128;
-constexpr int kWaves = 8;               // two waves per SIMD: one wave's softmax overlaps the other's MFMAs
+constexpr int kWaves = 4;               // one wave per SIMD and block; two or more blocks share a CU
 constexpr int kThreads = kWaves * 64;
 constexpr int kRowsPerWave = 32;        // one 32-query column tile per wave
 constexpr int kTileN = 64;              // keys per LDS tile
@@ -67,16 +67,16 @@ __device__ inline i16x4 lds_read_tr16(const uint16_t* p) {
 
 // How the waves of a block split (head, 32-row tile) tasks inside one KV group.
 struct TaskShape {
-  int heads_per_block;  // 8, 4, 2 or 1 query heads of the group
+  int heads_per_block;  // 4, 2 or 1 query heads of the group
   int tiles_per_block;  // kWaves / heads_per_block row tiles of 32
 };
 __host__ __device__ inline TaskShape task_shape(int G) {
-  const int hpb = (G % 8 == 0) ? 8 : (G % 4 == 0) ? 4 : ((G % 2 == 0) ? 2 : 1);
+  const int hpb = (G % 4 == 0) ? 4 : ((G % 2 == 0) ? 2 : 1);
   return TaskShape{hpb, kWaves / hpb};
 }
 
 template <bool HAS_PV>
-__global__ __launch_bounds__(kThreads) void attn_mfma_kernel(Dims dm, View q, int rows, Segments ks, Segments vs,
+__global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q, int rows, Segments ks, Segments vs,
                                                             int causal, View out, float* lse) {
   __shared__ __attribute__((aligned(16))) uint16_t k_s[2 * kTileN * kPitchK];  // double-buffered tiles
   __shared__ __attribute__((aligned(16))) uint16_t v_s[HAS_PV ? 2 * kTileN * kPitchV : 8];
@@ -133,40 +133,53 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(Dims dm, View q, in
   const uint16_t* k_chunk_u = unit_ptr(ks.chunk, b, l, g);
   const uint16_t* v_cache_u = HAS_PV ? unit_ptr(vs.cache, b, l, g) : nullptr;
   const uint16_t* v_chunk_u = HAS_PV ? unit_ptr(vs.chunk, b, l, g) : nullptr;
-  const int64_t k_ss_cache = ks.cache.ss, k_ss_chunk = ks.chunk.ss;
-  const int64_t v_ss_cache = vs.cache.ss, v_ss_chunk = vs.chunk.ss;
-  const int st_row = tid / 16, st_seg = tid % 16;  // piece i covers tile row st_row + 32 i
+  // element offsets inside one (document, layer, head) unit fit 32 bits (checked by the launcher)
+  const int k_ss_cache = static_cast<int>(ks.cache.ss), k_ss_chunk = static_cast<int>(ks.chunk.ss);
+  const int v_ss_cache = static_cast<int>(vs.cache.ss), v_ss_chunk = static_cast<int>(vs.chunk.ss);
+  const int st_row = tid / 16, st_seg = tid % 16;  // piece i covers tile row st_row + 16 i
   auto k_row_ptr = [&](int j) {
-    const uint16_t* pc = k_cache_u + j * k_ss_cache;
-    const uint16_t* pk = k_chunk_u + (j - n_c) * k_ss_chunk;
-    return reinterpret_cast<const uint4*>((j < n_c ? pc : pk) + 8 * st_seg);
+    const bool in_cache = j < n_c;
+    const uint32_t off = static_cast<uint32_t>(in_cache ? j * k_ss_cache : (j - n_c) * k_ss_chunk) + 8u * st_seg;
+    return reinterpret_cast<const uint4*>((in_cache ? k_cache_u : k_chunk_u) + off);
   };
   auto v_row_ptr = [&](int j) {
-    const uint16_t* pc = v_cache_u + j * v_ss_cache;
-    const uint16_t* pk = v_chunk_u + (j - n_c) * v_ss_chunk;
-    return reinterpret_cast<const uint4*>((j < n_c ? pc : pk) + 8 * st_seg);
+    const bool in_cache = j < n_c;
+    const uint32_t off = static_cast<uint32_t>(in_cache ? j * v_ss_cache : (j - n_c) * v_ss_chunk) + 8u * st_seg;
+    return reinterpret_cast<const uint4*>((in_cache ? v_cache_u : v_chunk_u) + off);
   };
-  uint4 k_st0, k_st1, v_st0 = {0u, 0u, 0u, 0u}, v_st1 = {0u, 0u, 0u, 0u};  // named, so they stay in registers
+  // named (not an array), so the staged pieces stay in registers
+  uint4 k_st0, k_st1, k_st2, k_st3;
+  uint4 v_st0 = {0u, 0u, 0u, 0u}, v_st1 = v_st0, v_st2 = v_st0, v_st3 = v_st0;
 #define CITRUS_FETCH_TILE(j0_)                                  \
   do {                                                          \
     const int ja_ = min((j0_) + st_row, n - 1);                 \
-    const int jb_ = min((j0_) + st_row + 32, n - 1);            \
+    const int jb_ = min((j0_) + st_row + 16, n - 1);            \
+    const int jc_ = min((j0_) + st_row + 32, n - 1);            \
+    const int jd_ = min((j0_) + st_row + 48, n - 1);            \
     k_st0 = *k_row_ptr(ja_);                                    \
     k_st1 = *k_row_ptr(jb_);                                    \
+    k_st2 = *k_row_ptr(jc_);                                    \
+    k_st3 = *k_row_ptr(jd_);                                    \
     if (HAS_PV) {                                               \
       v_st0 = *v_row_ptr(ja_);                                  \
       v_st1 = *v_row_ptr(jb_);                                  \
+      v_st2 = *v_row_ptr(jc_);                                  \
+      v_st3 = *v_row_ptr(jd_);                                  \
     }                                                           \
   } while (0)
 #define CITRUS_STAGE_TILE(buf_)                                                                          \
   do {                                                                                                   \
     uint16_t* kd_ = &k_s[(buf_) * kTileN * kPitchK + st_row * kPitchK + 8 * st_seg];                     \
     *reinterpret_cast<uint4*>(kd_) = k_st0;                                                              \
-    *reinterpret_cast<uint4*>(kd_ + 32 * kPitchK) = k_st1;                                               \
+    *reinterpret_cast<uint4*>(kd_ + 16 * kPitchK) = k_st1;                                               \
+    *reinterpret_cast<uint4*>(kd_ + 32 * kPitchK) = k_st2;                                               \
+    *reinterpret_cast<uint4*>(kd_ + 48 * kPitchK) = k_st3;                                               \
     if (HAS_PV) {                                                                                        \
       uint16_t* vd_ = &v_s[(buf_) * kTileN * kPitchV + st_row * kPitchV + 8 * st_seg];                   \
       *reinterpret_cast<uint4*>(vd_) = v_st0;                                                            \
-      *reinterpret_cast<uint4*>(vd_ + 32 * kPitchV) = v_st1;                                             \
+      *reinterpret_cast<uint4*>(vd_ + 16 * kPitchV) = v_st1;                                             \
+      *reinterpret_cast<uint4*>(vd_ + 32 * kPitchV) = v_st2;                                             \
+      *reinterpret_cast<uint4*>(vd_ + 48 * kPitchV) = v_st3;                                             \
     }                                                                                                    \
   } while (0)
 
@@ -190,6 +203,9 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(Dims dm, View q, in
   CITRUS_FETCH_TILE(0);
   CITRUS_STAGE_TILE(0);
   __syncthreads();
+  // All loads issued so far (the Q operand among them) have landed: say so explicitly, otherwise
+  // the first MFMA of every iteration waits for the tile prefetch issued just before it.
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 
   for (int jt = 0; jt < num_tiles; ++jt) {
     const int j0 = jt * kTileN;
@@ -201,15 +217,22 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(Dims dm, View q, in
       // S^T = K . Q^T for 64 keys x 32 queries
       f32x16 s_acc[2];
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-        Pack8 a[8];
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) a[kk].u = *reinterpret_cast<const uint4*>(k_t + 32 * mt * kPitchK + 16 * kk);
+      for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int i = 0; i < 16; ++i) s_acc[mt][i] = 0.f;
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk)
-          s_acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk].v, q_op[kk], s_acc[mt], 0, 0, 0);
+      for (int kh = 0; kh < 2; ++kh) {  // the two 32-key halves are independent MFMA chains: interleave them
+        Pack8 a[2][4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+            a[mt][kk].u = *reinterpret_cast<const uint4*>(k_t + 32 * mt * kPitchK + 16 * (4 * kh + kk));
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+            s_acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][kk].v, q_op[4 * kh + kk], s_acc[mt], 0, 0, 0);
       }
 
       if (j0 + kTileN - 1 > wave_limit_min) {  // wave-uniform: only tiles that touch the causal edge / the tail
@@ -385,8 +408,15 @@ __global__ __launch_bounds__(kColsumWaves * 64) void colsum_mfma_kernel(Dims dm,
 
 bool mfma_path_supported(int dtype, const Dims& dm) { return dtype == CITRUS_BF16 && dm.D == D; }
 
+static bool fits_i32(const View& v, int rows) {
+  return v.ss > 0 && v.ss * static_cast<int64_t>(rows > 0 ? rows : 1) < (int64_t{1} << 31);
+}
+
 hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments ks, Segments vs, int causal, View out,
                             float* lse, hipStream_t st) {
+  if (!fits_i32(ks.cache, ks.n_c) || !fits_i32(ks.chunk, ks.c) || !fits_i32(vs.cache, vs.n_c) ||
+      !fits_i32(vs.chunk, vs.c))
+    return hipErrorInvalidValue;
   const TaskShape ts = task_shape(dm.G);
   const int rows_per_block = ts.tiles_per_block * kRowsPerWave;
   dim3 grid(((rows + rows_per_block - 1) / rows_per_block) * (dm.G / ts.heads_per_block) * dm.Hkv * dm.B * dm.L);
