@@ -34,6 +34,7 @@ constexpr int kThreads = kWaves * 64;
 constexpr int kRowsPerWave = 32;        // one 32-query column tile per wave
 constexpr int kTileN = 64;              // keys per LDS tile
 constexpr int kXcds = 8;
+constexpr int kMaxKeySplits = 8;
 constexpr int kPitchK = D + 8;          // LDS row pitch of K in bf16 (272 B): conflict-free 16-byte column reads
 constexpr int kPitchV = D + 16;         // LDS row pitch of V in bf16 (288 B): conflict-free transpose reads
 constexpr float kLog2e = 1.4426950408889634f;
@@ -77,7 +78,8 @@ __host__ __device__ inline TaskShape task_shape(int G) {
 
 template <bool HAS_PV>
 __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q, int rows, Segments ks, Segments vs,
-                                                            int causal, View out, float* lse) {
+                                                               int causal, View out, float* lse, int key_splits,
+                                                               float2* part) {
   __shared__ __attribute__((aligned(16))) uint16_t k_s[2 * kTileN * kPitchK];  // double-buffered tiles
   __shared__ __attribute__((aligned(16))) uint16_t v_s[HAS_PV ? 2 * kTileN * kPitchV : 8];
 
@@ -93,6 +95,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
   int logical = blockIdx.x;
   const int total = gridDim.x;
   if (total % kXcds == 0) logical = (blockIdx.x % kXcds) * (total / kXcds) + blockIdx.x / kXcds;
+  // With key_splits > 1 (log-sum-exp only) each workgroup covers one contiguous range of key
+  // tiles and writes a partial (running maximum, sum) pair per row; the consumer merges them.
+  const int sp = logical % key_splits;
+  logical /= key_splits;
   const int rb = row_blocks - 1 - logical % row_blocks;
   const int hg = (logical / row_blocks) % head_groups;
   const int g = (logical / (row_blocks * head_groups)) % dm.Hkv;
@@ -106,7 +112,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
   // last candidate any row of this block / this wave can see
   const int blk_row_last = min(rows, (rb + 1) * rows_per_block) - 1;
   const int blk_limit = causal ? n_c + blk_row_last : n - 1;
-  const int num_tiles = blk_limit / kTileN + 1;
+  const int all_tiles = blk_limit / kTileN + 1;
+  const int tiles_per_split = (all_tiles + key_splits - 1) / key_splits;
+  const int t_begin = sp * tiles_per_split;
+  const int t_end = min(all_tiles, t_begin + tiles_per_split);
   const bool wave_active = row0 < rows;
   const int wave_row_last = min(rows, row0 + kRowsPerWave) - 1;
   const int wave_limit_max = causal ? n_c + wave_row_last : n - 1;  // beyond it the wave sees nothing
@@ -200,18 +209,20 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
 #pragma unroll
     for (int i = 0; i < 16; ++i) o_acc[r][i] = 0.f;
 
-  CITRUS_FETCH_TILE(0);
+  if (t_begin < t_end) {  // block-uniform
+  CITRUS_FETCH_TILE(t_begin * kTileN);
   CITRUS_STAGE_TILE(0);
   __syncthreads();
   // All loads issued so far (the Q operand among them) have landed: say so explicitly, otherwise
   // the first MFMA of every iteration waits for the tile prefetch issued just before it.
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 
-  for (int jt = 0; jt < num_tiles; ++jt) {
+  for (int jt = t_begin; jt < t_end; ++jt) {
     const int j0 = jt * kTileN;
-    const uint16_t* k_t = k_s + (jt & 1) * kTileN * kPitchK + k_lane_off;
-    const uint16_t* v_t = v_s + (HAS_PV ? (jt & 1) * kTileN * kPitchV + v_lane_off : 0);
-    if (jt + 1 < num_tiles) CITRUS_FETCH_TILE(j0 + kTileN);  // in flight while this tile is computed
+    const int buf = (jt - t_begin) & 1;
+    const uint16_t* k_t = k_s + buf * kTileN * kPitchK + k_lane_off;
+    const uint16_t* v_t = v_s + (HAS_PV ? buf * kTileN * kPitchV + v_lane_off : 0);
+    if (jt + 1 < t_end) CITRUS_FETCH_TILE(j0 + kTileN);  // in flight while this tile is computed
 
     if (wave_active && j0 <= wave_limit_max) {
       // S^T = K . Q^T for 64 keys x 32 queries
@@ -306,16 +317,19 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
 
     // The other buffer was last read one iteration ago and every wave has passed the barrier
     // that ended that iteration, so it can be overwritten now.
-    if (jt + 1 < num_tiles) CITRUS_STAGE_TILE((jt + 1) & 1);
+    if (jt + 1 < t_end) CITRUS_STAGE_TILE(buf ^ 1);
     __syncthreads();
+  }
   }
 
   if (!wave_active) return;
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const int t = row0 + col;
   if (t >= rows) return;
-  if (lse != nullptr && grp == 0)
-    lse[(static_cast<int64_t>(bl) * dm.Hq + h) * rows + t] = (m_run + log2f(l_tot)) * kLn2;
+  const int64_t row_id = (static_cast<int64_t>(bl) * dm.Hq + h) * rows + t;
+  if (part != nullptr && grp == 0)  // log2 domain; an empty or fully masked range leaves (-inf, 0)
+    part[static_cast<int64_t>(sp) * dm.B * dm.L * dm.Hq * rows + row_id] = make_float2(m_run, l_tot);
+  if (lse != nullptr && grp == 0) lse[row_id] = (m_run + log2f(l_tot)) * kLn2;
   if (HAS_PV) {
     const float inv = 1.f / l_tot;
     uint16_t* op = const_cast<uint16_t*>(unit_ptr(out, b, l, h)) + static_cast<int64_t>(t) * out.ss;
@@ -334,24 +348,30 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
   }
 }
 
-// One wave per 32 candidate keys: the keys stay in registers as the A operand,
-// the query rows of the KV group stream by as B operands.  Per-lane partial
-// sums are reduced across the 32 query lanes once at the end (fixed order).
+// Summed form of Eq. (1): score[g, j] = sum over the query rows of the KV group of
+// exp(s - lse).  One wave per 32 candidate keys, which stay in registers as the A operand; the
+// group's query rows (all its heads, flattened) are staged through LDS in chunks of 128 rows and
+// stream by as B operands.  Per-lane partial sums are reduced across the 32 query lanes once at
+// the end, in a fixed order: no atomics, bit-reproducible.
 constexpr int kColsumWaves = 4;
-__global__ __launch_bounds__(kColsumWaves * 64) void colsum_mfma_kernel(Dims dm, View q, int rows, Segments ks, int causal,
-                                                              const float* lse, float* score) {
+constexpr int kColsumQRows = 128;  // query rows per LDS chunk
+__global__ __launch_bounds__(kColsumWaves * 64) void colsum_mfma_kernel(Dims dm, View q, int rows, Segments ks,
+                                                                        int causal, const float* lse, int key_splits,
+                                                                        const float2* part, float* score) {
+  __shared__ __attribute__((aligned(16))) uint16_t q_s[kColsumQRows * kPitchK];
+  __shared__ float lse_s[kColsumQRows];  // log2-domain normaliser per staged row (+inf for padding rows)
   const int tid = threadIdx.x, lane = tid % 64, w = tid / 64;
   const int col = lane % 32, grp = lane / 32;
-  const int g = blockIdx.y, b = blockIdx.z / dm.L, l = blockIdx.z % dm.L;
-  const int n = ks.n_c + ks.c;
+  const int g = blockIdx.y, bl = blockIdx.z, b = bl / dm.L, l = bl % dm.L;
+  const int n_c = ks.n_c, n = n_c + ks.c;
   const int j0 = (blockIdx.x * kColsumWaves + w) * 32;
-  if (j0 >= n) return;  // no block-level synchronisation below
+  const bool wave_has_keys = j0 < n;
 
   bf16x8 k_op[8];
   {
     const int j = min(j0 + col, n - 1);
-    const uint16_t* kp = (j < ks.n_c ? unit_ptr(ks.cache, b, l, g) + static_cast<int64_t>(j) * ks.cache.ss
-                                     : unit_ptr(ks.chunk, b, l, g) + static_cast<int64_t>(j - ks.n_c) * ks.chunk.ss) +
+    const uint16_t* kp = (j < n_c ? unit_ptr(ks.cache, b, l, g) + static_cast<int64_t>(j) * ks.cache.ss
+                                  : unit_ptr(ks.chunk, b, l, g) + static_cast<int64_t>(j - n_c) * ks.chunk.ss) +
                          8 * grp;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
@@ -361,46 +381,76 @@ __global__ __launch_bounds__(kColsumWaves * 64) void colsum_mfma_kernel(Dims dm,
     }
   }
   const float c2 = dm.scale * kLog2e;
-  float part[16];
+  float acc[16];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) part[i] = 0.f;
+  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 
-  // rows before t_first see none of this wave's keys (causal, chunk keys only)
-  const int t_first = (causal && j0 > ks.n_c) ? ((j0 - ks.n_c) / 32) * 32 : 0;
-  for (int hh = 0; hh < dm.G; ++hh) {
-    const int h = g * dm.G + hh;
-    const uint16_t* q_u = unit_ptr(q, b, l, h);
-    const float* lse_h = lse + (static_cast<int64_t>(blockIdx.z) * dm.Hq + h) * rows;
-    for (int t0 = t_first; t0 < rows; t0 += 32) {
-      const int t = t0 + col;
-      const int tc = min(t, rows - 1);
-      const uint16_t* qp = q_u + static_cast<int64_t>(tc) * q.ss + 8 * grp;
-      const float lse2 = lse_h[tc] * kLog2e;
-      f32x16 s;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s[i] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < 8; ++kk) {
-        Pack8 p;
-        p.u = *reinterpret_cast<const uint4*>(qp + 16 * kk);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_op[kk], p.v, s, 0, 0, 0);
+  const int total_rows = dm.G * rows;  // flattened (head in group, row)
+  const int64_t part_stride = static_cast<int64_t>(dm.B) * dm.L * dm.Hq * rows;
+  for (int f0 = 0; f0 < total_rows; f0 += kColsumQRows) {
+    const int f_cnt = min(kColsumQRows, total_rows - f0);
+    __syncthreads();  // previous chunk fully consumed
+    // stage the chunk: 16 threads per row, 16 bytes each
+    for (int r = tid / 16; r < kColsumQRows; r += kColsumWaves * 4) {
+      const int f = min(f0 + r, total_rows - 1);
+      const int hh = f / rows, t = f % rows;
+      const uint16_t* qp = unit_ptr(q, b, l, g * dm.G + hh) + static_cast<int64_t>(t) * q.ss + 8 * (tid % 16);
+      *reinterpret_cast<uint4*>(&q_s[r * kPitchK + 8 * (tid % 16)]) = *reinterpret_cast<const uint4*>(qp);
+    }
+    if (tid < kColsumQRows) {
+      float v = INFINITY;  // padding rows contribute exp2(-inf) = 0
+      if (tid < f_cnt) {
+        const int f = f0 + tid;
+        const int64_t row_id = (static_cast<int64_t>(bl) * dm.Hq + g * dm.G + f / rows) * rows + f % rows;
+        if (part != nullptr) {  // merge the per-range (maximum, sum) pairs
+          float m = -INFINITY;
+          for (int s = 0; s < key_splits; ++s) m = fmaxf(m, part[s * part_stride + row_id].x);
+          float lsum = 0.f;
+          for (int s = 0; s < key_splits; ++s) {
+            const float2 ps = part[s * part_stride + row_id];
+            lsum += ps.y * exp2f(ps.x - m);
+          }
+          v = m + log2f(lsum);
+        } else {
+          v = lse[row_id] * kLog2e;
+        }
       }
-      const int limit = (t < rows) ? (causal ? ks.n_c + t : n - 1) : -1;
+      lse_s[tid] = v;
+    }
+    __syncthreads();
+    if (wave_has_keys) {
+      for (int qt = 0; qt * 32 < f_cnt; ++qt) {
+        f32x16 s_t;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int j = j0 + 8 * (i / 4) + 4 * grp + (i % 4);
-        const float p = exp2f(fmaf(s[i], c2, -lse2));
-        part[i] += (j <= limit) ? p : 0.f;
+        for (int i = 0; i < 16; ++i) s_t[i] = 0.f;
+        const uint16_t* qrow = &q_s[(32 * qt + col) * kPitchK + 8 * grp];
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+          Pack8 p;
+          p.u = *reinterpret_cast<const uint4*>(qrow + 16 * kk);
+          s_t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_op[kk], p.v, s_t, 0, 0, 0);
+        }
+        const float lse2 = lse_s[32 * qt + col];
+        // causal: row t of the chunk sees candidates j <= n_c + t
+        const int t = (f0 + 32 * qt + col) % rows;
+        const int limit = causal ? n_c + t : n;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int j = j0 + 8 * (i / 4) + 4 * grp + (i % 4);
+          const float p = __builtin_amdgcn_exp2f(fmaf(s_t[i], c2, -lse2));
+          acc[i] += (j <= limit) ? p : 0.f;
+        }
       }
     }
   }
+  if (!wave_has_keys) return;
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
-    float v = part[i];
+    float v = acc[i];
 #pragma unroll
     for (int o = 16; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
     const int j = j0 + 8 * (i / 4) + 4 * grp + (i % 4);
-    if (col == 0 && j < n) score[(static_cast<int64_t>(blockIdx.z) * dm.Hkv + g) * n + j] = v;
+    if (col == 0 && j < n) score[(static_cast<int64_t>(bl) * dm.Hkv + g) * n + j] = v;
   }
 }
 
@@ -413,26 +463,50 @@ static bool fits_i32(const View& v, int rows) {
 }
 
 hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments ks, Segments vs, int causal, View out,
-                            float* lse, hipStream_t st) {
+                            float* lse, int key_splits, float2* part, hipStream_t st) {
   if (!fits_i32(ks.cache, ks.n_c) || !fits_i32(ks.chunk, ks.c) || !fits_i32(vs.cache, vs.n_c) ||
       !fits_i32(vs.chunk, vs.c))
     return hipErrorInvalidValue;
+  if (key_splits < 1 || (key_splits > 1 && (out.ptr != nullptr || part == nullptr))) return hipErrorInvalidValue;
   const TaskShape ts = task_shape(dm.G);
   const int rows_per_block = ts.tiles_per_block * kRowsPerWave;
-  dim3 grid(((rows + rows_per_block - 1) / rows_per_block) * (dm.G / ts.heads_per_block) * dm.Hkv * dm.B * dm.L);
+  dim3 grid(((rows + rows_per_block - 1) / rows_per_block) * (dm.G / ts.heads_per_block) * dm.Hkv * dm.B * dm.L *
+            key_splits);
   if (out.ptr != nullptr)
-    hipLaunchKernelGGL((attn_mfma_kernel<true>), grid, dim3(kThreads), 0, st, dm, q, rows, ks, vs, causal, out, lse);
+    hipLaunchKernelGGL((attn_mfma_kernel<true>), grid, dim3(kThreads), 0, st, dm, q, rows, ks, vs, causal, out, lse,
+                       key_splits, part);
   else
-    hipLaunchKernelGGL((attn_mfma_kernel<false>), grid, dim3(kThreads), 0, st, dm, q, rows, ks, vs, causal, out, lse);
+    hipLaunchKernelGGL((attn_mfma_kernel<false>), grid, dim3(kThreads), 0, st, dm, q, rows, ks, vs, causal, out, lse,
+                       key_splits, part);
   return hipGetLastError();
 }
 
 hipError_t launch_colsum_mfma(const Dims& dm, View q, int rows, Segments ks, int causal, const float* lse,
-                              float* score, hipStream_t st) {
+                              int key_splits, const float2* part, float* score, hipStream_t st) {
   const int n = ks.n_c + ks.c;
   dim3 grid((n + 32 * kColsumWaves - 1) / (32 * kColsumWaves), dm.Hkv, dm.B * dm.L);
-  hipLaunchKernelGGL(colsum_mfma_kernel, grid, dim3(kColsumWaves * 64), 0, st, dm, q, rows, ks, causal, lse, score);
+  hipLaunchKernelGGL(colsum_mfma_kernel, grid, dim3(kColsumWaves * 64), 0, st, dm, q, rows, ks, causal, lse,
+                     key_splits, part, score);
   return hipGetLastError();
+}
+
+// Instruction score in two launches: partial log-sum-exp over ranges of key tiles (enough
+// workgroups to fill the chip although there are few instruction rows), then the column sums.
+size_t instr_score_mfma_workspace_floats(const Dims& dm, int rows) {
+  return static_cast<size_t>(2) * kMaxKeySplits * dm.B * dm.L * dm.Hq * rows;
+}
+
+hipError_t launch_instr_score_mfma(const Dims& dm, View q, int rows, Segments ks, float* workspace, float* score,
+                                   hipStream_t st) {
+  const int n = ks.n_c + ks.c;
+  const int tiles = (n + kTileN - 1) / kTileN;
+  int splits = (tiles + 3) / 4;  // about four key tiles per workgroup
+  splits = splits < 1 ? 1 : (splits > kMaxKeySplits ? kMaxKeySplits : splits);
+  float2* part = reinterpret_cast<float2*>(workspace);
+  View none{nullptr, 0, 0, 0, 0};
+  hipError_t e = launch_attn_mfma(dm, q, rows, ks, ks, /*causal=*/0, none, nullptr, splits, part, st);
+  if (e != hipSuccess) return e;
+  return launch_colsum_mfma(dm, q, rows, ks, /*causal=*/0, nullptr, splits, part, score, st);
 }
 
 }  // namespace citrus

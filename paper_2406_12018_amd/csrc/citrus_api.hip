@@ -79,7 +79,7 @@ Workspace workspace_layout(const citrus_config* c) {
   const bool dual = c->cache_mode == CITRUS_CACHE_DUAL;
   size_t off = 0;
   w.lse_chunk = off; off += align_up(units_q * c->chunk_len * sizeof(float));
-  w.lse_instr = off; off += align_up(units_q * c->instr_len * sizeof(float));
+  w.lse_instr = off; off += align_up(units_q * c->instr_len * sizeof(float) * 16);  // partial (max, sum) pairs x 8 ranges
   w.score = off;     off += align_up(units_kv * n_max * sizeof(float));
   w.score_lm = off;  off += dual ? align_up(units_kv * n_max * sizeof(float)) : 0;
   w.idx = off;       off += align_up(units_kv * c->budget * sizeof(int32_t));
@@ -98,13 +98,15 @@ citrus_status check_workspace(const citrus_config* c, const void* ws, size_t byt
 
 hipError_t run_attn(const citrus_config* c, const Dims& dm, View q, int rows, Segments ks, Segments vs, int causal,
                     View out, float* lse, hipStream_t st) {
-  if (mfma_path_supported(c->dtype, dm)) return launch_attn_mfma(dm, q, rows, ks, vs, causal, out, lse, st);
+  if (mfma_path_supported(c->dtype, dm))
+    return launch_attn_mfma(dm, q, rows, ks, vs, causal, out, lse, 1, nullptr, st);
   return launch_attn_generic(c->dtype, dm, q, rows, ks, vs, causal, out, lse, st);
 }
 
 hipError_t run_colsum(const citrus_config* c, const Dims& dm, View q, int rows, Segments ks, int causal,
                       const float* lse, float* score, hipStream_t st) {
-  if (mfma_path_supported(c->dtype, dm)) return launch_colsum_mfma(dm, q, rows, ks, causal, lse, score, st);
+  if (mfma_path_supported(c->dtype, dm))
+    return launch_colsum_mfma(dm, q, rows, ks, causal, lse, 1, nullptr, score, st);
   return launch_colsum_generic(c->dtype, dm, q, rows, ks, causal, lse, score, st);
 }
 
@@ -120,6 +122,8 @@ citrus_status do_chunk_attn(const citrus_config* c, const Dims& dm, const citrus
 
 citrus_status do_instr_score(const citrus_config* c, const Dims& dm, const citrus_tensor& q_instr, Segments ks,
                              float* lse_ws, float* score, hipStream_t st) {
+  if (mfma_path_supported(c->dtype, dm))
+    return hip_status(launch_instr_score_mfma(dm, make_view(q_instr), c->instr_len, ks, lse_ws, score, st));
   View none{nullptr, 0, 0, 0, 0};
   // pass 1: row normalisers (log-sum-exp over all n candidates, no mask)
   CITRUS_TRY(hip_status(run_attn(c, dm, make_view(q_instr), c->instr_len, ks, ks, /*causal=*/0, none, lse_ws, st)));

@@ -44,10 +44,16 @@ hipError_t launch_colsum_generic(int dtype, const Dims& dm, View q, int rows, Se
 
 // ---- bf16 MFMA kernels (head_dim 128), attn_mfma.hip ----
 bool mfma_path_supported(int dtype, const Dims& dm);
+// key_splits > 1: log-sum-exp only, one partial (log2-domain maximum, sum) pair per key range
+// and row in part[split][B*L*Hq*rows]; key_splits == 1: out and/or lse (natural log) as given.
 hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments kseg, Segments vseg, int causal, View out,
-                            float* lse, hipStream_t st);
+                            float* lse, int key_splits, float2* part, hipStream_t st);
+// normaliser per row from lse (natural log) or, if part != NULL, merged from key_splits partial pairs
 hipError_t launch_colsum_mfma(const Dims& dm, View q, int rows, Segments kseg, int causal, const float* lse,
-                              float* score, hipStream_t st);
+                              int key_splits, const float2* part, float* score, hipStream_t st);
+size_t instr_score_mfma_workspace_floats(const Dims& dm, int rows);
+hipError_t launch_instr_score_mfma(const Dims& dm, View q, int rows, Segments kseg, float* workspace, float* score,
+                                   hipStream_t st);
 
 // ---- selection and compaction, select_compact.hip ----
 // units = B*L*Hsel; score rows are [units*(per_layer?Hkv:1)] x n.
