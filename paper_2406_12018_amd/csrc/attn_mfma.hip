@@ -353,9 +353,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
 // group's query rows (all its heads, flattened) are staged through LDS in chunks of 128 rows and
 // stream by as B operands.  Per-lane partial sums are reduced across the 32 query lanes once at
 // the end, in a fixed order: no atomics, bit-reproducible.
-constexpr int kColsumWaves = 4;
-constexpr int kColsumQRows = 128;  // query rows per LDS chunk
-__global__ __launch_bounds__(kColsumWaves * 64) void colsum_mfma_kernel(Dims dm, View q, int rows, Segments ks,
+constexpr int kColsumWaves = 8;
+constexpr int kColsumKeyTiles = 1;  // 32-key tiles per wave: a workgroup covers 256 keys per staged Q chunk
+constexpr int kColsumQRows = 128;   // query rows per LDS chunk
+__global__ __launch_bounds__(kColsumWaves * 64, 2) void colsum_mfma_kernel(Dims dm, View q, int rows, Segments ks,
                                                                         int causal, const float* lse, int key_splits,
                                                                         const float2* part, float* score) {
   __shared__ __attribute__((aligned(16))) uint16_t q_s[kColsumQRows * kPitchK];
@@ -364,12 +365,14 @@ __global__ __launch_bounds__(kColsumWaves * 64) void colsum_mfma_kernel(Dims dm,
   const int col = lane % 32, grp = lane / 32;
   const int g = blockIdx.y, bl = blockIdx.z, b = bl / dm.L, l = bl % dm.L;
   const int n_c = ks.n_c, n = n_c + ks.c;
-  const int j0 = (blockIdx.x * kColsumWaves + w) * 32;
+  const int j0 = (blockIdx.x * kColsumWaves + w) * (32 * kColsumKeyTiles);
   const bool wave_has_keys = j0 < n;
+  const int j_last = j0 + 32 * kColsumKeyTiles - 1;
 
-  bf16x8 k_op[8];
-  {
-    const int j = min(j0 + col, n - 1);
+  bf16x8 k_op[kColsumKeyTiles][8];
+#pragma unroll
+  for (int kt = 0; kt < kColsumKeyTiles; ++kt) {
+    const int j = min(j0 + 32 * kt + col, n - 1);
     const uint16_t* kp = (j < n_c ? unit_ptr(ks.cache, b, l, g) + static_cast<int64_t>(j) * ks.cache.ss
                                   : unit_ptr(ks.chunk, b, l, g) + static_cast<int64_t>(j - n_c) * ks.chunk.ss) +
                          8 * grp;
@@ -377,13 +380,15 @@ __global__ __launch_bounds__(kColsumWaves * 64) void colsum_mfma_kernel(Dims dm,
     for (int kk = 0; kk < 8; ++kk) {
       Pack8 p;
       p.u = *reinterpret_cast<const uint4*>(kp + 16 * kk);
-      k_op[kk] = p.v;
+      k_op[kt][kk] = p.v;
     }
   }
   const float c2 = dm.scale * kLog2e;
-  float acc[16];
+  float acc[kColsumKeyTiles][16];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+  for (int kt = 0; kt < kColsumKeyTiles; ++kt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[kt][i] = 0.f;
 
   const int total_rows = dm.G * rows;  // flattened (head in group, row)
   const int64_t part_stride = static_cast<int64_t>(dm.B) * dm.L * dm.Hq * rows;
@@ -420,38 +425,54 @@ __global__ __launch_bounds__(kColsumWaves * 64) void colsum_mfma_kernel(Dims dm,
     __syncthreads();
     if (wave_has_keys) {
       for (int qt = 0; qt * 32 < f_cnt; ++qt) {
-        f32x16 s_t;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s_t[i] = 0.f;
+        Pack8 qb[8];
         const uint16_t* qrow = &q_s[(32 * qt + col) * kPitchK + 8 * grp];
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-          Pack8 p;
-          p.u = *reinterpret_cast<const uint4*>(qrow + 16 * kk);
-          s_t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_op[kk], p.v, s_t, 0, 0, 0);
-        }
+        for (int kk = 0; kk < 8; ++kk) qb[kk].u = *reinterpret_cast<const uint4*>(qrow + 16 * kk);
         const float lse2 = lse_s[32 * qt + col];
-        // causal: row t of the chunk sees candidates j <= n_c + t
-        const int t = (f0 + 32 * qt + col) % rows;
-        const int limit = causal ? n_c + t : n;
+        // A mask is needed only where a key of this wave can be invisible to a row of this tile:
+        // past the last candidate, or (causal) a chunk key later than the tile's first row.  The
+        // flattened rows of one 32-row tile span at most two heads; t_lo is the smallest chunk row.
+        const int f_first = f0 + 32 * qt;
+        int t_lo = f_first % rows;                                  // wave-uniform
+        if (t_lo + 31 >= rows) t_lo = 0;                            // tile wraps into the next head
+        const bool need_mask = (j_last >= n) || (causal && j_last > n_c + t_lo);
+        int limit = n - 1;
+        if (need_mask && causal) limit = n_c + (f_first + col) % rows;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int j = j0 + 8 * (i / 4) + 4 * grp + (i % 4);
-          const float p = __builtin_amdgcn_exp2f(fmaf(s_t[i], c2, -lse2));
-          acc[i] += (j <= limit) ? p : 0.f;
+        for (int kt = 0; kt < kColsumKeyTiles; ++kt) {
+          f32x16 s_t;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) s_t[i] = 0.f;
+#pragma unroll
+          for (int kk = 0; kk < 8; ++kk)
+            s_t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_op[kt][kk], qb[kk].v, s_t, 0, 0, 0);
+          if (need_mask) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int j = j0 + 32 * kt + 8 * (i / 4) + 4 * grp + (i % 4);
+              const float p = __builtin_amdgcn_exp2f(fmaf(s_t[i], c2, -lse2));
+              acc[kt][i] += (j <= limit) ? p : 0.f;
+            }
+          } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[kt][i] += __builtin_amdgcn_exp2f(fmaf(s_t[i], c2, -lse2));
+          }
         }
       }
     }
   }
   if (!wave_has_keys) return;
 #pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    float v = acc[i];
+  for (int kt = 0; kt < kColsumKeyTiles; ++kt)
 #pragma unroll
-    for (int o = 16; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    const int j = j0 + 8 * (i / 4) + 4 * grp + (i % 4);
-    if (col == 0 && j < n) score[(static_cast<int64_t>(bl) * dm.Hkv + g) * n + j] = v;
-  }
+    for (int i = 0; i < 16; ++i) {
+      float v = acc[kt][i];
+#pragma unroll
+      for (int o = 16; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+      const int j = j0 + 32 * kt + 8 * (i / 4) + 4 * grp + (i % 4);
+      if (col == 0 && j < n) score[(static_cast<int64_t>(bl) * dm.Hkv + g) * n + j] = v;
+    }
 }
 
 }  // namespace
@@ -484,7 +505,8 @@ hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments ks, Segme
 hipError_t launch_colsum_mfma(const Dims& dm, View q, int rows, Segments ks, int causal, const float* lse,
                               int key_splits, const float2* part, float* score, hipStream_t st) {
   const int n = ks.n_c + ks.c;
-  dim3 grid((n + 32 * kColsumWaves - 1) / (32 * kColsumWaves), dm.Hkv, dm.B * dm.L);
+  constexpr int kKeysPerBlock = 32 * kColsumKeyTiles * kColsumWaves;
+  dim3 grid((n + kKeysPerBlock - 1) / kKeysPerBlock, dm.Hkv, dm.B * dm.L);
   hipLaunchKernelGGL(colsum_mfma_kernel, grid, dim3(kColsumWaves * 64), 0, st, dm, q, rows, ks, causal, lse,
                      key_splits, part, score);
   return hipGetLastError();
