@@ -28,7 +28,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per chunk-attention launch measured offline with rocprofv3 --pmc
 # (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see
 # profiles/.  None until a measurement for that workload exists.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"cfg2_mistral7b": 432.1e6}
 
 
 class HipEvents:
@@ -116,6 +116,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="cfg2_mistral7b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch a plain elementwise copy of known size (256 MiB read + 256 MiB written) three "
+                         "times before the warm-up, as the reference for scaling rocprofv3 HBM counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -152,6 +155,14 @@ def main():
             pe = C.cast(C.byref(events.arr, ev_offset * C.sizeof(C.c_void_p)), C.c_void_p)
         done = api.citrus_process_document(cfg, state, ws, doc=rd, phase_events=pe)
         assert done == w.n_chunks
+
+    if args.calibrate_copy:
+        src = torch.ones(128 * 1024 * 1024, dtype=torch.bfloat16, device=dev)      # 256 MiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         one_document()

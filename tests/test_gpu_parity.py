@@ -424,3 +424,92 @@ def test_budget_at_least_document_is_full_causal_attention():
     assert torch.equal(kc, doc["k"]) and torch.equal(vc, doc["v"])
     ref = orc.full_causal_attention(np64(doc["q"][0, 0]), np64(doc["k"][0, 0]), np64(doc["v"][0, 0]))
     assert_close(np64(out[0, 0]), ref, "bf16", "full causal")
+
+
+# ----------------------------------------------------------------------------
+# full-size run in the launch configuration bench.py times (sampled checks)
+# ----------------------------------------------------------------------------
+
+def test_full_size_cfg2_sampled_against_oracle():
+    """The whole Mistral-7B-shaped document through citrus_process_document, as
+    bench.py runs it.  The oracle replays the GPU's selection history for a few
+    (document, layer) units (integer gathers only) and checks, at sampled
+    steps, the attention output, the selection against the oracle's scores
+    (band rule) and, at the end, the compacted cache bit for bit."""
+    w = WORKLOADS["cfg2_mistral7b"]
+    say(f"full size {w.name}")
+    cfg = api.Config.from_workload(w)
+    doc = make_document(w, DEV)
+    state, out, hist, _ = run_process_document(w, doc)
+    assert state.cache_len == w.budget
+    units = [(0, 0), (0, 13), (0, 31)]
+    steps = {0, 1, 2, 17, 31}
+    hist_h = hist.cpu().numpy()
+    kc_gpu, vc_gpu = state.current()
+    in_band = []
+    for (b, l) in units:
+        kd, vd = np64(doc["k"][b, l]), np64(doc["v"][b, l])
+        pos = np.zeros((w.kv_heads, 0), dtype=np.int64)
+        for i in range(w.n_chunks):
+            lo, hi = w.chunk_bounds(i)
+            cand = np.concatenate([pos, np.broadcast_to(np.arange(lo, hi), (w.kv_heads, hi - lo))], axis=1)
+            m = min(w.budget, cand.shape[1])
+            idx = hist_h[i, b, l][:, :m]
+            assert (np.diff(idx, axis=1) > 0).all() and idx.min() >= 0 and idx.max() < cand.shape[1]
+            if i in steps:
+                kcat = np.stack([kd[g, cand[g]] for g in range(w.kv_heads)])
+                vcat = np.stack([vd[g, cand[g]] for g in range(w.kv_heads)])
+                o_ref, _, _ = orc.chunk_attn(np64(doc["q"][b, l, :, lo:hi]), kcat, vcat, pos.shape[1])
+                assert_close(np64(out[b, l, :, lo:hi]), o_ref, w.dtype, f"out unit {(b, l)} step {i}")
+                s_ref = orc.instr_score(np64(doc["q_instr"][i, b, l]), kcat)
+                np.testing.assert_allclose(s_ref.sum(axis=1), w.instr_len * w.group, rtol=1e-9)
+                if cand.shape[1] > w.budget:
+                    atol, rtol = TOL[w.dtype]
+                    for g in range(w.kv_heads):
+                        ref_idx = orc.topk_select_1d(s_ref[g], w.budget)
+                        boundary = np.sort(s_ref[g])[::-1][w.budget - 1]
+                        band = np.abs(s_ref[g] - boundary) <= atol + rtol * abs(boundary)
+                        diff = np.setxor1d(idx[g], ref_idx)
+                        assert band[diff].all()
+                        in_band.append(band.mean())
+            pos = np.stack([cand[g][idx[g]] for g in range(w.kv_heads)])
+        for g in range(w.kv_heads):
+            p = torch.from_numpy(pos[g])
+            np.testing.assert_array_equal(bits(kc_gpu[b, l, g]), bits(doc["k"][b, l, g].cpu()[p]))
+            np.testing.assert_array_equal(bits(vc_gpu[b, l, g]), bits(doc["v"][b, l, g].cpu()[p]))
+    say(f"full size: fraction of positions inside the selection tolerance band = {np.mean(in_band):.3f}")
+
+
+def test_full_size_single_step_all_checks():
+    """One steady-state step of the Mistral-7B-shaped configuration through the
+    four entry points, all (document, layer) units launched, three checked:
+    outputs, log-sum-exp, scores, exact selection, bit-exact compaction."""
+    w = WORKLOADS["cfg2_mistral7b"]
+    cfg = api.Config.from_workload(w)
+    ch = make_chunk(w, 5, DEV)
+    n_c = w.budget
+    kc = rand((w.batch, w.layers, w.kv_heads, n_c, w.head_dim), torch.bfloat16, 11, w.head_dim ** -0.5)
+    vc = rand((w.batch, w.layers, w.kv_heads, n_c, w.head_dim), torch.bfloat16, 12, w.head_dim ** -0.5)
+    ws = api.alloc_workspace(cfg)
+    lse = torch.empty((w.batch, w.layers, w.q_heads, w.chunk_len), dtype=torch.float32, device=DEV)
+    out = api.citrus_chunk_attn(cfg, ch["q"], kc, vc, n_c, ch["k"], ch["v"], lse=lse)
+    score = api.citrus_instr_score(cfg, ch["q_instr"], kc, n_c, ch["k"], workspace=ws)
+    idx = api.citrus_topk_select(cfg, score, w.budget)
+    kn, vn = torch.zeros_like(kc), torch.zeros_like(vc)
+    api.citrus_kv_compact(cfg, kc, vc, n_c, ch["k"], ch["v"], idx, w.budget, kn, vn)
+    torch.cuda.synchronize()
+    for l in (0, 9, 31):
+        kcat = np.concatenate([np64(kc[0, l]), np64(ch["k"][0, l])], axis=1)
+        vcat = np.concatenate([np64(vc[0, l]), np64(ch["v"][0, l])], axis=1)
+        o_ref, lse_ref, _ = orc.chunk_attn(np64(ch["q"][0, l]), kcat, vcat, n_c)
+        assert_close(np64(out[0, l]), o_ref, "bf16", f"out l{l}")
+        assert_close(np64(lse[0, l]), lse_ref, "bf16", f"lse l{l}")
+        s_ref = orc.instr_score(np64(ch["q_instr"][0, l]), kcat)
+        assert_close(np64(score[0, l]), s_ref, "bf16", f"score l{l}")
+        kb = np.concatenate([bits(kc[0, l]), bits(ch["k"][0, l])], axis=1)
+        vb = np.concatenate([bits(vc[0, l]), bits(ch["v"][0, l])], axis=1)
+        for g in range(w.kv_heads):
+            check_selection(idx[0, l, g].cpu().numpy(), score[0, l, g].cpu().numpy(), s_ref[g], w.budget, "bf16")
+        k_ref, v_ref = orc.kv_compact(kb, vb, idx[0, l].cpu().numpy())
+        np.testing.assert_array_equal(bits(kn[0, l]), k_ref)
+        np.testing.assert_array_equal(bits(vn[0, l]), v_ref)
