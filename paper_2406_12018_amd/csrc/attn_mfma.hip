@@ -35,6 +35,7 @@ constexpr int kRowsPerWave = 32;        // one 32-query column tile per wave
 constexpr int kTileN = 64;              // keys per LDS tile
 constexpr int kXcds = 8;
 constexpr int kMaxKeySplits = 8;
+constexpr int kBufferFlags = 0x00020000;  // raw buffer resource word 3 on CDNA: 32-bit data format, no swizzle
 constexpr int kPitchK = D + 8;          // LDS row pitch of K in bf16 (272 B): conflict-free 16-byte column reads
 constexpr int kPitchV = D + 16;         // LDS row pitch of V in bf16 (288 B): conflict-free transpose reads
 constexpr float kLog2e = 1.4426950408889634f;
@@ -135,46 +136,68 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
   }
   const int limit_lane = causal ? n_c + t_lane : n - 1;
 
-  // ---- global -> register -> LDS staging of one 64-key tile (two K and two V pieces per thread) ----
-  // Rows past the last candidate re-read the last row (finite values; their logits are masked).
-  // Both candidate addresses are formed and one is selected, so the strides stay scalar.
-  const uint16_t* k_cache_u = unit_ptr(ks.cache, b, l, g);
-  const uint16_t* k_chunk_u = unit_ptr(ks.chunk, b, l, g);
-  const uint16_t* v_cache_u = HAS_PV ? unit_ptr(vs.cache, b, l, g) : nullptr;
-  const uint16_t* v_chunk_u = HAS_PV ? unit_ptr(vs.chunk, b, l, g) : nullptr;
-  // element offsets inside one (document, layer, head) unit fit 32 bits (checked by the launcher)
+  // ---- global -> register -> LDS staging of one 64-key tile (four K and four V pieces per thread) ----
+  // Buffer loads: a 128-bit resource per segment (base of this unit's rows, size in bytes), one
+  // per-lane byte offset and a scalar offset per load.  The address arithmetic stays on the scalar
+  // unit and rows past the end of a segment read as zeros (their logits are masked anyway).
   const int k_ss_cache = static_cast<int>(ks.cache.ss), k_ss_chunk = static_cast<int>(ks.chunk.ss);
   const int v_ss_cache = static_cast<int>(vs.cache.ss), v_ss_chunk = static_cast<int>(vs.chunk.ss);
+  auto seg_bytes = [](int rows_, int ss_) { return rows_ > 0 ? ((rows_ - 1) * ss_ + D) * 2 : 0; };
+  const __amdgpu_buffer_rsrc_t k_rs_cache = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(unit_ptr(ks.cache, b, l, g)), 0, seg_bytes(n_c, k_ss_cache), kBufferFlags);
+  const __amdgpu_buffer_rsrc_t k_rs_chunk = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(unit_ptr(ks.chunk, b, l, g)), 0, seg_bytes(ks.c, k_ss_chunk), kBufferFlags);
+  const __amdgpu_buffer_rsrc_t v_rs_cache = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(unit_ptr(HAS_PV ? vs.cache : ks.cache, b, l, g)), 0, seg_bytes(n_c, v_ss_cache), kBufferFlags);
+  const __amdgpu_buffer_rsrc_t v_rs_chunk = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(unit_ptr(HAS_PV ? vs.chunk : ks.chunk, b, l, g)), 0, seg_bytes(ks.c, v_ss_chunk), kBufferFlags);
   const int st_row = tid / 16, st_seg = tid % 16;  // piece i covers tile row st_row + 16 i
-  auto k_row_ptr = [&](int j) {
-    const bool in_cache = j < n_c;
-    const uint32_t off = static_cast<uint32_t>(in_cache ? j * k_ss_cache : (j - n_c) * k_ss_chunk) + 8u * st_seg;
-    return reinterpret_cast<const uint4*>((in_cache ? k_cache_u : k_chunk_u) + off);
-  };
-  auto v_row_ptr = [&](int j) {
-    const bool in_cache = j < n_c;
-    const uint32_t off = static_cast<uint32_t>(in_cache ? j * v_ss_cache : (j - n_c) * v_ss_chunk) + 8u * st_seg;
-    return reinterpret_cast<const uint4*>((in_cache ? v_cache_u : v_chunk_u) + off);
-  };
-  // named (not an array), so the staged pieces stay in registers
-  uint4 k_st0, k_st1, k_st2, k_st3;
+  uint4 k_st0, k_st1, k_st2, k_st3;                 // named (not an array), so the pieces stay in registers
   uint4 v_st0 = {0u, 0u, 0u, 0u}, v_st1 = v_st0, v_st2 = v_st0, v_st3 = v_st0;
-#define CITRUS_FETCH_TILE(j0_)                                  \
-  do {                                                          \
-    const int ja_ = min((j0_) + st_row, n - 1);                 \
-    const int jb_ = min((j0_) + st_row + 16, n - 1);            \
-    const int jc_ = min((j0_) + st_row + 32, n - 1);            \
-    const int jd_ = min((j0_) + st_row + 48, n - 1);            \
-    k_st0 = *k_row_ptr(ja_);                                    \
-    k_st1 = *k_row_ptr(jb_);                                    \
-    k_st2 = *k_row_ptr(jc_);                                    \
-    k_st3 = *k_row_ptr(jd_);                                    \
-    if (HAS_PV) {                                               \
-      v_st0 = *v_row_ptr(ja_);                                  \
-      v_st1 = *v_row_ptr(jb_);                                  \
-      v_st2 = *v_row_ptr(jc_);                                  \
-      v_st3 = *v_row_ptr(jd_);                                  \
-    }                                                           \
+  auto bload = [](__amdgpu_buffer_rsrc_t rs, int voff, int soff) {
+    return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, 0));
+  };
+  // a row that belongs to the other segment is pushed out of range and reads as zero
+  auto mixed = [&](__amdgpu_buffer_rsrc_t rc, __amdgpu_buffer_rsrc_t rk, int ssc, int ssk, int j) {
+    const int oc = j < n_c ? (j * ssc + 8 * st_seg) * 2 : 0x7ffffff0;
+    const int ok = j >= n_c ? ((j - n_c) * ssk + 8 * st_seg) * 2 : 0x7ffffff0;
+    const uint4 x = bload(rc, oc, 0), y = bload(rk, ok, 0);
+    return make_uint4(x.x | y.x, x.y | y.y, x.z | y.z, x.w | y.w);
+  };
+#define CITRUS_FETCH_TILE(j0_)                                                                 \
+  do {                                                                                         \
+    const int jf_ = (j0_);                                                                     \
+    if (jf_ + kTileN <= n_c || jf_ >= n_c) { /* block-uniform: the tile lies in one segment */ \
+      const bool c_ = jf_ < n_c;                                                               \
+      const int r0_ = c_ ? jf_ : jf_ - n_c;                                                    \
+      const int kss_ = c_ ? k_ss_cache : k_ss_chunk;                                           \
+      const __amdgpu_buffer_rsrc_t krs_ = c_ ? k_rs_cache : k_rs_chunk;                        \
+      const int kvo_ = (st_row * kss_ + 8 * st_seg) * 2;                                       \
+      k_st0 = bload(krs_, kvo_, (r0_ + 0) * kss_ * 2);                                         \
+      k_st1 = bload(krs_, kvo_, (r0_ + 16) * kss_ * 2);                                        \
+      k_st2 = bload(krs_, kvo_, (r0_ + 32) * kss_ * 2);                                        \
+      k_st3 = bload(krs_, kvo_, (r0_ + 48) * kss_ * 2);                                        \
+      if (HAS_PV) {                                                                            \
+        const int vss_ = c_ ? v_ss_cache : v_ss_chunk;                                         \
+        const __amdgpu_buffer_rsrc_t vrs_ = c_ ? v_rs_cache : v_rs_chunk;                      \
+        const int vvo_ = (st_row * vss_ + 8 * st_seg) * 2;                                     \
+        v_st0 = bload(vrs_, vvo_, (r0_ + 0) * vss_ * 2);                                       \
+        v_st1 = bload(vrs_, vvo_, (r0_ + 16) * vss_ * 2);                                      \
+        v_st2 = bload(vrs_, vvo_, (r0_ + 32) * vss_ * 2);                                      \
+        v_st3 = bload(vrs_, vvo_, (r0_ + 48) * vss_ * 2);                                      \
+      }                                                                                        \
+    } else { /* the one tile that straddles the cache / chunk boundary */                      \
+      k_st0 = mixed(k_rs_cache, k_rs_chunk, k_ss_cache, k_ss_chunk, jf_ + st_row);             \
+      k_st1 = mixed(k_rs_cache, k_rs_chunk, k_ss_cache, k_ss_chunk, jf_ + st_row + 16);        \
+      k_st2 = mixed(k_rs_cache, k_rs_chunk, k_ss_cache, k_ss_chunk, jf_ + st_row + 32);        \
+      k_st3 = mixed(k_rs_cache, k_rs_chunk, k_ss_cache, k_ss_chunk, jf_ + st_row + 48);        \
+      if (HAS_PV) {                                                                            \
+        v_st0 = mixed(v_rs_cache, v_rs_chunk, v_ss_cache, v_ss_chunk, jf_ + st_row);           \
+        v_st1 = mixed(v_rs_cache, v_rs_chunk, v_ss_cache, v_ss_chunk, jf_ + st_row + 16);      \
+        v_st2 = mixed(v_rs_cache, v_rs_chunk, v_ss_cache, v_ss_chunk, jf_ + st_row + 32);      \
+        v_st3 = mixed(v_rs_cache, v_rs_chunk, v_ss_cache, v_ss_chunk, jf_ + st_row + 48);      \
+      }                                                                                        \
+    }                                                                                          \
   } while (0)
 #define CITRUS_STAGE_TILE(buf_)                                                                          \
   do {                                                                                                   \
@@ -279,13 +302,19 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
       for (int mt = 0; mt < 2; ++mt) {
         float p[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          p[i] = __builtin_amdgcn_exp2f(fmaf(s_acc[mt][i], c2, -m_run));
-          psum += p[i];
-        }
+        for (int i = 0; i < 16; ++i) p[i] = __builtin_amdgcn_exp2f(fmaf(s_acc[mt][i], c2, -m_run));
         if (HAS_PV) {
+          // the row sum is taken over the bf16-rounded probabilities, the values P.V actually uses:
+          // one v_dot2 with (1, 1) adds a pair
 #pragma unroll
-          for (int i = 0; i < 8; ++i) p_pk[mt][i] = pack_bf16x2(p[2 * i], p[2 * i + 1]);
+          for (int i = 0; i < 8; ++i) {
+            p_pk[mt][i] = pack_bf16x2(p[2 * i], p[2 * i + 1]);
+            psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, p_pk[mt][i]),
+                                                   __builtin_bit_cast(bf16x2, 0x3f803f80u), psum, false);
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) psum += p[i];
         }
       }
       l_run += psum;
