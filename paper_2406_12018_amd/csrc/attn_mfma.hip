@@ -40,6 +40,7 @@ constexpr int kPitchK = D + 8;          // LDS row pitch of K in bf16 (272 B): c
 constexpr int kPitchV = D + 16;         // LDS row pitch of V in bf16 (288 B): conflict-free transpose reads
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kMaxSlack = 8.0f;  // probabilities stay below 2^8: exact in f32, same relative rounding in bf16
 
 union Pack8 {
   bf16x8 v;
@@ -100,41 +101,20 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
   // tiles and writes a partial (running maximum, sum) pair per row; the consumer merges them.
   const int sp = logical % key_splits;
   logical /= key_splits;
-  const int rb = row_blocks - 1 - logical % row_blocks;
-  const int hg = (logical / row_blocks) % head_groups;
-  const int g = (logical / (row_blocks * head_groups)) % dm.Hkv;
-  const int bl = logical / (row_blocks * head_groups * dm.Hkv);
+  // Causal attention: a workgroup takes the row block with the longest key range still free and then
+  // its mirror image (the shortest), so every workgroup does the same number of key tiles.
+  const bool paired = causal != 0 && key_splits == 1;
+  const int rb_slots = paired ? (row_blocks + 1) / 2 : row_blocks;
+  const int rb_first = row_blocks - 1 - logical % rb_slots;
+  const int rb_second = row_blocks - 1 - rb_first;
+  const int passes = (paired && rb_second != rb_first) ? 2 : 1;
+  const int hg = (logical / rb_slots) % head_groups;
+  const int g = (logical / (rb_slots * head_groups)) % dm.Hkv;
+  const int bl = logical / (rb_slots * head_groups * dm.Hkv);
   const int b = bl / dm.L, l = bl % dm.L;
   const int h = g * dm.G + hg * ts.heads_per_block + (w % ts.heads_per_block);
-  const int row0 = (rb * ts.tiles_per_block + w / ts.heads_per_block) * kRowsPerWave;
   const int n_c = ks.n_c;
   const int n = n_c + ks.c;
-
-  // last candidate any row of this block / this wave can see
-  const int blk_row_last = min(rows, (rb + 1) * rows_per_block) - 1;
-  const int blk_limit = causal ? n_c + blk_row_last : n - 1;
-  const int all_tiles = blk_limit / kTileN + 1;
-  const int tiles_per_split = (all_tiles + key_splits - 1) / key_splits;
-  const int t_begin = sp * tiles_per_split;
-  const int t_end = min(all_tiles, t_begin + tiles_per_split);
-  const bool wave_active = row0 < rows;
-  const int wave_row_last = min(rows, row0 + kRowsPerWave) - 1;
-  const int wave_limit_max = causal ? n_c + wave_row_last : n - 1;  // beyond it the wave sees nothing
-  const int wave_limit_min = causal ? n_c + row0 : n - 1;           // up to it every row sees everything
-
-  // ---- Q^T operand, kept in registers: q_op[kk] = Q[row0 + col][16 kk + 8 grp ..+7] ----
-  bf16x8 q_op[8];
-  const int t_lane = max(min(row0 + col, rows - 1), 0);
-  {
-    const uint16_t* qp = unit_ptr(q, b, l, h) + static_cast<int64_t>(t_lane) * q.ss + 8 * grp;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      Pack8 p;
-      p.u = *reinterpret_cast<const uint4*>(qp + 16 * kk);
-      q_op[kk] = p.v;
-    }
-  }
-  const int limit_lane = causal ? n_c + t_lane : n - 1;
 
   // ---- global -> register -> LDS staging of one 64-key tile (four K and four V pieces per thread) ----
   // Buffer loads: a 128-bit resource per segment (base of this unit's rows, size in bytes), one
@@ -223,6 +203,36 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
   const int s16 = lane % 16, q16 = lane / 16;
   const int v_lane_off = (4 * (q16 / 2) + s16 / 4) * kPitchV + 64 * (q16 % 2) + 4 * (s16 % 4);
 
+  for (int pass = 0; pass < passes; ++pass) {
+  const int rb = pass == 0 ? rb_first : rb_second;
+  const int row0 = (rb * ts.tiles_per_block + w / ts.heads_per_block) * kRowsPerWave;
+
+  // last candidate any row of this block / this wave can see
+  const int blk_row_last = min(rows, (rb + 1) * rows_per_block) - 1;
+  const int blk_limit = causal ? n_c + blk_row_last : n - 1;
+  const int all_tiles = blk_limit / kTileN + 1;
+  const int tiles_per_split = (all_tiles + key_splits - 1) / key_splits;
+  const int t_begin = sp * tiles_per_split;
+  const int t_end = min(all_tiles, t_begin + tiles_per_split);
+  const bool wave_active = row0 < rows;
+  const int wave_row_last = min(rows, row0 + kRowsPerWave) - 1;
+  const int wave_limit_max = causal ? n_c + wave_row_last : n - 1;  // beyond it the wave sees nothing
+  const int wave_limit_min = causal ? n_c + row0 : n - 1;           // up to it every row sees everything
+
+  // ---- Q^T operand, kept in registers: q_op[kk] = Q[row0 + col][16 kk + 8 grp ..+7] ----
+  bf16x8 q_op[8];
+  const int t_lane = max(min(row0 + col, rows - 1), 0);
+  {
+    const uint16_t* qp = unit_ptr(q, b, l, h) + static_cast<int64_t>(t_lane) * q.ss + 8 * grp;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      Pack8 p;
+      p.u = *reinterpret_cast<const uint4*>(qp + 16 * kk);
+      q_op[kk] = p.v;
+    }
+  }
+  const int limit_lane = causal ? n_c + t_lane : n - 1;
+
   // ---- running softmax state: one query per lane ----
   const float c2 = dm.scale * kLog2e;  // logits are kept in the log2 domain
   float m_run = -INFINITY, l_run = 0.f;
@@ -278,15 +288,20 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
             if (j > limit_lane) s_acc[mt][i] = -INFINITY;
           }
       }
+      // Running maximum, kept lazily: softmax is invariant to the subtracted value, so m_run only has
+      // to stay within kMaxSlack (log2 units) of the true row maximum to keep exp2 in range.  The fast
+      // path looks at this lane's own 32 logits only; the exchange with lane l ^ 32, the update of
+      // m_run and the rescale of the accumulators happen only when some row needs them.
       float mx = s_acc[0][0];
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s_acc[mt][i]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run, mx * c2);
-      if (__any(m_new > m_run)) {  // wave-uniform: skip the rescale when no row's maximum moved
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      if (__any(mx * c2 > m_run + kMaxSlack)) {  // wave-uniform and rare after the first tiles
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx * c2);
+        // 0 on a row's first visible tile (m_run = -inf); 1 for a row that has seen nothing yet
+        const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
         l_run *= alpha;
         if (HAS_PV) {
 #pragma unroll
@@ -351,10 +366,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
   }
   }
 
-  if (!wave_active) return;
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const int t = row0 + col;
-  if (t >= rows) return;
+  if (wave_active && t < rows) {
   const int64_t row_id = (static_cast<int64_t>(bl) * dm.Hq + h) * rows + t;
   if (part != nullptr && grp == 0)  // log2 domain; an empty or fully masked range leaves (-inf, 0)
     part[static_cast<int64_t>(sp) * dm.B * dm.L * dm.Hq * rows + row_id] = make_float2(m_run, l_tot);
@@ -375,6 +389,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
         *reinterpret_cast<uint2*>(op + d0) = wds;
       }
   }
+  }  // row valid
+  }  // pass
 }
 
 // Summed form of Eq. (1): score[g, j] = sum over the query rows of the KV group of
@@ -520,8 +536,9 @@ hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments ks, Segme
   if (key_splits < 1 || (key_splits > 1 && (out.ptr != nullptr || part == nullptr))) return hipErrorInvalidValue;
   const TaskShape ts = task_shape(dm.G);
   const int rows_per_block = ts.tiles_per_block * kRowsPerWave;
-  dim3 grid(((rows + rows_per_block - 1) / rows_per_block) * (dm.G / ts.heads_per_block) * dm.Hkv * dm.B * dm.L *
-            key_splits);
+  const int row_blocks = (rows + rows_per_block - 1) / rows_per_block;
+  const int rb_slots = (causal && key_splits == 1) ? (row_blocks + 1) / 2 : row_blocks;  // paired row blocks
+  dim3 grid(rb_slots * (dm.G / ts.heads_per_block) * dm.Hkv * dm.B * dm.L * key_splits);
   if (out.ptr != nullptr)
     hipLaunchKernelGGL((attn_mfma_kernel<true>), grid, dim3(kThreads), 0, st, dm, q, rows, ks, vs, causal, out, lse,
                        key_splits, part);
