@@ -36,8 +36,9 @@ constexpr int kTileN = 64;              // keys per LDS tile
 constexpr int kXcds = 8;
 constexpr int kMaxKeySplits = 8;
 constexpr int kBufferFlags = 0x00020000;  // raw buffer resource word 3 on CDNA: 32-bit data format, no swizzle
-constexpr int kPitchK = D + 8;          // LDS row pitch of K in bf16 (272 B): conflict-free 16-byte column reads
-constexpr int kPitchV = D + 16;         // LDS row pitch of V in bf16 (288 B): conflict-free transpose reads
+constexpr int kPitchK = D + 8;          // padded LDS row pitch in bf16 (272 B) of the column-sum kernel's Q chunk
+constexpr int kRowBytes = 2 * D;        // K/V tile rows in LDS are unpadded (256 B) and XOR-swizzled
+constexpr int kTileBytes = kTileN * kRowBytes;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kMaxSlack = 8.0f;  // probabilities stay below 2^8: exact in f32, same relative rounding in bf16
@@ -63,7 +64,7 @@ __device__ inline const uint16_t* unit_ptr(const View& v, int b, int l, int h) {
 // address of 4 consecutive bf16 and lane i receives element (i % 4) of lanes i/4, 4 + i/4,
 // 8 + i/4, 12 + i/4.  With lane s pointing at &V[key(s / 4)][d0 + 4 (s % 4)], lane i gets
 // V[key(0..3)][d0 + i]: four keys of one head_dim column, i.e. half of an MFMA A operand of V^T.
-__device__ inline i16x4 lds_read_tr16(const uint16_t* p) {
+__device__ inline i16x4 lds_read_tr16(const char* p) {
   typedef i16x4 __attribute__((address_space(3))) * lds_ptr;
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
 }
@@ -82,8 +83,8 @@ template <bool HAS_PV>
 __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q, int rows, Segments ks, Segments vs,
                                                                int causal, View out, float* lse, int key_splits,
                                                                float2* part) {
-  __shared__ __attribute__((aligned(16))) uint16_t k_s[2 * kTileN * kPitchK];  // double-buffered tiles
-  __shared__ __attribute__((aligned(16))) uint16_t v_s[HAS_PV ? 2 * kTileN * kPitchV : 8];
+  __shared__ __attribute__((aligned(1024))) char k_s[2 * kTileBytes];  // double-buffered tiles
+  __shared__ __attribute__((aligned(1024))) char v_s[HAS_PV ? 2 * kTileBytes : 16];
 
   const int tid = threadIdx.x, lane = tid % 64, w = tid / 64;
   const int col = lane % 32, grp = lane / 32;
@@ -116,10 +117,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
   const int n_c = ks.n_c;
   const int n = n_c + ks.c;
 
-  // ---- global -> register -> LDS staging of one 64-key tile (four K and four V pieces per thread) ----
-  // Buffer loads: a 128-bit resource per segment (base of this unit's rows, size in bytes), one
-  // per-lane byte offset and a scalar offset per load.  The address arithmetic stays on the scalar
-  // unit and rows past the end of a segment read as zeros (their logits are masked anyway).
+  // ---- global -> LDS staging of one 64-key tile, without a stop in registers ----
+  // buffer_load ... lds: a wave-level instruction moves 64 x 16 B from per-lane global addresses
+  // to 1 KB of consecutive LDS, i.e. four unpadded 256-byte rows.  Bank conflicts of the column
+  // reads below are avoided by an XOR swizzle instead of padding: the 16-byte segment `seg` of
+  // tile row `row` lives at segment position seg ^ f(row), f(row) = 2 (row % 8) ^ ((row / 8) % 2),
+  // which the loading lane realises by fetching global segment (its LDS position) ^ f(row).
+  // Wave w fills rows 16 w + 4 i .. + 3 with instruction i = 0..3.  Rows that fall outside the
+  // candidates re-read the last row (finite values; their logits are masked).
   const int k_ss_cache = static_cast<int>(ks.cache.ss), k_ss_chunk = static_cast<int>(ks.chunk.ss);
   const int v_ss_cache = static_cast<int>(vs.cache.ss), v_ss_chunk = static_cast<int>(vs.chunk.ss);
   auto seg_bytes = [](int rows_, int ss_) { return rows_ > 0 ? ((rows_ - 1) * ss_ + D) * 2 : 0; };
@@ -131,77 +136,55 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
       const_cast<uint16_t*>(unit_ptr(HAS_PV ? vs.cache : ks.cache, b, l, g)), 0, seg_bytes(n_c, v_ss_cache), kBufferFlags);
   const __amdgpu_buffer_rsrc_t v_rs_chunk = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint16_t*>(unit_ptr(HAS_PV ? vs.chunk : ks.chunk, b, l, g)), 0, seg_bytes(ks.c, v_ss_chunk), kBufferFlags);
-  const int st_row = tid / 16, st_seg = tid % 16;  // piece i covers tile row st_row + 16 i
-  uint4 k_st0, k_st1, k_st2, k_st3;                 // named (not an array), so the pieces stay in registers
-  uint4 v_st0 = {0u, 0u, 0u, 0u}, v_st1 = v_st0, v_st2 = v_st0, v_st3 = v_st0;
-  auto bload = [](__amdgpu_buffer_rsrc_t rs, int voff, int soff) {
-    return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, 0));
+  const int wu = __builtin_amdgcn_readfirstlane(w);
+  const int fill_row = 16 * wu + lane / 16;                       // tile row this lane fills with instruction 0
+  const int fill_seg16 = ((lane % 16) ^ (2 * (lane / 16))) * 16;  // byte offset of its global segment, before ^ c_i
+  typedef __attribute__((address_space(3))) void* lds_void_ptr;
+  auto fill4 = [&](char* lds_tile, __amdgpu_buffer_rsrc_t rs_cache, __amdgpu_buffer_rsrc_t rs_chunk, int ss_cache,
+                   int ss_chunk, int j0) {
+    const bool simple = (j0 + kTileN <= n_c) || (j0 >= n_c && j0 + kTileN <= n);  // block-uniform
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int ci16 = ((8 * (i & 1)) | (i >> 1)) * 16;
+      lds_void_ptr dst = (lds_void_ptr)(lds_tile + (16 * wu + 4 * i) * kRowBytes);
+      if (simple) {
+        const bool in_cache = j0 < n_c;
+        const int ss = in_cache ? ss_cache : ss_chunk;
+        const int r0 = in_cache ? j0 : j0 - n_c;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(in_cache ? rs_cache : rs_chunk, dst, 16,
+                                                 fill_row * ss * 2 + (fill_seg16 ^ ci16), (r0 + 4 * i) * ss * 2, 0, 0);
+      } else {  // the tile straddles the cache / chunk boundary or the end of the candidates
+        const int j = min(j0 + fill_row + 4 * i, n - 1);
+        if (j < n_c)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_cache, dst, 16, j * ss_cache * 2 + (fill_seg16 ^ ci16), 0, 0, 0);
+        else
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_chunk, dst, 16, (j - n_c) * ss_chunk * 2 + (fill_seg16 ^ ci16),
+                                                   0, 0, 0);
+      }
+    }
   };
-  // a row that belongs to the other segment is pushed out of range and reads as zero
-  auto mixed = [&](__amdgpu_buffer_rsrc_t rc, __amdgpu_buffer_rsrc_t rk, int ssc, int ssk, int j) {
-    const int oc = j < n_c ? (j * ssc + 8 * st_seg) * 2 : 0x7ffffff0;
-    const int ok = j >= n_c ? ((j - n_c) * ssk + 8 * st_seg) * 2 : 0x7ffffff0;
-    const uint4 x = bload(rc, oc, 0), y = bload(rk, ok, 0);
-    return make_uint4(x.x | y.x, x.y | y.y, x.z | y.z, x.w | y.w);
-  };
-#define CITRUS_FETCH_TILE(j0_)                                                                 \
-  do {                                                                                         \
-    const int jf_ = (j0_);                                                                     \
-    if (jf_ + kTileN <= n_c || jf_ >= n_c) { /* block-uniform: the tile lies in one segment */ \
-      const bool c_ = jf_ < n_c;                                                               \
-      const int r0_ = c_ ? jf_ : jf_ - n_c;                                                    \
-      const int kss_ = c_ ? k_ss_cache : k_ss_chunk;                                           \
-      const __amdgpu_buffer_rsrc_t krs_ = c_ ? k_rs_cache : k_rs_chunk;                        \
-      const int kvo_ = (st_row * kss_ + 8 * st_seg) * 2;                                       \
-      k_st0 = bload(krs_, kvo_, (r0_ + 0) * kss_ * 2);                                         \
-      k_st1 = bload(krs_, kvo_, (r0_ + 16) * kss_ * 2);                                        \
-      k_st2 = bload(krs_, kvo_, (r0_ + 32) * kss_ * 2);                                        \
-      k_st3 = bload(krs_, kvo_, (r0_ + 48) * kss_ * 2);                                        \
-      if (HAS_PV) {                                                                            \
-        const int vss_ = c_ ? v_ss_cache : v_ss_chunk;                                         \
-        const __amdgpu_buffer_rsrc_t vrs_ = c_ ? v_rs_cache : v_rs_chunk;                      \
-        const int vvo_ = (st_row * vss_ + 8 * st_seg) * 2;                                     \
-        v_st0 = bload(vrs_, vvo_, (r0_ + 0) * vss_ * 2);                                       \
-        v_st1 = bload(vrs_, vvo_, (r0_ + 16) * vss_ * 2);                                      \
-        v_st2 = bload(vrs_, vvo_, (r0_ + 32) * vss_ * 2);                                      \
-        v_st3 = bload(vrs_, vvo_, (r0_ + 48) * vss_ * 2);                                      \
-      }                                                                                        \
-    } else { /* the one tile that straddles the cache / chunk boundary */                      \
-      k_st0 = mixed(k_rs_cache, k_rs_chunk, k_ss_cache, k_ss_chunk, jf_ + st_row);             \
-      k_st1 = mixed(k_rs_cache, k_rs_chunk, k_ss_cache, k_ss_chunk, jf_ + st_row + 16);        \
-      k_st2 = mixed(k_rs_cache, k_rs_chunk, k_ss_cache, k_ss_chunk, jf_ + st_row + 32);        \
-      k_st3 = mixed(k_rs_cache, k_rs_chunk, k_ss_cache, k_ss_chunk, jf_ + st_row + 48);        \
-      if (HAS_PV) {                                                                            \
-        v_st0 = mixed(v_rs_cache, v_rs_chunk, v_ss_cache, v_ss_chunk, jf_ + st_row);           \
-        v_st1 = mixed(v_rs_cache, v_rs_chunk, v_ss_cache, v_ss_chunk, jf_ + st_row + 16);      \
-        v_st2 = mixed(v_rs_cache, v_rs_chunk, v_ss_cache, v_ss_chunk, jf_ + st_row + 32);      \
-        v_st3 = mixed(v_rs_cache, v_rs_chunk, v_ss_cache, v_ss_chunk, jf_ + st_row + 48);      \
-      }                                                                                        \
-    }                                                                                          \
-  } while (0)
-#define CITRUS_STAGE_TILE(buf_)                                                                          \
-  do {                                                                                                   \
-    uint16_t* kd_ = &k_s[(buf_) * kTileN * kPitchK + st_row * kPitchK + 8 * st_seg];                     \
-    *reinterpret_cast<uint4*>(kd_) = k_st0;                                                              \
-    *reinterpret_cast<uint4*>(kd_ + 16 * kPitchK) = k_st1;                                               \
-    *reinterpret_cast<uint4*>(kd_ + 32 * kPitchK) = k_st2;                                               \
-    *reinterpret_cast<uint4*>(kd_ + 48 * kPitchK) = k_st3;                                               \
-    if (HAS_PV) {                                                                                        \
-      uint16_t* vd_ = &v_s[(buf_) * kTileN * kPitchV + st_row * kPitchV + 8 * st_seg];                   \
-      *reinterpret_cast<uint4*>(vd_) = v_st0;                                                            \
-      *reinterpret_cast<uint4*>(vd_ + 16 * kPitchV) = v_st1;                                             \
-      *reinterpret_cast<uint4*>(vd_ + 32 * kPitchV) = v_st2;                                             \
-      *reinterpret_cast<uint4*>(vd_ + 48 * kPitchV) = v_st3;                                             \
-    }                                                                                                    \
+#define CITRUS_FETCH_TILE(j0_, buf_)                                                                        \
+  do {                                                                                                      \
+    fill4(k_s + (buf_) * kTileBytes, k_rs_cache, k_rs_chunk, k_ss_cache, k_ss_chunk, (j0_));                \
+    if (HAS_PV) fill4(v_s + (buf_) * kTileBytes, v_rs_cache, v_rs_chunk, v_ss_cache, v_ss_chunk, (j0_));    \
   } while (0)
 
-  // per-lane LDS offsets (elements)
-  const int k_lane_off = col * kPitchK + 8 * grp;  // A operand of S^T: key row `col`, contraction slots 8 grp..
+  // per-lane LDS read offsets (bytes inside a tile buffer), swizzle included
+  // A operand of S^T: key row `col`, head_dim segment 2 kk + grp
+  const int f_col = (2 * (col & 7)) ^ ((col >> 3) & 1);
+  int k_off[8];
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) k_off[kk] = col * kRowBytes + (((2 * kk + grp) ^ f_col) * 16);
   // V^T operand through transpose reads.  The 16-lane group q16 = lane / 16 serves MFMA rows
   // 16 (q16 % 2) .. +15 for contraction lane group q16 / 2; output row c' of tile r is head_dim
-  // 16 r + (c' % 16) + 64 (c' / 16), which keeps the two groups of a half-wave 128 B apart in LDS.
+  // 16 r + (c' % 16) + 64 (c' / 16).  Source lane s16 points at 4 consecutive head_dim values of key
+  // row 4 (q16 / 2) + s16 / 4 (+ 8 rd + 16 half + 32 mt): segment 2 r + 8 (q16 % 2) + (s16 % 4) / 2.
   const int s16 = lane % 16, q16 = lane / 16;
-  const int v_lane_off = (4 * (q16 / 2) + s16 / 4) * kPitchV + 64 * (q16 % 2) + 4 * (s16 % 4);
+  const int v_cl = (8 * (q16 % 2) + (s16 % 4) / 2) ^ (8 * (q16 / 2) + 2 * (s16 / 4));
+  int v_off[8];  // indexed by e = 2 r + rd: f(row) of read rd differs from read 0 by ^ rd
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+    v_off[e] = (4 * (q16 / 2) + s16 / 4) * kRowBytes + ((e ^ v_cl) * 16) + 8 * (s16 % 2);
 
   for (int pass = 0; pass < passes; ++pass) {
   const int rb = pass == 0 ? rb_first : rb_second;
@@ -243,8 +226,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
     for (int i = 0; i < 16; ++i) o_acc[r][i] = 0.f;
 
   if (t_begin < t_end) {  // block-uniform
-  CITRUS_FETCH_TILE(t_begin * kTileN);
-  CITRUS_STAGE_TILE(0);
+  CITRUS_FETCH_TILE(t_begin * kTileN, 0);
   __syncthreads();
   // All loads issued so far (the Q operand among them) have landed: say so explicitly, otherwise
   // the first MFMA of every iteration waits for the tile prefetch issued just before it.
@@ -253,9 +235,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
   for (int jt = t_begin; jt < t_end; ++jt) {
     const int j0 = jt * kTileN;
     const int buf = (jt - t_begin) & 1;
-    const uint16_t* k_t = k_s + buf * kTileN * kPitchK + k_lane_off;
-    const uint16_t* v_t = v_s + (HAS_PV ? buf * kTileN * kPitchV + v_lane_off : 0);
-    if (jt + 1 < t_end) CITRUS_FETCH_TILE(j0 + kTileN);  // in flight while this tile is computed
+    const char* k_t = k_s + buf * kTileBytes;
+    const char* v_t = v_s + (HAS_PV ? buf * kTileBytes : 0);
+    // The other buffer was last read one iteration ago and every wave has passed the barrier that
+    // ended that iteration: the next tile can stream into it while this one is computed.
+    if (jt + 1 < t_end) CITRUS_FETCH_TILE(j0 + kTileN, buf ^ 1);
 
     if (wave_active && j0 <= wave_limit_max) {
       // S^T = K . Q^T for 64 keys x 32 queries
@@ -271,7 +255,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
         for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
           for (int mt = 0; mt < 2; ++mt)
-            a[mt][kk].u = *reinterpret_cast<const uint4*>(k_t + 32 * mt * kPitchK + 16 * (4 * kh + kk));
+            a[mt][kk].u = *reinterpret_cast<const uint4*>(k_t + 32 * mt * kRowBytes + k_off[4 * kh + kk]);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
@@ -347,7 +331,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
             for (int r = 0; r < 4; ++r)
 #pragma unroll
               for (int rd = 0; rd < 2; ++rd)
-                a[r].h[rd] = lds_read_tr16(v_t + (32 * mt + 16 * half + 8 * rd) * kPitchV + 16 * r);
+                a[r].h[rd] = lds_read_tr16(v_t + (32 * mt + 16 * half + 8 * rd) * kRowBytes + v_off[2 * r + rd]);
             Pack8 pb;
 #pragma unroll
             for (int x = 0; x < 4; ++x) pb.w[x] = p_pk[mt][4 * half + x];
@@ -359,10 +343,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
       }
     }
 
-    // The other buffer was last read one iteration ago and every wave has passed the barrier
-    // that ended that iteration, so it can be overwritten now.
-    if (jt + 1 < t_end) CITRUS_STAGE_TILE(buf ^ 1);
-    __syncthreads();
+    __syncthreads();  // publishes the tile that streamed in; everyone is done with this one
   }
   }
 
