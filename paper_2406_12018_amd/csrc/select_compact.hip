@@ -56,14 +56,25 @@ __global__ __launch_bounds__(kSelThreads) void topk_kernel(const float* score, i
       if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 0xff], 1);
     }
     __syncthreads();
-    if (tid == 0) {
-      int cum = 0, bin = 255;
-      for (; bin > 0; --bin) {
-        if (cum + hist[bin] >= need) break;
-        cum += hist[bin];
+    // Find the bin where the count of keys in higher bins first reaches `need`: thread t owns bin t,
+    // computes the number of keys in bins above it with a suffix scan (wave shuffles + one LDS hop),
+    // and the one bin with above < need <= above + own announces itself.
+    {
+      const int own = hist[tid];
+      int incl = own;  // inclusive suffix sum within the wave: bins tid .. end of wave
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int v = __shfl_down(incl, o, 64);
+        if ((tid % 64) + o < 64) incl += v;
       }
-      s_prefix = prefix | (static_cast<uint32_t>(bin) << shift);
-      s_need = need - cum;
+      if (tid % 64 == 0) wave_tot[0][tid / 64] = incl;  // total of this wave's 64 bins
+      __syncthreads();
+      int above = incl - own;
+      for (int x = tid / 64 + 1; x < kSelWaves; ++x) above += wave_tot[0][x];
+      if (above < need && need <= above + own) {
+        s_prefix = prefix | (static_cast<uint32_t>(tid) << shift);
+        s_need = need - above;
+      }
     }
     __syncthreads();
     prefix = s_prefix;
