@@ -451,6 +451,11 @@ __global__ __launch_bounds__(kColsumWaves * 64, 2) void colsum_mfma_kernel(Dims 
     __syncthreads();
     if (wave_has_keys) {
       for (int qt = 0; qt * 32 < f_cnt; ++qt) {
+        if (causal) {  // wave-uniform: skip query tiles none of whose rows sees any key of this wave
+          const int t_first = (f0 + 32 * qt) % rows;
+          const int t_last = t_first + 31 >= rows ? rows - 1 : t_first + 31;  // a tile that wraps reaches a head's end
+          if (n_c + t_last < j0) continue;
+        }
         Pack8 qb[8];
         const uint16_t* qrow = &q_s[(32 * qt + col) * kPitchK + 8 * grp];
 #pragma unroll
