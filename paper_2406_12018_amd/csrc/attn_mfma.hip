@@ -506,6 +506,204 @@ __global__ __launch_bounds__(kColsumWaves * 64, 2) void colsum_mfma_kernel(Dims 
     }
 }
 
+// Sum of 16 per-lane values over the 32 lanes that share lane / 32, in 16 exchanges: each step
+// halves the values a lane still carries (the lane keeps the half its own bit selects and takes
+// the partner's partial sum of the same half).  On return lane c holds, for value index c / 2,
+// the total over its 32 lanes.
+__device__ inline float reduce16_over32(const float (&v)[16], int col) {
+  float a[8], b[4], c[2];
+  const bool u16 = col & 16, u8 = col & 8, u4 = col & 4, u2 = col & 2;
+#pragma unroll
+  for (int x = 0; x < 8; ++x) a[x] = (u16 ? v[x + 8] : v[x]) + __shfl_xor(u16 ? v[x] : v[x + 8], 16, 64);
+#pragma unroll
+  for (int x = 0; x < 4; ++x) b[x] = (u8 ? a[x + 4] : a[x]) + __shfl_xor(u8 ? a[x] : a[x + 4], 8, 64);
+#pragma unroll
+  for (int x = 0; x < 2; ++x) c[x] = (u4 ? b[x + 2] : b[x]) + __shfl_xor(u4 ? b[x] : b[x + 2], 4, 64);
+  const float d = (u2 ? c[1] : c[0]) + __shfl_xor(u2 ? c[0] : c[1], 2, 64);
+  return d + __shfl_xor(d, 1, 64);
+}
+
+// Instruction score (Eq. (1), summed form) in ONE launch for KV groups whose query rows
+// (instruction rows x heads of the group, flattened) fit one LDS chunk: a workgroup owns one
+// (document, layer, KV head).  All its query rows sit in LDS; wave (kw, qh) walks key tiles
+// kw, kw + KW, ... (32 keys, in registers as the A operand) against q-tiles of its share qh:
+//   pass 1  per-lane online (maximum, sum) over the wave's keys  -> merged over waves in LDS into
+//           the row normaliser (log2 domain);
+//   pass 2  the same products again, exp2(s - normaliser) summed down the query rows per key.
+// Partial column sums of the q shares meet in LDS and are added in a fixed order: no atomics.
+template <int QT_TOTAL, int Q_SPLIT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void instr_fused_kernel(Dims dm, View q, int rows, Segments ks,
+                                                                 float* score) {
+  constexpr int KW = WAVES / Q_SPLIT;         // waves that share the key tiles
+  constexpr int QT_PER = QT_TOTAL / Q_SPLIT;  // q-tiles per wave
+  constexpr int QROWS = QT_TOTAL * 32;
+  extern __shared__ __attribute__((aligned(16))) char fused_smem[];
+  uint16_t* q_s = reinterpret_cast<uint16_t*>(fused_smem);              // [QROWS][kPitchK]
+  float2* stats_s = reinterpret_cast<float2*>(q_s + QROWS * kPitchK);   // [KW][QROWS]
+  float* lse_s = reinterpret_cast<float*>(stats_s + KW * QROWS);        // [QROWS]
+  float* part_s = lse_s + QROWS;                                        // [Q_SPLIT][32 * tiles]
+
+  const int tid = threadIdx.x, lane = tid % 64, w = tid / 64;
+  const int col = lane % 32, grp = lane / 32;
+  const int kw = w / Q_SPLIT, qh = w % Q_SPLIT;
+  const int g = blockIdx.x % dm.Hkv, bl = blockIdx.x / dm.Hkv, b = bl / dm.L, l = bl % dm.L;
+  const int n_c = ks.n_c, n = n_c + ks.c;
+  const int tiles = (n + 31) / 32;
+  const int total_rows = dm.G * rows;  // <= QROWS (the launcher guarantees it)
+  const float c2 = dm.scale * kLog2e;
+
+  for (int r = tid / 16; r < QROWS; r += WAVES * 4) {  // 16 threads per row, 16 bytes each
+    const int f = min(r, total_rows - 1);               // padding rows repeat the last row; never summed
+    const int hh = f / rows, t = f % rows;
+    const uint16_t* qp = unit_ptr(q, b, l, g * dm.G + hh) + static_cast<int64_t>(t) * q.ss + 8 * (tid % 16);
+    *reinterpret_cast<uint4*>(&q_s[r * kPitchK + 8 * (tid % 16)]) = *reinterpret_cast<const uint4*>(qp);
+  }
+  __syncthreads();
+
+  const uint16_t* k_cache_u = unit_ptr(ks.cache, b, l, g) + 8 * grp;
+  const uint16_t* k_chunk_u = unit_ptr(ks.chunk, b, l, g) + 8 * grp;
+  auto load_keys = [&](int kt, bf16x8 (&k_op)[8]) {
+    const int j = min(32 * kt + col, n - 1);
+    const uint16_t* kp = j < n_c ? k_cache_u + static_cast<int64_t>(j) * ks.cache.ss
+                                 : k_chunk_u + static_cast<int64_t>(j - n_c) * ks.chunk.ss;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      Pack8 p;
+      p.u = *reinterpret_cast<const uint4*>(kp + 16 * kk);
+      k_op[kk] = p.v;
+    }
+  };
+  auto logits = [&](const bf16x8 (&k_op)[8], int qt) {  // S^T tile: 32 keys x the 32 rows of q-tile qt
+    Pack8 qb[8];
+    const uint16_t* qrow = &q_s[(32 * qt + col) * kPitchK + 8 * grp];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) qb[kk].u = *reinterpret_cast<const uint4*>(qrow + 16 * kk);
+    f32x16 s_t;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s_t[i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) s_t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_op[kk], qb[kk].v, s_t, 0, 0, 0);
+    return s_t;
+  };
+
+  // ---- pass 1: row normalisers ----
+  float m_run[QT_PER], l_run[QT_PER];
+#pragma unroll
+  for (int x = 0; x < QT_PER; ++x) {
+    m_run[x] = -INFINITY;
+    l_run[x] = 0.f;
+  }
+  for (int kt = kw; kt < tiles; kt += KW) {
+    bf16x8 k_op[8];
+    load_keys(kt, k_op);
+    const int valid = n - 32 * kt;  // keys of the tile that exist (wave-uniform)
+#pragma unroll
+    for (int x = 0; x < QT_PER; ++x) {
+      const int qt = qh * QT_PER + x;
+      if (32 * qt >= total_rows) continue;  // wave-uniform
+      f32x16 s_t = logits(k_op, qt);
+      if (valid < 32) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (8 * (i / 4) + 4 * grp + (i % 4) >= valid) s_t[i] = -INFINITY;
+      }
+      float mx = s_t[0];
+#pragma unroll
+      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s_t[i]);
+      const float m_new = fmaxf(m_run[x], mx * c2);  // -inf only while the lane has seen no key at all
+      const float alpha = (m_new == m_run[x]) ? 1.f : __builtin_amdgcn_exp2f(m_run[x] - m_new);
+      const float m_sub = m_new == -INFINITY ? 0.f : m_new;
+      float psum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) psum += __builtin_amdgcn_exp2f(fmaf(s_t[i], c2, -m_sub));
+      l_run[x] = fmaf(l_run[x], alpha, psum);
+      m_run[x] = m_new;
+    }
+  }
+#pragma unroll
+  for (int x = 0; x < QT_PER; ++x) {  // the two lane halves saw different keys of every tile
+    const float m_o = __shfl_xor(m_run[x], 32, 64), l_o = __shfl_xor(l_run[x], 32, 64);
+    const float mm = fmaxf(m_run[x], m_o);
+    const float lt = l_run[x] * (m_run[x] == mm ? 1.f : __builtin_amdgcn_exp2f(m_run[x] - mm)) +
+                     l_o * (m_o == mm ? 1.f : __builtin_amdgcn_exp2f(m_o - mm));
+    if (grp == 0) stats_s[kw * QROWS + 32 * (qh * QT_PER + x) + col] = make_float2(mm, lt);
+  }
+  __syncthreads();
+  if (tid < QROWS) {
+    float v = INFINITY;  // padding rows contribute exp2(-inf) = 0
+    if (tid < total_rows) {
+      float mm = -INFINITY;
+#pragma unroll
+      for (int x = 0; x < KW; ++x) mm = fmaxf(mm, stats_s[x * QROWS + tid].x);
+      float lsum = 0.f;
+#pragma unroll
+      for (int x = 0; x < KW; ++x) {
+        const float2 ps = stats_s[x * QROWS + tid];
+        lsum += ps.y * (ps.x == mm ? 1.f : exp2f(ps.x - mm));
+      }
+      v = mm + log2f(lsum);
+    }
+    lse_s[tid] = v;
+  }
+  __syncthreads();
+
+  // ---- pass 2: column sums of exp2(s - normaliser) ----
+  float lse2[QT_PER];
+#pragma unroll
+  for (int x = 0; x < QT_PER; ++x) lse2[x] = lse_s[32 * (qh * QT_PER + x) + col];
+  for (int kt = kw; kt < tiles; kt += KW) {
+    bf16x8 k_op[8];
+    load_keys(kt, k_op);
+    float acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+    for (int x = 0; x < QT_PER; ++x) {
+      const int qt = qh * QT_PER + x;
+      if (32 * qt >= total_rows) continue;  // wave-uniform
+      const f32x16 s_t = logits(k_op, qt);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[i] += __builtin_amdgcn_exp2f(fmaf(s_t[i], c2, -lse2[x]));
+    }
+    const float tot = reduce16_over32(acc, col);  // value index col / 2 -> key 8 (i / 4) + 4 grp + (i % 4)
+    const int i = col >> 1;
+    if ((col & 1) == 0) part_s[qh * 32 * tiles + 32 * kt + 8 * (i / 4) + 4 * grp + (i % 4)] = tot;
+  }
+  __syncthreads();
+  float* dst = score + (static_cast<int64_t>(bl) * dm.Hkv + g) * n;
+  for (int j = tid; j < n; j += WAVES * 64) {
+    float v = part_s[j];
+#pragma unroll
+    for (int x = 1; x < Q_SPLIT; ++x) v += part_s[x * 32 * tiles + j];
+    dst[j] = v;
+  }
+}
+
+template <int QT_TOTAL, int Q_SPLIT, int WAVES>
+size_t instr_fused_lds_bytes(int n) {
+  constexpr int QROWS = QT_TOTAL * 32;
+  const int tiles = (n + 31) / 32;
+  return static_cast<size_t>(QROWS) * kPitchK * 2 + static_cast<size_t>(WAVES / Q_SPLIT) * QROWS * 8 + QROWS * 4 +
+         static_cast<size_t>(Q_SPLIT) * 32 * tiles * 4;
+}
+
+template <int QT_TOTAL, int Q_SPLIT, int WAVES>
+hipError_t instr_fused_launch(const Dims& dm, View q, int rows, Segments ks, float* score, hipStream_t st) {
+  const size_t lds = instr_fused_lds_bytes<QT_TOTAL, Q_SPLIT, WAVES>(ks.n_c + ks.c);
+  auto kern = instr_fused_kernel<QT_TOTAL, Q_SPLIT, WAVES>;
+  static size_t allowed = 0;  // largest dynamic LDS size the kernel has been cleared for
+  if (lds > allowed) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    if (e != hipSuccess) return e;
+    allowed = lds;
+  }
+  hipLaunchKernelGGL(kern, dim3(dm.B * dm.L * dm.Hkv), dim3(WAVES * 64), lds, st, dm, q, rows, ks, score);
+  return hipGetLastError();
+}
+
+constexpr size_t kFusedLdsBudget = 150 * 1024;  // of the CU's 160 KB
+
 }  // namespace
 
 bool mfma_path_supported(int dtype, const Dims& dm) { return dtype == CITRUS_BF16 && dm.D == D; }
@@ -553,6 +751,12 @@ size_t instr_score_mfma_workspace_floats(const Dims& dm, int rows) {
 hipError_t launch_instr_score_mfma(const Dims& dm, View q, int rows, Segments ks, float* workspace, float* score,
                                    hipStream_t st) {
   const int n = ks.n_c + ks.c;
+  // few query rows per KV group (the usual case: a short instruction): one fused launch
+  const int total_rows = dm.G * rows;
+  if (total_rows <= 128 && instr_fused_lds_bytes<4, 1, 8>(n) <= kFusedLdsBudget)
+    return instr_fused_launch<4, 1, 8>(dm, q, rows, ks, score, st);
+  if (total_rows <= 256 && instr_fused_lds_bytes<8, 2, 16>(n) <= kFusedLdsBudget)
+    return instr_fused_launch<8, 2, 16>(dm, q, rows, ks, score, st);
   const int tiles = (n + kTileN - 1) / kTileN;
   int splits = (tiles + 3) / 4;  // about four key tiles per workgroup
   splits = splits < 1 ? 1 : (splits > kMaxKeySplits ? kMaxKeySplits : splits);

@@ -133,6 +133,7 @@ SHAPES = [
     ("bf16", 1, 1, 16, 2, 128, 130, 0, 64, 1.0),
     ("bf16", 1, 2, 4, 2, 64, 50, 77, 9, 0.5),
     ("bf16", 1, 1, 2, 1, 128, 1, 300, 1, 1.0),
+    ("bf16", 1, 2, 8, 2, 128, 45, 83, 37, 0.3),
 ]
 
 
