@@ -19,6 +19,8 @@
 // accumulators are directly the B operand (P^T) of the second product.
 #include "citrus_internal.h"
 
+#include <type_traits>
+
 namespace citrus {
 namespace {
 
@@ -67,6 +69,48 @@ __device__ inline const uint16_t* unit_ptr(const View& v, int b, int l, int h) {
 __device__ inline i16x4 lds_read_tr16(const char* p) {
   typedef i16x4 __attribute__((address_space(3))) * lds_ptr;
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+}
+
+// Instructions whose issue ORDER matters (a software pipeline that overlaps the matrix pipe with
+// the exponentials inside one wave) are written as volatile asm statements: the compiler keeps
+// volatile statements in source order and allocates their registers, but does not see inside
+// them, so the software-managed hazards are handled here: v_exp_f32 is followed by the one wait
+// state a non-transcendental consumer needs, and no vector instruction may read an MFMA result
+// sooner than the MFMA takes to complete (callers keep a whole MFMA group in between).
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+__device__ inline void mfma_pinned(f32x16& acc, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
+               : "+v"(acc)
+               : "v"(__builtin_bit_cast(i32x4, a)), "v"(__builtin_bit_cast(i32x4, b)));
+}
+__device__ inline f32x16 mfma_pinned_first(const bf16x8& a, const bf16x8& b) {  // accumulator starts at zero
+  f32x16 d;
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0"
+               : "=&v"(d)
+               : "v"(__builtin_bit_cast(i32x4, a)), "v"(__builtin_bit_cast(i32x4, b)));
+  return d;
+}
+__device__ inline float exp2_pinned(float x) {
+  float y;
+  asm volatile("v_exp_f32 %0, %1\n\ts_nop 0" : "=v"(y) : "v"(x));
+  return y;
+}
+
+// v_exp_f32 followed by an MFMA that does not read its result: the MFMA is the wait state.
+__device__ inline float exp2_then_mfma(float x, f32x16& acc, const bf16x8& a, const bf16x8& b) {
+  float y;
+  asm volatile("v_exp_f32 %0, %2\n\tv_mfma_f32_32x32x16_bf16 %1, %3, %4, %1"
+               : "=&v"(y), "+v"(acc)
+               : "v"(x), "v"(__builtin_bit_cast(i32x4, a)), "v"(__builtin_bit_cast(i32x4, b)));
+  return y;
+}
+
+// Barrier that publishes tiles streamed into LDS by buffer_load ... lds.  Those writes are tracked
+// by the issuing wave's vector-memory counter only, and the fence inside __syncthreads() covers
+// ordinary LDS traffic: every wave has to drain its own loads before it arrives.
+__device__ inline void barrier_after_lds_fill() {
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), nothing else
+  __syncthreads();
 }
 
 // How the waves of a block split (head, 32-row tile) tasks inside one KV group.
@@ -227,10 +271,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
 
   if (t_begin < t_end) {  // block-uniform
   CITRUS_FETCH_TILE(t_begin * kTileN, 0);
-  __syncthreads();
-  // All loads issued so far (the Q operand among them) have landed: say so explicitly, otherwise
-  // the first MFMA of every iteration waits for the tile prefetch issued just before it.
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+  barrier_after_lds_fill();  // also: the Q operand loads have landed
 
   for (int jt = t_begin; jt < t_end; ++jt) {
     const int j0 = jt * kTileN;
@@ -343,8 +384,392 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
       }
     }
 
-    __syncthreads();  // publishes the tile that streamed in; everyone is done with this one
+    barrier_after_lds_fill();  // publishes the tile that streamed in; everyone is done with this one
   }
+  }
+
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const int t = row0 + col;
+  if (wave_active && t < rows) {
+  const int64_t row_id = (static_cast<int64_t>(bl) * dm.Hq + h) * rows + t;
+  if (part != nullptr && grp == 0)  // log2 domain; an empty or fully masked range leaves (-inf, 0)
+    part[static_cast<int64_t>(sp) * dm.B * dm.L * dm.Hq * rows + row_id] = make_float2(m_run, l_tot);
+  if (lse != nullptr && grp == 0) lse[row_id] = (m_run + log2f(l_tot)) * kLn2;
+  if (HAS_PV) {
+    const float inv = 1.f / l_tot;
+    uint16_t* op = const_cast<uint16_t*>(unit_ptr(out, b, l, h)) + static_cast<int64_t>(t) * out.ss;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        // registers 4 i4 .. +3 are rows c' = 8 i4 + 4 grp + 0..3 -> head_dim 16 r + (c' % 16) + 64 (c' / 16)
+        const int c0 = 8 * i4 + 4 * grp;
+        const int d0 = 16 * r + (c0 % 16) + 64 * (c0 / 16);
+        uint2 wds;
+        wds.x = pack_bf16x2(o_acc[r][4 * i4] * inv, o_acc[r][4 * i4 + 1] * inv);
+        wds.y = pack_bf16x2(o_acc[r][4 * i4 + 2] * inv, o_acc[r][4 * i4 + 3] * inv);
+        *reinterpret_cast<uint2*>(op + d0) = wds;
+      }
+  }
+  }  // row valid
+  }  // pass
+}
+
+// The same attention, with output, as a software pipeline over half tiles of 32 keys: in step h the
+// MFMAs of S^T(h + 1) = K.Q^T and of O^T += V^T.P^T(h - 1) are issued between the exponentials of
+// half tile h, so that inside ONE wave the matrix pipe, the vector pipe and the LDS reads run at
+// the same time instead of taking turns (the scheduler is told the order with group directives).
+// K tiles are fetched one 64-key tile further ahead than V tiles; one barrier per 64 keys.
+__global__ __launch_bounds__(kThreads, 2) void attn_pipe_kernel(Dims dm, View q, int rows, Segments ks, Segments vs,
+                                                               int causal, View out, float* lse) {
+  constexpr bool HAS_PV = true;
+  constexpr int key_splits = 1;
+  float2* const part = nullptr;
+  __shared__ __attribute__((aligned(1024))) char k_s[2 * kTileBytes];  // double-buffered tiles
+  __shared__ __attribute__((aligned(1024))) char v_s[HAS_PV ? 2 * kTileBytes : 16];
+
+  const int tid = threadIdx.x, lane = tid % 64, w = tid / 64;
+  const int col = lane % 32, grp = lane / 32;
+  const TaskShape ts = task_shape(dm.G);
+  const int head_groups = dm.G / ts.heads_per_block;
+  const int rows_per_block = ts.tiles_per_block * kRowsPerWave;
+  const int row_blocks = (rows + rows_per_block - 1) / rows_per_block;
+  // Workgroups are handed to the 8 XCDs round-robin by their linear id.  Remap so that the
+  // workgroups of one (document, layer, KV head), which read the same K/V, land on ONE XCD and
+  // share its L2; within a unit the row blocks with the longest causal range come first.
+  int logical = blockIdx.x;
+  const int total = gridDim.x;
+  if (total % kXcds == 0) logical = (blockIdx.x % kXcds) * (total / kXcds) + blockIdx.x / kXcds;
+  // With key_splits > 1 (log-sum-exp only) each workgroup covers one contiguous range of key
+  // tiles and writes a partial (running maximum, sum) pair per row; the consumer merges them.
+  const int sp = logical % key_splits;
+  logical /= key_splits;
+  // Causal attention: a workgroup takes the row block with the longest key range still free and then
+  // its mirror image (the shortest), so every workgroup does the same number of key tiles.
+  const bool paired = causal != 0 && key_splits == 1;
+  const int rb_slots = paired ? (row_blocks + 1) / 2 : row_blocks;
+  const int rb_first = row_blocks - 1 - logical % rb_slots;
+  const int rb_second = row_blocks - 1 - rb_first;
+  const int passes = (paired && rb_second != rb_first) ? 2 : 1;
+  const int hg = (logical / rb_slots) % head_groups;
+  const int g = (logical / (rb_slots * head_groups)) % dm.Hkv;
+  const int bl = logical / (rb_slots * head_groups * dm.Hkv);
+  const int b = bl / dm.L, l = bl % dm.L;
+  const int h = g * dm.G + hg * ts.heads_per_block + (w % ts.heads_per_block);
+  const int n_c = ks.n_c;
+  const int n = n_c + ks.c;
+
+  // ---- global -> LDS staging of one 64-key tile, without a stop in registers ----
+  // buffer_load ... lds: a wave-level instruction moves 64 x 16 B from per-lane global addresses
+  // to 1 KB of consecutive LDS, i.e. four unpadded 256-byte rows.  Bank conflicts of the column
+  // reads below are avoided by an XOR swizzle instead of padding: the 16-byte segment `seg` of
+  // tile row `row` lives at segment position seg ^ f(row), f(row) = 2 (row % 8) ^ ((row / 8) % 2),
+  // which the loading lane realises by fetching global segment (its LDS position) ^ f(row).
+  // Wave w fills rows 16 w + 4 i .. + 3 with instruction i = 0..3.  Rows that fall outside the
+  // candidates re-read the last row (finite values; their logits are masked).
+  const int k_ss_cache = static_cast<int>(ks.cache.ss), k_ss_chunk = static_cast<int>(ks.chunk.ss);
+  const int v_ss_cache = static_cast<int>(vs.cache.ss), v_ss_chunk = static_cast<int>(vs.chunk.ss);
+  auto seg_bytes = [](int rows_, int ss_) { return rows_ > 0 ? ((rows_ - 1) * ss_ + D) * 2 : 0; };
+  const __amdgpu_buffer_rsrc_t k_rs_cache = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(unit_ptr(ks.cache, b, l, g)), 0, seg_bytes(n_c, k_ss_cache), kBufferFlags);
+  const __amdgpu_buffer_rsrc_t k_rs_chunk = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(unit_ptr(ks.chunk, b, l, g)), 0, seg_bytes(ks.c, k_ss_chunk), kBufferFlags);
+  const __amdgpu_buffer_rsrc_t v_rs_cache = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(unit_ptr(HAS_PV ? vs.cache : ks.cache, b, l, g)), 0, seg_bytes(n_c, v_ss_cache), kBufferFlags);
+  const __amdgpu_buffer_rsrc_t v_rs_chunk = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(unit_ptr(HAS_PV ? vs.chunk : ks.chunk, b, l, g)), 0, seg_bytes(ks.c, v_ss_chunk), kBufferFlags);
+  const int wu = __builtin_amdgcn_readfirstlane(w);
+  const int fill_row_c = 16 * wu + lane / 16;                       // tile row this lane fills with instruction 0
+  const int fill_seg16_c = ((lane % 16) ^ (2 * (lane / 16))) * 16;  // byte offset of its global segment, before ^ c_i
+  typedef __attribute__((address_space(3))) void* lds_void_ptr;
+  auto fill4 = [&](char* lds_tile, __amdgpu_buffer_rsrc_t rs_cache, __amdgpu_buffer_rsrc_t rs_chunk, int ss_cache,
+                   int ss_chunk, int j0) {
+    const bool simple = (j0 + kTileN <= n_c) || (j0 >= n_c && j0 + kTileN <= n);  // block-uniform
+    // the per-lane offsets are recomputed at every fill: hoisted out of the loop they would occupy
+    // registers the pipeline needs (the empty asm hides their loop invariance from the optimiser)
+    int fill_row = fill_row_c, fill_seg16 = fill_seg16_c;
+    asm volatile("" : "+v"(fill_row), "+v"(fill_seg16));
+    if (simple) {  // the whole tile lies in one segment: one resource, scalar row offsets
+      const bool in_cache = j0 < n_c;
+      const __amdgpu_buffer_rsrc_t rs = in_cache ? rs_cache : rs_chunk;
+      const int ss2 = (in_cache ? ss_cache : ss_chunk) * 2;
+      const int r0 = in_cache ? j0 : j0 - n_c;
+      const int row_off = fill_row * ss2;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_ptr)(lds_tile + (16 * wu + 4 * i) * kRowBytes), 16,
+                                                 row_off + (fill_seg16 ^ (((8 * (i & 1)) | (i >> 1)) * 16)),
+                                                 (r0 + 4 * i) * ss2, 0, 0);
+    } else {  // the tile straddles the cache / chunk boundary or the end of the candidates
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        lds_void_ptr dst = (lds_void_ptr)(lds_tile + (16 * wu + 4 * i) * kRowBytes);
+        const int seg = fill_seg16 ^ (((8 * (i & 1)) | (i >> 1)) * 16);
+        const int j = min(j0 + fill_row + 4 * i, n - 1);
+        if (j < n_c)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_cache, dst, 16, j * ss_cache * 2 + seg, 0, 0, 0);
+        else
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_chunk, dst, 16, (j - n_c) * ss_chunk * 2 + seg, 0, 0, 0);
+      }
+    }
+  };
+
+  // per-lane LDS read offsets (bytes inside a tile buffer), swizzle included
+  // A operand of S^T: key row `col`, head_dim segment 2 kk + grp
+  const int f_col = (2 * (col & 7)) ^ ((col >> 3) & 1);
+  // k_off(kk) = col * kRowBytes + ((2 kk + grp) ^ f_col) * 16 = k_off0 ^ (32 kk): one register instead of eight
+  const int k_off0 = col * kRowBytes + ((grp ^ f_col) * 16);
+  auto k_off = [&](int kk) { return k_off0 ^ (32 * kk); };
+  // V^T operand through transpose reads.  The 16-lane group q16 = lane / 16 serves MFMA rows
+  // 16 (q16 % 2) .. +15 for contraction lane group q16 / 2; output row c' of tile r is head_dim
+  // 16 r + (c' % 16) + 64 (c' / 16).  Source lane s16 points at 4 consecutive head_dim values of key
+  // row 4 (q16 / 2) + s16 / 4 (+ 8 rd + 16 half + 32 mt): segment 2 r + 8 (q16 % 2) + (s16 % 4) / 2.
+  const int s16 = lane % 16, q16 = lane / 16;
+  const int v_cl = (8 * (q16 % 2) + (s16 % 4) / 2) ^ (8 * (q16 / 2) + 2 * (s16 / 4));
+  // v_off(e), e = 2 r + rd (f(row) of read rd differs from read 0 by ^ rd), = v_off0 ^ (16 e)
+  const int v_off0 = (4 * (q16 / 2) + s16 / 4) * kRowBytes + (v_cl * 16) + 8 * (s16 % 2);
+  auto v_off = [&](int e) { return v_off0 ^ (16 * e); };
+
+  for (int pass = 0; pass < passes; ++pass) {
+  const int rb = pass == 0 ? rb_first : rb_second;
+  const int row0 = (rb * ts.tiles_per_block + w / ts.heads_per_block) * kRowsPerWave;
+
+  // last candidate any row of this block / this wave can see
+  const int blk_row_last = min(rows, (rb + 1) * rows_per_block) - 1;
+  const int blk_limit = causal ? n_c + blk_row_last : n - 1;
+  const int all_tiles = blk_limit / kTileN + 1;
+  const int tiles_per_split = (all_tiles + key_splits - 1) / key_splits;
+  const int t_begin = sp * tiles_per_split;
+  const int t_end = min(all_tiles, t_begin + tiles_per_split);
+  const bool wave_active = row0 < rows;
+  const int wave_row_last = min(rows, row0 + kRowsPerWave) - 1;
+  const int wave_limit_max = causal ? n_c + wave_row_last : n - 1;  // beyond it the wave sees nothing
+  const int wave_limit_min = causal ? n_c + row0 : n - 1;           // up to it every row sees everything
+
+  // ---- Q^T operand, kept in registers: q_op[kk] = Q[row0 + col][16 kk + 8 grp ..+7] ----
+  bf16x8 q_op[8];
+  const int t_lane = max(min(row0 + col, rows - 1), 0);
+  {
+    const uint16_t* qp = unit_ptr(q, b, l, h) + static_cast<int64_t>(t_lane) * q.ss + 8 * grp;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      Pack8 p;
+      p.u = *reinterpret_cast<const uint4*>(qp + 16 * kk);
+      q_op[kk] = p.v;
+    }
+  }
+  const int limit_lane = causal ? n_c + t_lane : n - 1;
+
+  // ---- running softmax state: one query per lane ----
+  const float c2 = dm.scale * kLog2e;  // logits are kept in the log2 domain
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x16 o_acc[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o_acc[r][i] = 0.f;
+
+  // fetch of one 64-key tile of K or of V into buffer (tile - t_begin) % 2
+  auto fetch_k = [&](int tile) {
+    fill4(k_s + ((tile - t_begin) & 1) * kTileBytes, k_rs_cache, k_rs_chunk, k_ss_cache, k_ss_chunk, tile * kTileN);
+  };
+  auto fetch_v = [&](int tile) {
+    fill4(v_s + ((tile - t_begin) & 1) * kTileBytes, v_rs_cache, v_rs_chunk, v_ss_cache, v_ss_chunk, tile * kTileN);
+  };
+  // A tile that lies inside one segment is fetched with four instructions that differ only in
+  // scalar operands; such fetches can be issued one by one between the MFMAs of a step.
+  struct FillPlan {
+    __amdgpu_buffer_rsrc_t rs;
+    char* lds;    // first row this wave fills
+    int soff;     // byte offset of instruction 0's first row inside the segment
+    int ss8;      // bytes between the rows of consecutive instructions (4 rows)
+    int row_off;  // per lane: its row inside the instruction's four rows, in bytes
+    int seg16;    // per lane: byte offset of its 16-byte segment before the per-instruction swizzle term
+  };
+  auto tile_is_simple = [&](int tile) {
+    const int j0 = tile * kTileN;
+    return (j0 + kTileN <= n_c) || (j0 >= n_c && j0 + kTileN <= n);
+  };
+  auto plan_fill = [&](char* buffers, int tile, __amdgpu_buffer_rsrc_t rs_cache, __amdgpu_buffer_rsrc_t rs_chunk,
+                       int ss_cache, int ss_chunk) {
+    const int j0 = tile * kTileN;
+    const bool in_cache = j0 < n_c;
+    const int ss2 = (in_cache ? ss_cache : ss_chunk) * 2;
+    int fill_row = lane / 16, fill_seg16 = fill_seg16_c;
+    asm volatile("" : "+v"(fill_row), "+v"(fill_seg16));  // formed per fetch: see fill4
+    FillPlan fp;
+    fp.rs = in_cache ? rs_cache : rs_chunk;
+    fp.lds = buffers + ((tile - t_begin) & 1) * kTileBytes + 16 * wu * kRowBytes;
+    fp.soff = ((in_cache ? j0 : j0 - n_c) + 16 * wu) * ss2;
+    fp.ss8 = 4 * ss2;
+    fp.row_off = fill_row * ss2;
+    fp.seg16 = fill_seg16;
+    return fp;
+  };
+  auto fill_one = [&](const FillPlan& fp, int i) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(fp.rs, (lds_void_ptr)(fp.lds + 4 * i * kRowBytes), 16,
+                                             fp.row_off + (fp.seg16 ^ (((8 * (i & 1)) | (i >> 1)) * 16)),
+                                             fp.soff + i * fp.ss8, 0, 0);
+  };
+
+  const int h_first = 2 * t_begin, h_last = 2 * t_end - 1;  // half tiles of 32 keys (block-uniform)
+  f32x16 s_cur;            // logits of the half tile whose probabilities are computed next
+  uint32_t p_prev[8];      // bf16 probabilities of the half tile before it, not yet multiplied with V
+  Pack8 ka[8];             // K operand of the next logit product, read one step ahead
+#pragma unroll
+  for (int x = 0; x < 8; ++x) p_prev[x] = 0u;
+  auto read_k_ops = [&](int hn_raw) {  // half tile hn_raw, clamped to the last one
+    const int hn = min(hn_raw, h_last);
+    const char* k_t = k_s + (((hn >> 1) - t_begin) & 1) * kTileBytes + (hn & 1) * 32 * kRowBytes;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) ka[kk].u = *reinterpret_cast<const uint4*>(k_t + k_off(kk));
+  };
+
+  // One step: finish the softmax of half tile h (logits in s_cur) while the logits of h + 1 and the
+  // product P(h - 1).V run on the matrix pipe.  Past either end the neighbour is clamped: the
+  // logits computed past the end are never used, and p_prev is zero before the first step.
+  // With FILL the eight fetch instructions of the plans are issued between the MFMAs.
+  auto half_step = [&](int hc, auto fill_tag, const FillPlan& fk, const FillPlan& fv) {
+    constexpr bool FILL = decltype(fill_tag)::value;
+    const int jb = 32 * hc;
+    if (jb + 31 > wave_limit_min) {  // wave-uniform: the causal edge and the ragged end only
+      const int lim_rel = limit_lane - jb - 4 * grp;
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        if (8 * (i / 4) + (i % 4) > lim_rel) s_cur[i] = -INFINITY;
+    }
+    // Running maximum, kept lazily: softmax is invariant to the subtracted value, so m_run only has
+    // to stay within kMaxSlack (log2 units) of the true row maximum to keep exp2 in range.
+    float mx = s_cur[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s_cur[i]);
+    if (__any(mx * c2 > m_run + kMaxSlack)) {  // wave-uniform and rare after the first tiles
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run, mx * c2);
+      // 0 on a row's first visible tile (m_run = -inf); 1 for a row that has seen nothing yet
+      const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
+      l_run *= alpha;
+      // the last P.V MFMAs of the previous step may still be in flight and the compiler cannot see them
+      asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o_acc[r][i] *= alpha;
+      // the probabilities still waiting for their product with V were taken against the old maximum
+#pragma unroll
+      for (int x = 0; x < 8; ++x) {
+        const float lo = __uint_as_float(p_prev[x] << 16), hi = __uint_as_float(p_prev[x] & 0xffff0000u);
+        p_prev[x] = pack_bf16x2(lo * alpha, hi * alpha);
+      }
+      m_run = m_new;
+    }
+    const int hp = max(hc - 1, h_first);
+    const char* v_t = v_s + (((hp >> 1) - t_begin) & 1) * kTileBytes + (hp & 1) * 32 * kRowBytes;
+    const float m_sub = m_run == -INFINITY ? 0.f : m_run;  // a row that has seen nothing yet: exp2(-inf) = 0
+    __builtin_amdgcn_sched_barrier(0);
+
+    // O^T += V^T . P^T: contraction step `half` covers keys 16 half .. +15 of the half tile in the slot
+    // order the S^T accumulators have: slot i of lane group grp is key 8 (i / 4) + 4 grp + (i % 4) of
+    // the step, so slots 0..3 / 4..7 are two transpose reads.
+    Pack8 va[2][4];
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int rd = 0; rd < 2; ++rd)
+          va[half][r].h[rd] = lds_read_tr16(v_t + (16 * half + 8 * rd) * kRowBytes + v_off(2 * r + rd));
+    // sixteen MFMAs; the exponential of logit x of half tile h is issued right before MFMA x + 1
+    float p[16];
+    f32x16 s_nxt = mfma_pinned_first(ka[0].v, q_op[0]);
+#pragma unroll
+    for (int kk = 1; kk < 8; ++kk) {
+      p[kk - 1] = exp2_then_mfma(fmaf(s_cur[kk - 1], c2, -m_sub), s_nxt, ka[kk].v, q_op[kk]);
+      if (FILL && (kk & 1)) fill_one(fk, kk / 2);
+    }
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      Pack8 pb;
+#pragma unroll
+      for (int x = 0; x < 4; ++x) pb.w[x] = p_prev[4 * half + x];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int x = 7 + 4 * half + r;
+        p[x] = exp2_then_mfma(fmaf(s_cur[x], c2, -m_sub), o_acc[r], va[half][r].v, pb.v);
+        if (FILL && (r & 1)) fill_one(fv, 2 * half + r / 2);
+      }
+    }
+    p[15] = exp2_pinned(fmaf(s_cur[15], c2, -m_sub));
+    // the row sum is taken over the bf16-rounded probabilities, the values P.V uses: one v_dot2
+    // with (1, 1) adds a pair
+    uint32_t p_cur[8];
+    float psum = 0.f;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+      p_cur[x] = pack_bf16x2(p[2 * x], p[2 * x + 1]);
+      psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, p_cur[x]),
+                                             __builtin_bit_cast(bf16x2, 0x3f803f80u), psum, false);
+    }
+    l_run += psum;
+    // keep the probabilities in this block: without a use here the optimiser sinks the exponentials
+    // to their first use in the next step, behind the MFMAs they are meant to overlap with
+    asm volatile("" : "+v"(p_cur[0]), "+v"(p_cur[1]), "+v"(p_cur[2]), "+v"(p_cur[3]), "+v"(p_cur[4]), "+v"(p_cur[5]),
+                 "+v"(p_cur[6]), "+v"(p_cur[7]), "+v"(l_run));
+    __builtin_amdgcn_sched_barrier(0);
+    s_cur = s_nxt;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) p_prev[x] = p_cur[x];
+  };
+  const FillPlan no_plan{};
+
+  if (t_begin < t_end) {  // block-uniform
+  fetch_k(t_begin);
+  fetch_v(t_begin);
+  if (t_begin + 1 < t_end) fetch_k(t_begin + 1);
+  barrier_after_lds_fill();  // also: the Q operand loads have landed
+  read_k_ops(h_first);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s_cur[i] = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk)  // logits of the first half tile
+    s_cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk].v, q_op[kk], s_cur, 0, 0, 0);
+  read_k_ops(h_first + 1);
+  for (int jt = t_begin; jt < t_end; ++jt) {
+    half_step(2 * jt, std::false_type{}, no_plan, no_plan);
+    // Every wave has read the second half of K tile jt and the last of V tile jt - 1: their buffers
+    // take K tile jt + 2 and V tile jt + 1, which are first read after the next barrier.
+    barrier_after_lds_fill();
+    read_k_ops(2 * jt + 2);  // first half of K tile jt + 1, published by this barrier
+    const bool want_k = jt + 2 < t_end, want_v = jt + 1 < t_end;
+    if (false && want_k && want_v && tile_is_simple(jt + 2) && tile_is_simple(jt + 1)) {  // block-uniform
+      const FillPlan fk = plan_fill(k_s, jt + 2, k_rs_cache, k_rs_chunk, k_ss_cache, k_ss_chunk);
+      const FillPlan fv = plan_fill(v_s, jt + 1, v_rs_cache, v_rs_chunk, v_ss_cache, v_ss_chunk);
+      half_step(2 * jt + 1, std::true_type{}, fk, fv);
+    } else {
+      if (want_k) fetch_k(jt + 2);
+      if (want_v) fetch_v(jt + 1);
+      half_step(2 * jt + 1, std::false_type{}, no_plan, no_plan);
+    }
+    read_k_ops(2 * jt + 3);  // second half of K tile jt + 1
+  }
+  {  // the product of the last half tile
+    const char* v_t = v_s + ((t_end - 1 - t_begin) & 1) * kTileBytes + 32 * kRowBytes;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      Pack8 va[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int rd = 0; rd < 2; ++rd)
+          va[r].h[rd] = lds_read_tr16(v_t + (16 * half + 8 * rd) * kRowBytes + v_off(2 * r + rd));
+      Pack8 pb;
+#pragma unroll
+      for (int x = 0; x < 4; ++x) pb.w[x] = p_prev[4 * half + x];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) o_acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[r].v, pb.v, o_acc[r], 0, 0, 0);
+    }
+  }
+  __syncthreads();  // the buffers are free for the next row block
   }
 
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -724,8 +1149,7 @@ hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments ks, Segme
   const int rb_slots = (causal && key_splits == 1) ? (row_blocks + 1) / 2 : row_blocks;  // paired row blocks
   dim3 grid(rb_slots * (dm.G / ts.heads_per_block) * dm.Hkv * dm.B * dm.L * key_splits);
   if (out.ptr != nullptr)
-    hipLaunchKernelGGL((attn_mfma_kernel<true>), grid, dim3(kThreads), 0, st, dm, q, rows, ks, vs, causal, out, lse,
-                       key_splits, part);
+    hipLaunchKernelGGL(attn_pipe_kernel, grid, dim3(kThreads), 0, st, dm, q, rows, ks, vs, causal, out, lse);
   else
     hipLaunchKernelGGL((attn_mfma_kernel<false>), grid, dim3(kThreads), 0, st, dm, q, rows, ks, vs, causal, out, lse,
                        key_splits, part);
