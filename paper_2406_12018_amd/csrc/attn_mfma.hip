@@ -19,7 +19,6 @@
 // accumulators are directly the B operand (P^T) of the second product.
 #include "citrus_internal.h"
 
-#include <type_traits>
 
 namespace citrus {
 namespace {
@@ -105,6 +104,15 @@ __device__ inline float exp2_then_mfma(float x, f32x16& acc, const bf16x8& a, co
   return y;
 }
 
+// Small fences for the optimiser, as functions so that kernel templates hold no asm of their own.
+__device__ inline void hide_loop_invariance(int& a, int& b) { asm volatile("" : "+v"(a), "+v"(b)); }
+__device__ inline void keep_values_here(uint32_t (&p)[8], float& l) {
+  asm volatile("" : "+v"(p[0]), "+v"(p[1]), "+v"(p[2]), "+v"(p[3]), "+v"(p[4]), "+v"(p[5]), "+v"(p[6]), "+v"(p[7]), "+v"(l));
+}
+__device__ inline void no_memory_motion() { asm volatile("" ::: "memory"); }
+// enough wait states for every MFMA issued through the pinned helpers above to have written its result
+__device__ inline void wait_for_pinned_mfmas() { asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory"); }
+
 // Barrier that publishes tiles streamed into LDS by buffer_load ... lds.  Those writes are tracked
 // by the issuing wave's vector-memory counter only, and the fence inside __syncthreads() covers
 // ordinary LDS traffic: every wave has to drain its own loads before it arrives.
@@ -118,9 +126,9 @@ struct TaskShape {
   int heads_per_block;  // 4, 2 or 1 query heads of the group
   int tiles_per_block;  // kWaves / heads_per_block row tiles of 32
 };
-__host__ __device__ inline TaskShape task_shape(int G) {
+__host__ __device__ inline TaskShape task_shape(int G, int waves = kWaves) {
   const int hpb = (G % 4 == 0) ? 4 : ((G % 2 == 0) ? 2 : 1);
-  return TaskShape{hpb, kWaves / hpb};
+  return TaskShape{hpb, waves / hpb};
 }
 
 template <bool HAS_PV>
@@ -420,8 +428,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
 // half tile h, so that inside ONE wave the matrix pipe, the vector pipe and the LDS reads run at
 // the same time instead of taking turns (the scheduler is told the order with group directives).
 // K tiles are fetched one 64-key tile further ahead than V tiles; one barrier per 64 keys.
-__global__ __launch_bounds__(kThreads, 2) void attn_pipe_kernel(Dims dm, View q, int rows, Segments ks, Segments vs,
-                                                               int causal, View out, float* lse) {
+template <int WAVES>
+__device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, int rows, const Segments& ks,
+                                               const Segments& vs, int causal, const View& out, float* lse) {
   constexpr bool HAS_PV = true;
   constexpr int key_splits = 1;
   float2* const part = nullptr;
@@ -430,7 +439,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_pipe_kernel(Dims dm, View q,
 
   const int tid = threadIdx.x, lane = tid % 64, w = tid / 64;
   const int col = lane % 32, grp = lane / 32;
-  const TaskShape ts = task_shape(dm.G);
+  constexpr int kFillRows = kTileN / WAVES;  // rows of a tile each wave fetches: 4 per instruction
+  constexpr int kFillInstr = kFillRows / 4;
+  const TaskShape ts = task_shape(dm.G, WAVES);
   const int head_groups = dm.G / ts.heads_per_block;
   const int rows_per_block = ts.tiles_per_block * kRowsPerWave;
   const int row_blocks = (rows + rows_per_block - 1) / rows_per_block;
@@ -479,8 +490,13 @@ __global__ __launch_bounds__(kThreads, 2) void attn_pipe_kernel(Dims dm, View q,
   const __amdgpu_buffer_rsrc_t v_rs_chunk = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint16_t*>(unit_ptr(HAS_PV ? vs.chunk : ks.chunk, b, l, g)), 0, seg_bytes(ks.c, v_ss_chunk), kBufferFlags);
   const int wu = __builtin_amdgcn_readfirstlane(w);
-  const int fill_row_c = 16 * wu + lane / 16;                       // tile row this lane fills with instruction 0
+  const int fill_row_c = kFillRows * wu + lane / 16;                // tile row this lane fills with instruction 0
   const int fill_seg16_c = ((lane % 16) ^ (2 * (lane / 16))) * 16;  // byte offset of its global segment, before ^ c_i
+  // instruction i covers rows r = kFillRows wu + 4 i .. + 3; the lane-independent part of f(row)
+  auto swz16 = [&](int i) {
+    const int r = kFillRows * wu + 4 * i;
+    return ((2 * (r % 8)) ^ ((r / 8) % 2)) * 16;
+  };
   typedef __attribute__((address_space(3))) void* lds_void_ptr;
   auto fill4 = [&](char* lds_tile, __amdgpu_buffer_rsrc_t rs_cache, __amdgpu_buffer_rsrc_t rs_chunk, int ss_cache,
                    int ss_chunk, int j0) {
@@ -488,7 +504,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_pipe_kernel(Dims dm, View q,
     // the per-lane offsets are recomputed at every fill: hoisted out of the loop they would occupy
     // registers the pipeline needs (the empty asm hides their loop invariance from the optimiser)
     int fill_row = fill_row_c, fill_seg16 = fill_seg16_c;
-    asm volatile("" : "+v"(fill_row), "+v"(fill_seg16));
+    hide_loop_invariance(fill_row, fill_seg16);
     if (simple) {  // the whole tile lies in one segment: one resource, scalar row offsets
       const bool in_cache = j0 < n_c;
       const __amdgpu_buffer_rsrc_t rs = in_cache ? rs_cache : rs_chunk;
@@ -496,15 +512,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_pipe_kernel(Dims dm, View q,
       const int r0 = in_cache ? j0 : j0 - n_c;
       const int row_off = fill_row * ss2;
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_ptr)(lds_tile + (16 * wu + 4 * i) * kRowBytes), 16,
-                                                 row_off + (fill_seg16 ^ (((8 * (i & 1)) | (i >> 1)) * 16)),
-                                                 (r0 + 4 * i) * ss2, 0, 0);
+      for (int i = 0; i < kFillInstr; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_ptr)(lds_tile + (kFillRows * wu + 4 * i) * kRowBytes), 16,
+                                                 row_off + (fill_seg16 ^ swz16(i)), (r0 + 4 * i) * ss2, 0, 0);
     } else {  // the tile straddles the cache / chunk boundary or the end of the candidates
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        lds_void_ptr dst = (lds_void_ptr)(lds_tile + (16 * wu + 4 * i) * kRowBytes);
-        const int seg = fill_seg16 ^ (((8 * (i & 1)) | (i >> 1)) * 16);
+      for (int i = 0; i < kFillInstr; ++i) {
+        lds_void_ptr dst = (lds_void_ptr)(lds_tile + (kFillRows * wu + 4 * i) * kRowBytes);
+        const int seg = fill_seg16 ^ swz16(i);
         const int j = min(j0 + fill_row + 4 * i, n - 1);
         if (j < n_c)
           __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_cache, dst, 16, j * ss_cache * 2 + seg, 0, 0, 0);
@@ -596,11 +611,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_pipe_kernel(Dims dm, View q,
     const bool in_cache = j0 < n_c;
     const int ss2 = (in_cache ? ss_cache : ss_chunk) * 2;
     int fill_row = lane / 16, fill_seg16 = fill_seg16_c;
-    asm volatile("" : "+v"(fill_row), "+v"(fill_seg16));  // formed per fetch: see fill4
+    hide_loop_invariance(fill_row, fill_seg16);  // formed per fetch: see fill4
     FillPlan fp;
     fp.rs = in_cache ? rs_cache : rs_chunk;
-    fp.lds = buffers + ((tile - t_begin) & 1) * kTileBytes + 16 * wu * kRowBytes;
-    fp.soff = ((in_cache ? j0 : j0 - n_c) + 16 * wu) * ss2;
+    fp.lds = buffers + ((tile - t_begin) & 1) * kTileBytes + kFillRows * wu * kRowBytes;
+    fp.soff = ((in_cache ? j0 : j0 - n_c) + kFillRows * wu) * ss2;
     fp.ss8 = 4 * ss2;
     fp.row_off = fill_row * ss2;
     fp.seg16 = fill_seg16;
@@ -608,7 +623,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_pipe_kernel(Dims dm, View q,
   };
   auto fill_one = [&](const FillPlan& fp, int i) {
     __builtin_amdgcn_raw_ptr_buffer_load_lds(fp.rs, (lds_void_ptr)(fp.lds + 4 * i * kRowBytes), 16,
-                                             fp.row_off + (fp.seg16 ^ (((8 * (i & 1)) | (i >> 1)) * 16)),
+                                             fp.row_off + (fp.seg16 ^ swz16(i)),
                                              fp.soff + i * fp.ss8, 0, 0);
   };
 
@@ -628,9 +643,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_pipe_kernel(Dims dm, View q,
   // One step: finish the softmax of half tile h (logits in s_cur) while the logits of h + 1 and the
   // product P(h - 1).V run on the matrix pipe.  Past either end the neighbour is clamped: the
   // logits computed past the end are never used, and p_prev is zero before the first step.
-  // With FILL the eight fetch instructions of the plans are issued between the MFMAs.
-  auto half_step = [&](int hc, auto fill_tag, const FillPlan& fk, const FillPlan& fv) {
-    constexpr bool FILL = decltype(fill_tag)::value;
+  // With fill_k / fill_v the four fetch instructions of that plan are issued between the MFMAs.
+  auto half_step = [&](int hc, bool fill_k, bool fill_v, const FillPlan& fk, const FillPlan& fv) {
     const int jb = 32 * hc;
     if (jb + 31 > wave_limit_min) {  // wave-uniform: the causal edge and the ragged end only
       const int lim_rel = limit_lane - jb - 4 * grp;
@@ -650,7 +664,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_pipe_kernel(Dims dm, View q,
       const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
       l_run *= alpha;
       // the last P.V MFMAs of the previous step may still be in flight and the compiler cannot see them
-      asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+      wait_for_pinned_mfmas();
 #pragma unroll
       for (int r = 0; r < 4; ++r)
 #pragma unroll
@@ -671,21 +685,29 @@ __global__ __launch_bounds__(kThreads, 2) void attn_pipe_kernel(Dims dm, View q,
     // O^T += V^T . P^T: contraction step `half` covers keys 16 half .. +15 of the half tile in the slot
     // order the S^T accumulators have: slot i of lane group grp is key 8 (i / 4) + 4 grp + (i % 4) of
     // the step, so slots 0..3 / 4..7 are two transpose reads.
+    // The V^T operands of the second contraction step are read once half of the K operands are
+    // spent (the empty asm with a memory clobber keeps the reads from being hoisted above it):
+    // all sixteen up front would not fit the register budget.
     Pack8 va[2][4];
-#pragma unroll
-    for (int half = 0; half < 2; ++half)
+    auto read_v_ops = [&](int half) {
 #pragma unroll
       for (int r = 0; r < 4; ++r)
 #pragma unroll
         for (int rd = 0; rd < 2; ++rd)
           va[half][r].h[rd] = lds_read_tr16(v_t + (16 * half + 8 * rd) * kRowBytes + v_off(2 * r + rd));
+    };
+    read_v_ops(0);
     // sixteen MFMAs; the exponential of logit x of half tile h is issued right before MFMA x + 1
     float p[16];
     f32x16 s_nxt = mfma_pinned_first(ka[0].v, q_op[0]);
 #pragma unroll
     for (int kk = 1; kk < 8; ++kk) {
       p[kk - 1] = exp2_then_mfma(fmaf(s_cur[kk - 1], c2, -m_sub), s_nxt, ka[kk].v, q_op[kk]);
-      if (FILL && (kk & 1)) fill_one(fk, kk / 2);
+      if ((kk & 1) && kk / 2 < kFillInstr && fill_k) fill_one(fk, kk / 2);  // block-uniform
+      if (kk == 4) {
+        no_memory_motion();
+        read_v_ops(1);
+      }
     }
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
@@ -696,7 +718,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_pipe_kernel(Dims dm, View q,
       for (int r = 0; r < 4; ++r) {
         const int x = 7 + 4 * half + r;
         p[x] = exp2_then_mfma(fmaf(s_cur[x], c2, -m_sub), o_acc[r], va[half][r].v, pb.v);
-        if (FILL && (r & 1)) fill_one(fv, 2 * half + r / 2);
+        if ((r & 1) && 2 * half + r / 2 < kFillInstr && fill_v) fill_one(fv, 2 * half + r / 2);  // block-uniform
       }
     }
     p[15] = exp2_pinned(fmaf(s_cur[15], c2, -m_sub));
@@ -713,8 +735,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_pipe_kernel(Dims dm, View q,
     l_run += psum;
     // keep the probabilities in this block: without a use here the optimiser sinks the exponentials
     // to their first use in the next step, behind the MFMAs they are meant to overlap with
-    asm volatile("" : "+v"(p_cur[0]), "+v"(p_cur[1]), "+v"(p_cur[2]), "+v"(p_cur[3]), "+v"(p_cur[4]), "+v"(p_cur[5]),
-                 "+v"(p_cur[6]), "+v"(p_cur[7]), "+v"(l_run));
+    keep_values_here(p_cur, l_run);
     __builtin_amdgcn_sched_barrier(0);
     s_cur = s_nxt;
 #pragma unroll
@@ -735,21 +756,20 @@ __global__ __launch_bounds__(kThreads, 2) void attn_pipe_kernel(Dims dm, View q,
     s_cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk].v, q_op[kk], s_cur, 0, 0, 0);
   read_k_ops(h_first + 1);
   for (int jt = t_begin; jt < t_end; ++jt) {
-    half_step(2 * jt, std::false_type{}, no_plan, no_plan);
+    half_step(2 * jt, false, false, no_plan, no_plan);
     // Every wave has read the second half of K tile jt and the last of V tile jt - 1: their buffers
     // take K tile jt + 2 and V tile jt + 1, which are first read after the next barrier.
     barrier_after_lds_fill();
     read_k_ops(2 * jt + 2);  // first half of K tile jt + 1, published by this barrier
+    // Tiles inside one segment are fetched from within the step, one instruction between two
+    // MFMAs (plans of tiles that are not wanted are formed but never used); the others here.
     const bool want_k = jt + 2 < t_end, want_v = jt + 1 < t_end;
-    if (false && want_k && want_v && tile_is_simple(jt + 2) && tile_is_simple(jt + 1)) {  // block-uniform
-      const FillPlan fk = plan_fill(k_s, jt + 2, k_rs_cache, k_rs_chunk, k_ss_cache, k_ss_chunk);
-      const FillPlan fv = plan_fill(v_s, jt + 1, v_rs_cache, v_rs_chunk, v_ss_cache, v_ss_chunk);
-      half_step(2 * jt + 1, std::true_type{}, fk, fv);
-    } else {
-      if (want_k) fetch_k(jt + 2);
-      if (want_v) fetch_v(jt + 1);
-      half_step(2 * jt + 1, std::false_type{}, no_plan, no_plan);
-    }
+    const bool k_inside = want_k && tile_is_simple(jt + 2), v_inside = want_v && tile_is_simple(jt + 1);
+    if (want_k && !k_inside) fetch_k(jt + 2);
+    if (want_v && !v_inside) fetch_v(jt + 1);
+    const FillPlan fk = plan_fill(k_s, jt + 2, k_rs_cache, k_rs_chunk, k_ss_cache, k_ss_chunk);
+    const FillPlan fv = plan_fill(v_s, jt + 1, v_rs_cache, v_rs_chunk, v_ss_cache, v_ss_chunk);
+    half_step(2 * jt + 1, k_inside, v_inside, fk, fv);
     read_k_ops(2 * jt + 3);  // second half of K tile jt + 1
   }
   {  // the product of the last half tile
@@ -797,6 +817,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_pipe_kernel(Dims dm, View q,
   }
   }  // row valid
   }  // pass
+}
+
+// Eight waves per workgroup: two 32-row tiles of the four heads of a KV group (or the equivalent
+// split for smaller groups) share every K/V tile, which halves the fetch traffic per MFMA
+// against four waves; one workgroup per CU, two waves per SIMD.
+__global__ __launch_bounds__(512, 1) void attn_pipe_kernel_w8(Dims dm, View q, int rows, Segments ks, Segments vs,
+                                                             int causal, View out, float* lse) {
+  attn_pipe_body<8>(dm, q, rows, ks, vs, causal, out, lse);
 }
 
 // Summed form of Eq. (1): score[g, j] = sum over the query rows of the KV group of
@@ -1143,13 +1171,15 @@ hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments ks, Segme
       !fits_i32(vs.chunk, vs.c))
     return hipErrorInvalidValue;
   if (key_splits < 1 || (key_splits > 1 && (out.ptr != nullptr || part == nullptr))) return hipErrorInvalidValue;
-  const TaskShape ts = task_shape(dm.G);
+  constexpr int kPipeWaves = 8;
+  const bool pipe = out.ptr != nullptr;
+  const TaskShape ts = task_shape(dm.G, pipe ? kPipeWaves : kWaves);
   const int rows_per_block = ts.tiles_per_block * kRowsPerWave;
   const int row_blocks = (rows + rows_per_block - 1) / rows_per_block;
   const int rb_slots = (causal && key_splits == 1) ? (row_blocks + 1) / 2 : row_blocks;  // paired row blocks
   dim3 grid(rb_slots * (dm.G / ts.heads_per_block) * dm.Hkv * dm.B * dm.L * key_splits);
-  if (out.ptr != nullptr)
-    hipLaunchKernelGGL(attn_pipe_kernel, grid, dim3(kThreads), 0, st, dm, q, rows, ks, vs, causal, out, lse);
+  if (pipe)
+    hipLaunchKernelGGL(attn_pipe_kernel_w8, grid, dim3(kPipeWaves * 64), 0, st, dm, q, rows, ks, vs, causal, out, lse);
   else
     hipLaunchKernelGGL((attn_mfma_kernel<false>), grid, dim3(kThreads), 0, st, dm, q, rows, ks, vs, causal, out, lse,
                        key_splits, part);
