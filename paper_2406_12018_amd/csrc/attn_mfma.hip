@@ -601,10 +601,11 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
     int row_off;  // per lane: its row inside the instruction's four rows, in bytes
     int seg16;    // per lane: byte offset of its 16-byte segment before the per-instruction swizzle term
   };
-  auto tile_is_simple = [&](int tile) {
-    const int j0 = tile * kTileN;
-    return (j0 + kTileN <= n_c) || (j0 >= n_c && j0 + kTileN <= n);
-  };
+  // At most two tiles are not: the one that holds the cache / chunk boundary and the one that holds
+  // the end of the candidates.
+  const int straddle_tile = (n_c % kTileN) ? n_c / kTileN : -1;
+  const int ragged_tile = (n % kTileN) ? n / kTileN : -1;
+  auto tile_is_simple = [&](int tile) { return tile != straddle_tile && tile != ragged_tile; };
   auto plan_fill = [&](char* buffers, int tile, __amdgpu_buffer_rsrc_t rs_cache, __amdgpu_buffer_rsrc_t rs_chunk,
                        int ss_cache, int ss_chunk) {
     const int j0 = tile * kTileN;
