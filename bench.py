@@ -28,7 +28,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per chunk-attention launch measured offline with rocprofv3 --pmc
 # (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see
 # profiles/.  None until a measurement for that workload exists.
-MEASURED_TRAFFIC_BYTES = {"cfg2_mistral7b": 432.1e6}
+MEASURED_TRAFFIC_BYTES = {"cfg2_mistral7b": 562.0e6}
 
 
 class HipEvents:
@@ -246,7 +246,7 @@ def main():
                    "budget": w.budget, "instr_len": w.instr_len,
                    "cache_mode": ["instr", "shared", "dual"][w.cache_mode], "select": "per_kv_head",
                    "inputs": "resident document" if ring == 0 else f"ring of {ring} pre-staged chunk buffers"},
-        "roofline": {"kernel": "attn_mfma_kernel (chunk attention)", "bound": "mfma",
+        "roofline": {"kernel": "attn_pipe_kernel_w8 (chunk attention)", "bound": "mfma",
                      "achieved": round(achieved, 2), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": traffic,
                      "avg_launch_ms": round(avg_ms, 5), "algorithmic_flops_per_launch": avg_fl},
