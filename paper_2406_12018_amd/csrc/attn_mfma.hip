@@ -95,6 +95,11 @@ __device__ inline float exp2_pinned(float x) {
   return y;
 }
 
+__device__ inline float max3_pinned(float a, float b, float c) {
+  float y;
+  asm volatile("v_max3_f32 %0, %1, %2, %3" : "=v"(y) : "v"(a), "v"(b), "v"(c));
+  return y;
+}
 // v_exp_f32 followed by an MFMA that does not read its result: the MFMA is the wait state.
 __device__ inline float exp2_then_mfma(float x, f32x16& acc, const bf16x8& a, const bf16x8& b) {
   float y;
@@ -632,6 +637,7 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
   f32x16 s_cur;            // logits of the half tile whose probabilities are computed next
   uint32_t p_prev[8];      // bf16 probabilities of the half tile before it, not yet multiplied with V
   Pack8 ka[8];             // K operand of the next logit product, read one step ahead
+  float mx_cur = 0.f;      // this lane's maximum over s_cur (before masking)
 #pragma unroll
   for (int x = 0; x < 8; ++x) p_prev[x] = 0u;
   auto read_k_ops = [&](int hn_raw) {  // half tile hn_raw, clamped to the last one
@@ -652,12 +658,14 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
 #pragma unroll
       for (int i = 0; i < 16; ++i)
         if (8 * (i / 4) + (i % 4) > lim_rel) s_cur[i] = -INFINITY;
+      mx_cur = s_cur[0];
+#pragma unroll
+      for (int i = 1; i < 16; ++i) mx_cur = fmaxf(mx_cur, s_cur[i]);
     }
     // Running maximum, kept lazily: softmax is invariant to the subtracted value, so m_run only has
-    // to stay within kMaxSlack (log2 units) of the true row maximum to keep exp2 in range.
-    float mx = s_cur[0];
-#pragma unroll
-    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s_cur[i]);
+    // to stay within kMaxSlack (log2 units) of the true row maximum to keep exp2 in range.  The
+    // lane's maximum over the half tile was taken at the end of the previous step.
+    float mx = mx_cur;
     if (__any(mx * c2 > m_run + kMaxSlack)) {  // wave-uniform and rare after the first tiles
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float m_new = fmaxf(m_run, mx * c2);
@@ -700,6 +708,7 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
     read_v_ops(0);
     // sixteen MFMAs; the exponential of logit x of half tile h is issued right before MFMA x + 1
     float p[16];
+    float mx_nxt = 0.f;
     f32x16 s_nxt = mfma_pinned_first(ka[0].v, q_op[0]);
 #pragma unroll
     for (int kk = 1; kk < 8; ++kk) {
@@ -720,9 +729,16 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
         const int x = 7 + 4 * half + r;
         p[x] = exp2_then_mfma(fmaf(s_cur[x], c2, -m_sub), o_acc[r], va[half][r].v, pb.v);
         if ((r & 1) && 2 * half + r / 2 < kFillInstr && fill_v) fill_one(fv, 2 * half + r / 2);  // block-uniform
+        // The lane's maximum of the next half tile's logits, one v_max3 per MFMA slot.  s_nxt was
+        // completed by the eighth MFMA of the step; three further MFMAs have been issued since.
+        const int y = 4 * half + r - 2;  // 0 .. 5
+        if (y == 0) mx_nxt = max3_pinned(s_nxt[0], s_nxt[1], s_nxt[2]);
+        if (y > 0) mx_nxt = max3_pinned(mx_nxt, s_nxt[2 * y + 1], s_nxt[2 * y + 2]);
       }
     }
     p[15] = exp2_pinned(fmaf(s_cur[15], c2, -m_sub));
+    mx_nxt = max3_pinned(mx_nxt, s_nxt[13], s_nxt[14]);
+    mx_nxt = fmaxf(mx_nxt, s_nxt[15]);
     // the row sum is taken over the bf16-rounded probabilities, the values P.V uses: one v_dot2
     // with (1, 1) adds a pair
     uint32_t p_cur[8];
@@ -739,6 +755,7 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
     keep_values_here(p_cur, l_run);
     __builtin_amdgcn_sched_barrier(0);
     s_cur = s_nxt;
+    mx_cur = mx_nxt;
 #pragma unroll
     for (int x = 0; x < 8; ++x) p_prev[x] = p_cur[x];
   };
@@ -755,6 +772,9 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
 #pragma unroll
   for (int kk = 0; kk < 8; ++kk)  // logits of the first half tile
     s_cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk].v, q_op[kk], s_cur, 0, 0, 0);
+  mx_cur = s_cur[0];
+#pragma unroll
+  for (int i = 1; i < 16; ++i) mx_cur = fmaxf(mx_cur, s_cur[i]);
   read_k_ops(h_first + 1);
   for (int jt = t_begin; jt < t_end; ++jt) {
     half_step(2 * jt, false, false, no_plan, no_plan);
