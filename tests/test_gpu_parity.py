@@ -194,6 +194,40 @@ def test_chunk_attn_parity(shape):
     assert torch.equal(out, out2) and torch.equal(lm, lm2)
 
 
+@pytest.mark.parametrize("direction", ["rising", "falling", "spike"])
+def test_chunk_attn_moving_row_maximum(direction):
+    """Logits whose row maximum keeps moving from tile to tile (rising), never moves after the first tile
+    (falling), or jumps once by a large amount in the middle of the keys (spike): the running maximum is
+    updated lazily and the accumulators, row sums and pending probabilities are rescaled on the way."""
+    dtype, B, L, Hq, Hkv, d, c, n_c = "bf16", 1, 2, 8, 2, 128, 160, 416
+    say(f"chunk_attn moving maximum {direction}")
+    x = step_inputs(dtype, B, L, Hq, Hkv, d, c, n_c, 8, 1.0, seed=300)
+    n = n_c + c
+    pos = torch.arange(n, device=DEV, dtype=torch.float32)
+    if direction == "rising":
+        gain = 0.5 + 6.0 * pos / n
+    elif direction == "falling":
+        gain = 6.5 - 6.0 * pos / n
+    else:
+        gain = torch.where((pos >= 301) & (pos < 304), 12.0, 1.0)
+    # keys share a direction with the queries so that the gain moves the logits, not only their spread
+    bias = rand((1, 1, 1, 1, d), torch.bfloat16, 777, 1.0)
+    kc = ((x["kc"][..., :n_c, :].float() + bias.float()) * gain[:n_c, None]).to(torch.bfloat16)
+    kk = ((x["k"].float() + bias.float()) * gain[n_c:, None]).to(torch.bfloat16)
+    q = (x["q"].float() + bias.float()).to(torch.bfloat16)
+    cfg = make_cfg(dtype, B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, c=c, k=n_c, n_i=8)
+    lse = torch.empty((B, L, Hq, c), dtype=torch.float32, device=DEV)
+    out = api.citrus_chunk_attn(cfg, q, kc, x["vc"][..., :n_c, :], n_c, kk, x["v"], lse=lse)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all() and torch.isfinite(lse).all()
+    for l in range(L):
+        kcat = np.concatenate([np64(kc[0, l]), np64(kk[0, l])], axis=1)
+        vcat = np.concatenate([np64(x["vc"][0, l, :, :n_c]), np64(x["v"][0, l])], axis=1)
+        o_ref, lse_ref, _ = orc.chunk_attn(np64(q[0, l]), kcat, vcat, n_c)
+        assert_close(np64(out[0, l]), o_ref, dtype, f"out l{l}")
+        np.testing.assert_allclose(np64(lse[0, l]), lse_ref, rtol=1e-2, atol=2e-2)
+
+
 def test_chunk_attn_strided_views_and_short_chunk():
     """Chunk tensors that are slices of document tensors; chunk shorter than cfg.chunk_len."""
     dtype, B, L, Hq, Hkv, d = "bf16", 1, 2, 8, 2, 128
