@@ -1005,7 +1005,9 @@ __device__ inline float reduce16_over32(const float (&v)[16], int col) {
 //           the row normaliser (log2 domain);
 //   pass 2  the same products again, exp2(s - normaliser) summed down the query rows per key.
 // Partial column sums of the q shares meet in LDS and are added in a fixed order: no atomics.
-template <int QT_TOTAL, int Q_SPLIT, int WAVES>
+// With KREG > 0 a wave keeps its (at most KREG) key tiles in registers from the first pass to the
+// second: K is read from memory once, and all its loads are in flight together at the start.
+template <int QT_TOTAL, int Q_SPLIT, int WAVES, int KREG>
 __global__ __launch_bounds__(WAVES * 64) void instr_fused_kernel(Dims dm, View q, int rows, Segments ks,
                                                                  float* score) {
   constexpr int KW = WAVES / Q_SPLIT;         // waves that share the key tiles
@@ -1025,14 +1027,6 @@ __global__ __launch_bounds__(WAVES * 64) void instr_fused_kernel(Dims dm, View q
   const int tiles = (n + 31) / 32;
   const int total_rows = dm.G * rows;  // <= QROWS (the launcher guarantees it)
   const float c2 = dm.scale * kLog2e;
-
-  for (int r = tid / 16; r < QROWS; r += WAVES * 4) {  // 16 threads per row, 16 bytes each
-    const int f = min(r, total_rows - 1);               // padding rows repeat the last row; never summed
-    const int hh = f / rows, t = f % rows;
-    const uint16_t* qp = unit_ptr(q, b, l, g * dm.G + hh) + static_cast<int64_t>(t) * q.ss + 8 * (tid % 16);
-    *reinterpret_cast<uint4*>(&q_s[r * kPitchK + 8 * (tid % 16)]) = *reinterpret_cast<const uint4*>(qp);
-  }
-  __syncthreads();
 
   const uint16_t* k_cache_u = unit_ptr(ks.cache, b, l, g) + 8 * grp;
   const uint16_t* k_chunk_u = unit_ptr(ks.chunk, b, l, g) + 8 * grp;
@@ -1060,6 +1054,34 @@ __global__ __launch_bounds__(WAVES * 64) void instr_fused_kernel(Dims dm, View q
     return s_t;
   };
 
+  bf16x8 k_res[KREG > 0 ? KREG : 1][8];
+  if constexpr (KREG > 0) {  // the launcher guarantees tiles <= KW * KREG
+#pragma unroll
+    for (int i = 0; i < KREG; ++i) load_keys(min(kw + KW * i, tiles - 1), k_res[i]);
+  }
+  // the query rows go through LDS (the key loads above are in flight meanwhile)
+  for (int r = tid / 16; r < QROWS; r += WAVES * 4) {  // 16 threads per row, 16 bytes each
+    const int f = min(r, total_rows - 1);               // padding rows repeat the last row; never summed
+    const int hh = f / rows, t = f % rows;
+    const uint16_t* qp = unit_ptr(q, b, l, g * dm.G + hh) + static_cast<int64_t>(t) * q.ss + 8 * (tid % 16);
+    *reinterpret_cast<uint4*>(&q_s[r * kPitchK + 8 * (tid % 16)]) = *reinterpret_cast<const uint4*>(qp);
+  }
+  __syncthreads();
+
+  auto for_my_tiles = [&](auto&& tile_fn) {
+    if constexpr (KREG > 0) {
+#pragma unroll
+      for (int i = 0; i < KREG; ++i)
+        if (kw + KW * i < tiles) tile_fn(k_res[i], kw + KW * i);  // wave-uniform
+    } else {
+      for (int kt = kw; kt < tiles; kt += KW) {
+        bf16x8 k_op[8];
+        load_keys(kt, k_op);
+        tile_fn(k_op, kt);
+      }
+    }
+  };
+
   // ---- pass 1: row normalisers ----
   float m_run[QT_PER], l_run[QT_PER];
 #pragma unroll
@@ -1067,9 +1089,7 @@ __global__ __launch_bounds__(WAVES * 64) void instr_fused_kernel(Dims dm, View q
     m_run[x] = -INFINITY;
     l_run[x] = 0.f;
   }
-  for (int kt = kw; kt < tiles; kt += KW) {
-    bf16x8 k_op[8];
-    load_keys(kt, k_op);
+  for_my_tiles([&](const bf16x8 (&k_op)[8], int kt) {
     const int valid = n - 32 * kt;  // keys of the tile that exist (wave-uniform)
 #pragma unroll
     for (int x = 0; x < QT_PER; ++x) {
@@ -1093,7 +1113,7 @@ __global__ __launch_bounds__(WAVES * 64) void instr_fused_kernel(Dims dm, View q
       l_run[x] = fmaf(l_run[x], alpha, psum);
       m_run[x] = m_new;
     }
-  }
+  });
 #pragma unroll
   for (int x = 0; x < QT_PER; ++x) {  // the two lane halves saw different keys of every tile
     const float m_o = __shfl_xor(m_run[x], 32, 64), l_o = __shfl_xor(l_run[x], 32, 64);
@@ -1125,9 +1145,7 @@ __global__ __launch_bounds__(WAVES * 64) void instr_fused_kernel(Dims dm, View q
   float lse2[QT_PER];
 #pragma unroll
   for (int x = 0; x < QT_PER; ++x) lse2[x] = lse_s[32 * (qh * QT_PER + x) + col];
-  for (int kt = kw; kt < tiles; kt += KW) {
-    bf16x8 k_op[8];
-    load_keys(kt, k_op);
+  for_my_tiles([&](const bf16x8 (&k_op)[8], int kt) {
     float acc[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = 0.f;
@@ -1142,7 +1160,7 @@ __global__ __launch_bounds__(WAVES * 64) void instr_fused_kernel(Dims dm, View q
     const float tot = reduce16_over32(acc, col);  // value index col / 2 -> key 8 (i / 4) + 4 grp + (i % 4)
     const int i = col >> 1;
     if ((col & 1) == 0) part_s[qh * 32 * tiles + 32 * kt + 8 * (i / 4) + 4 * grp + (i % 4)] = tot;
-  }
+  });
   __syncthreads();
   float* dst = score + (static_cast<int64_t>(bl) * dm.Hkv + g) * n;
   for (int j = tid; j < n; j += WAVES * 64) {
@@ -1161,10 +1179,10 @@ size_t instr_fused_lds_bytes(int n) {
          static_cast<size_t>(Q_SPLIT) * 32 * tiles * 4;
 }
 
-template <int QT_TOTAL, int Q_SPLIT, int WAVES>
+template <int QT_TOTAL, int Q_SPLIT, int WAVES, int KREG>
 hipError_t instr_fused_launch(const Dims& dm, View q, int rows, Segments ks, float* score, hipStream_t st) {
   const size_t lds = instr_fused_lds_bytes<QT_TOTAL, Q_SPLIT, WAVES>(ks.n_c + ks.c);
-  auto kern = instr_fused_kernel<QT_TOTAL, Q_SPLIT, WAVES>;
+  auto kern = instr_fused_kernel<QT_TOTAL, Q_SPLIT, WAVES, KREG>;
   static size_t allowed = 0;  // largest dynamic LDS size the kernel has been cleared for
   if (lds > allowed) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1177,6 +1195,7 @@ hipError_t instr_fused_launch(const Dims& dm, View q, int rows, Segments ks, flo
 }
 
 constexpr size_t kFusedLdsBudget = 150 * 1024;  // of the CU's 160 KB
+constexpr int kFusedKeyTilesInRegs = 5;           // 160 of a wave's 256 registers
 
 }  // namespace
 
@@ -1228,10 +1247,13 @@ hipError_t launch_instr_score_mfma(const Dims& dm, View q, int rows, Segments ks
   const int n = ks.n_c + ks.c;
   // few query rows per KV group (the usual case: a short instruction): one fused launch
   const int total_rows = dm.G * rows;
+  const int tiles32 = (n + 31) / 32;
   if (total_rows <= 128 && instr_fused_lds_bytes<4, 1, 8>(n) <= kFusedLdsBudget)
-    return instr_fused_launch<4, 1, 8>(dm, q, rows, ks, score, st);
+    return instr_fused_launch<4, 1, 8, 0>(dm, q, rows, ks, score, st);
+  if (total_rows <= 256 && tiles32 <= 8 * kFusedKeyTilesInRegs && instr_fused_lds_bytes<8, 1, 8>(n) <= kFusedLdsBudget)
+    return instr_fused_launch<8, 1, 8, kFusedKeyTilesInRegs>(dm, q, rows, ks, score, st);
   if (total_rows <= 256 && instr_fused_lds_bytes<8, 2, 16>(n) <= kFusedLdsBudget)
-    return instr_fused_launch<8, 2, 16>(dm, q, rows, ks, score, st);
+    return instr_fused_launch<8, 2, 16, 0>(dm, q, rows, ks, score, st);
   const int tiles = (n + kTileN - 1) / kTileN;
   int splits = (tiles + 3) / 4;  // about four key tiles per workgroup
   splits = splits < 1 ? 1 : (splits > kMaxKeySplits ? kMaxKeySplits : splits);

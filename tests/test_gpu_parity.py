@@ -134,6 +134,7 @@ SHAPES = [
     ("bf16", 1, 2, 4, 2, 64, 50, 77, 9, 0.5),
     ("bf16", 1, 1, 2, 1, 128, 1, 300, 1, 1.0),
     ("bf16", 1, 2, 8, 2, 128, 45, 83, 37, 0.3),
+    ("bf16", 1, 1, 8, 2, 128, 200, 1150, 40, 0.09),
 ]
 
 
