@@ -174,26 +174,31 @@ def lm_score(q, k_cat, n_c: int, scale: Optional[float] = None) -> np.ndarray:
     return score
 
 
-def topk_select_1d(score: np.ndarray, k: int) -> np.ndarray:
+def topk_select_1d(score: np.ndarray, k: int, start_size: int = 0) -> np.ndarray:
     """Eq. (2)-(3) for one score vector: positions of the min(k, n) highest
-    scores, ties to the lower index, returned in ascending position order."""
+    scores, ties to the lower index, returned in ascending position order.
+
+    ``start_size`` > 0 is the variant of the appendix "Analysis on initial
+    tokens": the first start_size candidates are always preserved and the
+    remaining k - start_size places go to the best of the others."""
     score = np.asarray(score)
     n = score.shape[0]
     if n <= k:
         return np.arange(n, dtype=np.int64)
+    s0 = min(start_size, k)
     # stable sort on the negated score: equal scores keep ascending index order
-    order = np.argsort(-score, kind="stable")
-    return np.sort(order[:k]).astype(np.int64)
+    order = s0 + np.argsort(-score[s0:], kind="stable")
+    return np.sort(np.concatenate([np.arange(s0), order[:k - s0]])).astype(np.int64)
 
 
-def topk_select(score, k: int, select_mode: int = SELECT_PER_KV_HEAD) -> np.ndarray:
+def topk_select(score, k: int, select_mode: int = SELECT_PER_KV_HEAD, start_size: int = 0) -> np.ndarray:
     """score [Hkv, n] -> idx [Hkv, min(k, n)] (per KV head) or [1, min(k, n)]
     (layer-wise: the scores of all heads are added first, Section 4.1 last
     paragraph)."""
     score = np.asarray(score)
     if select_mode == SELECT_PER_LAYER:
-        return topk_select_1d(score.sum(axis=0), k)[None, :]
-    return np.stack([topk_select_1d(score[g], k) for g in range(score.shape[0])])
+        return topk_select_1d(score.sum(axis=0), k, start_size)[None, :]
+    return np.stack([topk_select_1d(score[g], k, start_size) for g in range(score.shape[0])])
 
 
 def kv_compact(k_cat, v_cat, idx):
@@ -240,7 +245,7 @@ def process_document(q, k, v, q_instr: Sequence[np.ndarray], chunk_len: int, bud
                      budget_lm: Optional[int] = None, scale: Optional[float] = None,
                      forced_idx: Optional[Sequence[np.ndarray]] = None,
                      forced_idx_lm: Optional[Sequence[np.ndarray]] = None,
-                     keep_trace: bool = True) -> DocumentResult:
+                     keep_trace: bool = True, start_size: int = 0) -> DocumentResult:
     """The chunk loop for one (document, layer).
 
     q [Hq, T, d]; k, v [Hkv, T, d]; q_instr: one [Hq, n_i, d] array per chunk
@@ -257,6 +262,9 @@ def process_document(q, k, v, q_instr: Sequence[np.ndarray], chunk_len: int, bud
     ``forced_idx`` replays a given selection history instead of the oracle's
     own (the per-step scores are still computed), so a trajectory can be
     compared step by step without one near-tie changing all later steps.
+    ``start_size``: the first start_size states of the document are never
+    evicted (appendix "Analysis on initial tokens"); they are the first
+    candidates of every step because retained states keep their order.
     """
     q, k, v = _f64(q), _f64(k), _f64(v)
     hq, t_total, d = q.shape
@@ -293,7 +301,7 @@ def process_document(q, k, v, q_instr: Sequence[np.ndarray], chunk_len: int, bud
             g_size = hq // hkv
             s_lm = probs.reshape(hkv, g_size, c, -1).sum(axis=(1, 2))
             idx_lm = (np.asarray(forced_idx_lm[i]) if forced_idx_lm is not None
-                      else topk_select(s_lm, budget_lm, select_mode))
+                      else topk_select(s_lm, budget_lm, select_mode, start_size))
             kc_lm, vc_lm = kv_compact(k_cat_lm, v_cat_lm, idx_lm)
             pos_lm = np.stack([pos_cat_lm[g][idx_lm[g % idx_lm.shape[0]]] for g in range(hkv)])
             tr_lm = dict(n_c_lm=n_c_lm, score_lm=s_lm, idx_lm=idx_lm)
@@ -302,7 +310,7 @@ def process_document(q, k, v, q_instr: Sequence[np.ndarray], chunk_len: int, bud
 
         s_in = instr_score(q_instr[i], k_cat, scale)
         idx = (np.asarray(forced_idx[i]) if forced_idx is not None
-               else topk_select(s_in, budget, select_mode))
+               else topk_select(s_in, budget, select_mode, start_size))
         kc, vc = kv_compact(k_cat, v_cat, idx)
         pos = np.stack([pos_cat[g][idx[g % idx.shape[0]]] for g in range(hkv)])
         if keep_trace:

@@ -154,6 +154,75 @@ def test_topk_equals_full_sort_set():
     assert np.all(np.diff(idx) > 0)
 
 
+def _py_topk_start(score, k, s0):
+    """The appendix variant written out on its own: the first s0 candidates are taken, then the best
+    remaining candidate (highest score, then lowest index) is taken k - s0 times."""
+    n = len(score)
+    if n <= k:
+        return list(range(n))
+    chosen = list(range(min(s0, k)))
+    alive = [j for j in range(n) if j not in chosen]
+    while len(chosen) < k:
+        best = alive[0]
+        for j in alive[1:]:
+            if score[j] > score[best]:
+                best = j
+        chosen.append(best)
+        alive.remove(best)
+    return sorted(chosen)
+
+
+@pytest.mark.parametrize("n,k,s0,levels", [(17, 5, 2, None), (40, 39, 4, 3), (33, 4, 4, 2), (50, 20, 1, 4), (9, 30, 3, None),
+                                          (25, 6, 0, None)])
+def test_topk_with_start_size_vs_bruteforce(n, k, s0, levels):
+    r = rng(n * 977 + k + s0)
+    for _ in range(20):
+        s = r.random(n) if levels is None else r.integers(0, levels, n).astype(np.float64)
+        got = orc.topk_select_1d(s, k, s0).tolist()
+        assert got == _py_topk_start(s.tolist(), k, s0)
+        if n > k:
+            assert got[:min(s0, k)] == list(range(min(s0, k)))
+    # start_size = 0 is the plain selection
+    s = r.random(30)
+    assert orc.topk_select_1d(s, 7, 0).tolist() == _py_topk(s.tolist(), 7)
+
+
+def test_start_size_changes_nothing_when_the_first_states_win_anyway():
+    r = rng(77)
+    s = r.random(60)
+    s[:4] += 10.0  # the first four are the four best
+    np.testing.assert_array_equal(orc.topk_select_1d(s, 12, 4), orc.topk_select_1d(s, 12))
+    s[:4] -= 20.0  # now the four worst: forced in, and the eight best of the rest beside them
+    forced = orc.topk_select_1d(s, 12, 4)
+    np.testing.assert_array_equal(forced[:4], np.arange(4))
+    np.testing.assert_array_equal(forced[4:], 4 + orc.topk_select_1d(s[4:], 8))
+    assert not set(range(4)) & set(orc.topk_select_1d(s, 12).tolist())
+
+
+@pytest.mark.parametrize("mode", [orc.CACHE_INSTR, orc.CACHE_DUAL])
+def test_document_start_size_keeps_the_first_states(mode):
+    """Keys at document positions 0..3 are made repulsive for every query, so that plain eviction drops
+    them; with start_size = 4 they stay at the front of every cache, the rest follows the usual rule."""
+    hq, hkv, t, d, chunk, budget = 4, 2, 64, 8, 8, 12
+    q, k, v, qi = _doc(91, hq, hkv, t, d, 3, chunk)
+    q, qi = np.abs(q), [np.abs(x) for x in qi]
+    k[:, :4] = -3.0 * np.abs(k[:, :4]) - 1.0   # all logits against positive queries strongly negative
+    plain = orc.process_document(q, k, v, qi, chunk, budget, cache_mode=mode, budget_lm=budget)
+    kept = orc.process_document(q, k, v, qi, chunk, budget, cache_mode=mode, budget_lm=budget, start_size=4)
+    assert not (plain.positions < 4).any()
+    np.testing.assert_array_equal(kept.positions[:, :4], np.tile(np.arange(4), (hkv, 1)))
+    np.testing.assert_array_equal(kept.k_cache[:, :4], k[:, :4])
+    assert np.all(np.diff(kept.positions, axis=1) > 0) and kept.positions.shape == (hkv, budget)
+    if mode == orc.CACHE_DUAL:
+        np.testing.assert_array_equal(kept.positions_lm[:, :4], np.tile(np.arange(4), (hkv, 1)))
+    # every step's selection: the first four candidates, then the plain rule on the rest with k - 4 places
+    for tr in kept.trace:
+        if tr.idx.shape[1] < tr.score.shape[1]:
+            for g in range(hkv):
+                np.testing.assert_array_equal(tr.idx[g, :4], np.arange(4))
+                np.testing.assert_array_equal(tr.idx[g, 4:], 4 + orc.topk_select_1d(tr.score[g, 4:], budget - 4))
+
+
 def test_topk_per_layer_sums_heads():
     s = np.array([[0.9, 0.1, 0.5, 0.0], [0.0, 0.2, 0.6, 0.3]])
     # per head: top-2 are {0,2} and {2,3}; layer-wise sums are .9 .3 1.1 .3 -> {0,2}
