@@ -58,7 +58,7 @@
 extern "C" {
 #endif
 
-#define CITRUS_ABI_VERSION 1
+#define CITRUS_ABI_VERSION 2
 #define CITRUS_EVENTS_PER_STEP 8
 
 typedef enum {
@@ -100,6 +100,8 @@ typedef struct {
   int32_t dtype;          /* citrus_dtype                                        */
   int32_t cache_mode;     /* citrus_cache_mode                                   */
   int32_t select_mode;    /* citrus_select_mode                                  */
+  int32_t start_size;     /* leading document states that are never evicted (appendix "Analysis on
+                             initial tokens"); 0 = plain Eq. (2)-(3); < budget (and < budget_lm)  */
   float softmax_scale;    /* 0 -> 1/sqrt(head_dim), the scaling of Eq. (1)       */
 } citrus_config;
 
@@ -166,7 +168,9 @@ int32_t citrus_instr_score(const citrus_config* cfg, citrus_tensor q_instr, citr
  * Selection (Eq. (2)-(3)): the positions of the min(k, n) highest scores.
  * Equal scores: the lower position wins.  Output positions are ascending, so
  * kept states stay in their original order.  n <= k keeps everything
- * (0..n-1), as the first chunk does in the paper.
+ * (0..n-1), as the first chunk does in the paper.  With cfg->start_size = s > 0
+ * (appendix "Analysis on initial tokens") and n > k, candidates 0..min(s,k)-1 are
+ * always kept and the other places go to the best of the remaining candidates.
  *
  * score dense [B, L, Hkv, n] f32 (finite values).
  * idx   dense int32, row pitch k:  [B, L, Hkv, k] (PER_KV_HEAD) or [B, L, 1, k]

@@ -43,7 +43,7 @@ class CitrusError(RuntimeError):
 class CConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "batch", "layers", "q_heads", "kv_heads", "head_dim", "chunk_len", "budget", "budget_lm", "instr_len",
-        "cache_capacity", "dtype", "cache_mode", "select_mode")] + [("softmax_scale", C.c_float)]
+        "cache_capacity", "dtype", "cache_mode", "select_mode", "start_size")] + [("softmax_scale", C.c_float)]
 
 
 class CTensor(C.Structure):
@@ -115,6 +115,7 @@ class Config:
     budget_lm: int = 0
     cache_capacity: int = 0          # 0 -> max(budget, budget_lm)
     softmax_scale: float = 0.0
+    start_size: int = 0              # leading document states that are never evicted
 
     def __post_init__(self):
         if self.cache_capacity == 0:
@@ -123,7 +124,7 @@ class Config:
     def c(self) -> CConfig:
         return CConfig(self.batch, self.layers, self.q_heads, self.kv_heads, self.head_dim, self.chunk_len,
                        self.budget, self.budget_lm, self.instr_len, self.cache_capacity, self.dtype,
-                       self.cache_mode, self.select_mode, self.softmax_scale)
+                       self.cache_mode, self.select_mode, self.start_size, self.softmax_scale)
 
     @property
     def torch_dtype(self) -> torch.dtype:
@@ -138,7 +139,7 @@ class Config:
         kw = dict(batch=w.batch, layers=w.layers, q_heads=w.q_heads, kv_heads=w.kv_heads, head_dim=w.head_dim,
                   chunk_len=w.chunk_len, budget=w.budget, instr_len=w.instr_len,
                   dtype=F32 if w.dtype == "f32" else BF16, cache_mode=w.cache_mode, select_mode=w.select_mode,
-                  budget_lm=w.budget_lm)
+                  budget_lm=w.budget_lm, start_size=getattr(w, "start_size", 0))
         kw.update(overrides)
         return Config(**kw)
 

@@ -32,6 +32,8 @@ citrus_status check_config(const citrus_config* c) {
   if (c->cache_mode == CITRUS_CACHE_DUAL && c->budget_lm < 1) return CITRUS_ERR_SHAPE;
   const int need = c->cache_mode == CITRUS_CACHE_DUAL && c->budget_lm > c->budget ? c->budget_lm : c->budget;
   if (c->cache_capacity < need) return CITRUS_ERR_SHAPE;
+  if (c->start_size < 0 || c->start_size >= c->budget) return CITRUS_ERR_SHAPE;
+  if (c->cache_mode == CITRUS_CACHE_DUAL && c->start_size >= c->budget_lm) return CITRUS_ERR_SHAPE;
   if (!(c->softmax_scale >= 0.0f) || isinf(c->softmax_scale)) return CITRUS_ERR_SHAPE;
   return CITRUS_OK;
 }
@@ -137,7 +139,7 @@ int sel_heads(const citrus_config* c) { return c->select_mode == CITRUS_SELECT_P
 citrus_status do_topk(const citrus_config* c, const float* score, int n, int k, int32_t* idx, hipStream_t st) {
   const bool per_layer = c->select_mode == CITRUS_SELECT_PER_LAYER;
   const int units = c->batch * c->layers * (per_layer ? 1 : c->kv_heads);
-  return hip_status(launch_topk(score, units, per_layer ? c->kv_heads : 1, n, k, idx, st));
+  return hip_status(launch_topk(score, units, per_layer ? c->kv_heads : 1, n, k, c->start_size, idx, st));
 }
 
 citrus_status do_compact(const citrus_config* c, const Dims& dm, Segments ks, Segments vs, const int32_t* idx,

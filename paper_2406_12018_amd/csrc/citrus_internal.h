@@ -57,7 +57,8 @@ hipError_t launch_instr_score_mfma(const Dims& dm, View q, int rows, Segments ks
 
 // ---- selection and compaction, select_compact.hip ----
 // units = B*L*Hsel; score rows are [units*(per_layer?Hkv:1)] x n.
-hipError_t launch_topk(const float* score, int units, int heads_to_sum, int n, int k, int32_t* idx, hipStream_t st);
+hipError_t launch_topk(const float* score, int units, int heads_to_sum, int n, int k, int forced, int32_t* idx,
+                       hipStream_t st);
 hipError_t launch_compact(int elem_bytes, const Dims& dm, Segments kseg, Segments vseg, const int32_t* idx,
                           int idx_pitch, int idx_heads, int m, View k_new, View v_new, hipStream_t st);
 

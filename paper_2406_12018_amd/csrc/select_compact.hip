@@ -24,13 +24,19 @@ __device__ inline float unit_score(const float* base, int heads_to_sum, int n, i
   return s;
 }
 
+// The key candidate j is ranked by.  The first `forced` candidates (the initial document states
+// that are never evicted) rank above every score.
+__device__ inline uint32_t unit_key(const float* base, int heads_to_sum, int n, int forced, int j) {
+  return j < forced ? 0xffffffffu : order_key(unit_score(base, heads_to_sum, n, j));
+}
+
 // One workgroup per selection unit.  A radix select over the 32-bit order keys
 // (4 passes of 8 bits, integer LDS histograms) finds the k-th largest key T;
 // then one ordered pass emits, in ascending position, every candidate with
 // key > T and the first (k - count(key > T)) candidates with key == T.  The
 // result is exactly the top-k under (score descending, position ascending).
 __global__ __launch_bounds__(kSelThreads) void topk_kernel(const float* score, int heads_to_sum, int n, int k,
-                                                          int32_t* idx) {
+                                                          int forced, int32_t* idx) {
   __shared__ int hist[256];
   __shared__ uint32_t s_prefix;
   __shared__ int s_need;
@@ -52,7 +58,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_kernel(const float* score, i
     __syncthreads();
     const uint32_t hi_mask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
     for (int j = tid; j < n; j += kSelThreads) {
-      const uint32_t key = order_key(unit_score(base, heads_to_sum, n, j));
+      const uint32_t key = unit_key(base, heads_to_sum, n, forced, j);
       if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 0xff], 1);
     }
     __syncthreads();
@@ -90,7 +96,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_kernel(const float* score, i
     const int j = j0 + tid;
     uint32_t key = 0;
     bool in = j < n;
-    if (in) key = order_key(unit_score(base, heads_to_sum, n, j));
+    if (in) key = unit_key(base, heads_to_sum, n, forced, j);
     const bool gt = in && key > thr, eq = in && key == thr;
     const uint64_t eq_ballot = __ballot(eq);
     const uint64_t below = (1ull << lane) - 1ull;
@@ -169,8 +175,9 @@ hipError_t compact_launch(int elem_bytes, const Dims& dm, Segments ks, Segments 
 
 }  // namespace
 
-hipError_t launch_topk(const float* score, int units, int heads_to_sum, int n, int k, int32_t* idx, hipStream_t st) {
-  hipLaunchKernelGGL(topk_kernel, dim3(units), dim3(kSelThreads), 0, st, score, heads_to_sum, n, k, idx);
+hipError_t launch_topk(const float* score, int units, int heads_to_sum, int n, int k, int forced, int32_t* idx,
+                       hipStream_t st) {
+  hipLaunchKernelGGL(topk_kernel, dim3(units), dim3(kSelThreads), 0, st, score, heads_to_sum, n, k, min(forced, k), idx);
   return hipGetLastError();
 }
 

@@ -33,28 +33,35 @@ def assert_close(gpu, ref, dtype: str, what: str = ""):
     assert np.isfinite(gpu).all(), what
 
 
-def check_selection(gpu_idx, gpu_score, ref_score, k: int, dtype: str, what: str = ""):
+def check_selection(gpu_idx, gpu_score, ref_score, k: int, dtype: str, what: str = "", start_size: int = 0):
     """The two selection checks for one score vector.
 
     1. Exact: the GPU's indices are exactly the top-k (lower index wins ties,
-       ascending output) of the GPU's OWN f32 score vector.
+       ascending output; the first start_size candidates always kept) of the
+       GPU's OWN f32 score vector.
     2. Band rule: against the oracle's selection on the oracle's scores, the
        sets may differ only at positions whose oracle score lies within the
-       tolerance of the oracle's k-th best score.
+       tolerance of the oracle's last kept score (among the candidates that
+       are not kept unconditionally).
     Returns the fraction of positions inside the band.
     """
     gpu_idx = np.asarray(gpu_idx)
     n = ref_score.shape[0]
     m = min(k, n)
-    own = orc.topk_select_1d(np.asarray(gpu_score, dtype=np.float32), k)
+    own = orc.topk_select_1d(np.asarray(gpu_score, dtype=np.float32), k, start_size)
     np.testing.assert_array_equal(gpu_idx[:m], own, err_msg=f"{what}: not the exact top-k of its own scores")
-    ref_idx = orc.topk_select_1d(ref_score, k)
+    ref_idx = orc.topk_select_1d(ref_score, k, start_size)
     if n <= k:
         np.testing.assert_array_equal(gpu_idx[:m], ref_idx)
         return 0.0
     atol, rtol = TOL[dtype]
-    boundary = np.sort(ref_score)[::-1][k - 1]
+    s0 = min(start_size, k)
+    if s0 == k:
+        np.testing.assert_array_equal(gpu_idx[:m], ref_idx)
+        return 0.0
+    boundary = np.sort(ref_score[s0:])[::-1][k - s0 - 1]
     band = np.abs(ref_score - boundary) <= atol + rtol * abs(boundary)
+    band[:s0] = False  # the unconditional ones can never differ
     diff = np.setxor1d(gpu_idx[:m], ref_idx)
     assert band[diff].all(), f"{what}: selection differs outside the tolerance band at {diff[~band[diff]][:8]}"
     return float(band.mean())

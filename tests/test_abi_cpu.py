@@ -24,11 +24,11 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(B.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
-    assert B.abi_version() == 1
+    assert B.abi_version() == 2
 
 
 def test_struct_layouts_match_the_header():
-    assert C.sizeof(B.CConfig) == 14 * 4
+    assert C.sizeof(B.CConfig) == 15 * 4
     assert C.sizeof(B.CTensor) == 5 * 8
     assert C.sizeof(B.CChunkIO) == 5 * 40 + 8
     assert C.sizeof(B.CResidentDoc) == 5 * 40 + 8 + 16
@@ -93,6 +93,10 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     assert lib.citrus_kv_compact(C.byref(c), fake(), fake(), 4, fake(), fake(), 8, C.c_void_p(0x2000), 8, 0, fake(0x9000), fake(0xA000), None) == B.ERR_SHAPE
     assert lib.citrus_kv_compact(C.byref(c), fake(), fake(), 4, fake(), fake(), 8, C.c_void_p(0x2000), 4, 8, fake(0x9000), fake(0xA000), None) == B.ERR_SHAPE
     assert lib.citrus_kv_compact(C.byref(c), fake(), fake(), 4, fake(), fake(), 8, C.c_void_p(0x2000), 8, 8, fake(), fake(0xA000), None) == B.ERR_SHAPE
+    # start_size must leave room for at least one scored state
+    for bad_start in (-1, cfg().budget):
+        bs = cfg(start_size=bad_start).c()
+        assert lib.citrus_topk_select(C.byref(bs), C.c_void_p(0x2000), 8, 4, C.c_void_p(0x3000), None, 0, None) == B.ERR_SHAPE
     # unsupported head_dim
     bad = cfg(head_dim=96).c()
     assert lib.citrus_topk_select(C.byref(bad), C.c_void_p(0x2000), 8, 4, C.c_void_p(0x3000), None, 0, None) == B.ERR_UNSUPPORTED

@@ -111,6 +111,34 @@ def test_topk_select_exact(n, k, levels, per_layer):
     assert (idx[..., m:] == -1).all()
 
 
+@pytest.mark.parametrize("n,k,start,levels", [(300, 100, 4, None), (1280, 768, 4, None), (97, 5, 5 - 1, 3), (600, 64, 1, 2),
+                                              (50, 80, 4, None)])
+@pytest.mark.parametrize("per_layer", [False, True])
+def test_topk_select_with_start_size_exact(n, k, start, levels, per_layer):
+    """The first start_size candidates are always kept, also when their scores are the lowest."""
+    B, L, Hkv = 2, 1, 2
+    cfg = make_cfg("f32", B=B, L=L, Hq=2, Hkv=Hkv, k=k, start_size=start,
+                   select_mode=api.SELECT_PER_LAYER if per_layer else api.SELECT_PER_KV_HEAD)
+    say(f"topk start_size n={n} k={k} start={start} levels={levels} per_layer={per_layer}")
+    r = np.random.default_rng(n * 13 + k + start)
+    s = r.random((B, L, Hkv, n)).astype(np.float32) if levels is None else \
+        (r.integers(0, levels, (B, L, Hkv, n)) * 0.125).astype(np.float32)
+    s[..., :start] = -5.0  # worst of all: plain selection would drop them
+    idx = api.citrus_topk_select(cfg, torch.from_numpy(s).to(DEV), k).cpu().numpy()
+    m = min(n, k)
+    for b in range(B):
+        for l in range(L):
+            if per_layer:
+                layer = s[b, l, 0].copy()
+                for g in range(1, Hkv):
+                    layer = (layer + s[b, l, g]).astype(np.float32)
+                np.testing.assert_array_equal(idx[b, l, 0, :m], orc.topk_select_1d(layer, k, start))
+            else:
+                np.testing.assert_array_equal(idx[b, l, :, :m], orc.topk_select(s[b, l], k, start_size=start))
+    if n > k:
+        assert (idx[..., :start] == np.arange(start)).all()
+
+
 def test_topk_all_equal_scores_keep_lowest_indices():
     cfg = make_cfg("f32", B=1, L=1, Hq=2, Hkv=2, k=100)
     s = torch.full((1, 1, 2, 333), 0.2, device=DEV)
@@ -309,7 +337,7 @@ def run_document_stepwise(w: Workload, sample_units=None, check_every=1):
                         ref_vec = s_lm_ref.sum(0) if hs == 1 else s_lm_ref[g]
                         gpu_vec = layer_sum_f32(rec["score_lm"][b, l]) if hs == 1 else rec["score_lm"][b, l, g].cpu().numpy()
                         band_fracs.append(check_selection(idx_lm[g], gpu_vec, ref_vec, w.budget_lm, w.dtype,
-                                                          f"lm select step {i}"))
+                                                          f"lm select step {i}", w.start_size))
                 pos_lm[(b, l)] = np.stack([cand_lm[g][idx_lm[g % hs]] for g in range(w.kv_heads)])
             elif check:
                 o_ref, lse_ref, _ = orc.chunk_attn(qd, kcat, vcat, n_c)
@@ -321,7 +349,8 @@ def run_document_stepwise(w: Workload, sample_units=None, check_every=1):
                 for g in range(hs):
                     ref_vec = s_ref.sum(0) if hs == 1 else s_ref[g]
                     gpu_vec = layer_sum_f32(rec["score"][b, l]) if hs == 1 else rec["score"][b, l, g].cpu().numpy()
-                    band_fracs.append(check_selection(idx[g], gpu_vec, ref_vec, w.budget, w.dtype, f"select step {i}"))
+                    band_fracs.append(check_selection(idx[g], gpu_vec, ref_vec, w.budget, w.dtype, f"select step {i}",
+                                                      w.start_size))
             pos[(b, l)] = np.stack([cand[g][idx[g % hs]] for g in range(w.kv_heads)])
             if check:
                 # compaction bit-exact: cache row r holds document row pos[r]
@@ -338,6 +367,13 @@ def run_document_stepwise(w: Workload, sample_units=None, check_every=1):
                         np.testing.assert_array_equal(bits(kl_gpu[b, l, g]), bits(host["k"][b, l, g][p]))
                         np.testing.assert_array_equal(bits(vl_gpu[b, l, g]), bits(host["v"][b, l, g][p]))
     say(f"{w.name}: mean in-band fraction of the selection band rule = {np.mean(band_fracs):.3f}")
+    if w.start_size and w.doc_len > w.budget:
+        # the initial states are never evicted: the first rows of every cache are the first document rows
+        for u in units:
+            np.testing.assert_array_equal(pos[u][:, :w.start_size], np.tile(np.arange(w.start_size), (w.kv_heads, 1)))
+            if dual:
+                np.testing.assert_array_equal(pos_lm[u][:, :w.start_size],
+                                              np.tile(np.arange(w.start_size), (w.kv_heads, 1)))
     return run, doc
 
 
@@ -357,7 +393,11 @@ DOC_CASES = {
                                   select_mode=api.SELECT_PER_LAYER),
     "cfg1_dual": scaled_down(peaked(WORKLOADS["cfg1_tiny_f32"]), doc_len=256, cache_mode=api.CACHE_DUAL, budget_lm=48),
     "cfg1_chunk_gt_budget": scaled_down(WORKLOADS["cfg1_tiny_f32"], doc_len=300, chunk_len=80, budget=50),
+    "cfg1_start4": scaled_down(peaked(WORKLOADS["cfg1_tiny_f32"]), doc_len=256, layers=2, kv_heads=2, start_size=4),
+    "cfg1_dual_start4": scaled_down(peaked(WORKLOADS["cfg1_tiny_f32"]), doc_len=256, cache_mode=api.CACHE_DUAL,
+                                    budget_lm=48, start_size=4),
     "cfg2_small": scaled_down(WORKLOADS["cfg2_mistral7b"], layers=2, doc_len=2560),
+    "cfg2_small_start4": scaled_down(WORKLOADS["cfg2_mistral7b"], layers=2, doc_len=2560, start_size=4),
     "cfg2_small_peaked": scaled_down(peaked(WORKLOADS["cfg2_mistral7b"]), layers=1, doc_len=2000),
     "cfg3_small_shared_mha": scaled_down(WORKLOADS["cfg3_llama2_7b_shared"], batch=2, layers=1, q_heads=4, kv_heads=4,
                                          doc_len=2100, chunk_len=256, budget=384, instr_len=32),
@@ -415,7 +455,8 @@ def run_process_document(w, doc, split_at=None, use_python_provider=False):
     return state, out, hist, hist_lm
 
 
-@pytest.mark.parametrize("case", ["cfg1", "cfg1_ragged", "cfg1_dual", "cfg2_small", "cfg4_small_dual"])
+@pytest.mark.parametrize("case", ["cfg1", "cfg1_ragged", "cfg1_dual", "cfg1_dual_start4", "cfg2_small", "cfg2_small_start4",
+                                  "cfg4_small_dual"])
 def test_process_document_equals_stepwise_and_resumes(case):
     w = DOC_CASES[case]
     say(f"process_document {case}")

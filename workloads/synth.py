@@ -68,6 +68,7 @@ class Workload:
     cache_mode: int = CACHE_INSTR
     select_mode: int = SELECT_PER_KV_HEAD
     budget_lm: int = 0
+    start_size: int = 0        # leading document states that are never evicted (0 = plain selection)
     sink_scale: float = 4.0
     heavy_prob: float = 0.0
     heavy_scale: float = 2.5
