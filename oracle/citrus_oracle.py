@@ -62,6 +62,9 @@ from typing import List, Optional, Sequence, Tuple
 
 import numpy as np
 
+LM_SCORE_AFTER_APPEND = 0   # the chunk's own causal attention scores [LM cache ; chunk] right away
+LM_EVICT_THEN_APPEND = 1    # Section 4.1 as printed: evict the cache by the chunk's attention to it, then append
+
 SELECT_PER_KV_HEAD = 0
 SELECT_PER_LAYER = 1
 
@@ -245,7 +248,8 @@ def process_document(q, k, v, q_instr: Sequence[np.ndarray], chunk_len: int, bud
                      budget_lm: Optional[int] = None, scale: Optional[float] = None,
                      forced_idx: Optional[Sequence[np.ndarray]] = None,
                      forced_idx_lm: Optional[Sequence[np.ndarray]] = None,
-                     keep_trace: bool = True, start_size: int = 0) -> DocumentResult:
+                     keep_trace: bool = True, start_size: int = 0,
+                     lm_ordering: int = LM_SCORE_AFTER_APPEND) -> DocumentResult:
     """The chunk loop for one (document, layer).
 
     q [Hq, T, d]; k, v [Hkv, T, d]; q_instr: one [Hq, n_i, d] array per chunk
@@ -262,6 +266,15 @@ def process_document(q, k, v, q_instr: Sequence[np.ndarray], chunk_len: int, bud
     ``forced_idx`` replays a given selection history instead of the oracle's
     own (the per-step scores are still computed), so a trajectory can be
     compared step by step without one near-tie changing all later steps.
+    ``lm_ordering`` (DUAL only) chooses how the language-modelling cache is
+    evicted.  LM_SCORE_AFTER_APPEND: as described above.  LM_EVICT_THEN_APPEND
+    is the three steps of Section 4.1 in the order printed: the chunk is
+    encoded given the cache C (which still holds the whole previous chunk, up
+    to budget_lm + chunk_len states), the states of C are scored by Eq. (1)
+    with s = the chunk and the softmax normalised over the states of C only,
+    the budget_lm best stay, and then all states of the chunk are put into
+    the cache.  (The instruction cache is the same computation in both
+    orderings, hoisted by one step.)
     ``start_size``: the first start_size states of the document are never
     evicted (appendix "Analysis on initial tokens"); they are the first
     candidates of every step because retained states keep their order.
@@ -299,11 +312,29 @@ def process_document(q, k, v, q_instr: Sequence[np.ndarray], chunk_len: int, bud
             pos_cat_lm = np.concatenate([pos_lm, chunk_pos], axis=1)
             out, lse, probs = chunk_attn(qs, k_cat_lm, v_cat_lm, n_c_lm, scale)
             g_size = hq // hkv
-            s_lm = probs.reshape(hkv, g_size, c, -1).sum(axis=(1, 2))
-            idx_lm = (np.asarray(forced_idx_lm[i]) if forced_idx_lm is not None
-                      else topk_select(s_lm, budget_lm, select_mode, start_size))
-            kc_lm, vc_lm = kv_compact(k_cat_lm, v_cat_lm, idx_lm)
-            pos_lm = np.stack([pos_cat_lm[g][idx_lm[g % idx_lm.shape[0]]] for g in range(hkv)])
+            if lm_ordering == LM_EVICT_THEN_APPEND:
+                # step 2 of Section 4.1: Eq. (1) with s = chunk over the states of the cache alone
+                # (every chunk token sees the whole cache, so there is no mask)
+                if n_c_lm > 0:
+                    s_lm = instr_score(qs, kc_lm, scale)
+                    idx_lm = (np.asarray(forced_idx_lm[i]) if forced_idx_lm is not None
+                              else topk_select(s_lm, budget_lm, select_mode, start_size))
+                else:
+                    s_lm = np.zeros((hkv, 0))
+                    idx_lm = np.zeros((1 if select_mode == SELECT_PER_LAYER else hkv, 0), dtype=np.int64)
+                kept_k, kept_v = (kv_compact(kc_lm, vc_lm, idx_lm) if n_c_lm > 0 else (kc_lm, vc_lm))
+                kept_pos = (np.stack([pos_lm[g][idx_lm[g % idx_lm.shape[0]]] for g in range(hkv)])
+                            if n_c_lm > 0 else pos_lm)
+                # step 3: all states of the chunk enter the cache
+                kc_lm = np.concatenate([kept_k, ks], axis=1)
+                vc_lm = np.concatenate([kept_v, vs], axis=1)
+                pos_lm = np.concatenate([kept_pos, chunk_pos], axis=1)
+            else:
+                s_lm = probs.reshape(hkv, g_size, c, -1).sum(axis=(1, 2))
+                idx_lm = (np.asarray(forced_idx_lm[i]) if forced_idx_lm is not None
+                          else topk_select(s_lm, budget_lm, select_mode, start_size))
+                kc_lm, vc_lm = kv_compact(k_cat_lm, v_cat_lm, idx_lm)
+                pos_lm = np.stack([pos_cat_lm[g][idx_lm[g % idx_lm.shape[0]]] for g in range(hkv)])
             tr_lm = dict(n_c_lm=n_c_lm, score_lm=s_lm, idx_lm=idx_lm)
         else:
             out, lse, _ = chunk_attn(qs, k_cat, v_cat, n_c, scale)

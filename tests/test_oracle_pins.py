@@ -453,3 +453,87 @@ def test_kv_compact_is_a_bit_copy_and_broadcasts():
         np.testing.assert_array_equal(vn[g], v[g, [1, 4, 9]])
     kn, _ = orc.kv_compact(k, v, np.tile(np.arange(10), (3, 1)))
     np.testing.assert_array_equal(kn, k)
+
+
+# ----------------------------------------------------------------------------
+# the language-modelling cache in the order Section 4.1 prints (evict, then append)
+# ----------------------------------------------------------------------------
+
+def _standard_cse_by_hand(q, k, v, chunk, budget):
+    """Standard chunked state eviction for ONE head, written with plain loops from the three steps of
+    Section 4.1: encode the chunk given the cache; evict the cache by Eq. (1) (s = chunk, normalised over
+    the cache states); put the chunk into the cache.  Returns (outputs [T, d], final cache positions)."""
+    t_total, d = q.shape
+    cache = []                                   # document positions, in order
+    outs = np.zeros((t_total, v.shape[1]))
+    for lo in range(0, t_total, chunk):
+        hi = min(t_total, lo + chunk)
+        # step 1: token t attends to the cache and to the chunk tokens up to itself
+        for t in range(lo, hi):
+            cand = cache + list(range(lo, t + 1))
+            logit = [sum(q[t][x] * k[j][x] for x in range(d)) / math.sqrt(d) for j in cand]
+            mx = max(logit)
+            w = [math.exp(a - mx) for a in logit]
+            z = sum(w)
+            for x in range(v.shape[1]):
+                outs[t][x] = sum(w[a] * v[cand[a]][x] for a in range(len(cand))) / z
+        # step 2: importance of every cache state = mean over chunk tokens of the softmax over the cache alone
+        if len(cache) > budget:
+            imp = [0.0] * len(cache)
+            for t in range(lo, hi):
+                logit = [sum(q[t][x] * k[j][x] for x in range(d)) / math.sqrt(d) for j in cache]
+                mx = max(logit)
+                w = [math.exp(a - mx) for a in logit]
+                z = sum(w)
+                for a in range(len(cache)):
+                    imp[a] += w[a] / z / (hi - lo)
+            order = sorted(range(len(cache)), key=lambda a: (-imp[a], a))[:budget]
+            cache = [cache[a] for a in sorted(order)]
+        # step 3
+        cache = cache + list(range(lo, hi))
+    return outs, cache
+
+
+def test_lm_evict_then_append_vs_hand_written_standard_cse():
+    hq, hkv, t, d, chunk, budget = 1, 1, 37, 4, 5, 7
+    q, k, v, qi = _doc(131, hq, hkv, t, d, 2, chunk)
+    res = orc.process_document(q, k, v, qi, chunk, budget=6, cache_mode=orc.CACHE_DUAL, budget_lm=budget,
+                               lm_ordering=orc.LM_EVICT_THEN_APPEND)
+    outs, cache = _standard_cse_by_hand(q[0], k[0], v[0], chunk, budget)
+    np.testing.assert_allclose(np.concatenate([tr.out for tr in res.trace], axis=1)[0], outs, atol=1e-12)
+    assert res.positions_lm[0].tolist() == cache
+    np.testing.assert_array_equal(res.k_cache_lm[0], k[0][cache])
+
+
+def test_lm_evict_then_append_invariants():
+    hq, hkv, t, d, chunk, budget, budget_lm = 4, 2, 75, 8, 16, 20, 24
+    q, k, v, qi = _doc(132, hq, hkv, t, d, 3, chunk)
+    res = orc.process_document(q, k, v, qi, chunk, budget, cache_mode=orc.CACHE_DUAL, budget_lm=budget_lm,
+                               lm_ordering=orc.LM_EVICT_THEN_APPEND)
+    ref = orc.process_document(q, k, v, qi, chunk, budget, cache_mode=orc.CACHE_DUAL, budget_lm=budget_lm)
+    held = 0
+    for i, tr in enumerate(res.trace):
+        c = min(chunk, t - i * chunk)
+        assert tr.n_c_lm == held                       # the cache still holds the whole previous chunk
+        assert tr.score_lm.shape == (hkv, held)        # only cache states are scored
+        if held:
+            np.testing.assert_allclose(tr.score_lm.sum(axis=1), c * 2, atol=1e-10)   # each row's softmax over the cache sums to 1
+        assert tr.idx_lm.shape[1] == min(held, budget_lm)
+        held = min(held, budget_lm) + c
+        # the instruction cache does not depend on the ordering of the other cache
+        np.testing.assert_array_equal(tr.idx, ref.trace[i].idx)
+    assert res.positions_lm.shape == (hkv, held)
+    last = t - (t - 1) // chunk * chunk
+    np.testing.assert_array_equal(res.positions_lm[:, -last:], np.tile(np.arange(t - last, t), (hkv, 1)))
+    assert np.all(np.diff(res.positions_lm, axis=1) > 0)
+    np.testing.assert_array_equal(res.positions, ref.positions)
+
+
+def test_lm_evict_then_append_with_large_budget_is_full_attention():
+    hq, hkv, t, d, chunk = 4, 2, 45, 8, 8
+    q, k, v, qi = _doc(133, hq, hkv, t, d, 3, chunk)
+    res = orc.process_document(q, k, v, qi, chunk, budget=64, cache_mode=orc.CACHE_DUAL, budget_lm=64,
+                               lm_ordering=orc.LM_EVICT_THEN_APPEND)
+    out = np.concatenate([tr.out for tr in res.trace], axis=1)
+    np.testing.assert_allclose(out, _sdpa(q, k, v, causal=True, group=2), atol=1e-12)
+    np.testing.assert_array_equal(res.k_cache_lm, k)
