@@ -58,7 +58,7 @@
 extern "C" {
 #endif
 
-#define CITRUS_ABI_VERSION 2
+#define CITRUS_ABI_VERSION 3
 #define CITRUS_EVENTS_PER_STEP 8
 
 typedef enum {
@@ -79,6 +79,15 @@ typedef enum { CITRUS_F32 = 0, CITRUS_BF16 = 1 } citrus_dtype;
  * cache to differ from); DUAL keeps a language-modelling cache, scored by the
  * chunk's own attention (Eq. (1) with s = chunk), next to the instruction cache. */
 typedef enum { CITRUS_CACHE_INSTR = 0, CITRUS_CACHE_SHARED = 1, CITRUS_CACHE_DUAL = 2 } citrus_cache_mode;
+
+/* How the language-modelling cache of the DUAL design is evicted.
+ * SCORE_AFTER_APPEND: the chunk's own causal attention scores [cache ; chunk] in the step that encodes it.
+ * EVICT_THEN_APPEND:  the three steps of Section 4.1 in the order printed: the chunk is encoded given the
+ *   cache (which still holds the whole previous chunk: up to budget_lm + chunk_len states), the states of
+ *   the cache are scored by Eq. (1) with s = the chunk and the softmax normalised over the cache states
+ *   only, the budget_lm best stay, and then all states of the chunk are put into the cache.
+ * The instruction cache is the same computation in both orderings (hoisted by one step). */
+typedef enum { CITRUS_LM_SCORE_AFTER_APPEND = 0, CITRUS_LM_EVICT_THEN_APPEND = 1 } citrus_lm_ordering;
 
 /* PER_KV_HEAD: one index set per (document, layer, KV head).
  * PER_LAYER:   scores of all KV heads are added first and one index set is used
@@ -102,6 +111,8 @@ typedef struct {
   int32_t select_mode;    /* citrus_select_mode                                  */
   int32_t start_size;     /* leading document states that are never evicted (appendix "Analysis on
                              initial tokens"); 0 = plain Eq. (2)-(3); < budget (and < budget_lm)  */
+  int32_t lm_ordering;    /* citrus_lm_ordering (DUAL only); EVICT_THEN_APPEND needs
+                             cache_capacity >= budget_lm + chunk_len                          */
   float softmax_scale;    /* 0 -> 1/sqrt(head_dim), the scaling of Eq. (1)       */
 } citrus_config;
 
@@ -163,6 +174,24 @@ int32_t citrus_chunk_attn(const citrus_config* cfg, citrus_tensor q, citrus_tens
 int32_t citrus_instr_score(const citrus_config* cfg, citrus_tensor q_instr, citrus_tensor k_cache, int32_t cache_len,
                            citrus_tensor k_chunk, int32_t chunk_len, float* score, void* workspace,
                            size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Importance of the cache states exactly as Eq. (1) prints it: attention of the rows of q to the states of
+ * the cache, softmax normalised over the cache states alone, summed over the rows and over the query heads of
+ * each KV group (divide by rows*G for the mean):
+ *   score[b,l,g,j] = sum_{h in g} sum_{t < rows} softmax_{j' < cache_len}(scale * q[b,l,h,t,:] . K[b,l,g,j',:])_j
+ * Used with q = the chunk's queries by the EVICT_THEN_APPEND ordering (Section 4.1, step 2); every row sees
+ * the whole cache, so there is no mask.
+ *
+ * q       [B, L, Hq, rows, d], 1 <= rows <= cfg->chunk_len
+ * k_cache [B, L, Hkv, >= cache_len, d], 1 <= cache_len <= cfg->cache_capacity
+ * score   dense [B, L, Hkv, cache_len] f32
+ * Needs cfg->cache_mode == DUAL with cfg->lm_ordering == EVICT_THEN_APPEND (the workspace is sized for it),
+ * otherwise CITRUS_ERR_UNSUPPORTED.  workspace: >= citrus_workspace_bytes(cfg).
+ */
+int32_t citrus_cache_score(const citrus_config* cfg, citrus_tensor q, int32_t rows, citrus_tensor k_cache,
+                           int32_t cache_len, float* score, void* workspace, size_t workspace_bytes,
+                           void* hip_stream);
 
 /*
  * Selection (Eq. (2)-(3)): the positions of the min(k, n) highest scores.
@@ -235,6 +264,14 @@ int32_t citrus_resident_provider(void* user, int32_t chunk_index, void* hip_stre
  *                    [LM cache ; chunk], topk_select(budget_lm), kv_compact of
  *                    the LM pair; then instr_score / topk_select(budget) /
  *                    kv_compact on the instruction pair.
+ *   DUAL with lm_ordering = EVICT_THEN_APPEND: chunk_attn over [LM cache ; chunk]
+ *                    where the LM cache holds up to budget_lm + chunk_len states;
+ *                    cache_score of the chunk's queries over the LM cache alone,
+ *                    topk_select(budget_lm) among its states, then the kept states
+ *                    followed by all states of the chunk are written to the other LM
+ *                    buffer (cache_len_lm grows to kept + chunk_len; no eviction
+ *                    happens after the last chunk).  idx_history_lm then holds the
+ *                    kept positions of the LM cache (not the appended chunk rows).
  * An empty cache (length 0) is the start of a document: the first chunk enters
  * whole if it fits the budget.
  *

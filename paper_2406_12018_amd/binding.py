@@ -21,6 +21,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libcitrus.so")
 F32, BF16 = 0, 1
 CACHE_INSTR, CACHE_SHARED, CACHE_DUAL = 0, 1, 2
 SELECT_PER_KV_HEAD, SELECT_PER_LAYER = 0, 1
+LM_SCORE_AFTER_APPEND, LM_EVICT_THEN_APPEND = 0, 1
 
 EVENTS_PER_STEP = 8
 
@@ -28,7 +29,7 @@ OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE, ERR_PROVIDE
 
 EXPORTS = (
     "citrus_abi_version", "citrus_status_string", "citrus_workspace_bytes", "citrus_chunk_attn",
-    "citrus_instr_score", "citrus_topk_select", "citrus_kv_compact", "citrus_resident_provider",
+    "citrus_instr_score", "citrus_cache_score", "citrus_topk_select", "citrus_kv_compact", "citrus_resident_provider",
     "citrus_process_document",
 )
 
@@ -43,7 +44,7 @@ class CitrusError(RuntimeError):
 class CConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "batch", "layers", "q_heads", "kv_heads", "head_dim", "chunk_len", "budget", "budget_lm", "instr_len",
-        "cache_capacity", "dtype", "cache_mode", "select_mode", "start_size")] + [("softmax_scale", C.c_float)]
+        "cache_capacity", "dtype", "cache_mode", "select_mode", "start_size", "lm_ordering")] + [("softmax_scale", C.c_float)]
 
 
 class CTensor(C.Structure):
@@ -86,6 +87,8 @@ def _lib():
     lib.citrus_chunk_attn.argtypes = [P(CConfig), CTensor, CTensor, CTensor, I, CTensor, CTensor, I, CTensor, V, V, V, S, V]
     lib.citrus_instr_score.restype = I
     lib.citrus_instr_score.argtypes = [P(CConfig), CTensor, CTensor, I, CTensor, I, V, V, S, V]
+    lib.citrus_cache_score.restype = I
+    lib.citrus_cache_score.argtypes = [P(CConfig), CTensor, I, CTensor, I, V, V, S, V]
     lib.citrus_topk_select.restype = I
     lib.citrus_topk_select.argtypes = [P(CConfig), V, I, I, V, V, S, V]
     lib.citrus_kv_compact.restype = I
@@ -113,18 +116,22 @@ class Config:
     cache_mode: int = CACHE_INSTR
     select_mode: int = SELECT_PER_KV_HEAD
     budget_lm: int = 0
-    cache_capacity: int = 0          # 0 -> max(budget, budget_lm)
+    cache_capacity: int = 0          # 0 -> the smallest capacity the configuration needs
     softmax_scale: float = 0.0
     start_size: int = 0              # leading document states that are never evicted
+    lm_ordering: int = LM_SCORE_AFTER_APPEND
 
     def __post_init__(self):
         if self.cache_capacity == 0:
-            self.cache_capacity = max(self.budget, self.budget_lm)
+            lm = self.budget_lm
+            if self.cache_mode == CACHE_DUAL and self.lm_ordering == LM_EVICT_THEN_APPEND:
+                lm += self.chunk_len  # the LM cache keeps the whole previous chunk until the next eviction
+            self.cache_capacity = max(self.budget, lm)
 
     def c(self) -> CConfig:
         return CConfig(self.batch, self.layers, self.q_heads, self.kv_heads, self.head_dim, self.chunk_len,
                        self.budget, self.budget_lm, self.instr_len, self.cache_capacity, self.dtype,
-                       self.cache_mode, self.select_mode, self.start_size, self.softmax_scale)
+                       self.cache_mode, self.select_mode, self.start_size, self.lm_ordering, self.softmax_scale)
 
     @property
     def torch_dtype(self) -> torch.dtype:
@@ -139,7 +146,8 @@ class Config:
         kw = dict(batch=w.batch, layers=w.layers, q_heads=w.q_heads, kv_heads=w.kv_heads, head_dim=w.head_dim,
                   chunk_len=w.chunk_len, budget=w.budget, instr_len=w.instr_len,
                   dtype=F32 if w.dtype == "f32" else BF16, cache_mode=w.cache_mode, select_mode=w.select_mode,
-                  budget_lm=w.budget_lm, start_size=getattr(w, "start_size", 0))
+                  budget_lm=w.budget_lm, start_size=getattr(w, "start_size", 0),
+                  lm_ordering=getattr(w, "lm_ordering", 0))
         kw.update(overrides)
         return Config(**kw)
 
@@ -213,6 +221,18 @@ def citrus_instr_score(cfg: Config, q_instr, k_cache, cache_len: int, k_chunk, s
                                    chunk_len, _ptr(score), _ptr(workspace),
                                    0 if workspace is None else workspace.numel(), _stream(stream))
     _check(st, "citrus_instr_score")
+    return score
+
+
+def citrus_cache_score(cfg: Config, q, k_cache, cache_len: int, score=None, workspace=None, stream=None,
+                       rows: Optional[int] = None):
+    rows = q.shape[3] if rows is None else rows
+    if score is None:
+        score = torch.empty((cfg.batch, cfg.layers, cfg.kv_heads, cache_len), dtype=torch.float32, device=q.device)
+    cc = cfg.c()
+    st = _lib().citrus_cache_score(C.byref(cc), tensor(q), rows, tensor(k_cache), cache_len, _ptr(score),
+                                   _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream))
+    _check(st, "citrus_cache_score")
     return score
 
 

@@ -562,8 +562,6 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
   const int t_begin = sp * tiles_per_split;
   const int t_end = min(all_tiles, t_begin + tiles_per_split);
   const bool wave_active = row0 < rows;
-  const int wave_row_last = min(rows, row0 + kRowsPerWave) - 1;
-  const int wave_limit_max = causal ? n_c + wave_row_last : n - 1;  // beyond it the wave sees nothing
   const int wave_limit_min = causal ? n_c + row0 : n - 1;           // up to it every row sees everything
 
   // ---- Q^T operand, kept in registers: q_op[kk] = Q[row0 + col][16 kk + 8 grp ..+7] ----

@@ -33,6 +33,11 @@ citrus_status check_config(const citrus_config* c) {
   const int need = c->cache_mode == CITRUS_CACHE_DUAL && c->budget_lm > c->budget ? c->budget_lm : c->budget;
   if (c->cache_capacity < need) return CITRUS_ERR_SHAPE;
   if (c->start_size < 0 || c->start_size >= c->budget) return CITRUS_ERR_SHAPE;
+  if (c->lm_ordering != CITRUS_LM_SCORE_AFTER_APPEND && c->lm_ordering != CITRUS_LM_EVICT_THEN_APPEND)
+    return CITRUS_ERR_UNSUPPORTED;
+  if (c->cache_mode == CITRUS_CACHE_DUAL && c->lm_ordering == CITRUS_LM_EVICT_THEN_APPEND &&
+      c->cache_capacity < c->budget_lm + c->chunk_len)
+    return CITRUS_ERR_SHAPE;
   if (c->cache_mode == CITRUS_CACHE_DUAL && c->start_size >= c->budget_lm) return CITRUS_ERR_SHAPE;
   if (!(c->softmax_scale >= 0.0f) || isinf(c->softmax_scale)) return CITRUS_ERR_SHAPE;
   return CITRUS_OK;
@@ -70,8 +75,12 @@ citrus_status check_lengths(const citrus_config* c, int cache_len, int chunk_len
 
 // Workspace layout (all blocks kAlign-aligned).
 struct Workspace {
-  size_t lse_chunk, lse_instr, score, score_lm, idx, idx_lm, total;
+  size_t lse_chunk, lse_instr, lse_cache, score, score_lm, idx, idx_lm, iota, total;
 };
+
+bool evict_then_append(const citrus_config* c) {
+  return c->cache_mode == CITRUS_CACHE_DUAL && c->lm_ordering == CITRUS_LM_EVICT_THEN_APPEND;
+}
 
 Workspace workspace_layout(const citrus_config* c) {
   Workspace w;
@@ -82,10 +91,12 @@ Workspace workspace_layout(const citrus_config* c) {
   size_t off = 0;
   w.lse_chunk = off; off += align_up(units_q * c->chunk_len * sizeof(float));
   w.lse_instr = off; off += align_up(units_q * c->instr_len * sizeof(float) * 16);  // partial (max, sum) pairs x 8 ranges
+  w.lse_cache = off; off += evict_then_append(c) ? align_up(units_q * c->chunk_len * sizeof(float) * 16) : 0;  // same, chunk rows
   w.score = off;     off += align_up(units_kv * n_max * sizeof(float));
   w.score_lm = off;  off += dual ? align_up(units_kv * n_max * sizeof(float)) : 0;
   w.idx = off;       off += align_up(units_kv * c->budget * sizeof(int32_t));
   w.idx_lm = off;    off += dual ? align_up(units_kv * c->budget_lm * sizeof(int32_t)) : 0;
+  w.iota = off;      off += evict_then_append(c) ? align_up(c->chunk_len * sizeof(int32_t)) : 0;
   w.total = off;
   return w;
 }
@@ -134,6 +145,23 @@ citrus_status do_instr_score(const citrus_config* c, const Dims& dm, const citru
   return CITRUS_OK;
 }
 
+// Eq. (1) as printed: the rows of q score the states of one cache, softmax over those states alone.
+// The cache is handed to the kernels as the only key segment.
+citrus_status do_cache_score(const citrus_config* c, const Dims& dm, const citrus_tensor& q, int rows,
+                             const citrus_tensor& k_cache, int cache_len, float* lse_ws, float* score, hipStream_t st) {
+  Segments ks;
+  ks.cache = make_view(k_cache);
+  ks.chunk = make_view(k_cache);
+  ks.n_c = 0;
+  ks.c = cache_len;
+  if (mfma_path_supported(c->dtype, dm))
+    return hip_status(launch_instr_score_mfma(dm, make_view(q), rows, ks, lse_ws, score, st));
+  View none{nullptr, 0, 0, 0, 0};
+  CITRUS_TRY(hip_status(run_attn(c, dm, make_view(q), rows, ks, ks, /*causal=*/0, none, lse_ws, st)));
+  CITRUS_TRY(hip_status(run_colsum(c, dm, make_view(q), rows, ks, /*causal=*/0, lse_ws, score, st)));
+  return CITRUS_OK;
+}
+
 int sel_heads(const citrus_config* c) { return c->select_mode == CITRUS_SELECT_PER_LAYER ? 1 : c->kv_heads; }
 
 citrus_status do_topk(const citrus_config* c, const float* score, int n, int k, int32_t* idx, hipStream_t st) {
@@ -147,6 +175,12 @@ citrus_status do_compact(const citrus_config* c, const Dims& dm, Segments ks, Se
                          hipStream_t st) {
   return hip_status(launch_compact(elem_bytes(c->dtype), dm, ks, vs, idx, idx_pitch, sel_heads(c), m,
                                    make_view(k_new), make_view(v_new), st));
+}
+
+// The same tensor starting at sequence row `row`.
+citrus_tensor rows_from(citrus_tensor t, int64_t row, int dtype) {
+  t.ptr = static_cast<char*>(t.ptr) + row * t.stride_s * elem_bytes(dtype);
+  return t;
 }
 
 Segments segments(const citrus_tensor& cache, int cache_len, const citrus_tensor& chunk, int chunk_len) {
@@ -219,6 +253,21 @@ int32_t citrus_instr_score(const citrus_config* cfg, citrus_tensor q_instr, citr
   float* lse_ws = reinterpret_cast<float*>(static_cast<char*>(workspace) + workspace_layout(cfg).lse_instr);
   return do_instr_score(cfg, dm, q_instr, segments(k_cache, cache_len, k_chunk, chunk_len), lse_ws, score,
                         static_cast<hipStream_t>(hip_stream));
+}
+
+int32_t citrus_cache_score(const citrus_config* cfg, citrus_tensor q, int32_t rows, citrus_tensor k_cache,
+                           int32_t cache_len, float* score, void* workspace, size_t workspace_bytes,
+                           void* hip_stream) {
+  CITRUS_TRY(check_config(cfg));
+  if (!evict_then_append(cfg)) return CITRUS_ERR_UNSUPPORTED;
+  if (rows < 1 || rows > cfg->chunk_len || cache_len < 1 || cache_len > cfg->cache_capacity) return CITRUS_ERR_SHAPE;
+  if (score == nullptr) return CITRUS_ERR_NULL;
+  CITRUS_TRY(check_tensor(q, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(k_cache, cfg->dtype, false));
+  CITRUS_TRY(check_workspace(cfg, workspace, workspace_bytes));
+  const Dims dm = dims_of(cfg);
+  float* lse_ws = reinterpret_cast<float*>(static_cast<char*>(workspace) + workspace_layout(cfg).lse_cache);
+  return do_cache_score(cfg, dm, q, rows, k_cache, cache_len, lse_ws, score, static_cast<hipStream_t>(hip_stream));
 }
 
 int32_t citrus_topk_select(const citrus_config* cfg, const float* score, int32_t n, int32_t k, int32_t* idx,
@@ -300,7 +349,9 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
   }
   if (k_cache[0].ptr == k_cache[1].ptr || v_cache[0].ptr == v_cache[1].ptr) return CITRUS_ERR_SHAPE;
   if (*cache_len < 0 || *cache_len > cfg->budget || (*buffer_index != 0 && *buffer_index != 1)) return CITRUS_ERR_SHAPE;
-  if (dual && (*cache_len_lm < 0 || *cache_len_lm > cfg->budget_lm || (*buffer_index_lm != 0 && *buffer_index_lm != 1)))
+  const bool paper_lm = evict_then_append(cfg);
+  if (dual && (*cache_len_lm < 0 || *cache_len_lm > cfg->budget_lm + (paper_lm ? cfg->chunk_len : 0) ||
+               (*buffer_index_lm != 0 && *buffer_index_lm != 1)))
     return CITRUS_ERR_SHAPE;
   CITRUS_TRY(check_workspace(cfg, workspace, workspace_bytes));
 
@@ -309,6 +360,8 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
   char* ws = static_cast<char*>(workspace);
   float* lse_chunk = reinterpret_cast<float*>(ws + wl.lse_chunk);
   float* lse_instr = reinterpret_cast<float*>(ws + wl.lse_instr);
+  float* lse_cache = reinterpret_cast<float*>(ws + wl.lse_cache);
+  int32_t* iota_ws = reinterpret_cast<int32_t*>(ws + wl.iota);
   float* score = reinterpret_cast<float*>(ws + wl.score);
   float* score_lm = reinterpret_cast<float*>(ws + wl.score_lm);
   int32_t* idx_ws = reinterpret_cast<int32_t*>(ws + wl.idx);
@@ -344,7 +397,34 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
     const int m = n < cfg->budget ? n : cfg->budget;
 
     mark(done, 0);
-    if (dual) {
+    if (paper_lm) {
+      // language-modelling thread in the order Section 4.1 prints: encode the chunk given the cache
+      // (it still holds the whole previous chunk), evict the cache by the chunk's attention to it,
+      // then put the chunk in
+      const Segments kl = segments(k_cache_lm[cur_lm], n_c_lm, io.k, c), vl = segments(v_cache_lm[cur_lm], n_c_lm, io.v, c);
+      const int m_lm = n_c_lm < cfg->budget_lm ? n_c_lm : cfg->budget_lm;
+      int32_t* idx_lm = idx_history_lm ? idx_history_lm + static_cast<size_t>(done) * units_sel * cfg->budget_lm : idx_lm_ws;
+      if ((status = do_chunk_attn(cfg, dm, io.q, kl, vl, io.out, nullptr, nullptr, st)) != CITRUS_OK) break;
+      mark(done, 1);
+      if (n_c_lm > cfg->budget_lm &&
+          (status = do_cache_score(cfg, dm, io.q, c, k_cache_lm[cur_lm], n_c_lm, lse_cache, score_lm, st)) != CITRUS_OK)
+        break;
+      mark(done, 2);
+      if (n_c_lm > 0 && (status = do_topk(cfg, score_lm, n_c_lm, cfg->budget_lm, idx_lm, st)) != CITRUS_OK) break;
+      mark(done, 3);
+      // kept cache states first, then the chunk's states behind them (positions n_c_lm .. of the candidates)
+      if (m_lm > 0 && (status = do_compact(cfg, dm, kl, vl, idx_lm, cfg->budget_lm, m_lm, k_cache_lm[cur_lm ^ 1],
+                                           v_cache_lm[cur_lm ^ 1], st)) != CITRUS_OK)
+        break;
+      if ((status = hip_status(launch_iota(iota_ws, n_c_lm, c, st))) != CITRUS_OK) break;
+      if ((status = hip_status(launch_compact(elem_bytes(cfg->dtype), dm, kl, vl, iota_ws, /*idx_pitch=*/0,
+                                              /*idx_heads=*/1, c, make_view(rows_from(k_cache_lm[cur_lm ^ 1], m_lm, cfg->dtype)),
+                                              make_view(rows_from(v_cache_lm[cur_lm ^ 1], m_lm, cfg->dtype)), st))) != CITRUS_OK)
+        break;
+      mark(done, 4);
+      cur_lm ^= 1;
+      n_c_lm = m_lm + c;
+    } else if (dual) {
       // language-modelling thread: the chunk attends over [LM cache ; chunk] and scores it itself
       const Segments kl = segments(k_cache_lm[cur_lm], n_c_lm, io.k, c), vl = segments(v_cache_lm[cur_lm], n_c_lm, io.v, c);
       const int n_lm = n_c_lm + c;

@@ -59,6 +59,8 @@ hipError_t launch_instr_score_mfma(const Dims& dm, View q, int rows, Segments ks
 // units = B*L*Hsel; score rows are [units*(per_layer?Hkv:1)] x n.
 hipError_t launch_topk(const float* score, int units, int heads_to_sum, int n, int k, int forced, int32_t* idx,
                        hipStream_t st);
+// p[i] = base + i for i < count
+hipError_t launch_iota(int32_t* p, int base, int count, hipStream_t st);
 hipError_t launch_compact(int elem_bytes, const Dims& dm, Segments kseg, Segments vseg, const int32_t* idx,
                           int idx_pitch, int idx_heads, int m, View k_new, View v_new, hipStream_t st);
 

@@ -125,6 +125,11 @@ __global__ __launch_bounds__(kSelThreads) void topk_kernel(const float* score, i
   }
 }
 
+__global__ void iota_kernel(int32_t* p, int base, int count) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) p[i] = base + i;
+}
+
 // Row gather: every thread moves 16 bytes of a K row and 16 bytes of a V row.
 template <int ROW_BYTES>
 __global__ __launch_bounds__(256) void compact_kernel(Dims dm, Segments ks, Segments vs, int elem_bytes,
@@ -178,6 +183,11 @@ hipError_t compact_launch(int elem_bytes, const Dims& dm, Segments ks, Segments 
 hipError_t launch_topk(const float* score, int units, int heads_to_sum, int n, int k, int forced, int32_t* idx,
                        hipStream_t st) {
   hipLaunchKernelGGL(topk_kernel, dim3(units), dim3(kSelThreads), 0, st, score, heads_to_sum, n, k, min(forced, k), idx);
+  return hipGetLastError();
+}
+
+hipError_t launch_iota(int32_t* p, int base, int count, hipStream_t st) {
+  hipLaunchKernelGGL(iota_kernel, dim3((count + 255) / 256), dim3(256), 0, st, p, base, count);
   return hipGetLastError();
 }
 

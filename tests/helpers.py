@@ -84,7 +84,31 @@ class StepwiseRun:
         rec = {"n_c": st.cache_len}
         kc, vc = st.k_cache[st.buffer_index], st.v_cache[st.buffer_index]
         n = st.cache_len + c
-        if dual:
+        if dual and cfg.lm_ordering == api.LM_EVICT_THEN_APPEND:
+            # Section 4.1's order: encode given the cache, evict the cache by the chunk's attention to it,
+            # then append the whole chunk
+            kl, vl = st.k_cache_lm[st.buffer_index_lm], st.v_cache_lm[st.buffer_index_lm]
+            kl_new, vl_new = st.k_cache_lm[st.buffer_index_lm ^ 1], st.v_cache_lm[st.buffer_index_lm ^ 1]
+            n_c_lm = st.cache_len_lm
+            m_lm = min(cfg.budget_lm, n_c_lm)
+            lse = torch.empty((cfg.batch, cfg.layers, cfg.q_heads, c), dtype=torch.float32, device=q.device)
+            out = api.citrus_chunk_attn(cfg, q, kl, vl, n_c_lm, k, v, lse=lse)
+            score_lm = idx_lm = None
+            if n_c_lm > 0:
+                if n_c_lm > cfg.budget_lm:
+                    score_lm = api.citrus_cache_score(cfg, q, kl, n_c_lm, workspace=self.ws)
+                    idx_lm = api.citrus_topk_select(cfg, score_lm, cfg.budget_lm)
+                else:  # everything stays: the selection does not read the scores
+                    unread = torch.zeros((cfg.batch, cfg.layers, cfg.kv_heads, n_c_lm), dtype=torch.float32, device=q.device)
+                    idx_lm = api.citrus_topk_select(cfg, unread, cfg.budget_lm)
+                api.citrus_kv_compact(cfg, kl, vl, n_c_lm, k, v, idx_lm, m_lm, kl_new, vl_new)
+            tail = torch.arange(n_c_lm, n_c_lm + c, dtype=torch.int32, device=q.device).expand(
+                cfg.batch, cfg.layers, cfg.sel_heads, c).contiguous()
+            api.citrus_kv_compact(cfg, kl, vl, n_c_lm, k, v, tail, c, kl_new[:, :, :, m_lm:], vl_new[:, :, :, m_lm:])
+            rec.update(n_c_lm=n_c_lm, score_lm=score_lm, idx_lm=idx_lm, m_lm=m_lm, lse=lse)
+            st.buffer_index_lm ^= 1
+            st.cache_len_lm = m_lm + c
+        elif dual:
             kl, vl = st.k_cache_lm[st.buffer_index_lm], st.v_cache_lm[st.buffer_index_lm]
             n_lm = st.cache_len_lm + c
             lm_score = torch.empty((cfg.batch, cfg.layers, cfg.kv_heads, n_lm), dtype=torch.float32, device=q.device)

@@ -24,11 +24,11 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(B.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
-    assert B.abi_version() == 2
+    assert B.abi_version() == 3
 
 
 def test_struct_layouts_match_the_header():
-    assert C.sizeof(B.CConfig) == 15 * 4
+    assert C.sizeof(B.CConfig) == 16 * 4
     assert C.sizeof(B.CTensor) == 5 * 8
     assert C.sizeof(B.CChunkIO) == 5 * 40 + 8
     assert C.sizeof(B.CResidentDoc) == 5 * 40 + 8 + 16
@@ -50,7 +50,10 @@ def test_status_strings():
     ({}, True), ({"q_heads": 3}, False), ({"head_dim": 96}, False), ({"budget": 0}, False), ({"dtype": 7}, False),
     ({"cache_mode": B.CACHE_DUAL}, False), ({"cache_mode": B.CACHE_DUAL, "budget_lm": 16}, True),
     ({"cache_capacity": 8}, False), ({"softmax_scale": -1.0}, False), ({"select_mode": 5}, False),
-    ({"batch": 70000}, False),
+    ({"batch": 70000}, False), ({"lm_ordering": 2}, False),
+    ({"cache_mode": B.CACHE_DUAL, "budget_lm": 16, "lm_ordering": B.LM_EVICT_THEN_APPEND}, True),
+    # the evict-then-append cache keeps a whole chunk beside the budget
+    ({"cache_mode": B.CACHE_DUAL, "budget_lm": 48, "lm_ordering": B.LM_EVICT_THEN_APPEND, "cache_capacity": 64}, False),
 ])
 def test_workspace_bytes_validates_config(kw, ok):
     assert (B.workspace_bytes(cfg(**kw)) > 0) == ok
@@ -97,6 +100,18 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     for bad_start in (-1, cfg().budget):
         bs = cfg(start_size=bad_start).c()
         assert lib.citrus_topk_select(C.byref(bs), C.c_void_p(0x2000), 8, 4, C.c_void_p(0x3000), None, 0, None) == B.ERR_SHAPE
+    # cache_score exists only for the evict-then-append ordering of the DUAL design
+    sc = C.c_void_p(0x2000)
+    assert lib.citrus_cache_score(C.byref(c), fake(), 8, fake(), 8, sc, ws, big, None) == B.ERR_UNSUPPORTED
+    e = cfg(cache_mode=B.CACHE_DUAL, budget_lm=16, lm_ordering=B.LM_EVICT_THEN_APPEND).c()
+    assert lib.citrus_cache_score(C.byref(e), null, 8, fake(), 8, sc, ws, big, None) == B.ERR_NULL
+    assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 8, None, ws, big, None) == B.ERR_NULL
+    assert lib.citrus_cache_score(C.byref(e), fake(), 0, fake(), 8, sc, ws, big, None) == B.ERR_SHAPE
+    assert lib.citrus_cache_score(C.byref(e), fake(), 33, fake(), 8, sc, ws, big, None) == B.ERR_SHAPE
+    assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 0, sc, ws, big, None) == B.ERR_SHAPE
+    assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 65, sc, ws, big, None) == B.ERR_SHAPE
+    assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 8, sc, None, 0, None) == B.ERR_WORKSPACE
+    assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 8, sc, ws, 16, None) == B.ERR_WORKSPACE
     # unsupported head_dim
     bad = cfg(head_dim=96).c()
     assert lib.citrus_topk_select(C.byref(bad), C.c_void_p(0x2000), 8, 4, C.c_void_p(0x3000), None, 0, None) == B.ERR_UNSUPPORTED

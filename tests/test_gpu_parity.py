@@ -196,6 +196,32 @@ def test_instr_score_parity(shape):
     assert torch.equal(score, again)
 
 
+@pytest.mark.parametrize("shape", [s for s in SHAPES if s[7] > 0], ids=lambda s: "-".join(str(x) for x in s[:9]))
+def test_cache_score_parity(shape):
+    """Eq. (1) as printed, with the chunk's queries: softmax over the cache states alone, no mask."""
+    dtype, B, L, Hq, Hkv, d, c, n_c, n_i, s = shape
+    say(f"cache_score {shape}")
+    x = step_inputs(*shape, seed=200)
+    cfg = make_cfg(dtype, B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, c=c, k=8, n_i=n_i, cache_mode=api.CACHE_DUAL, budget_lm=4,
+                   lm_ordering=api.LM_EVICT_THEN_APPEND, cache_capacity=n_c + c + 3)
+    ws = api.alloc_workspace(cfg)
+    for rows in sorted({c, max(1, c // 3)}):
+        score = api.citrus_cache_score(cfg, x["q"], x["kc"], n_c, workspace=ws, rows=rows)
+        torch.cuda.synchronize()
+        got = np64(score)
+        for b in range(B):
+            for l in range(L):
+                ref = orc.instr_score(np64(x["q"][b, l, :, :rows]), np64(x["kc"][b, l, :, :n_c]))
+                assert_close(got[b, l], ref, dtype, f"cache score rows {rows} b{b} l{l}")
+        np.testing.assert_allclose(got.sum(-1), rows * (Hq // Hkv), rtol=2e-3 if dtype == "bf16" else 1e-5)
+        again = api.citrus_cache_score(cfg, x["q"], x["kc"], n_c, workspace=ws, rows=rows)
+        assert torch.equal(score, again)
+    # the ordering this entry point belongs to must be configured
+    plain = make_cfg(dtype, B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, c=c, k=n_c + 3, n_i=n_i)
+    with pytest.raises(api.CitrusError):
+        api.citrus_cache_score(plain, x["q"], x["kc"], n_c, workspace=api.alloc_workspace(plain))
+
+
 @pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "-".join(str(x) for x in s[:9]))
 def test_chunk_attn_parity(shape):
     dtype, B, L, Hq, Hkv, d, c, n_c, n_i, s = shape
@@ -298,6 +324,7 @@ def run_document_stepwise(w: Workload, sample_units=None, check_every=1):
     doc = make_document(w, DEV)
     run = StepwiseRun(api, cfg, DEV)
     dual = w.cache_mode == api.CACHE_DUAL
+    paper_lm = dual and w.lm_ordering == api.LM_EVICT_THEN_APPEND
     units = sample_units or [(b, l) for b in range(w.batch) for l in range(w.layers)]
     hs = cfg.sel_heads
     # oracle-side state per unit: document positions held by each cache row
@@ -328,17 +355,41 @@ def run_document_stepwise(w: Workload, sample_units=None, check_every=1):
                 kcat_lm = np.stack([kd[g, cand_lm[g]] for g in range(w.kv_heads)])
                 vcat_lm = np.stack([vd[g, cand_lm[g]] for g in range(w.kv_heads)])
                 n_c_lm = pos_lm[(b, l)].shape[1]
-                idx_lm = rec["idx_lm"][b, l].cpu().numpy()[:, :rec["m_lm"]]
+                assert n_c_lm == rec["n_c_lm"]
                 if check:
                     o_ref, lse_ref, _ = orc.chunk_attn(qd, kcat_lm, vcat_lm, n_c_lm)
-                    s_lm_ref = orc.lm_score(qd, kcat_lm, n_c_lm)
-                    assert_close(np64(rec["score_lm"][b, l]), s_lm_ref, w.dtype, f"lm_score step {i} unit {(b, l)}")
-                    for g in range(hs):
-                        ref_vec = s_lm_ref.sum(0) if hs == 1 else s_lm_ref[g]
-                        gpu_vec = layer_sum_f32(rec["score_lm"][b, l]) if hs == 1 else rec["score_lm"][b, l, g].cpu().numpy()
-                        band_fracs.append(check_selection(idx_lm[g], gpu_vec, ref_vec, w.budget_lm, w.dtype,
-                                                          f"lm select step {i}", w.start_size))
-                pos_lm[(b, l)] = np.stack([cand_lm[g][idx_lm[g % hs]] for g in range(w.kv_heads)])
+                if paper_lm:
+                    # the chunk's queries score the cache states alone; the kept ones stay in order and
+                    # the whole chunk goes in behind them
+                    kept = pos_lm[(b, l)]
+                    if n_c_lm > 0:
+                        idx_lm = rec["idx_lm"][b, l].cpu().numpy()[:, :rec["m_lm"]]
+                        if check and n_c_lm > w.budget_lm:
+                            s_lm_ref = orc.instr_score(qd, kcat_lm[:, :n_c_lm])
+                            assert_close(np64(rec["score_lm"][b, l]), s_lm_ref, w.dtype,
+                                         f"cache score step {i} unit {(b, l)}")
+                            for g in range(hs):
+                                ref_vec = s_lm_ref.sum(0) if hs == 1 else s_lm_ref[g]
+                                gpu_vec = (layer_sum_f32(rec["score_lm"][b, l]) if hs == 1
+                                           else rec["score_lm"][b, l, g].cpu().numpy())
+                                band_fracs.append(check_selection(idx_lm[g], gpu_vec, ref_vec, w.budget_lm, w.dtype,
+                                                                  f"lm cache select step {i}", w.start_size))
+                        elif check:
+                            np.testing.assert_array_equal(idx_lm, np.tile(np.arange(n_c_lm), (hs, 1)))
+                        kept = np.stack([kept[g][idx_lm[g % hs]] for g in range(w.kv_heads)])
+                    pos_lm[(b, l)] = np.concatenate([kept, chunk_pos], axis=1)
+                else:
+                    idx_lm = rec["idx_lm"][b, l].cpu().numpy()[:, :rec["m_lm"]]
+                    if check:
+                        s_lm_ref = orc.lm_score(qd, kcat_lm, n_c_lm)
+                        assert_close(np64(rec["score_lm"][b, l]), s_lm_ref, w.dtype, f"lm_score step {i} unit {(b, l)}")
+                        for g in range(hs):
+                            ref_vec = s_lm_ref.sum(0) if hs == 1 else s_lm_ref[g]
+                            gpu_vec = (layer_sum_f32(rec["score_lm"][b, l]) if hs == 1
+                                       else rec["score_lm"][b, l, g].cpu().numpy())
+                            band_fracs.append(check_selection(idx_lm[g], gpu_vec, ref_vec, w.budget_lm, w.dtype,
+                                                              f"lm select step {i}", w.start_size))
+                    pos_lm[(b, l)] = np.stack([cand_lm[g][idx_lm[g % hs]] for g in range(w.kv_heads)])
             elif check:
                 o_ref, lse_ref, _ = orc.chunk_attn(qd, kcat, vcat, n_c)
             if check:
@@ -396,6 +447,11 @@ DOC_CASES = {
     "cfg1_start4": scaled_down(peaked(WORKLOADS["cfg1_tiny_f32"]), doc_len=256, layers=2, kv_heads=2, start_size=4),
     "cfg1_dual_start4": scaled_down(peaked(WORKLOADS["cfg1_tiny_f32"]), doc_len=256, cache_mode=api.CACHE_DUAL,
                                     budget_lm=48, start_size=4),
+    "cfg1_dual_paper_order": scaled_down(peaked(WORKLOADS["cfg1_tiny_f32"]), doc_len=301, cache_mode=api.CACHE_DUAL,
+                                         budget_lm=48, lm_ordering=api.LM_EVICT_THEN_APPEND),
+    "cfg1_dual_paper_order_start4_per_layer": scaled_down(
+        peaked(WORKLOADS["cfg1_tiny_f32"]), doc_len=256, layers=2, kv_heads=2, cache_mode=api.CACHE_DUAL, budget_lm=20,
+        start_size=4, select_mode=api.SELECT_PER_LAYER, lm_ordering=api.LM_EVICT_THEN_APPEND),
     "cfg2_small": scaled_down(WORKLOADS["cfg2_mistral7b"], layers=2, doc_len=2560),
     "cfg2_small_start4": scaled_down(WORKLOADS["cfg2_mistral7b"], layers=2, doc_len=2560, start_size=4),
     "cfg2_small_peaked": scaled_down(peaked(WORKLOADS["cfg2_mistral7b"]), layers=1, doc_len=2000),
@@ -403,6 +459,9 @@ DOC_CASES = {
                                          doc_len=2100, chunk_len=256, budget=384, instr_len=32),
     "cfg4_small_dual": scaled_down(peaked(WORKLOADS["cfg4_dual"]), batch=2, layers=1, q_heads=8, kv_heads=2,
                                    doc_len=1536, chunk_len=256, budget=320, budget_lm=384),
+    "cfg4_small_dual_paper_order": scaled_down(peaked(WORKLOADS["cfg4_dual"]), batch=2, layers=1, q_heads=8, kv_heads=2,
+                                               doc_len=1500, chunk_len=256, budget=320, budget_lm=384,
+                                               lm_ordering=api.LM_EVICT_THEN_APPEND),
     "cfg5_small_g8": scaled_down(WORKLOADS["cfg5_large"], batch=1, layers=1, q_heads=16, kv_heads=2, doc_len=2048,
                                  chunk_len=512, budget=640, instr_len=96),
 }
@@ -455,8 +514,9 @@ def run_process_document(w, doc, split_at=None, use_python_provider=False):
     return state, out, hist, hist_lm
 
 
-@pytest.mark.parametrize("case", ["cfg1", "cfg1_ragged", "cfg1_dual", "cfg1_dual_start4", "cfg2_small", "cfg2_small_start4",
-                                  "cfg4_small_dual"])
+@pytest.mark.parametrize("case", ["cfg1", "cfg1_ragged", "cfg1_dual", "cfg1_dual_start4", "cfg1_dual_paper_order",
+                                  "cfg1_dual_paper_order_start4_per_layer", "cfg2_small", "cfg2_small_start4",
+                                  "cfg4_small_dual", "cfg4_small_dual_paper_order"])
 def test_process_document_equals_stepwise_and_resumes(case):
     w = DOC_CASES[case]
     say(f"process_document {case}")
@@ -474,11 +534,12 @@ def test_process_document_equals_stepwise_and_resumes(case):
     state, out, hist, hist_lm = run_process_document(w, doc)
     assert torch.equal(out, out_step)
     assert state.cache_len == run.state.cache_len == min(w.budget, w.doc_len)
+    assert state.cache_len_lm == run.state.cache_len_lm
     for a, b in zip(state.current(), run.state.current()):
         assert torch.equal(a, b)
     for i, rec in enumerate(run.steps):
         assert torch.equal(hist[i][..., :rec["m"]], rec["idx"][..., :rec["m"]])
-        if hist_lm is not None:
+        if hist_lm is not None and rec["idx_lm"] is not None:  # None: first chunk of the evict-then-append order
             assert torch.equal(hist_lm[i][..., :rec["m_lm"]], rec["idx_lm"][..., :rec["m_lm"]])
     if hist_lm is not None:
         for a, b in zip(state.current_lm(), run.state.current_lm()):
