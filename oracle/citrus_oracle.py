@@ -26,6 +26,11 @@ What each function follows in the paper:
 * ``process_document``: the chunk loop of Section 4.1 / 4.3 with the cache
   designs of Section 4.2 (individual, shared) and the dual form
   (language-modelling cache next to the instruction cache).
+* ``evict_cache``: one eviction of a cache by a text (Section 4.1 step 2, and
+  the extra eviction by the instruction after the last chunk that the same
+  paragraph describes): Eq. (1) over the cache states alone, Eq. (2)-(3).
+* ``standard_cse``: the Standard CSE process of Section 4.1 on its own (one
+  cache, evicted by the document chunks), ending with that extra eviction.
 
 Readings taken where the paper is silent (all listed again in the design
 notes of the repository):
@@ -351,6 +356,102 @@ def process_document(q, k, v, q_instr: Sequence[np.ndarray], chunk_len: int, bud
                           k_cache_lm=kc_lm if dual else None,
                           v_cache_lm=vc_lm if dual else None,
                           positions_lm=pos_lm if dual else None, trace=trace)
+
+
+def evict_cache(q_text, k_cache, v_cache, k: int, select_mode: int = SELECT_PER_KV_HEAD, start_size: int = 0,
+                scale: Optional[float] = None, forced_idx: Optional[np.ndarray] = None):
+    """One eviction of a cache by a text (Section 4.1, step 2; with the
+    instruction as the text it is the additional eviction after the last
+    chunk that removes the bias towards that chunk).
+
+    q_text [Hq, rows, d]: queries of the text's tokens; k_cache, v_cache
+    [Hkv, n, d].  The states are scored by Eq. (1), the softmax running over
+    the n states of the cache alone (every token of the text sees the whole
+    cache); the k best stay in their order (Eq. (2)-(3)).
+    Returns (k_new, v_new, idx, score).
+    """
+    score = instr_score(q_text, k_cache, scale)
+    idx = np.asarray(forced_idx) if forced_idx is not None else topk_select(score, k, select_mode, start_size)
+    k_new, v_new = kv_compact(k_cache, v_cache, idx)
+    return k_new, v_new, idx, score
+
+
+@dataclass
+class StandardCseResult:
+    out: np.ndarray                      # [Hq, T, d] chunk outputs over the whole document
+    k_cache: np.ndarray                  # [Hkv, n_c, d] cache when the document ends (before a final eviction)
+    v_cache: np.ndarray
+    positions: np.ndarray                # [Hkv, n_c]
+    idx: List[np.ndarray]                # per chunk: kept positions among that step's candidates
+    score: List[np.ndarray]              # per chunk: the scores they were chosen by
+    k_final: Optional[np.ndarray] = None  # after the eviction by the instruction, if one was asked for
+    v_final: Optional[np.ndarray] = None
+    positions_final: Optional[np.ndarray] = None
+    idx_final: Optional[np.ndarray] = None
+    score_final: Optional[np.ndarray] = None
+
+
+def standard_cse(q, k, v, chunk_len: int, budget: int, lm_ordering: int = LM_EVICT_THEN_APPEND,
+                 select_mode: int = SELECT_PER_KV_HEAD, start_size: int = 0, scale: Optional[float] = None,
+                 q_instr_final=None, forced_idx: Optional[Sequence[np.ndarray]] = None,
+                 forced_idx_final: Optional[np.ndarray] = None) -> StandardCseResult:
+    """Standard CSE alone (Section 4.1, "Overall process"): one cache, evicted
+    by the document's own chunks, no instruction during encoding.
+
+    LM_EVICT_THEN_APPEND is the printed order: encode the chunk given the
+    cache, evict the cache down to ``budget`` states by the chunk's attention
+    to it (Eq. (1) over the cache states alone), put all states of the chunk
+    in; the first chunk just enters.  LM_SCORE_AFTER_APPEND is this
+    repository's other reading: the chunk's states are appended first and the
+    chunk's own causal attention over [cache ; chunk] decides which ``budget``
+    of them stay.
+    If ``q_instr_final`` [Hq, n_i, d] is given, the cache is evicted one more
+    time with the instruction as the text once the document has ended, down to
+    ``budget`` states (the end of the same paragraph).
+    """
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    hq, t_total, d = q.shape
+    hkv = k.shape[0]
+    n_chunks = (t_total + chunk_len - 1) // chunk_len
+    kc = np.zeros((hkv, 0, d)); vc = np.zeros((hkv, 0, d))
+    pos = np.zeros((hkv, 0), dtype=np.int64)
+    outs, idxs, scores = [], [], []
+    for i in range(n_chunks):
+        lo, hi = i * chunk_len, min(t_total, (i + 1) * chunk_len)
+        qs, ks, vs = q[:, lo:hi], k[:, lo:hi], v[:, lo:hi]
+        chunk_pos = np.broadcast_to(np.arange(lo, hi, dtype=np.int64), (hkv, hi - lo))
+        n_c = kc.shape[1]
+        forced = None if forced_idx is None else forced_idx[i]
+        # step 1: encode the chunk given the cache
+        out, _, _ = chunk_attn(qs, np.concatenate([kc, ks], axis=1), np.concatenate([vc, vs], axis=1), n_c, scale)
+        outs.append(out)
+        if lm_ordering == LM_EVICT_THEN_APPEND:
+            if n_c > 0:
+                # step 2: the chunk evicts the cache
+                kc, vc, idx, sc = evict_cache(qs, kc, vc, budget, select_mode, start_size, scale, forced)
+                pos = np.stack([pos[g][idx[g % idx.shape[0]]] for g in range(hkv)])
+            else:
+                idx, sc = np.zeros((1 if select_mode == SELECT_PER_LAYER else hkv, 0), dtype=np.int64), np.zeros((hkv, 0))
+            # step 3: the chunk's states enter
+            kc = np.concatenate([kc, ks], axis=1)
+            vc = np.concatenate([vc, vs], axis=1)
+            pos = np.concatenate([pos, chunk_pos], axis=1)
+        else:
+            k_cat, v_cat = np.concatenate([kc, ks], axis=1), np.concatenate([vc, vs], axis=1)
+            pos_cat = np.concatenate([pos, chunk_pos], axis=1)
+            sc = lm_score(qs, k_cat, n_c, scale)
+            idx = np.asarray(forced) if forced is not None else topk_select(sc, budget, select_mode, start_size)
+            kc, vc = kv_compact(k_cat, v_cat, idx)
+            pos = np.stack([pos_cat[g][idx[g % idx.shape[0]]] for g in range(hkv)])
+        idxs.append(idx)
+        scores.append(sc)
+    res = StandardCseResult(out=np.concatenate(outs, axis=1), k_cache=kc, v_cache=vc, positions=pos, idx=idxs,
+                            score=scores)
+    if q_instr_final is not None:
+        res.k_final, res.v_final, res.idx_final, res.score_final = evict_cache(
+            _f64(q_instr_final), kc, vc, budget, select_mode, start_size, scale, forced_idx_final)
+        res.positions_final = np.stack([pos[g][res.idx_final[g % res.idx_final.shape[0]]] for g in range(hkv)])
+    return res
 
 
 def full_causal_attention(q, k, v, scale: Optional[float] = None) -> np.ndarray:

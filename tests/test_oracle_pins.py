@@ -459,10 +459,26 @@ def test_kv_compact_is_a_bit_copy_and_broadcasts():
 # the language-modelling cache in the order Section 4.1 prints (evict, then append)
 # ----------------------------------------------------------------------------
 
-def _standard_cse_by_hand(q, k, v, chunk, budget):
+def _importance_by_hand(q_rows, k, cache):
+    """Eq. (1) with plain loops for one head: mean over the text's tokens of the softmax over the cache alone."""
+    d = k.shape[1]
+    imp = [0.0] * len(cache)
+    for qt in q_rows:
+        logit = [sum(qt[x] * k[j][x] for x in range(d)) / math.sqrt(d) for j in cache]
+        mx = max(logit)
+        w = [math.exp(a - mx) for a in logit]
+        z = sum(w)
+        for a in range(len(cache)):
+            imp[a] += w[a] / z / len(q_rows)
+    return imp
+
+
+def _standard_cse_by_hand(q, k, v, chunk, budget, q_final=None):
     """Standard chunked state eviction for ONE head, written with plain loops from the three steps of
     Section 4.1: encode the chunk given the cache; evict the cache by Eq. (1) (s = chunk, normalised over
-    the cache states); put the chunk into the cache.  Returns (outputs [T, d], final cache positions)."""
+    the cache states); put the chunk into the cache.  With ``q_final`` (the instruction's queries) the cache
+    is evicted once more by the instruction when the document has ended.
+    Returns (outputs [T, d], final cache positions)."""
     t_total, d = q.shape
     cache = []                                   # document positions, in order
     outs = np.zeros((t_total, v.shape[1]))
@@ -491,6 +507,10 @@ def _standard_cse_by_hand(q, k, v, chunk, budget):
             cache = [cache[a] for a in sorted(order)]
         # step 3
         cache = cache + list(range(lo, hi))
+    if q_final is not None and len(cache) > budget:
+        imp = _importance_by_hand(q_final, k, cache)
+        order = sorted(range(len(cache)), key=lambda a: (-imp[a], a))[:budget]
+        cache = [cache[a] for a in sorted(order)]
     return outs, cache
 
 
@@ -537,3 +557,92 @@ def test_lm_evict_then_append_with_large_budget_is_full_attention():
     out = np.concatenate([tr.out for tr in res.trace], axis=1)
     np.testing.assert_allclose(out, _sdpa(q, k, v, causal=True, group=2), atol=1e-12)
     np.testing.assert_array_equal(res.k_cache_lm, k)
+
+
+# ----------------------------------------------------------------------------
+# Standard CSE on its own, and the extra eviction by the instruction at the end
+# ----------------------------------------------------------------------------
+
+def test_standard_cse_vs_hand_written_loop_with_final_instruction_eviction():
+    hq, hkv, t, d, chunk, budget = 1, 1, 43, 4, 6, 8
+    q, k, v, qi = _doc(141, hq, hkv, t, d, 3, chunk)
+    res = orc.standard_cse(q, k, v, chunk, budget, q_instr_final=qi[-1])
+    outs, cache_before = _standard_cse_by_hand(q[0], k[0], v[0], chunk, budget)
+    _, cache_after = _standard_cse_by_hand(q[0], k[0], v[0], chunk, budget, q_final=qi[-1][0])
+    np.testing.assert_allclose(res.out[0], outs, atol=1e-12)
+    assert res.positions[0].tolist() == cache_before
+    assert res.positions_final[0].tolist() == cache_after and len(cache_after) == budget
+    np.testing.assert_array_equal(res.k_final[0], k[0][cache_after])
+    np.testing.assert_array_equal(res.v_final[0], v[0][cache_after])
+    # the hand-written importance is the mean, the oracle's score the sum over the text's tokens
+    imp = _importance_by_hand(qi[-1][0], k[0], cache_before)
+    np.testing.assert_allclose(res.score_final[0] / qi[-1].shape[1], imp, atol=1e-12)
+
+
+def _append_then_evict_by_hand(q, k, chunk, budget):
+    """The other ordering for ONE head with plain loops: the chunk's states are appended, the chunk's own
+    causal attention over [cache ; chunk] is summed per state, the best ``budget`` stay."""
+    t_total, d = q.shape
+    cache = []
+    for lo in range(0, t_total, chunk):
+        hi = min(t_total, lo + chunk)
+        cand = cache + list(range(lo, hi))
+        imp = [0.0] * len(cand)
+        for t in range(lo, hi):
+            seen = len(cache) + (t - lo) + 1
+            logit = [sum(q[t][x] * k[j][x] for x in range(d)) / math.sqrt(d) for j in cand[:seen]]
+            mx = max(logit)
+            w = [math.exp(a - mx) for a in logit]
+            z = sum(w)
+            for a in range(seen):
+                imp[a] += w[a] / z
+        order = sorted(range(len(cand)), key=lambda a: (-imp[a], a))[:budget]
+        cache = [cand[a] for a in sorted(order)]
+    return cache
+
+
+def test_standard_cse_score_after_append_vs_hand_written_loop_and_dual_lm_thread():
+    hq, hkv, t, d, chunk, budget = 1, 1, 41, 4, 7, 9
+    q, k, v, qi = _doc(142, hq, hkv, t, d, 2, chunk)
+    res = orc.standard_cse(q, k, v, chunk, budget, lm_ordering=orc.LM_SCORE_AFTER_APPEND)
+    assert res.positions[0].tolist() == _append_then_evict_by_hand(q[0], k[0], chunk, budget)
+    # several heads: the language-modelling thread of the dual design is the same process
+    hq, hkv = 4, 2
+    q, k, v, qi = _doc(143, hq, hkv, t, d, 2, chunk)
+    for ordering in (orc.LM_SCORE_AFTER_APPEND, orc.LM_EVICT_THEN_APPEND):
+        for mode in (orc.SELECT_PER_KV_HEAD, orc.SELECT_PER_LAYER):
+            alone = orc.standard_cse(q, k, v, chunk, budget, lm_ordering=ordering, select_mode=mode, start_size=2)
+            dual = orc.process_document(q, k, v, qi, chunk, budget=5, cache_mode=orc.CACHE_DUAL, budget_lm=budget,
+                                        select_mode=mode, start_size=2, lm_ordering=ordering)
+            np.testing.assert_array_equal(alone.positions, dual.positions_lm)
+            np.testing.assert_allclose(alone.out, np.concatenate([tr.out for tr in dual.trace], axis=1), atol=1e-12)
+
+
+def test_evict_cache_one_token_one_head_keeps_the_largest_dot_products():
+    """A text of one token and one head: softmax is monotone, so the kept states are those with the k largest
+    q.k, whatever the normalisation; a transposed operand or a wrong sign would choose others."""
+    rng = np.random.default_rng(144)
+    n, d, keep = 23, 6, 5
+    qt, kc, vc = rng.standard_normal((1, 1, d)), rng.standard_normal((1, n, d)), rng.standard_normal((1, n, d))
+    k_new, v_new, idx, score = orc.evict_cache(qt, kc, vc, keep)
+    dots = [float(sum(qt[0, 0, x] * kc[0, j, x] for x in range(d))) for j in range(n)]
+    want = sorted(sorted(range(n), key=lambda j: -dots[j])[:keep])
+    assert idx[0].tolist() == want
+    np.testing.assert_array_equal(k_new[0], kc[0][want])
+    np.testing.assert_array_equal(v_new[0], vc[0][want])
+    np.testing.assert_allclose(score.sum(), 1.0, atol=1e-12)
+
+
+def test_evict_cache_invariants_and_small_cache():
+    rng = np.random.default_rng(145)
+    hq, hkv, n, d, rows = 4, 2, 30, 8, 5
+    qt, kc, vc = rng.standard_normal((hq, rows, d)), rng.standard_normal((hkv, n, d)), rng.standard_normal((hkv, n, d))
+    k_new, v_new, idx, score = orc.evict_cache(qt, kc, vc, 12, start_size=3)
+    np.testing.assert_allclose(score.sum(axis=1), rows * (hq // hkv), atol=1e-10)
+    assert idx.shape == (hkv, 12) and np.all(np.diff(idx, axis=1) > 0) and np.all(idx[:, :3] == np.arange(3))
+    for g in range(hkv):
+        np.testing.assert_array_equal(k_new[g], kc[g][idx[g]])
+    # a cache that fits the budget stays whole
+    k_all, v_all, idx_all, _ = orc.evict_cache(qt, kc, vc, 64)
+    np.testing.assert_array_equal(k_all, kc)
+    np.testing.assert_array_equal(idx_all, np.tile(np.arange(n), (hkv, 1)))
