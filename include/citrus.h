@@ -58,7 +58,7 @@
 extern "C" {
 #endif
 
-#define CITRUS_ABI_VERSION 3
+#define CITRUS_ABI_VERSION 4
 #define CITRUS_EVENTS_PER_STEP 8
 
 typedef enum {
@@ -77,10 +77,20 @@ typedef enum { CITRUS_F32 = 0, CITRUS_BF16 = 1 } citrus_dtype;
  * on one cache that the chunk attends over and the instruction scores (with
  * layer-independent synthetic inputs there is no separate language-modelling
  * cache to differ from); DUAL keeps a language-modelling cache, scored by the
- * chunk's own attention (Eq. (1) with s = chunk), next to the instruction cache. */
-typedef enum { CITRUS_CACHE_INSTR = 0, CITRUS_CACHE_SHARED = 1, CITRUS_CACHE_DUAL = 2 } citrus_cache_mode;
+ * chunk's own attention (Eq. (1) with s = chunk), next to the instruction cache.
+ * STANDARD is the Standard CSE process of Section 4.1 on its own: one cache
+ * (budget `budget`), evicted by the document's chunks; the instruction takes no
+ * part in the loop, and the extra eviction by the instruction after the last
+ * chunk is citrus_evict_cache. */
+typedef enum {
+  CITRUS_CACHE_INSTR = 0,
+  CITRUS_CACHE_SHARED = 1,
+  CITRUS_CACHE_DUAL = 2,
+  CITRUS_CACHE_STANDARD = 3
+} citrus_cache_mode;
 
-/* How the language-modelling cache of the DUAL design is evicted.
+/* How the cache that the document's own chunks evict (the language-modelling cache of DUAL, the only cache
+ * of STANDARD; budget_lm reads budget for the latter) is evicted.
  * SCORE_AFTER_APPEND: the chunk's own causal attention scores [cache ; chunk] in the step that encodes it.
  * EVICT_THEN_APPEND:  the three steps of Section 4.1 in the order printed: the chunk is encoded given the
  *   cache (which still holds the whole previous chunk: up to budget_lm + chunk_len states), the states of
@@ -111,8 +121,8 @@ typedef struct {
   int32_t select_mode;    /* citrus_select_mode                                  */
   int32_t start_size;     /* leading document states that are never evicted (appendix "Analysis on
                              initial tokens"); 0 = plain Eq. (2)-(3); < budget (and < budget_lm)  */
-  int32_t lm_ordering;    /* citrus_lm_ordering (DUAL only); EVICT_THEN_APPEND needs
-                             cache_capacity >= budget_lm + chunk_len                          */
+  int32_t lm_ordering;    /* citrus_lm_ordering (DUAL, STANDARD); EVICT_THEN_APPEND needs cache_capacity >=
+                             budget_lm + chunk_len (DUAL) or budget + chunk_len (STANDARD)             */
   float softmax_scale;    /* 0 -> 1/sqrt(head_dim), the scaling of Eq. (1)       */
 } citrus_config;
 
@@ -180,17 +190,37 @@ int32_t citrus_instr_score(const citrus_config* cfg, citrus_tensor q_instr, citr
  * the cache, softmax normalised over the cache states alone, summed over the rows and over the query heads of
  * each KV group (divide by rows*G for the mean):
  *   score[b,l,g,j] = sum_{h in g} sum_{t < rows} softmax_{j' < cache_len}(scale * q[b,l,h,t,:] . K[b,l,g,j',:])_j
- * Used with q = the chunk's queries by the EVICT_THEN_APPEND ordering (Section 4.1, step 2); every row sees
- * the whole cache, so there is no mask.
+ * Used with q = the chunk's queries by the EVICT_THEN_APPEND ordering (Section 4.1, step 2) and with q = the
+ * instruction's queries by the extra eviction after the last chunk; every row sees the whole cache, so there
+ * is no mask.
  *
- * q       [B, L, Hq, rows, d], 1 <= rows <= cfg->chunk_len
+ * q       [B, L, Hq, rows, d]; rows >= 1 and at most cfg->instr_len, or at most cfg->chunk_len when the
+ *         configuration runs a cache in the EVICT_THEN_APPEND order (the workspace is sized by these);
+ *         more rows: CITRUS_ERR_SHAPE
  * k_cache [B, L, Hkv, >= cache_len, d], 1 <= cache_len <= cfg->cache_capacity
  * score   dense [B, L, Hkv, cache_len] f32
- * Needs cfg->cache_mode == DUAL with cfg->lm_ordering == EVICT_THEN_APPEND (the workspace is sized for it),
- * otherwise CITRUS_ERR_UNSUPPORTED.  workspace: >= citrus_workspace_bytes(cfg).
+ * workspace: >= citrus_workspace_bytes(cfg).
  */
 int32_t citrus_cache_score(const citrus_config* cfg, citrus_tensor q, int32_t rows, citrus_tensor k_cache,
                            int32_t cache_len, float* score, void* workspace, size_t workspace_bytes,
+                           void* hip_stream);
+
+/*
+ * One eviction of a cache by a text (Section 4.1 step 2; with the instruction as the text: the additional
+ * eviction after the last chunk, which removes the bias towards that chunk and leaves the k states the
+ * instruction and the response are encoded with): citrus_cache_score of q over the cache, selection of the
+ * min(k, cache_len) best as in citrus_topk_select (cfg->select_mode, cfg->start_size), and the kept K/V rows
+ * written to k_new / v_new rows 0 .. min(k, cache_len)-1 in their order, as in citrus_kv_compact.  A cache
+ * of at most k states is copied whole.
+ *
+ * q, rows, k_cache, cache_len   as in citrus_cache_score; v_cache like k_cache
+ * k       1 .. cfg->budget
+ * k_new, v_new [B, L, Hkv, >= min(k, cache_len), d]; must not overlap the sources
+ * idx     optional dense int32 [B, L, Hsel, k]: the kept positions (NULL: kept in the workspace only)
+ */
+int32_t citrus_evict_cache(const citrus_config* cfg, citrus_tensor q, int32_t rows, citrus_tensor k_cache,
+                           citrus_tensor v_cache, int32_t cache_len, int32_t k, citrus_tensor k_new,
+                           citrus_tensor v_new, int32_t* idx, void* workspace, size_t workspace_bytes,
                            void* hip_stream);
 
 /*
@@ -272,6 +302,9 @@ int32_t citrus_resident_provider(void* user, int32_t chunk_index, void* hip_stre
  *                    buffer (cache_len_lm grows to kept + chunk_len; no eviction
  *                    happens after the last chunk).  idx_history_lm then holds the
  *                    kept positions of the LM cache (not the appended chunk rows).
+ *   STANDARD:        the language-modelling steps of DUAL (in either ordering) on
+ *                    the only cache pair with budget `budget`; io.q_instr is not
+ *                    read and may be NULL; idx_history holds its selections.
  * An empty cache (length 0) is the start of a document: the first chunk enters
  * whole if it fits the budget.
  *

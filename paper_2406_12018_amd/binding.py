@@ -19,7 +19,7 @@ _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG_DIR, "libcitrus.so")
 
 F32, BF16 = 0, 1
-CACHE_INSTR, CACHE_SHARED, CACHE_DUAL = 0, 1, 2
+CACHE_INSTR, CACHE_SHARED, CACHE_DUAL, CACHE_STANDARD = 0, 1, 2, 3
 SELECT_PER_KV_HEAD, SELECT_PER_LAYER = 0, 1
 LM_SCORE_AFTER_APPEND, LM_EVICT_THEN_APPEND = 0, 1
 
@@ -29,7 +29,7 @@ OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE, ERR_PROVIDE
 
 EXPORTS = (
     "citrus_abi_version", "citrus_status_string", "citrus_workspace_bytes", "citrus_chunk_attn",
-    "citrus_instr_score", "citrus_cache_score", "citrus_topk_select", "citrus_kv_compact", "citrus_resident_provider",
+    "citrus_instr_score", "citrus_cache_score", "citrus_evict_cache", "citrus_topk_select", "citrus_kv_compact", "citrus_resident_provider",
     "citrus_process_document",
 )
 
@@ -89,6 +89,8 @@ def _lib():
     lib.citrus_instr_score.argtypes = [P(CConfig), CTensor, CTensor, I, CTensor, I, V, V, S, V]
     lib.citrus_cache_score.restype = I
     lib.citrus_cache_score.argtypes = [P(CConfig), CTensor, I, CTensor, I, V, V, S, V]
+    lib.citrus_evict_cache.restype = I
+    lib.citrus_evict_cache.argtypes = [P(CConfig), CTensor, I, CTensor, CTensor, I, I, CTensor, CTensor, V, V, S, V]
     lib.citrus_topk_select.restype = I
     lib.citrus_topk_select.argtypes = [P(CConfig), V, I, I, V, V, S, V]
     lib.citrus_kv_compact.restype = I
@@ -123,10 +125,14 @@ class Config:
 
     def __post_init__(self):
         if self.cache_capacity == 0:
-            lm = self.budget_lm
-            if self.cache_mode == CACHE_DUAL and self.lm_ordering == LM_EVICT_THEN_APPEND:
-                lm += self.chunk_len  # the LM cache keeps the whole previous chunk until the next eviction
-            self.cache_capacity = max(self.budget, lm)
+            # a cache run in the printed order keeps the whole previous chunk until the next eviction
+            held = self.chunk_len if self.lm_ordering == LM_EVICT_THEN_APPEND else 0
+            if self.cache_mode == CACHE_DUAL:
+                self.cache_capacity = max(self.budget, self.budget_lm + held)
+            elif self.cache_mode == CACHE_STANDARD:
+                self.cache_capacity = self.budget + held
+            else:
+                self.cache_capacity = max(self.budget, self.budget_lm)
 
     def c(self) -> CConfig:
         return CConfig(self.batch, self.layers, self.q_heads, self.kv_heads, self.head_dim, self.chunk_len,
@@ -234,6 +240,18 @@ def citrus_cache_score(cfg: Config, q, k_cache, cache_len: int, score=None, work
                                    _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream))
     _check(st, "citrus_cache_score")
     return score
+
+
+def citrus_evict_cache(cfg: Config, q, k_cache, v_cache, cache_len: int, k: int, k_new, v_new, idx=None,
+                       workspace=None, stream=None, rows: Optional[int] = None) -> int:
+    """Returns the number of states kept, min(k, cache_len)."""
+    rows = q.shape[3] if rows is None else rows
+    cc = cfg.c()
+    st = _lib().citrus_evict_cache(C.byref(cc), tensor(q), rows, tensor(k_cache), tensor(v_cache), cache_len, k,
+                                   tensor(k_new), tensor(v_new), _ptr(idx), _ptr(workspace),
+                                   0 if workspace is None else workspace.numel(), _stream(stream))
+    _check(st, "citrus_evict_cache")
+    return min(k, cache_len)
 
 
 def citrus_topk_select(cfg: Config, score, k: int, idx=None, stream=None, n: Optional[int] = None):

@@ -23,7 +23,7 @@ citrus_status check_config(const citrus_config* c) {
   if (c->chunk_len < 1 || c->budget < 1 || c->instr_len < 1) return CITRUS_ERR_SHAPE;
   if (static_cast<int64_t>(c->batch) * c->layers > 65535 || c->q_heads > 65535) return CITRUS_ERR_SHAPE;
   if (c->cache_mode != CITRUS_CACHE_INSTR && c->cache_mode != CITRUS_CACHE_SHARED &&
-      c->cache_mode != CITRUS_CACHE_DUAL)
+      c->cache_mode != CITRUS_CACHE_DUAL && c->cache_mode != CITRUS_CACHE_STANDARD)
     return CITRUS_ERR_UNSUPPORTED;
   if (c->select_mode != CITRUS_SELECT_PER_KV_HEAD && c->select_mode != CITRUS_SELECT_PER_LAYER)
     return CITRUS_ERR_UNSUPPORTED;
@@ -35,9 +35,11 @@ citrus_status check_config(const citrus_config* c) {
   if (c->start_size < 0 || c->start_size >= c->budget) return CITRUS_ERR_SHAPE;
   if (c->lm_ordering != CITRUS_LM_SCORE_AFTER_APPEND && c->lm_ordering != CITRUS_LM_EVICT_THEN_APPEND)
     return CITRUS_ERR_UNSUPPORTED;
-  if (c->cache_mode == CITRUS_CACHE_DUAL && c->lm_ordering == CITRUS_LM_EVICT_THEN_APPEND &&
-      c->cache_capacity < c->budget_lm + c->chunk_len)
-    return CITRUS_ERR_SHAPE;
+  if (c->lm_ordering == CITRUS_LM_EVICT_THEN_APPEND) {
+    // the cache the chunk evicts still holds the whole previous chunk
+    if (c->cache_mode == CITRUS_CACHE_DUAL && c->cache_capacity < c->budget_lm + c->chunk_len) return CITRUS_ERR_SHAPE;
+    if (c->cache_mode == CITRUS_CACHE_STANDARD && c->cache_capacity < c->budget + c->chunk_len) return CITRUS_ERR_SHAPE;
+  }
   if (c->cache_mode == CITRUS_CACHE_DUAL && c->start_size >= c->budget_lm) return CITRUS_ERR_SHAPE;
   if (!(c->softmax_scale >= 0.0f) || isinf(c->softmax_scale)) return CITRUS_ERR_SHAPE;
   return CITRUS_OK;
@@ -78,8 +80,11 @@ struct Workspace {
   size_t lse_chunk, lse_instr, lse_cache, score, score_lm, idx, idx_lm, iota, total;
 };
 
+// A cache evicted by the document's own chunks exists (DUAL's second cache, or the only one of STANDARD)
+// and is run in the order Section 4.1 prints.
 bool evict_then_append(const citrus_config* c) {
-  return c->cache_mode == CITRUS_CACHE_DUAL && c->lm_ordering == CITRUS_LM_EVICT_THEN_APPEND;
+  return (c->cache_mode == CITRUS_CACHE_DUAL || c->cache_mode == CITRUS_CACHE_STANDARD) &&
+         c->lm_ordering == CITRUS_LM_EVICT_THEN_APPEND;
 }
 
 Workspace workspace_layout(const citrus_config* c) {
@@ -145,15 +150,22 @@ citrus_status do_instr_score(const citrus_config* c, const Dims& dm, const citru
   return CITRUS_OK;
 }
 
+// A cache as the only key segment (the kernels take [cache ; chunk]; the chunk part is empty here and
+// the cache is passed as the "chunk" so that every row index is a chunk row index).
+Segments cache_only(const citrus_tensor& cache, int cache_len) {
+  Segments s;
+  s.cache = make_view(cache);
+  s.chunk = make_view(cache);
+  s.n_c = 0;
+  s.c = cache_len;
+  return s;
+}
+
 // Eq. (1) as printed: the rows of q score the states of one cache, softmax over those states alone.
 // The cache is handed to the kernels as the only key segment.
 citrus_status do_cache_score(const citrus_config* c, const Dims& dm, const citrus_tensor& q, int rows,
                              const citrus_tensor& k_cache, int cache_len, float* lse_ws, float* score, hipStream_t st) {
-  Segments ks;
-  ks.cache = make_view(k_cache);
-  ks.chunk = make_view(k_cache);
-  ks.n_c = 0;
-  ks.c = cache_len;
+  const Segments ks = cache_only(k_cache, cache_len);
   if (mfma_path_supported(c->dtype, dm))
     return hip_status(launch_instr_score_mfma(dm, make_view(q), rows, ks, lse_ws, score, st));
   View none{nullptr, 0, 0, 0, 0};
@@ -191,6 +203,15 @@ Segments segments(const citrus_tensor& cache, int cache_len, const citrus_tensor
   s.c = chunk_len;
   if (cache_len == 0) s.cache = s.chunk;  // never dereferenced, but keep it a valid pointer
   return s;
+}
+
+// Partial-softmax block of the workspace that fits `rows` query rows, or NULL.
+float* cache_score_block(const citrus_config* c, void* workspace, int rows) {
+  const Workspace wl = workspace_layout(c);
+  char* ws = static_cast<char*>(workspace);
+  if (rows <= c->instr_len) return reinterpret_cast<float*>(ws + wl.lse_instr);
+  if (evict_then_append(c) && rows <= c->chunk_len) return reinterpret_cast<float*>(ws + wl.lse_cache);
+  return nullptr;
 }
 
 }  // namespace
@@ -259,15 +280,44 @@ int32_t citrus_cache_score(const citrus_config* cfg, citrus_tensor q, int32_t ro
                            int32_t cache_len, float* score, void* workspace, size_t workspace_bytes,
                            void* hip_stream) {
   CITRUS_TRY(check_config(cfg));
-  if (!evict_then_append(cfg)) return CITRUS_ERR_UNSUPPORTED;
-  if (rows < 1 || rows > cfg->chunk_len || cache_len < 1 || cache_len > cfg->cache_capacity) return CITRUS_ERR_SHAPE;
+  if (rows < 1 || cache_len < 1 || cache_len > cfg->cache_capacity) return CITRUS_ERR_SHAPE;
   if (score == nullptr) return CITRUS_ERR_NULL;
   CITRUS_TRY(check_tensor(q, cfg->dtype, false));
   CITRUS_TRY(check_tensor(k_cache, cfg->dtype, false));
   CITRUS_TRY(check_workspace(cfg, workspace, workspace_bytes));
+  float* lse_ws = cache_score_block(cfg, workspace, rows);
+  if (lse_ws == nullptr) return CITRUS_ERR_SHAPE;
+  return do_cache_score(cfg, dims_of(cfg), q, rows, k_cache, cache_len, lse_ws, score,
+                        static_cast<hipStream_t>(hip_stream));
+}
+
+int32_t citrus_evict_cache(const citrus_config* cfg, citrus_tensor q, int32_t rows, citrus_tensor k_cache,
+                           citrus_tensor v_cache, int32_t cache_len, int32_t k, citrus_tensor k_new,
+                           citrus_tensor v_new, int32_t* idx, void* workspace, size_t workspace_bytes,
+                           void* hip_stream) {
+  CITRUS_TRY(check_config(cfg));
+  if (rows < 1 || cache_len < 1 || cache_len > cfg->cache_capacity || k < 1 || k > cfg->budget) return CITRUS_ERR_SHAPE;
+  CITRUS_TRY(check_tensor(q, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(k_cache, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(v_cache, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(k_new, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(v_new, cfg->dtype, false));
+  if (k_new.ptr == k_cache.ptr || v_new.ptr == v_cache.ptr) return CITRUS_ERR_SHAPE;
+  CITRUS_TRY(check_workspace(cfg, workspace, workspace_bytes));
+  float* lse_ws = cache_score_block(cfg, workspace, rows);
+  if (lse_ws == nullptr) return CITRUS_ERR_SHAPE;
   const Dims dm = dims_of(cfg);
-  float* lse_ws = reinterpret_cast<float*>(static_cast<char*>(workspace) + workspace_layout(cfg).lse_cache);
-  return do_cache_score(cfg, dm, q, rows, k_cache, cache_len, lse_ws, score, static_cast<hipStream_t>(hip_stream));
+  const Workspace wl = workspace_layout(cfg);
+  char* ws = static_cast<char*>(workspace);
+  float* score = reinterpret_cast<float*>(ws + wl.score);
+  if (idx == nullptr) idx = reinterpret_cast<int32_t*>(ws + wl.idx);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int m = cache_len < k ? cache_len : k;
+  // a cache that fits stays whole: the selection is the identity and reads no score
+  if (cache_len > k) CITRUS_TRY(do_cache_score(cfg, dm, q, rows, k_cache, cache_len, lse_ws, score, st));
+  CITRUS_TRY(do_topk(cfg, score, cache_len, k, idx, st));
+  const Segments ks = cache_only(k_cache, cache_len), vs = cache_only(v_cache, cache_len);
+  return do_compact(cfg, dm, ks, vs, idx, k, m, k_new, v_new, st);
 }
 
 int32_t citrus_topk_select(const citrus_config* cfg, const float* score, int32_t n, int32_t k, int32_t* idx,
@@ -336,6 +386,7 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
   if (next == nullptr || k_cache == nullptr || v_cache == nullptr || cache_len == nullptr || buffer_index == nullptr)
     return CITRUS_ERR_NULL;
   const bool dual = cfg->cache_mode == CITRUS_CACHE_DUAL;
+  const bool standard = cfg->cache_mode == CITRUS_CACHE_STANDARD;
   if (dual && (k_cache_lm == nullptr || v_cache_lm == nullptr || cache_len_lm == nullptr || buffer_index_lm == nullptr))
     return CITRUS_ERR_NULL;
   if (first_chunk < 0) return CITRUS_ERR_SHAPE;
@@ -348,9 +399,12 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
     }
   }
   if (k_cache[0].ptr == k_cache[1].ptr || v_cache[0].ptr == v_cache[1].ptr) return CITRUS_ERR_SHAPE;
-  if (*cache_len < 0 || *cache_len > cfg->budget || (*buffer_index != 0 && *buffer_index != 1)) return CITRUS_ERR_SHAPE;
-  const bool paper_lm = evict_then_append(cfg);
-  if (dual && (*cache_len_lm < 0 || *cache_len_lm > cfg->budget_lm + (paper_lm ? cfg->chunk_len : 0) ||
+  // a cache run in the printed order still holds the previous chunk between two steps
+  const bool paper_order = evict_then_append(cfg);
+  const int held = paper_order ? cfg->chunk_len : 0;
+  if (*cache_len < 0 || *cache_len > cfg->budget + (standard ? held : 0) || (*buffer_index != 0 && *buffer_index != 1))
+    return CITRUS_ERR_SHAPE;
+  if (dual && (*cache_len_lm < 0 || *cache_len_lm > cfg->budget_lm + held ||
                (*buffer_index_lm != 0 && *buffer_index_lm != 1)))
     return CITRUS_ERR_SHAPE;
   CITRUS_TRY(check_workspace(cfg, workspace, workspace_bytes));
@@ -377,6 +431,56 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
     if (phase_events != nullptr)
       (void)hipEventRecord(static_cast<hipEvent_t>(phase_events[step * CITRUS_EVENTS_PER_STEP + phase]), st);
   };
+
+  // One step of a cache that the document's own chunks evict (Section 4.1): the second cache of DUAL, the
+  // only cache of STANDARD.  Marks phases 1..4.
+  struct ChunkEvicted {
+    const citrus_tensor *k, *v;  // ping-pong pair
+    int* len;
+    int* cur;
+    int budget;
+    float* score;
+    int32_t* idx;  // where this step's selection goes (pitch = budget)
+  };
+  auto chunk_evicted_step = [&](const ChunkEvicted& t, const citrus_chunk_io& io, int c) -> citrus_status {
+    const int n_old = *t.len, from = *t.cur, to = from ^ 1;
+    const Segments kl = segments(t.k[from], n_old, io.k, c), vl = segments(t.v[from], n_old, io.v, c);
+    if (paper_order) {
+      // the order Section 4.1 prints: encode the chunk given the cache (it still holds the whole previous
+      // chunk), evict the cache by the chunk's attention to it, then put the chunk in
+      const int kept = n_old < t.budget ? n_old : t.budget;
+      CITRUS_TRY(do_chunk_attn(cfg, dm, io.q, kl, vl, io.out, nullptr, nullptr, st));
+      mark(done, 1);
+      if (n_old > t.budget) CITRUS_TRY(do_cache_score(cfg, dm, io.q, c, t.k[from], n_old, lse_cache, t.score, st));
+      mark(done, 2);
+      if (n_old > 0) CITRUS_TRY(do_topk(cfg, t.score, n_old, t.budget, t.idx, st));
+      mark(done, 3);
+      // kept cache states first, then the chunk's states behind them (positions n_old .. of the candidates)
+      if (kept > 0) CITRUS_TRY(do_compact(cfg, dm, kl, vl, t.idx, t.budget, kept, t.k[to], t.v[to], st));
+      CITRUS_TRY(hip_status(launch_iota(iota_ws, n_old, c, st)));
+      CITRUS_TRY(hip_status(launch_compact(elem_bytes(cfg->dtype), dm, kl, vl, iota_ws, /*idx_pitch=*/0,
+                                           /*idx_heads=*/1, c, make_view(rows_from(t.k[to], kept, cfg->dtype)),
+                                           make_view(rows_from(t.v[to], kept, cfg->dtype)), st)));
+      mark(done, 4);
+      *t.len = kept + c;
+    } else {
+      // the chunk attends over [cache ; chunk] and scores all of it itself; eviction in the same step
+      const int n_new = n_old + c;
+      const int kept = n_new < t.budget ? n_new : t.budget;
+      CITRUS_TRY(do_chunk_attn(cfg, dm, io.q, kl, vl, io.out, lse_chunk, nullptr, st));
+      mark(done, 1);
+      CITRUS_TRY(hip_status(run_colsum(cfg, dm, make_view(io.q), c, kl, /*causal=*/1, lse_chunk, t.score, st)));
+      mark(done, 2);
+      CITRUS_TRY(do_topk(cfg, t.score, n_new, t.budget, t.idx, st));
+      mark(done, 3);
+      CITRUS_TRY(do_compact(cfg, dm, kl, vl, t.idx, t.budget, kept, t.k[to], t.v[to], st));
+      mark(done, 4);
+      *t.len = kept;
+    }
+    *t.cur = to;
+    return CITRUS_OK;
+  };
+
   for (; max_chunks < 0 || done < max_chunks; ++done) {
     citrus_chunk_io io;
     memset(&io, 0, sizeof(io));
@@ -388,62 +492,27 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
     if ((status = check_tensor(io.q, cfg->dtype, false)) != CITRUS_OK) break;
     if ((status = check_tensor(io.k, cfg->dtype, false)) != CITRUS_OK) break;
     if ((status = check_tensor(io.v, cfg->dtype, false)) != CITRUS_OK) break;
-    if ((status = check_tensor(io.q_instr, cfg->dtype, false)) != CITRUS_OK) break;
+    if ((status = check_tensor(io.q_instr, cfg->dtype, /*may_be_null=*/standard)) != CITRUS_OK) break;
     if ((status = check_tensor(io.out, cfg->dtype, false)) != CITRUS_OK) break;
+
+    mark(done, 0);
+    if (standard) {
+      // Standard CSE alone: the instruction takes no part in the encoding of the document
+      int32_t* idx = idx_history ? idx_history + static_cast<size_t>(done) * units_sel * cfg->budget : idx_ws;
+      const ChunkEvicted t{k_cache, v_cache, &n_c, &cur, cfg->budget, score, idx};
+      if ((status = chunk_evicted_step(t, io, c)) != CITRUS_OK) break;
+      for (int p = 5; p <= 7; ++p) mark(done, p);
+      continue;
+    }
 
     // instruction (or only) cache: candidates [cache ; chunk]
     const Segments ks = segments(k_cache[cur], n_c, io.k, c), vs = segments(v_cache[cur], n_c, io.v, c);
     const int n = n_c + c;
     const int m = n < cfg->budget ? n : cfg->budget;
-
-    mark(done, 0);
-    if (paper_lm) {
-      // language-modelling thread in the order Section 4.1 prints: encode the chunk given the cache
-      // (it still holds the whole previous chunk), evict the cache by the chunk's attention to it,
-      // then put the chunk in
-      const Segments kl = segments(k_cache_lm[cur_lm], n_c_lm, io.k, c), vl = segments(v_cache_lm[cur_lm], n_c_lm, io.v, c);
-      const int m_lm = n_c_lm < cfg->budget_lm ? n_c_lm : cfg->budget_lm;
+    if (dual) {
       int32_t* idx_lm = idx_history_lm ? idx_history_lm + static_cast<size_t>(done) * units_sel * cfg->budget_lm : idx_lm_ws;
-      if ((status = do_chunk_attn(cfg, dm, io.q, kl, vl, io.out, nullptr, nullptr, st)) != CITRUS_OK) break;
-      mark(done, 1);
-      if (n_c_lm > cfg->budget_lm &&
-          (status = do_cache_score(cfg, dm, io.q, c, k_cache_lm[cur_lm], n_c_lm, lse_cache, score_lm, st)) != CITRUS_OK)
-        break;
-      mark(done, 2);
-      if (n_c_lm > 0 && (status = do_topk(cfg, score_lm, n_c_lm, cfg->budget_lm, idx_lm, st)) != CITRUS_OK) break;
-      mark(done, 3);
-      // kept cache states first, then the chunk's states behind them (positions n_c_lm .. of the candidates)
-      if (m_lm > 0 && (status = do_compact(cfg, dm, kl, vl, idx_lm, cfg->budget_lm, m_lm, k_cache_lm[cur_lm ^ 1],
-                                           v_cache_lm[cur_lm ^ 1], st)) != CITRUS_OK)
-        break;
-      if ((status = hip_status(launch_iota(iota_ws, n_c_lm, c, st))) != CITRUS_OK) break;
-      if ((status = hip_status(launch_compact(elem_bytes(cfg->dtype), dm, kl, vl, iota_ws, /*idx_pitch=*/0,
-                                              /*idx_heads=*/1, c, make_view(rows_from(k_cache_lm[cur_lm ^ 1], m_lm, cfg->dtype)),
-                                              make_view(rows_from(v_cache_lm[cur_lm ^ 1], m_lm, cfg->dtype)), st))) != CITRUS_OK)
-        break;
-      mark(done, 4);
-      cur_lm ^= 1;
-      n_c_lm = m_lm + c;
-    } else if (dual) {
-      // language-modelling thread: the chunk attends over [LM cache ; chunk] and scores it itself
-      const Segments kl = segments(k_cache_lm[cur_lm], n_c_lm, io.k, c), vl = segments(v_cache_lm[cur_lm], n_c_lm, io.v, c);
-      const int n_lm = n_c_lm + c;
-      const int m_lm = n_lm < cfg->budget_lm ? n_lm : cfg->budget_lm;
-      int32_t* idx_lm = idx_history_lm ? idx_history_lm + static_cast<size_t>(done) * units_sel * cfg->budget_lm : idx_lm_ws;
-      if ((status = do_chunk_attn(cfg, dm, io.q, kl, vl, io.out, lse_chunk, nullptr, st)) != CITRUS_OK) break;
-      mark(done, 1);
-      if ((status = hip_status(run_colsum(cfg, dm, make_view(io.q), c, kl, /*causal=*/1, lse_chunk, score_lm, st))) !=
-          CITRUS_OK)
-        break;
-      mark(done, 2);
-      if ((status = do_topk(cfg, score_lm, n_lm, cfg->budget_lm, idx_lm, st)) != CITRUS_OK) break;
-      mark(done, 3);
-      if ((status = do_compact(cfg, dm, kl, vl, idx_lm, cfg->budget_lm, m_lm, k_cache_lm[cur_lm ^ 1],
-                               v_cache_lm[cur_lm ^ 1], st)) != CITRUS_OK)
-        break;
-      mark(done, 4);
-      cur_lm ^= 1;
-      n_c_lm = m_lm;
+      const ChunkEvicted t{k_cache_lm, v_cache_lm, &n_c_lm, &cur_lm, cfg->budget_lm, score_lm, idx_lm};
+      if ((status = chunk_evicted_step(t, io, c)) != CITRUS_OK) break;
     } else {
       if ((status = do_chunk_attn(cfg, dm, io.q, ks, vs, io.out, nullptr, nullptr, st)) != CITRUS_OK) break;
       for (int p = 1; p <= 4; ++p) mark(done, p);

@@ -77,51 +77,61 @@ class StepwiseRun:
         self.ws = api.alloc_workspace(cfg, device)
         self.steps = []
 
+    def _chunk_evicted_step(self, q, k, v, k_pair, v_pair, n_old, cur, budget):
+        """One step of a cache that the document's own chunks evict (the second cache of DUAL, the only
+        cache of STANDARD), in the configured ordering, through the public entry points.  Returns the
+        intermediates and the cache length after the step; the result is in buffer cur ^ 1."""
+        api, cfg = self.api, self.cfg
+        c = q.shape[3]
+        kl, vl, kl_new, vl_new = k_pair[cur], v_pair[cur], k_pair[cur ^ 1], v_pair[cur ^ 1]
+        lse = torch.empty((cfg.batch, cfg.layers, cfg.q_heads, c), dtype=torch.float32, device=q.device)
+        if cfg.lm_ordering == api.LM_EVICT_THEN_APPEND:
+            # Section 4.1's order: encode given the cache, evict the cache by the chunk's attention to it,
+            # then append the whole chunk
+            kept = min(budget, n_old)
+            out = api.citrus_chunk_attn(cfg, q, kl, vl, n_old, k, v, lse=lse)
+            score = idx = None
+            if n_old > 0:
+                if n_old > budget:
+                    score = api.citrus_cache_score(cfg, q, kl, n_old, workspace=self.ws)
+                    idx = api.citrus_topk_select(cfg, score, budget)
+                else:  # everything stays: the selection does not read the scores
+                    unread = torch.zeros((cfg.batch, cfg.layers, cfg.kv_heads, n_old), dtype=torch.float32, device=q.device)
+                    idx = api.citrus_topk_select(cfg, unread, budget)
+                api.citrus_kv_compact(cfg, kl, vl, n_old, k, v, idx, kept, kl_new, vl_new)
+            tail = torch.arange(n_old, n_old + c, dtype=torch.int32, device=q.device).expand(
+                cfg.batch, cfg.layers, cfg.sel_heads, c).contiguous()
+            api.citrus_kv_compact(cfg, kl, vl, n_old, k, v, tail, c, kl_new[:, :, :, kept:], vl_new[:, :, :, kept:])
+            return dict(out=out, lse=lse, score=score, idx=idx, kept=kept, new_len=kept + c)
+        n_new = n_old + c
+        score = torch.empty((cfg.batch, cfg.layers, cfg.kv_heads, n_new), dtype=torch.float32, device=q.device)
+        out = api.citrus_chunk_attn(cfg, q, kl, vl, n_old, k, v, lse=lse, lm_score=score, workspace=self.ws)
+        idx = api.citrus_topk_select(cfg, score, budget)
+        kept = min(budget, n_new)
+        api.citrus_kv_compact(cfg, kl, vl, n_old, k, v, idx, kept, kl_new, vl_new)
+        return dict(out=out, lse=lse, score=score, idx=idx, kept=kept, new_len=kept)
+
     def step(self, q, k, v, q_instr):
         api, cfg, st = self.api, self.cfg, self.state
         dual = cfg.cache_mode == api.CACHE_DUAL
         c = q.shape[3]
         rec = {"n_c": st.cache_len}
+        if cfg.cache_mode == api.CACHE_STANDARD:
+            r = self._chunk_evicted_step(q, k, v, st.k_cache, st.v_cache, st.cache_len, st.buffer_index, cfg.budget)
+            st.buffer_index ^= 1
+            st.cache_len = r["new_len"]
+            rec.update(out=r["out"], lse=r["lse"], score=r["score"], idx=r["idx"], m=r["kept"])
+            self.steps.append(rec)
+            return rec
         kc, vc = st.k_cache[st.buffer_index], st.v_cache[st.buffer_index]
         n = st.cache_len + c
-        if dual and cfg.lm_ordering == api.LM_EVICT_THEN_APPEND:
-            # Section 4.1's order: encode given the cache, evict the cache by the chunk's attention to it,
-            # then append the whole chunk
-            kl, vl = st.k_cache_lm[st.buffer_index_lm], st.v_cache_lm[st.buffer_index_lm]
-            kl_new, vl_new = st.k_cache_lm[st.buffer_index_lm ^ 1], st.v_cache_lm[st.buffer_index_lm ^ 1]
-            n_c_lm = st.cache_len_lm
-            m_lm = min(cfg.budget_lm, n_c_lm)
-            lse = torch.empty((cfg.batch, cfg.layers, cfg.q_heads, c), dtype=torch.float32, device=q.device)
-            out = api.citrus_chunk_attn(cfg, q, kl, vl, n_c_lm, k, v, lse=lse)
-            score_lm = idx_lm = None
-            if n_c_lm > 0:
-                if n_c_lm > cfg.budget_lm:
-                    score_lm = api.citrus_cache_score(cfg, q, kl, n_c_lm, workspace=self.ws)
-                    idx_lm = api.citrus_topk_select(cfg, score_lm, cfg.budget_lm)
-                else:  # everything stays: the selection does not read the scores
-                    unread = torch.zeros((cfg.batch, cfg.layers, cfg.kv_heads, n_c_lm), dtype=torch.float32, device=q.device)
-                    idx_lm = api.citrus_topk_select(cfg, unread, cfg.budget_lm)
-                api.citrus_kv_compact(cfg, kl, vl, n_c_lm, k, v, idx_lm, m_lm, kl_new, vl_new)
-            tail = torch.arange(n_c_lm, n_c_lm + c, dtype=torch.int32, device=q.device).expand(
-                cfg.batch, cfg.layers, cfg.sel_heads, c).contiguous()
-            api.citrus_kv_compact(cfg, kl, vl, n_c_lm, k, v, tail, c, kl_new[:, :, :, m_lm:], vl_new[:, :, :, m_lm:])
-            rec.update(n_c_lm=n_c_lm, score_lm=score_lm, idx_lm=idx_lm, m_lm=m_lm, lse=lse)
+        if dual:
+            r = self._chunk_evicted_step(q, k, v, st.k_cache_lm, st.v_cache_lm, st.cache_len_lm, st.buffer_index_lm,
+                                         cfg.budget_lm)
+            rec.update(n_c_lm=st.cache_len_lm, score_lm=r["score"], idx_lm=r["idx"], m_lm=r["kept"], lse=r["lse"])
+            out = r["out"]
             st.buffer_index_lm ^= 1
-            st.cache_len_lm = m_lm + c
-        elif dual:
-            kl, vl = st.k_cache_lm[st.buffer_index_lm], st.v_cache_lm[st.buffer_index_lm]
-            n_lm = st.cache_len_lm + c
-            lm_score = torch.empty((cfg.batch, cfg.layers, cfg.kv_heads, n_lm), dtype=torch.float32, device=q.device)
-            lse = torch.empty((cfg.batch, cfg.layers, cfg.q_heads, c), dtype=torch.float32, device=q.device)
-            out = api.citrus_chunk_attn(cfg, q, kl, vl, st.cache_len_lm, k, v, lse=lse, lm_score=lm_score,
-                                        workspace=self.ws)
-            idx_lm = api.citrus_topk_select(cfg, lm_score, cfg.budget_lm)
-            m_lm = min(cfg.budget_lm, n_lm)
-            api.citrus_kv_compact(cfg, kl, vl, st.cache_len_lm, k, v, idx_lm, m_lm,
-                                  st.k_cache_lm[st.buffer_index_lm ^ 1], st.v_cache_lm[st.buffer_index_lm ^ 1])
-            rec.update(n_c_lm=st.cache_len_lm, score_lm=lm_score, idx_lm=idx_lm, m_lm=m_lm, lse=lse)
-            st.buffer_index_lm ^= 1
-            st.cache_len_lm = m_lm
+            st.cache_len_lm = r["new_len"]
         else:
             lse = torch.empty((cfg.batch, cfg.layers, cfg.q_heads, c), dtype=torch.float32, device=q.device)
             out = api.citrus_chunk_attn(cfg, q, kc, vc, st.cache_len, k, v, lse=lse)

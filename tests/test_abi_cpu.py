@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(B.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
-    assert B.abi_version() == 3
+    assert B.abi_version() == 4
 
 
 def test_struct_layouts_match_the_header():
@@ -54,6 +54,9 @@ def test_status_strings():
     ({"cache_mode": B.CACHE_DUAL, "budget_lm": 16, "lm_ordering": B.LM_EVICT_THEN_APPEND}, True),
     # the evict-then-append cache keeps a whole chunk beside the budget
     ({"cache_mode": B.CACHE_DUAL, "budget_lm": 48, "lm_ordering": B.LM_EVICT_THEN_APPEND, "cache_capacity": 64}, False),
+    ({"cache_mode": B.CACHE_STANDARD}, True), ({"cache_mode": B.CACHE_STANDARD, "lm_ordering": B.LM_EVICT_THEN_APPEND}, True),
+    ({"cache_mode": B.CACHE_STANDARD, "lm_ordering": B.LM_EVICT_THEN_APPEND, "cache_capacity": 64}, False),
+    ({"cache_mode": 4}, False),
 ])
 def test_workspace_bytes_validates_config(kw, ok):
     assert (B.workspace_bytes(cfg(**kw)) > 0) == ok
@@ -100,18 +103,29 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     for bad_start in (-1, cfg().budget):
         bs = cfg(start_size=bad_start).c()
         assert lib.citrus_topk_select(C.byref(bs), C.c_void_p(0x2000), 8, 4, C.c_void_p(0x3000), None, 0, None) == B.ERR_SHAPE
-    # cache_score exists only for the evict-then-append ordering of the DUAL design
+    # cache_score: the rows must fit the workspace (instr_len rows, or chunk_len rows for a configuration
+    # that runs a cache in the evict-then-append order)
     sc = C.c_void_p(0x2000)
-    assert lib.citrus_cache_score(C.byref(c), fake(), 8, fake(), 8, sc, ws, big, None) == B.ERR_UNSUPPORTED
-    e = cfg(cache_mode=B.CACHE_DUAL, budget_lm=16, lm_ordering=B.LM_EVICT_THEN_APPEND).c()
-    assert lib.citrus_cache_score(C.byref(e), null, 8, fake(), 8, sc, ws, big, None) == B.ERR_NULL
-    assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 8, None, ws, big, None) == B.ERR_NULL
-    assert lib.citrus_cache_score(C.byref(e), fake(), 0, fake(), 8, sc, ws, big, None) == B.ERR_SHAPE
-    assert lib.citrus_cache_score(C.byref(e), fake(), 33, fake(), 8, sc, ws, big, None) == B.ERR_SHAPE
-    assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 0, sc, ws, big, None) == B.ERR_SHAPE
-    assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 65, sc, ws, big, None) == B.ERR_SHAPE
-    assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 8, sc, None, 0, None) == B.ERR_WORKSPACE
-    assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 8, sc, ws, 16, None) == B.ERR_WORKSPACE
+    assert lib.citrus_cache_score(C.byref(c), fake(), 9, fake(), 8, sc, ws, big, None) == B.ERR_SHAPE
+    for mode_kw in (dict(cache_mode=B.CACHE_DUAL, budget_lm=16), dict(cache_mode=B.CACHE_STANDARD)):
+        e = cfg(lm_ordering=B.LM_EVICT_THEN_APPEND, **mode_kw).c()
+        assert lib.citrus_cache_score(C.byref(e), null, 8, fake(), 8, sc, ws, big, None) == B.ERR_NULL
+        assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 8, None, ws, big, None) == B.ERR_NULL
+        assert lib.citrus_cache_score(C.byref(e), fake(), 0, fake(), 8, sc, ws, big, None) == B.ERR_SHAPE
+        assert lib.citrus_cache_score(C.byref(e), fake(), 33, fake(), 8, sc, ws, big, None) == B.ERR_SHAPE
+        assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 0, sc, ws, big, None) == B.ERR_SHAPE
+        assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 97, sc, ws, big, None) == B.ERR_SHAPE
+        assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 8, sc, None, 0, None) == B.ERR_WORKSPACE
+        assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 8, sc, ws, 16, None) == B.ERR_WORKSPACE
+    # evict_cache: rows as above, k within the budget, destinations distinct from the sources
+    ev = lambda cc, rows=8, n=40, k=16, kn=fake(0x9000), vn=fake(0xA000), w=ws, wb=big: lib.citrus_evict_cache(
+        C.byref(cc), fake(), rows, fake(0x5000), fake(0x6000), n, k, kn, vn, None, w, wb, None)
+    assert ev(c, rows=9) == B.ERR_SHAPE
+    assert ev(c, n=0) == B.ERR_SHAPE and ev(c, n=65) == B.ERR_SHAPE
+    assert ev(c, k=0) == B.ERR_SHAPE and ev(c, k=65) == B.ERR_SHAPE
+    assert ev(c, kn=fake(0x5000)) == B.ERR_SHAPE and ev(c, vn=fake(0x6000)) == B.ERR_SHAPE
+    assert ev(c, kn=null) == B.ERR_NULL
+    assert ev(c, w=None, wb=0) == B.ERR_WORKSPACE
     # unsupported head_dim
     bad = cfg(head_dim=96).c()
     assert lib.citrus_topk_select(C.byref(bad), C.c_void_p(0x2000), 8, 4, C.c_void_p(0x3000), None, 0, None) == B.ERR_UNSUPPORTED

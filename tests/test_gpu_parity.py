@@ -216,10 +216,15 @@ def test_cache_score_parity(shape):
         np.testing.assert_allclose(got.sum(-1), rows * (Hq // Hkv), rtol=2e-3 if dtype == "bf16" else 1e-5)
         again = api.citrus_cache_score(cfg, x["q"], x["kc"], n_c, workspace=ws, rows=rows)
         assert torch.equal(score, again)
-    # the ordering this entry point belongs to must be configured
+    # a configuration without such a cache has workspace for instr_len rows only
     plain = make_cfg(dtype, B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, c=c, k=n_c + 3, n_i=n_i)
-    with pytest.raises(api.CitrusError):
-        api.citrus_cache_score(plain, x["q"], x["kc"], n_c, workspace=api.alloc_workspace(plain))
+    ws_plain = api.alloc_workspace(plain)
+    if c > n_i:
+        with pytest.raises(api.CitrusError):
+            api.citrus_cache_score(plain, x["q"], x["kc"], n_c, workspace=ws_plain)
+    few = api.citrus_cache_score(plain, x["q"], x["kc"], n_c, workspace=ws_plain, rows=min(c, n_i))
+    ref = orc.instr_score(np64(x["q"][0, 0, :, :min(c, n_i)]), np64(x["kc"][0, 0, :, :n_c]))
+    assert_close(np64(few[0, 0]), ref, dtype, "cache score, instruction-sized text")
 
 
 @pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "-".join(str(x) for x in s[:9]))
@@ -474,6 +479,94 @@ def test_document_stepwise_teacher_forced(case):
 
 
 # ----------------------------------------------------------------------------
+# Standard CSE on its own, and the extra eviction by the instruction after the last chunk
+# ----------------------------------------------------------------------------
+
+STANDARD_CASES = {
+    "cfg1_standard_paper_order": scaled_down(peaked(WORKLOADS["cfg1_tiny_f32"]), doc_len=301,
+                                             cache_mode=api.CACHE_STANDARD, lm_ordering=api.LM_EVICT_THEN_APPEND),
+    "cfg1_standard_after_append_per_layer_start2": scaled_down(
+        peaked(WORKLOADS["cfg1_tiny_f32"]), doc_len=256, layers=2, kv_heads=2, cache_mode=api.CACHE_STANDARD,
+        select_mode=api.SELECT_PER_LAYER, start_size=2),
+    "cfg2_small_standard_paper_order": scaled_down(WORKLOADS["cfg2_mistral7b"], layers=1, doc_len=2300,
+                                                   cache_mode=api.CACHE_STANDARD, lm_ordering=api.LM_EVICT_THEN_APPEND),
+    "cfg2_small_standard_paper_order_per_layer": scaled_down(
+        peaked(WORKLOADS["cfg2_mistral7b"]), layers=2, doc_len=1700, cache_mode=api.CACHE_STANDARD,
+        lm_ordering=api.LM_EVICT_THEN_APPEND, select_mode=api.SELECT_PER_LAYER, start_size=4),
+}
+
+
+def _selection_checks(idx_gpu, score_gpu_blg, score_ref, k, w, what):
+    """Band rule and exactness for every selection head of one (document, layer)."""
+    hs = idx_gpu.shape[0]
+    for g in range(hs):
+        ref_vec = score_ref.sum(0) if hs == 1 else score_ref[g]
+        gpu_vec = layer_sum_f32(score_gpu_blg) if hs == 1 else score_gpu_blg[g].cpu().numpy()
+        check_selection(idx_gpu[g], gpu_vec, ref_vec, k, w.dtype, what, w.start_size)
+
+
+@pytest.mark.parametrize("case", list(STANDARD_CASES), ids=list(STANDARD_CASES))
+def test_standard_cse_document_and_final_instruction_eviction(case):
+    w = STANDARD_CASES[case]
+    say(f"standard CSE {case}")
+    cfg = api.Config.from_workload(w)
+    doc = make_document(w, DEV)
+    run = StepwiseRun(api, cfg, DEV)
+    outs = []
+    for i in range(w.n_chunks):
+        lo, hi = w.chunk_bounds(i)
+        outs.append(run.step(doc["q"][:, :, :, lo:hi], doc["k"][:, :, :, lo:hi], doc["v"][:, :, :, lo:hi], None)["out"])
+    torch.cuda.synchronize()
+    out_gpu = torch.cat(outs, dim=3)
+    st = run.state
+    hs = cfg.sel_heads
+    # the extra eviction with the instruction as the text, into the other buffer of the pair
+    qi = doc["q_instr"][w.n_chunks - 1]
+    idx_f = torch.full((w.batch, w.layers, hs, w.budget), -1, dtype=torch.int32, device=DEV)
+    k_cur, v_cur = st.k_cache[st.buffer_index], st.v_cache[st.buffer_index]
+    k_fin, v_fin = st.k_cache[st.buffer_index ^ 1], st.v_cache[st.buffer_index ^ 1]
+    kept = api.citrus_evict_cache(cfg, qi, k_cur, v_cur, st.cache_len, w.budget, k_fin, v_fin, idx=idx_f, workspace=run.ws)
+    score_f = api.citrus_cache_score(cfg, qi, k_cur, st.cache_len, workspace=run.ws)
+    torch.cuda.synchronize()
+    assert kept == min(w.budget, st.cache_len)
+    host = {name: t.cpu() for name, t in doc.items()}
+    for b in range(w.batch):
+        for l in range(w.layers):
+            # the oracle follows the GPU's selections, so one near-tie cannot change the later steps
+            forced = [np.zeros((hs, 0), dtype=np.int64) if rec["idx"] is None
+                      else rec["idx"][b, l].cpu().numpy()[:, :rec["m"]].astype(np.int64) for rec in run.steps]
+            idx_f_bl = idx_f[b, l].cpu().numpy()[:, :kept].astype(np.int64)
+            res = orc.standard_cse(np64(host["q"][b, l]), np64(host["k"][b, l]), np64(host["v"][b, l]), w.chunk_len,
+                                   w.budget, lm_ordering=w.lm_ordering, select_mode=w.select_mode,
+                                   start_size=w.start_size, q_instr_final=np64(host["q_instr"][w.n_chunks - 1, b, l]),
+                                   forced_idx=forced, forced_idx_final=idx_f_bl)
+            assert_close(np64(out_gpu[b, l]), res.out, w.dtype, f"out unit {(b, l)}")
+            for i, rec in enumerate(run.steps):
+                if rec["score"] is None:
+                    continue   # nothing had to be evicted at this step
+                assert_close(np64(rec["score"][b, l]), res.score[i], w.dtype, f"score step {i} unit {(b, l)}")
+                _selection_checks(forced[i], rec["score"][b, l], res.score[i], w.budget, w, f"select step {i}")
+            # cache when the document has ended: bit copies of the document rows the oracle holds
+            assert res.positions.shape[1] == st.cache_len
+            for g in range(w.kv_heads):
+                p = torch.from_numpy(res.positions[g])
+                np.testing.assert_array_equal(bits(k_cur[b, l, g, :st.cache_len]), bits(host["k"][b, l, g][p]))
+                np.testing.assert_array_equal(bits(v_cur[b, l, g, :st.cache_len]), bits(host["v"][b, l, g][p]))
+            # final eviction by the instruction
+            if st.cache_len > w.budget:
+                assert_close(np64(score_f[b, l]), res.score_final, w.dtype, f"final score unit {(b, l)}")
+                _selection_checks(idx_f_bl, score_f[b, l], res.score_final, w.budget, w, "final select")
+            else:
+                np.testing.assert_array_equal(idx_f_bl, np.tile(np.arange(kept), (hs, 1)))
+            for g in range(w.kv_heads):
+                p = torch.from_numpy(res.positions_final[g])
+                np.testing.assert_array_equal(bits(k_fin[b, l, g, :kept]), bits(host["k"][b, l, g][p]))
+                np.testing.assert_array_equal(bits(v_fin[b, l, g, :kept]), bits(host["v"][b, l, g][p]))
+    if w.start_size:
+        assert (idx_f[..., :w.start_size].cpu() == torch.arange(w.start_size)).all()
+
+
+# ----------------------------------------------------------------------------
 # the chunk loop entry point
 # ----------------------------------------------------------------------------
 
@@ -516,9 +609,10 @@ def run_process_document(w, doc, split_at=None, use_python_provider=False):
 
 @pytest.mark.parametrize("case", ["cfg1", "cfg1_ragged", "cfg1_dual", "cfg1_dual_start4", "cfg1_dual_paper_order",
                                   "cfg1_dual_paper_order_start4_per_layer", "cfg2_small", "cfg2_small_start4",
-                                  "cfg4_small_dual", "cfg4_small_dual_paper_order"])
+                                  "cfg4_small_dual", "cfg4_small_dual_paper_order", "cfg1_standard_paper_order",
+                                  "cfg1_standard_after_append_per_layer_start2", "cfg2_small_standard_paper_order"])
 def test_process_document_equals_stepwise_and_resumes(case):
-    w = DOC_CASES[case]
+    w = DOC_CASES.get(case) or STANDARD_CASES[case]
     say(f"process_document {case}")
     cfg = api.Config.from_workload(w)
     doc = make_document(w, DEV)
@@ -533,12 +627,14 @@ def test_process_document_equals_stepwise_and_resumes(case):
     out_step = torch.cat(outs, dim=3)
     state, out, hist, hist_lm = run_process_document(w, doc)
     assert torch.equal(out, out_step)
-    assert state.cache_len == run.state.cache_len == min(w.budget, w.doc_len)
-    assert state.cache_len_lm == run.state.cache_len_lm
+    assert state.cache_len == run.state.cache_len and state.cache_len_lm == run.state.cache_len_lm
+    if not (w.cache_mode == api.CACHE_STANDARD and w.lm_ordering == api.LM_EVICT_THEN_APPEND):
+        assert state.cache_len == min(w.budget, w.doc_len)
     for a, b in zip(state.current(), run.state.current()):
         assert torch.equal(a, b)
     for i, rec in enumerate(run.steps):
-        assert torch.equal(hist[i][..., :rec["m"]], rec["idx"][..., :rec["m"]])
+        if rec["idx"] is not None:  # None: first chunk of the evict-then-append order
+            assert torch.equal(hist[i][..., :rec["m"]], rec["idx"][..., :rec["m"]])
         if hist_lm is not None and rec["idx_lm"] is not None:  # None: first chunk of the evict-then-append order
             assert torch.equal(hist_lm[i][..., :rec["m_lm"]], rec["idx_lm"][..., :rec["m_lm"]])
     if hist_lm is not None:
