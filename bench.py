@@ -59,12 +59,18 @@ class HipEvents:
             self.hip.hipEventDestroy(ev)
 
 
-def attn_flops_per_launch(w, i: int, budget: int) -> float:
+def attn_flops_per_launch(w, i: int, budget: int, holds_previous_chunk: bool = False) -> float:
     """Algorithmic (causal-masked) flops of chunk i's attention launch:
-    4 * d * Hq * B * L * sum_t (n_c + t + 1)."""
+    4 * d * Hq * B * L * sum_t (n_c + t + 1).  A cache run in the evict-then-append order still holds the
+    whole previous chunk next to its budget."""
     lo, hi = w.chunk_bounds(i)
     c = hi - lo
-    n_c = w.cache_len_before(i, budget)
+    if holds_previous_chunk:
+        n_c = 0
+        for j in range(i):
+            n_c = min(n_c, budget) + (w.chunk_bounds(j)[1] - w.chunk_bounds(j)[0])
+    else:
+        n_c = w.cache_len_before(i, budget)
     return 4.0 * w.head_dim * w.q_heads * w.batch * w.layers * (c * n_c + c * (c + 1) / 2.0)
 
 
@@ -116,6 +122,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="cfg2_mistral7b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cache-mode", choices=["instr", "shared", "dual", "standard"], default=None,
+                    help="override the workload's cache design (dual needs a workload with budget_lm)")
+    ap.add_argument("--lm-ordering", choices=["score-after-append", "evict-then-append"], default=None,
+                    help="override how the chunk-evicted cache of dual / standard is run")
     ap.add_argument("--ring", type=int, default=0,
                     help="stream the document through a ring of this many pre-staged chunk buffers (a provider "
                          "callback cycles through them) instead of keeping the whole document resident; chosen "
@@ -138,8 +148,22 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     w = WORKLOADS[args.workload]
+    mode_names = ["instr", "shared", "dual", "standard"]
+    if args.cache_mode is not None or args.lm_ordering is not None:
+        from dataclasses import replace
+        over = {}
+        if args.cache_mode is not None:
+            over["cache_mode"] = mode_names.index(args.cache_mode)
+        if args.lm_ordering is not None:
+            over["lm_ordering"] = ["score-after-append", "evict-then-append"].index(args.lm_ordering)
+        w = replace(w, **over)
+        if w.cache_mode == api.CACHE_DUAL and w.budget_lm < 1:
+            w = replace(w, budget_lm=w.budget)
     cfg = api.Config.from_workload(w)
     dual = w.cache_mode == api.CACHE_DUAL
+    standard = w.cache_mode == api.CACHE_STANDARD
+    chunk_evicted = dual or standard            # a cache evicted by the document's own chunks exists
+    paper_order = chunk_evicted and w.lm_ordering == api.LM_EVICT_THEN_APPEND
 
     esize = 4 if w.dtype == "f32" else 2
     resident_bytes = esize * w.head_dim * w.batch * w.layers * (
@@ -224,17 +248,18 @@ def main():
         for i in range(w.n_chunks):
             base = (s * w.n_chunks + i) * E
             for p, name in names.items():
-                if not dual and p in (2, 3, 4):
+                if (not chunk_evicted and p in (2, 3, 4)) or (standard and p in (5, 6, 7)):
                     continue
                 phase_ms[name] += events.elapsed_ms(base + p - 1, base + p)
             attn_ms.append(events.elapsed_ms(base, base + 1))
-            attn_fl.append(attn_flops_per_launch(w, i, w.budget_lm if dual else w.budget))
+            attn_fl.append(attn_flops_per_launch(w, i, w.budget_lm if dual else w.budget, paper_order))
     events.destroy()
-    phase_ms = {k: round(v / args.steps, 4) for k, v in phase_ms.items() if dual or not k.startswith("lm_")}
+    phase_ms = {k: round(v / args.steps, 4) for k, v in phase_ms.items()
+                if (chunk_evicted or not k.startswith("lm_")) and not (standard and k in ("instr_score", "select", "compact"))}
     avg_ms = sum(attn_ms) / len(attn_ms)
     avg_fl = sum(attn_fl) / len(attn_fl)
     achieved = avg_fl / (avg_ms * 1e-3) / 1e12
-    traffic = MEASURED_TRAFFIC_BYTES.get(w.name)
+    traffic = MEASURED_TRAFFIC_BYTES.get(w.name) if args.cache_mode is None and args.lm_ordering is None else None
 
     result = {
         "metric": "document tokens/sec per layer-stack + % HBM/MFMA peak, Mistral-7B shape",
@@ -244,7 +269,9 @@ def main():
         "config": {"workload": w.name, "batch": w.batch, "layers": w.layers, "q_heads": w.q_heads,
                    "kv_heads": w.kv_heads, "head_dim": w.head_dim, "doc_len": w.doc_len, "chunk_len": w.chunk_len,
                    "budget": w.budget, "instr_len": w.instr_len,
-                   "cache_mode": ["instr", "shared", "dual"][w.cache_mode], "select": "per_kv_head",
+                   "cache_mode": mode_names[w.cache_mode],
+                   "lm_ordering": ["score_after_append", "evict_then_append"][w.lm_ordering] if chunk_evicted else None,
+                   "select": "per_kv_head",
                    "inputs": "resident document" if ring == 0 else f"ring of {ring} pre-staged chunk buffers"},
         "roofline": {"kernel": "attn_pipe_kernel_w8 (chunk attention)", "bound": "mfma",
                      "achieved": round(achieved, 2), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
@@ -252,7 +279,8 @@ def main():
                      "avg_launch_ms": round(avg_ms, 5), "algorithmic_flops_per_launch": avg_fl},
         "phase_ms_per_step": phase_ms,
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.cache_mode is None and args.lm_ordering is None:
+        # (the baseline times the default step sequence; it is not reported for overridden designs)
         result["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(result), flush=True)
 

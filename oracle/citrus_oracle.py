@@ -31,6 +31,9 @@ What each function follows in the paper:
   paragraph describes): Eq. (1) over the cache states alone, Eq. (2)-(3).
 * ``standard_cse``: the Standard CSE process of Section 4.1 on its own (one
   cache, evicted by the document chunks), ending with that extra eviction.
+* ``decode_step``: one step of generating the response from the retained
+  states (Section 4.3): the new token's state joins the cache and its query
+  attends over all of it, the same softmax attention as in Eq. (1).
 
 Readings taken where the paper is silent (all listed again in the design
 notes of the repository):
@@ -452,6 +455,30 @@ def standard_cse(q, k, v, chunk_len: int, budget: int, lm_ordering: int = LM_EVI
             _f64(q_instr_final), kc, vc, budget, select_mode, start_size, scale, forced_idx_final)
         res.positions_final = np.stack([pos[g][res.idx_final[g % res.idx_final.shape[0]]] for g in range(hkv)])
     return res
+
+
+def decode_step(q_new, k_new, v_new, k_cache, v_cache, scale: Optional[float] = None):
+    """One generation step over the retained cache (Section 4.3: the k states
+    left by the last eviction encode the instruction and the response).
+
+    q_new [Hq, d]; k_new, v_new [Hkv, d]: the new token; k_cache, v_cache
+    [Hkv, n, d].  The token's own state is appended (nothing is evicted while
+    the response is generated) and its query attends over all n + 1 states.
+    Returns (out [Hq, d], k_cache' [Hkv, n + 1, d], v_cache').
+    """
+    q_new, k_new, v_new = _f64(q_new), _f64(k_new), _f64(v_new)
+    k_all = np.concatenate([_f64(k_cache), k_new[:, None, :]], axis=1)
+    v_all = np.concatenate([_f64(v_cache), v_new[:, None, :]], axis=1)
+    hq, d = q_new.shape
+    hkv = k_all.shape[0]
+    g_size = hq // hkv
+    sc = _scale(d, scale)
+    out = np.zeros((hq, d))
+    for h in range(hq):
+        g = h // g_size
+        p, _ = softmax_rows((k_all[g] @ q_new[h])[None, :] * sc)
+        out[h] = p[0] @ v_all[g]
+    return out, k_all, v_all
 
 
 def full_causal_attention(q, k, v, scale: Optional[float] = None) -> np.ndarray:

@@ -646,3 +646,49 @@ def test_evict_cache_invariants_and_small_cache():
     k_all, v_all, idx_all, _ = orc.evict_cache(qt, kc, vc, 64)
     np.testing.assert_array_equal(k_all, kc)
     np.testing.assert_array_equal(idx_all, np.tile(np.arange(n), (hkv, 1)))
+
+
+# ----------------------------------------------------------------------------
+# one decoding step over the retained cache
+# ----------------------------------------------------------------------------
+
+def test_decode_step_vs_torch_sdpa_and_token_by_token_equals_causal_attention():
+    hq, hkv, n, d = 4, 2, 19, 8
+    r = rng(151)
+    q, kn, vn = r.normal(size=(hq, d)), r.normal(size=(hkv, d)), r.normal(size=(hkv, d))
+    kc, vc = r.normal(size=(hkv, n, d)), r.normal(size=(hkv, n, d))
+    out, k2, v2 = orc.decode_step(q, kn, vn, kc, vc)
+    np.testing.assert_array_equal(k2[:, :n], kc)
+    np.testing.assert_array_equal(k2[:, n], kn)
+    np.testing.assert_array_equal(v2[:, n], vn)
+    np.testing.assert_allclose(out, _sdpa(q[:, None, :], k2, v2, group=2)[:, 0], atol=1e-12)
+    # generating a sequence token by token from an empty cache is causal attention over it
+    t = 11
+    qs, ks, vs = r.normal(size=(hq, t, d)), r.normal(size=(hkv, t, d)), r.normal(size=(hkv, t, d))
+    kc, vc = np.zeros((hkv, 0, d)), np.zeros((hkv, 0, d))
+    rows = []
+    for i in range(t):
+        o, kc, vc = orc.decode_step(qs[:, i], ks[:, i], vs[:, i], kc, vc)
+        rows.append(o)
+    np.testing.assert_allclose(np.stack(rows, axis=1), _sdpa(qs, ks, vs, causal=True, group=2), atol=1e-12)
+
+
+def test_decode_step_closed_forms():
+    hq, hkv, n, d = 2, 1, 6, 4
+    r = rng(152)
+    vc, vn = r.normal(size=(hkv, n, d)), r.normal(size=(hkv, d))
+    # a zero query weighs all n + 1 states equally: the output is the mean of their values
+    out, _, v2 = orc.decode_step(np.zeros((hq, d)), r.normal(size=(hkv, d)), vn, r.normal(size=(hkv, n, d)), vc)
+    np.testing.assert_allclose(out, np.tile(v2[0].mean(axis=0), (hq, 1)), atol=1e-12)
+    # a key that dominates takes all the weight, the token's own key included
+    q = np.zeros((hq, d)); q[:, 0] = 50.0
+    kc = np.zeros((hkv, n, d)); kc[0, 3, 0] = 40.0
+    out, _, _ = orc.decode_step(q, np.zeros((hkv, d)), vn, kc, vc)
+    np.testing.assert_allclose(out, np.tile(vc[0, 3], (hq, 1)), atol=1e-9)
+    kn = np.zeros((hkv, d)); kn[0, 0] = 80.0
+    out, _, _ = orc.decode_step(q, kn, vn, kc, vc)
+    np.testing.assert_allclose(out, np.tile(vn[0], (hq, 1)), atol=1e-9)
+    # custom scale: doubling the scale equals doubling the query
+    a, _, _ = orc.decode_step(r.normal(size=(hq, d)) * 0 + 1.0, kn * 0.01, vn, kc * 0.01, vc, scale=0.6)
+    b, _, _ = orc.decode_step(np.full((hq, d), 2.0), kn * 0.01, vn, kc * 0.01, vc, scale=0.3)
+    np.testing.assert_allclose(a, b, atol=1e-12)
