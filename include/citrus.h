@@ -58,7 +58,7 @@
 extern "C" {
 #endif
 
-#define CITRUS_ABI_VERSION 4
+#define CITRUS_ABI_VERSION 5
 #define CITRUS_EVENTS_PER_STEP 8
 
 typedef enum {
@@ -222,6 +222,25 @@ int32_t citrus_evict_cache(const citrus_config* cfg, citrus_tensor q, int32_t ro
                            citrus_tensor v_cache, int32_t cache_len, int32_t k, citrus_tensor k_new,
                            citrus_tensor v_new, int32_t* idx, void* workspace, size_t workspace_bytes,
                            void* hip_stream);
+
+/*
+ * One decoding step of the response over the retained states (Section 4.3: the k states left by the last
+ * eviction encode the instruction and the response; nothing is evicted while the response is generated).
+ * The new token's key and value become row cache_len of the cache and its query attends over rows
+ * 0 .. cache_len (softmax with the scaling of Eq. (1)):
+ *   out[b,l,h,0,:] = softmax_j(scale * q[b,l,h,0,:] . K[b,l,h/G,j,:]) . V[b,l,h/G,j,:],  j <= cache_len
+ *
+ * q              [B, L, Hq, 1, d]
+ * k_new, v_new   [B, L, Hkv, 1, d]: the token's own state
+ * k_cache, v_cache [B, L, Hkv, >= cache_len + 1, d], in/out: rows 0 .. cache_len-1 are read, row cache_len
+ *                is written with k_new / v_new (bit copies); 0 <= cache_len < cfg->cache_capacity.
+ *                The caller's cache length becomes cache_len + 1.
+ * out            [B, L, Hq, 1, d]
+ * workspace      >= citrus_workspace_bytes(cfg)
+ */
+int32_t citrus_decode_step(const citrus_config* cfg, citrus_tensor q, citrus_tensor k_new, citrus_tensor v_new,
+                           citrus_tensor k_cache, citrus_tensor v_cache, int32_t cache_len, citrus_tensor out,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Selection (Eq. (2)-(3)): the positions of the min(k, n) highest scores.

@@ -29,7 +29,7 @@ OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE, ERR_PROVIDE
 
 EXPORTS = (
     "citrus_abi_version", "citrus_status_string", "citrus_workspace_bytes", "citrus_chunk_attn",
-    "citrus_instr_score", "citrus_cache_score", "citrus_evict_cache", "citrus_topk_select", "citrus_kv_compact", "citrus_resident_provider",
+    "citrus_instr_score", "citrus_cache_score", "citrus_evict_cache", "citrus_decode_step", "citrus_topk_select", "citrus_kv_compact", "citrus_resident_provider",
     "citrus_process_document",
 )
 
@@ -91,6 +91,8 @@ def _lib():
     lib.citrus_cache_score.argtypes = [P(CConfig), CTensor, I, CTensor, I, V, V, S, V]
     lib.citrus_evict_cache.restype = I
     lib.citrus_evict_cache.argtypes = [P(CConfig), CTensor, I, CTensor, CTensor, I, I, CTensor, CTensor, V, V, S, V]
+    lib.citrus_decode_step.restype = I
+    lib.citrus_decode_step.argtypes = [P(CConfig), CTensor, CTensor, CTensor, CTensor, CTensor, I, CTensor, V, S, V]
     lib.citrus_topk_select.restype = I
     lib.citrus_topk_select.argtypes = [P(CConfig), V, I, I, V, V, S, V]
     lib.citrus_kv_compact.restype = I
@@ -252,6 +254,19 @@ def citrus_evict_cache(cfg: Config, q, k_cache, v_cache, cache_len: int, k: int,
                                    0 if workspace is None else workspace.numel(), _stream(stream))
     _check(st, "citrus_evict_cache")
     return min(k, cache_len)
+
+
+def citrus_decode_step(cfg: Config, q, k_new, v_new, k_cache, v_cache, cache_len: int, out=None, workspace=None,
+                       stream=None):
+    """Appends the token's state to row cache_len of the cache (in place) and returns the attention output."""
+    if out is None:
+        out = torch.empty_like(q)
+    cc = cfg.c()
+    st = _lib().citrus_decode_step(C.byref(cc), tensor(q), tensor(k_new), tensor(v_new), tensor(k_cache),
+                                   tensor(v_cache), cache_len, tensor(out), _ptr(workspace),
+                                   0 if workspace is None else workspace.numel(), _stream(stream))
+    _check(st, "citrus_decode_step")
+    return out
 
 
 def citrus_topk_select(cfg: Config, score, k: int, idx=None, stream=None, n: Optional[int] = None):

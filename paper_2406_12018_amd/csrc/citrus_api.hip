@@ -77,7 +77,7 @@ citrus_status check_lengths(const citrus_config* c, int cache_len, int chunk_len
 
 // Workspace layout (all blocks kAlign-aligned).
 struct Workspace {
-  size_t lse_chunk, lse_instr, lse_cache, score, score_lm, idx, idx_lm, iota, total;
+  size_t lse_chunk, lse_instr, lse_cache, score, score_lm, idx, idx_lm, iota, decode, total;
 };
 
 // A cache evicted by the document's own chunks exists (DUAL's second cache, or the only one of STANDARD)
@@ -101,7 +101,11 @@ Workspace workspace_layout(const citrus_config* c) {
   w.score_lm = off;  off += dual ? align_up(units_kv * n_max * sizeof(float)) : 0;
   w.idx = off;       off += align_up(units_kv * c->budget * sizeof(int32_t));
   w.idx_lm = off;    off += dual ? align_up(units_kv * c->budget_lm * sizeof(int32_t)) : 0;
-  w.iota = off;      off += evict_then_append(c) ? align_up(c->chunk_len * sizeof(int32_t)) : 0;
+  w.iota = off;      off += align_up(c->chunk_len * sizeof(int32_t));
+  {
+    const Dims dm = dims_of(c);
+    w.decode = off;  off += decode_mfma_supported(c->dtype, dm) ? align_up(decode_mfma_workspace_floats(dm) * sizeof(float)) : 0;
+  }
   w.total = off;
   return w;
 }
@@ -318,6 +322,38 @@ int32_t citrus_evict_cache(const citrus_config* cfg, citrus_tensor q, int32_t ro
   CITRUS_TRY(do_topk(cfg, score, cache_len, k, idx, st));
   const Segments ks = cache_only(k_cache, cache_len), vs = cache_only(v_cache, cache_len);
   return do_compact(cfg, dm, ks, vs, idx, k, m, k_new, v_new, st);
+}
+
+int32_t citrus_decode_step(const citrus_config* cfg, citrus_tensor q, citrus_tensor k_new, citrus_tensor v_new,
+                           citrus_tensor k_cache, citrus_tensor v_cache, int32_t cache_len, citrus_tensor out,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+  CITRUS_TRY(check_config(cfg));
+  if (cache_len < 0 || cache_len >= cfg->cache_capacity) return CITRUS_ERR_SHAPE;
+  CITRUS_TRY(check_tensor(q, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(k_new, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(v_new, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(k_cache, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(v_cache, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(out, cfg->dtype, false));
+  if (k_new.ptr == k_cache.ptr || v_new.ptr == v_cache.ptr) return CITRUS_ERR_SHAPE;
+  CITRUS_TRY(check_workspace(cfg, workspace, workspace_bytes));
+  const Dims dm = dims_of(cfg);
+  const Workspace wl = workspace_layout(cfg);
+  char* ws = static_cast<char*>(workspace);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  // candidates: the cache rows, then the new token's own state
+  const Segments ks = segments(k_cache, cache_len, k_new, 1), vs = segments(v_cache, cache_len, v_new, 1);
+  if (decode_mfma_supported(cfg->dtype, dm))
+    CITRUS_TRY(hip_status(launch_decode_mfma(dm, make_view(q), ks, vs, make_view(out),
+                                             reinterpret_cast<float*>(ws + wl.decode), st)));
+  else
+    CITRUS_TRY(hip_status(run_attn(cfg, dm, make_view(q), 1, ks, vs, /*causal=*/1, make_view(out), nullptr, st)));
+  // the token's state becomes row cache_len of the cache (nothing is evicted while the response is generated)
+  int32_t* one = reinterpret_cast<int32_t*>(ws + wl.iota);
+  CITRUS_TRY(hip_status(launch_iota(one, cache_len, 1, st)));
+  return hip_status(launch_compact(elem_bytes(cfg->dtype), dm, ks, vs, one, /*idx_pitch=*/0, /*idx_heads=*/1, 1,
+                                   make_view(rows_from(k_cache, cache_len, cfg->dtype)),
+                                   make_view(rows_from(v_cache, cache_len, cfg->dtype)), st));
 }
 
 int32_t citrus_topk_select(const citrus_config* cfg, const float* score, int32_t n, int32_t k, int32_t* idx,

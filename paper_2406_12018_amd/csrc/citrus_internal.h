@@ -55,6 +55,14 @@ size_t instr_score_mfma_workspace_floats(const Dims& dm, int rows);
 hipError_t launch_instr_score_mfma(const Dims& dm, View q, int rows, Segments kseg, float* workspace, float* score,
                                    hipStream_t st);
 
+// ---- bf16 MFMA decoding step (head_dim 128), decode_attn.hip ----
+bool decode_mfma_supported(int dtype, const Dims& dm);
+size_t decode_mfma_workspace_floats(const Dims& dm);
+// One query row per head over [cache ; the new token's row] (kseg.c == 1); workspace holds the partial
+// results of the key ranges (decode_mfma_workspace_floats).
+hipError_t launch_decode_mfma(const Dims& dm, View q, Segments kseg, Segments vseg, View out, float* workspace,
+                              hipStream_t st);
+
 // ---- selection and compaction, select_compact.hip ----
 // units = B*L*Hsel; score rows are [units*(per_layer?Hkv:1)] x n.
 hipError_t launch_topk(const float* score, int units, int heads_to_sum, int n, int k, int forced, int32_t* idx,

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(B.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
-    assert B.abi_version() == 4
+    assert B.abi_version() == 5
 
 
 def test_struct_layouts_match_the_header():
@@ -126,6 +126,13 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     assert ev(c, kn=fake(0x5000)) == B.ERR_SHAPE and ev(c, vn=fake(0x6000)) == B.ERR_SHAPE
     assert ev(c, kn=null) == B.ERR_NULL
     assert ev(c, w=None, wb=0) == B.ERR_WORKSPACE
+    # decode_step: the cache needs a free row; the token's tensors must not be the cache itself
+    dec = lambda n=8, kn=fake(0x7000), w=ws, wb=big, qq=fake(): lib.citrus_decode_step(
+        C.byref(c), qq, kn, fake(0x8000), fake(0x5000), fake(0x6000), n, fake(0x9000), w, wb, None)
+    assert dec(n=-1) == B.ERR_SHAPE and dec(n=64) == B.ERR_SHAPE
+    assert dec(kn=fake(0x5000)) == B.ERR_SHAPE
+    assert dec(qq=null) == B.ERR_NULL
+    assert dec(w=None, wb=0) == B.ERR_WORKSPACE
     # unsupported head_dim
     bad = cfg(head_dim=96).c()
     assert lib.citrus_topk_select(C.byref(bad), C.c_void_p(0x2000), 8, 4, C.c_void_p(0x3000), None, 0, None) == B.ERR_UNSUPPORTED

@@ -567,6 +567,77 @@ def test_standard_cse_document_and_final_instruction_eviction(case):
 
 
 # ----------------------------------------------------------------------------
+# decoding steps over the retained cache
+# ----------------------------------------------------------------------------
+
+DECODE_SHAPES = [
+    # dtype, B, L, Hq, Hkv, d, cache_len, qk_scale
+    ("bf16", 1, 2, 8, 2, 128, 0, 1.0),
+    ("bf16", 1, 1, 4, 4, 128, 31, 1.0),
+    ("bf16", 2, 1, 8, 2, 128, 32, 0.5),
+    ("bf16", 1, 2, 32, 8, 128, 832, 0.09),
+    ("bf16", 1, 1, 16, 2, 128, 1201, 0.3),
+    ("bf16", 1, 1, 64, 2, 128, 300, 0.3),
+    ("bf16", 3, 2, 4, 1, 128, 4500, 0.09),
+    ("bf16", 1, 2, 4, 2, 64, 77, 0.5),
+    ("f32", 2, 1, 4, 2, 64, 45, 1.0),
+    ("f32", 1, 1, 2, 2, 128, 130, 0.5),
+]
+
+
+@pytest.mark.parametrize("shape", DECODE_SHAPES, ids=lambda s: "-".join(str(x) for x in s[:7]))
+def test_decode_step_parity(shape):
+    dtype, B, L, Hq, Hkv, d, n, s = shape
+    say(f"decode_step {shape}")
+    t = tdt(dtype)
+    steps = 3
+    cap = n + steps + 2
+    cfg = make_cfg(dtype, B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, c=16, k=max(n, 1), n_i=4, cache_capacity=cap)
+    ws = api.alloc_workspace(cfg)
+    # the cache is a view with a longer row pitch than its capacity (strides are honoured)
+    kbuf, vbuf = rand((B, L, Hkv, cap + 5, d), t, 401, s), rand((B, L, Hkv, cap + 5, d), t, 402)
+    kc, vc = kbuf[:, :, :, :cap], vbuf[:, :, :, :cap]
+    k_before, v_before = kc.clone(), vc.clone()
+    ref_k = [[np64(kc[b, l, :, :n]) for l in range(L)] for b in range(B)]
+    ref_v = [[np64(vc[b, l, :, :n]) for l in range(L)] for b in range(B)]
+    for i in range(steps):
+        q = rand((B, L, Hq, 1, d), t, 410 + i, s)
+        kn, vn = rand((B, L, Hkv, 1, d), t, 420 + i, s), rand((B, L, Hkv, 1, d), t, 430 + i)
+        out = api.citrus_decode_step(cfg, q, kn, vn, kc, vc, n + i, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(kc[:, :, :, n + i], kn[:, :, :, 0]) and torch.equal(vc[:, :, :, n + i], vn[:, :, :, 0])
+        for b in range(B):
+            for l in range(L):
+                o_ref, ref_k[b][l], ref_v[b][l] = orc.decode_step(np64(q[b, l, :, 0]), np64(kn[b, l, :, 0]),
+                                                                  np64(vn[b, l, :, 0]), ref_k[b][l], ref_v[b][l])
+                assert_close(np64(out[b, l, :, 0]), o_ref, dtype, f"decode step {i} b{b} l{l}")
+    # nothing but the appended rows changed, inside the view and outside
+    assert torch.equal(kc[:, :, :, :n], k_before[:, :, :, :n]) and torch.equal(vc[:, :, :, :n], v_before[:, :, :, :n])
+    assert torch.equal(kc[:, :, :, n + steps:], k_before[:, :, :, n + steps:])
+    assert torch.equal(vc[:, :, :, n + steps:], v_before[:, :, :, n + steps:])
+    # a full cache is refused
+    with pytest.raises(api.CitrusError):
+        api.citrus_decode_step(cfg, q, kn, vn, kc, vc, cap, workspace=ws)
+
+
+def test_decode_step_repeats_bit_identically_and_matches_chunk_attention_of_one_token():
+    """The same step twice gives the same bits; a chunk of one token through citrus_chunk_attn is the same
+    computation by another kernel (agreement within the bf16 tolerance)."""
+    B, L, Hq, Hkv, d, n = 1, 2, 32, 8, 128, 832
+    cfg = make_cfg("bf16", B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, c=16, k=n, n_i=4, cache_capacity=n + 4)
+    ws = api.alloc_workspace(cfg)
+    kc, vc = rand((B, L, Hkv, n + 4, d), torch.bfloat16, 441, 0.09), rand((B, L, Hkv, n + 4, d), torch.bfloat16, 442)
+    q = rand((B, L, Hq, 1, d), torch.bfloat16, 443, 0.09)
+    kn, vn = rand((B, L, Hkv, 1, d), torch.bfloat16, 444, 0.09), rand((B, L, Hkv, 1, d), torch.bfloat16, 445)
+    by_chunk = api.citrus_chunk_attn(cfg, q, kc, vc, n, kn, vn)
+    a = api.citrus_decode_step(cfg, q, kn, vn, kc, vc, n, workspace=ws)
+    b = api.citrus_decode_step(cfg, q, kn, vn, kc, vc, n, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    np.testing.assert_allclose(np64(a), np64(by_chunk), atol=2e-2, rtol=1e-2)
+
+
+# ----------------------------------------------------------------------------
 # the chunk loop entry point
 # ----------------------------------------------------------------------------
 
