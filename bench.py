@@ -7,6 +7,10 @@ all layers and heads).  Inputs are synthetic, seeded, and resident in HBM before
 the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+    python bench.py --decode [--steps K] [--warmup W] [--workload NAME]
+        a secondary measurement: K decoding steps (citrus_decode_step) over the cache the document loop
+        leaves behind (budget + instr_len states, growing by one per step), as its own JSON line.
 """
 
 from __future__ import annotations
@@ -115,6 +119,53 @@ def cpu_baseline(w, target_seconds: float = 15.0):
                       f"unit, {dt:.1f} s, scaled by batch*layers={w.batch * w.layers}; numpy float64, BLAS threads={threads}"}
 
 
+def decode_mode(args, w, api, torch):
+    """K decoding steps of one token (all layers) over budget + instr_len retained states."""
+    dev = "cuda:0"
+    n0 = w.budget + w.instr_len
+    total = args.warmup + args.steps
+    cfg = api.Config.from_workload(w, cache_capacity=n0 + total)
+    ws = api.alloc_workspace(cfg, dev)
+    g = torch.Generator(device="cpu").manual_seed(w.seed)
+    mk = lambda shape, scale: (torch.randn(shape, generator=g) * scale).to(w.torch_dtype).to(dev)
+    ksc = w.head_dim ** -0.25
+    kc = mk((w.batch, w.layers, w.kv_heads, n0 + total, w.head_dim), ksc)
+    vc = mk((w.batch, w.layers, w.kv_heads, n0 + total, w.head_dim), 1.0)
+    # a few distinct tokens, cycled
+    toks = [(mk((w.batch, w.layers, w.q_heads, 1, w.head_dim), ksc), mk((w.batch, w.layers, w.kv_heads, 1, w.head_dim), ksc),
+             mk((w.batch, w.layers, w.kv_heads, 1, w.head_dim), 1.0)) for _ in range(4)]
+    out = torch.empty_like(toks[0][0])
+    torch.cuda.synchronize()
+    for i in range(args.warmup):
+        q, kn, vn = toks[i % 4]
+        api.citrus_decode_step(cfg, q, kn, vn, kc, vc, n0 + i, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(args.warmup, total):
+        q, kn, vn = toks[i % 4]
+        api.citrus_decode_step(cfg, q, kn, vn, kc, vc, n0 + i, out=out, workspace=ws)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    dev_ms = e0.elapsed_time(e1) / args.steps
+    esize = 4 if w.dtype == "f32" else 2
+    n_avg = n0 + args.warmup + (args.steps - 1) / 2.0 + 1      # states read per step, the token's own included
+    byt = w.batch * w.layers * esize * w.head_dim * (2 * w.kv_heads * n_avg + 2 * w.q_heads + 4 * w.kv_heads)
+    print(json.dumps({
+        "metric": "decoding steps/s over the retained cache (one token through all layers)",
+        "value": round(1e3 / wall_ms, 1), "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name + " decode", "batch": w.batch, "layers": w.layers, "q_heads": w.q_heads,
+                   "kv_heads": w.kv_heads, "head_dim": w.head_dim, "cache_states": n0, "grows_by": 1},
+        "roofline": {"kernel": "decode_attn_kernel", "bound": "hbm", "achieved": round(byt / (dev_ms * 1e-3) / 1e9, 1),
+                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(byt / (dev_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                     "traffic": None, "avg_launch_ms": round(dev_ms, 5), "algorithmic_bytes_per_launch": byt},
+    }), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -122,6 +173,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="cfg2_mistral7b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--decode", action="store_true",
+                    help="measure decoding steps over the retained cache instead of the document loop")
     ap.add_argument("--cache-mode", choices=["instr", "shared", "dual", "standard"], default=None,
                     help="override the workload's cache design (dual needs a workload with budget_lm)")
     ap.add_argument("--lm-ordering", choices=["score-after-append", "evict-then-append"], default=None,
@@ -148,6 +201,9 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     w = WORKLOADS[args.workload]
+    if args.decode:
+        decode_mode(args, w, api, torch)
+        return
     mode_names = ["instr", "shared", "dual", "standard"]
     if args.cache_mode is not None or args.lm_ordering is not None:
         from dataclasses import replace

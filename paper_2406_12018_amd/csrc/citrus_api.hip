@@ -342,13 +342,15 @@ int32_t citrus_decode_step(const citrus_config* cfg, citrus_tensor q, citrus_ten
   char* ws = static_cast<char*>(workspace);
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   // candidates: the cache rows, then the new token's own state
-  const Segments ks = segments(k_cache, cache_len, k_new, 1), vs = segments(v_cache, cache_len, v_new, 1);
+  Segments ks = segments(k_cache, cache_len, k_new, 1), vs = segments(v_cache, cache_len, v_new, 1);
+  ks.cache = make_view(k_cache);  // also when it is empty: row cache_len of it is written
+  vs.cache = make_view(v_cache);
+  // the token's state also becomes row cache_len of the cache (nothing is evicted while the response is
+  // generated): inside the same launch on the MFMA path, by a one-row gather otherwise
   if (decode_mfma_supported(cfg->dtype, dm))
-    CITRUS_TRY(hip_status(launch_decode_mfma(dm, make_view(q), ks, vs, make_view(out),
-                                             reinterpret_cast<float*>(ws + wl.decode), st)));
-  else
-    CITRUS_TRY(hip_status(run_attn(cfg, dm, make_view(q), 1, ks, vs, /*causal=*/1, make_view(out), nullptr, st)));
-  // the token's state becomes row cache_len of the cache (nothing is evicted while the response is generated)
+    return hip_status(launch_decode_mfma(dm, make_view(q), ks, vs, make_view(out),
+                                         reinterpret_cast<float*>(ws + wl.decode), /*append_token=*/1, st));
+  CITRUS_TRY(hip_status(run_attn(cfg, dm, make_view(q), 1, ks, vs, /*causal=*/1, make_view(out), nullptr, st)));
   int32_t* one = reinterpret_cast<int32_t*>(ws + wl.iota);
   CITRUS_TRY(hip_status(launch_iota(one, cache_len, 1, st)));
   return hip_status(launch_compact(elem_bytes(cfg->dtype), dm, ks, vs, one, /*idx_pitch=*/0, /*idx_heads=*/1, 1,

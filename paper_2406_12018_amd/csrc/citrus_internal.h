@@ -59,9 +59,10 @@ hipError_t launch_instr_score_mfma(const Dims& dm, View q, int rows, Segments ks
 bool decode_mfma_supported(int dtype, const Dims& dm);
 size_t decode_mfma_workspace_floats(const Dims& dm);
 // One query row per head over [cache ; the new token's row] (kseg.c == 1); workspace holds the partial
-// results of the key ranges (decode_mfma_workspace_floats).
+// results of the key ranges (decode_mfma_workspace_floats).  append_token != 0: the token's K/V row is
+// also written to row kseg.n_c of the cache tensors (which must have room for it).
 hipError_t launch_decode_mfma(const Dims& dm, View q, Segments kseg, Segments vseg, View out, float* workspace,
-                              hipStream_t st);
+                              int append_token, hipStream_t st);
 
 // ---- selection and compaction, select_compact.hip ----
 // units = B*L*Hsel; score rows are [units*(per_layer?Hkv:1)] x n.

@@ -26,13 +26,10 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) short i16x4;
 
 constexpr int D = 128;
-constexpr int kWaves = 4;
-constexpr int kThreads = kWaves * 64;
 constexpr int kTileKeys = 32;             // keys per wave tile = rows of one MFMA
 constexpr int kRowBytes = 2 * D;          // unpadded, XOR-swizzled rows
 constexpr int kTileBytes = kTileKeys * kRowBytes;          // 8 KB of K, the same of V
 constexpr int kWaveLdsBytes = 4 * kTileBytes;              // {K, V} x two buffers
-constexpr int kLdsBytes = kWaves * kWaveLdsBytes;          // 128 KB
 constexpr int kBufferFlags = 0x00020000;  // raw buffer resource word 3 on CDNA: 32-bit data format, no swizzle
 constexpr int kLoadsPerTile = 2 * kTileKeys / 4;           // 16 instructions of 1 KB
 constexpr int kMaxSplits = 8;
@@ -56,10 +53,56 @@ __device__ inline const uint16_t* unit_ptr(const View& v, int b, int l, int h) {
   return static_cast<const uint16_t*>(v.ptr) + (b * v.sb + l * v.sl + h * v.sh);
 }
 
-// ds_read_b64_tr_b16: see the chunk-attention kernels for the lane mapping.
-__device__ inline i16x4 lds_read_tr16(const char* p) {
-  typedef i16x4 __attribute__((address_space(3))) * lds_ptr;
-  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(2))) int i32x2;
+
+// LDS reads of a tile, written as asm: the compiler drains the vector-memory counter in front of every
+// LDS read it can see while LDS-direct loads are in flight (it cannot tell that they fill the OTHER
+// buffer), which would make each wave wait for the tile it has just requested.  Each block waits for
+// its own reads, so nothing the compiler does not know about is left pending.
+// The eight 16-byte A operands (32 keys x 16 head_dim values each) of S^T = K.Q^T:
+__device__ inline void lds_read_k_operands(Pack8 (&a)[8], const uint32_t (&addr)[8]) {
+  i32x4 r0, r1, r2, r3, r4, r5, r6, r7;
+  asm volatile(
+      "ds_read_b128 %0, %8\n\t"
+      "ds_read_b128 %1, %9\n\t"
+      "ds_read_b128 %2, %10\n\t"
+      "ds_read_b128 %3, %11\n\t"
+      "ds_read_b128 %4, %12\n\t"
+      "ds_read_b128 %5, %13\n\t"
+      "ds_read_b128 %6, %14\n\t"
+      "ds_read_b128 %7, %15\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(r0), "=&v"(r1), "=&v"(r2), "=&v"(r3), "=&v"(r4), "=&v"(r5), "=&v"(r6), "=&v"(r7)
+      : "v"(addr[0]), "v"(addr[1]), "v"(addr[2]), "v"(addr[3]), "v"(addr[4]), "v"(addr[5]), "v"(addr[6]), "v"(addr[7])
+      : "memory");
+  a[0].v = __builtin_bit_cast(bf16x8, r0); a[1].v = __builtin_bit_cast(bf16x8, r1);
+  a[2].v = __builtin_bit_cast(bf16x8, r2); a[3].v = __builtin_bit_cast(bf16x8, r3);
+  a[4].v = __builtin_bit_cast(bf16x8, r4); a[5].v = __builtin_bit_cast(bf16x8, r5);
+  a[6].v = __builtin_bit_cast(bf16x8, r6); a[7].v = __builtin_bit_cast(bf16x8, r7);
+}
+// The four A operands of one 16-key contraction step of O^T = V^T.P^T through transpose reads
+// (ds_read_b64_tr_b16; lane mapping as in the chunk-attention kernels): operand r = head_dim tile r,
+// read rd = keys 8 rd .. +7 of the step, which lie 8 rows = 2048 bytes further on.
+__device__ inline void lds_read_v_operands(Pack8 (&a)[4], const uint32_t (&addr)[8]) {
+  i32x2 r0, r1, r2, r3, r4, r5, r6, r7;
+  asm volatile(
+      "ds_read_b64_tr_b16 %0, %8\n\t"
+      "ds_read_b64_tr_b16 %1, %9 offset:2048\n\t"
+      "ds_read_b64_tr_b16 %2, %10\n\t"
+      "ds_read_b64_tr_b16 %3, %11 offset:2048\n\t"
+      "ds_read_b64_tr_b16 %4, %12\n\t"
+      "ds_read_b64_tr_b16 %5, %13 offset:2048\n\t"
+      "ds_read_b64_tr_b16 %6, %14\n\t"
+      "ds_read_b64_tr_b16 %7, %15 offset:2048\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(r0), "=&v"(r1), "=&v"(r2), "=&v"(r3), "=&v"(r4), "=&v"(r5), "=&v"(r6), "=&v"(r7)
+      : "v"(addr[0]), "v"(addr[1]), "v"(addr[2]), "v"(addr[3]), "v"(addr[4]), "v"(addr[5]), "v"(addr[6]), "v"(addr[7])
+      : "memory");
+  a[0].h[0] = __builtin_bit_cast(i16x4, r0); a[0].h[1] = __builtin_bit_cast(i16x4, r1);
+  a[1].h[0] = __builtin_bit_cast(i16x4, r2); a[1].h[1] = __builtin_bit_cast(i16x4, r3);
+  a[2].h[0] = __builtin_bit_cast(i16x4, r4); a[2].h[1] = __builtin_bit_cast(i16x4, r5);
+  a[3].h[0] = __builtin_bit_cast(i16x4, r6); a[3].h[1] = __builtin_bit_cast(i16x4, r7);
 }
 
 // The tile whose loads were issued before the newest kLoadsPerTile ones has landed in LDS.  LDS-direct
@@ -88,8 +131,12 @@ struct Partials {
   float* o;    // [splits][B*L*Hq][D]
 };
 
-__global__ __launch_bounds__(kThreads, 1) void decode_attn_kernel(Dims dm, View q, Segments ks, Segments vs, View out,
-                                                                 int key_splits, Partials part) {
+template <int WAVES>
+__device__ __forceinline__ void decode_attn_body(const Dims& dm, const View& q, const Segments& ks, const Segments& vs,
+                                                 const View& out, int key_splits, const Partials& part,
+                                                 int append_token) {
+  constexpr int kWaves = WAVES;
+  constexpr int kThreads = kWaves * 64;
   extern __shared__ __attribute__((aligned(1024))) char lds[];
 
   const int tid = threadIdx.x, lane = tid % 64;
@@ -125,6 +172,8 @@ __global__ __launch_bounds__(kThreads, 1) void decode_attn_kernel(Dims dm, View 
       const_cast<uint16_t*>(unit_ptr(vs.chunk, b, l, g)), 0, seg_bytes(ks.c, v_ss_chunk), kBufferFlags);
   typedef __attribute__((address_space(3))) void* lds_void_ptr;
   char* const wave_lds = lds + wu * kWaveLdsBytes;  // [buffer][K | V][tile]
+  typedef __attribute__((address_space(3))) char* lds_char_ptr;
+  const uint32_t wave_lds_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_char_ptr)wave_lds));
   const int fill_row = lane / 16;                   // row inside the 4-row group of one instruction
   const int fill_pos = lane % 16;                   // 16-byte position inside the LDS row
   auto fill_tile = [&](int tile, int buf) {
@@ -186,6 +235,16 @@ __global__ __launch_bounds__(kThreads, 1) void decode_attn_kernel(Dims dm, View 
     }
   }
 
+  // The token's own state becomes row n_c of the cache.  Candidates j >= n_c are always read from the
+  // token's tensors, never from the cache, so no workgroup reads the row that is written here.
+  if (append_token && sp == key_splits - 1 && wu == kWaves - 1 && lane < 32) {
+    const int part16 = lane % 16;  // 16 x 16 bytes per row; lanes 0..15 copy K, lanes 16..31 copy V
+    const bool is_v = lane >= 16;
+    const uint16_t* src = is_v ? unit_ptr(vs.chunk, b, l, g) : unit_ptr(ks.chunk, b, l, g);
+    const View& cv = is_v ? vs.cache : ks.cache;
+    uint16_t* dst = const_cast<uint16_t*>(unit_ptr(cv, b, l, g)) + static_cast<int64_t>(n_c) * cv.ss;
+    *reinterpret_cast<uint4*>(dst + 8 * part16) = *reinterpret_cast<const uint4*>(src + 8 * part16);
+  }
   wait_all_loads();  // the query operand has landed before the first tile is requested
 
   const float c2 = dm.scale * kLog2e;  // logits in the log2 domain
@@ -207,8 +266,8 @@ __global__ __launch_bounds__(kThreads, 1) void decode_attn_kernel(Dims dm, View 
     } else {
       wait_all_loads();
     }
-    const char* k_t = wave_lds + buf * 2 * kTileBytes;
-    const char* v_t = k_t + kTileBytes;
+    const uint32_t k_t = wave_lds_addr + buf * 2 * kTileBytes;  // LDS byte addresses
+    const uint32_t v_t = k_t + kTileBytes;
     const int j0 = tile * kTileKeys;
 
     // S^T = K . Q^T for 32 keys x 32 query columns
@@ -216,8 +275,12 @@ __global__ __launch_bounds__(kThreads, 1) void decode_attn_kernel(Dims dm, View 
 #pragma unroll
     for (int i = 0; i < 16; ++i) s_acc[i] = 0.f;
     Pack8 a[8];
+    {
+      uint32_t addr[8];
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) a[kk].u = *reinterpret_cast<const uint4*>(k_t + k_off[kk]);
+      for (int kk = 0; kk < 8; ++kk) addr[kk] = k_t + k_off[kk];
+      lds_read_k_operands(a, addr);
+    }
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) s_acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk].v, q_op[kk], s_acc, 0, 0, 0);
 
@@ -260,11 +323,12 @@ __global__ __launch_bounds__(kThreads, 1) void decode_attn_kernel(Dims dm, View 
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       Pack8 av[4];
+      {
+        uint32_t addr[8];
 #pragma unroll
-      for (int r = 0; r < 4; ++r)
-#pragma unroll
-        for (int rd = 0; rd < 2; ++rd)
-          av[r].h[rd] = lds_read_tr16(v_t + (16 * half + 8 * rd) * kRowBytes + v_off[2 * r + rd]);
+        for (int e = 0; e < 8; ++e) addr[e] = v_t + 16 * half * kRowBytes + v_off[e];
+        lds_read_v_operands(av, addr);
+      }
       Pack8 pb;
 #pragma unroll
       for (int x = 0; x < 4; ++x) pb.w[x] = p_pk[4 * half + x];
@@ -318,6 +382,15 @@ __global__ __launch_bounds__(kThreads, 1) void decode_attn_kernel(Dims dm, View 
   }
 }
 
+// Four waves per workgroup and 32 KB of LDS per wave: one workgroup per compute unit.  Narrower
+// workgroups (one or two waves, 5 or 2 of them per compute unit) were measured 2 to 7 % slower at every
+// shape tried, so this is the only instance.
+constexpr int kWaves = 4;
+__global__ __launch_bounds__(64 * kWaves) void decode_attn_kernel(Dims dm, View q, Segments ks, Segments vs, View out,
+                                                                 int key_splits, Partials part, int append_token) {
+  decode_attn_body<kWaves>(dm, q, ks, vs, out, key_splits, part, append_token);
+}
+
 // Merge of the key ranges: one thread per (document, layer, query head, head_dim element).
 __global__ __launch_bounds__(256) void decode_merge_kernel(Dims dm, View out, int key_splits, Partials part) {
   const int64_t rows = static_cast<int64_t>(dm.B) * dm.L * dm.Hq;
@@ -340,13 +413,15 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(Dims dm, View out, in
   op[d] = static_cast<uint16_t>(pack_bf16x2(o_all / l_all, 0.f) & 0xffffu);
 }
 
+// Key ranges per unit.  A unit's keys are split over several workgroups only when there are fewer units
+// than compute units (a second launch merges the ranges; measured slower whenever one workgroup per
+// unit already fills the chip), and only while every wave keeps at least two tiles.
 int choose_splits(int units, int n) {
-  // One workgroup per compute unit at a time (its LDS): aim at two rounds of workgroups or more, but
-  // leave every wave of a workgroup at least two tiles.
   const int tiles = (n + kTileKeys - 1) / kTileKeys;
   int splits = 1;
-  while (splits < kMaxSplits && units * splits < 512 && tiles / (2 * splits) >= 2 * kWaves) splits *= 2;
-  return splits;
+  while (splits < kMaxSplits && units * splits < 256 && tiles / (2 * splits) >= 2 * kWaves) splits *= 2;
+  const int per = (tiles + splits - 1) / splits;
+  return (tiles + per - 1) / per;  // no empty key range
 }
 
 }  // namespace
@@ -358,22 +433,21 @@ size_t decode_mfma_workspace_floats(const Dims& dm) {
 }
 
 hipError_t launch_decode_mfma(const Dims& dm, View q, Segments ks, Segments vs, View out, float* workspace,
-                              hipStream_t st) {
+                              int append_token, hipStream_t st) {
+  if (ks.c != 1) return hipErrorInvalidValue;  // one new token
   const int units = dm.B * dm.L * dm.Hkv;
   const int n = ks.n_c + ks.c;
-  int splits = choose_splits(units, n);
-  const int tiles = (n + kTileKeys - 1) / kTileKeys;
-  const int per = (tiles + splits - 1) / splits;
-  splits = (tiles + per - 1) / per;  // no empty key range
+  const int splits = choose_splits(units, n);
   const int64_t rows = static_cast<int64_t>(dm.B) * dm.L * dm.Hq;
   Partials part;
   part.ml = reinterpret_cast<float2*>(workspace);
   part.o = workspace + 2 * static_cast<size_t>(kMaxSplits) * rows;
+  constexpr int kLdsBytes = kWaves * kWaveLdsBytes;  // 128 KB
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_attn_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(decode_attn_kernel, dim3(units * splits), dim3(kThreads), kLdsBytes, st, dm, q, ks, vs, out,
-                     splits, part);
+  hipLaunchKernelGGL(decode_attn_kernel, dim3(units * splits), dim3(64 * kWaves), kLdsBytes, st, dm, q, ks, vs, out,
+                     splits, part, append_token);
   e = hipGetLastError();
   if (e != hipSuccess || splits == 1) return e;
   const int64_t elems = rows * D;

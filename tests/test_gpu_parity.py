@@ -579,6 +579,7 @@ DECODE_SHAPES = [
     ("bf16", 1, 1, 16, 2, 128, 1201, 0.3),
     ("bf16", 1, 1, 64, 2, 128, 300, 0.3),
     ("bf16", 3, 2, 4, 1, 128, 4500, 0.09),
+    ("bf16", 4, 8, 16, 8, 128, 100, 0.3),
     ("bf16", 1, 2, 4, 2, 64, 77, 0.5),
     ("f32", 2, 1, 4, 2, 64, 45, 1.0),
     ("f32", 1, 1, 2, 2, 128, 130, 0.5),
