@@ -73,6 +73,9 @@ import numpy as np
 LM_SCORE_AFTER_APPEND = 0   # the chunk's own causal attention scores [LM cache ; chunk] right away
 LM_EVICT_THEN_APPEND = 1    # Section 4.1 as printed: evict the cache by the chunk's attention to it, then append
 
+SCORE_PER_STEP = 0      # Eq. (1) of the current step decides (the paper's method)
+SCORE_ACCUMULATED = 1   # the sum of the scores a state received since it entered the cache decides (H2O's rule)
+
 SELECT_PER_KV_HEAD = 0
 SELECT_PER_LAYER = 1
 
@@ -249,6 +252,7 @@ class DocumentResult:
     v_cache_lm: Optional[np.ndarray] = None
     positions_lm: Optional[np.ndarray] = None
     trace: List[ChunkTrace] = field(default_factory=list)
+    acc_score: Optional[np.ndarray] = None   # [Hkv, n_c] accumulated scores of the kept states (SCORE_ACCUMULATED)
 
 
 def process_document(q, k, v, q_instr: Sequence[np.ndarray], chunk_len: int, budget: int,
@@ -257,7 +261,8 @@ def process_document(q, k, v, q_instr: Sequence[np.ndarray], chunk_len: int, bud
                      forced_idx: Optional[Sequence[np.ndarray]] = None,
                      forced_idx_lm: Optional[Sequence[np.ndarray]] = None,
                      keep_trace: bool = True, start_size: int = 0,
-                     lm_ordering: int = LM_SCORE_AFTER_APPEND) -> DocumentResult:
+                     lm_ordering: int = LM_SCORE_AFTER_APPEND,
+                     score_mode: int = SCORE_PER_STEP) -> DocumentResult:
     """The chunk loop for one (document, layer).
 
     q [Hq, T, d]; k, v [Hkv, T, d]; q_instr: one [Hq, n_i, d] array per chunk
@@ -286,6 +291,12 @@ def process_document(q, k, v, q_instr: Sequence[np.ndarray], chunk_len: int, bud
     ``start_size``: the first start_size states of the document are never
     evicted (appendix "Analysis on initial tokens"); they are the first
     candidates of every step because retained states keep their order.
+    ``score_mode`` = SCORE_ACCUMULATED is the accumulative-attention rule that
+    Section 5.2 ("Baselines", H2O and "H2O + Shared Cache") pairs with the
+    instruction-aware cache: a state's importance is the sum of the Eq. (1)
+    scores it has received from the instruction in every step since it entered
+    the cache (a new state starts at its first score); the k largest sums stay
+    and carry their sums on.  Only the instruction-scored cache uses it.
     """
     q, k, v = _f64(q), _f64(k), _f64(v)
     hq, t_total, d = q.shape
@@ -299,6 +310,7 @@ def process_document(q, k, v, q_instr: Sequence[np.ndarray], chunk_len: int, bud
     pos = np.zeros((hkv, 0), dtype=np.int64)
     kc_lm = np.zeros((hkv, 0, d)); vc_lm = np.zeros((hkv, 0, d))
     pos_lm = np.zeros((hkv, 0), dtype=np.int64)
+    acc = np.zeros((hkv, 0))             # accumulated score of every cache state (SCORE_ACCUMULATED)
     trace: List[ChunkTrace] = []
 
     for i in range(n_chunks):
@@ -348,8 +360,12 @@ def process_document(q, k, v, q_instr: Sequence[np.ndarray], chunk_len: int, bud
             out, lse, _ = chunk_attn(qs, k_cat, v_cat, n_c, scale)
 
         s_in = instr_score(q_instr[i], k_cat, scale)
+        if score_mode == SCORE_ACCUMULATED:
+            s_in = s_in + np.concatenate([acc, np.zeros((hkv, c))], axis=1)
         idx = (np.asarray(forced_idx[i]) if forced_idx is not None
                else topk_select(s_in, budget, select_mode, start_size))
+        if score_mode == SCORE_ACCUMULATED:
+            acc = np.stack([s_in[g][idx[g % idx.shape[0]]] for g in range(hkv)])
         kc, vc = kv_compact(k_cat, v_cat, idx)
         pos = np.stack([pos_cat[g][idx[g % idx.shape[0]]] for g in range(hkv)])
         if keep_trace:
@@ -358,7 +374,8 @@ def process_document(q, k, v, q_instr: Sequence[np.ndarray], chunk_len: int, bud
     return DocumentResult(k_cache=kc, v_cache=vc, positions=pos,
                           k_cache_lm=kc_lm if dual else None,
                           v_cache_lm=vc_lm if dual else None,
-                          positions_lm=pos_lm if dual else None, trace=trace)
+                          positions_lm=pos_lm if dual else None, trace=trace,
+                          acc_score=acc if score_mode == SCORE_ACCUMULATED else None)
 
 
 def evict_cache(q_text, k_cache, v_cache, k: int, select_mode: int = SELECT_PER_KV_HEAD, start_size: int = 0,

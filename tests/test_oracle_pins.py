@@ -692,3 +692,68 @@ def test_decode_step_closed_forms():
     a, _, _ = orc.decode_step(r.normal(size=(hq, d)) * 0 + 1.0, kn * 0.01, vn, kc * 0.01, vc, scale=0.6)
     b, _, _ = orc.decode_step(np.full((hq, d), 2.0), kn * 0.01, vn, kc * 0.01, vc, scale=0.3)
     np.testing.assert_allclose(a, b, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------
+# accumulated scores (the H2O rule on the instruction-aware cache)
+# ----------------------------------------------------------------------------
+
+def _accumulated_by_hand(k, q_instr, chunk, budget):
+    """ONE head, plain loops: every state carries the sum of the instruction-attention mass it has received
+    in the steps since it entered the cache; after each step the ``budget`` largest sums stay."""
+    t_total, d = k.shape
+    cache, total = [], {}
+    step = 0
+    for lo in range(0, t_total, chunk):
+        hi = min(t_total, lo + chunk)
+        cand = cache + list(range(lo, hi))
+        for qt in q_instr[step]:
+            logit = [sum(qt[x] * k[j][x] for x in range(d)) / math.sqrt(d) for j in cand]
+            mx = max(logit)
+            w = [math.exp(a - mx) for a in logit]
+            z = sum(w)
+            for a, j in enumerate(cand):
+                total[j] = total.get(j, 0.0) + w[a] / z
+        keep = sorted(sorted(cand, key=lambda j: (-total[j], j))[:budget])
+        total = {j: total[j] for j in keep}     # an evicted state and its sum are gone for good
+        cache = keep
+        step += 1
+    return cache, total
+
+
+def test_accumulated_scores_vs_hand_written_loop():
+    hq, hkv, t, d, chunk, budget = 1, 1, 47, 4, 6, 9
+    q, k, v, qi = _doc(161, hq, hkv, t, d, 3, chunk)
+    res = orc.process_document(q, k, v, qi, chunk, budget, score_mode=orc.SCORE_ACCUMULATED)
+    cache, total = _accumulated_by_hand(k[0], [x[0] for x in qi], chunk, budget)
+    assert res.positions[0].tolist() == cache
+    np.testing.assert_allclose(res.acc_score[0], [total[j] for j in cache], atol=1e-12)
+    # the rule matters: the plain per-step rule keeps a different set on this document
+    plain = orc.process_document(q, k, v, qi, chunk, budget)
+    assert plain.positions[0].tolist() != cache
+
+
+def test_accumulated_scores_invariants():
+    hq, hkv, t, d, chunk, budget = 4, 2, 60, 8, 8, 12
+    q, k, v, qi = _doc(162, hq, hkv, t, d, 3, chunk)
+    for mode in (orc.SELECT_PER_KV_HEAD, orc.SELECT_PER_LAYER):
+        res = orc.process_document(q, k, v, qi, chunk, budget, select_mode=mode, score_mode=orc.SCORE_ACCUMULATED,
+                                   start_size=2)
+        plain = orc.process_document(q, k, v, qi, chunk, budget, select_mode=mode, start_size=2)
+        # the first step has nothing to add to: same selection; outputs of step 0 and 1 are those of the plain rule
+        np.testing.assert_array_equal(res.trace[0].idx, plain.trace[0].idx)
+        np.testing.assert_allclose(res.trace[1].out, plain.trace[1].out, atol=1e-12)
+        # a kept state's sum is at least its latest score, and the sums of a step add up to the mass received
+        # by the kept states over their life time, which is at most steps * rows * heads per KV head
+        assert res.acc_score.shape == (hkv, budget) and np.all(res.acc_score > 0)
+        assert np.all(res.acc_score.sum(axis=1) <= len(res.trace) * 3 * 2 + 1e-9)
+        assert np.all(np.diff(res.positions, axis=1) > 0) and np.all(res.positions[:, :2] == np.arange(2))
+    # a budget that holds the whole document never evicts: the cache is the document, the sums are the
+    # column sums over all steps a state has seen
+    res = orc.process_document(q, k, v, qi, chunk, budget=64, score_mode=orc.SCORE_ACCUMULATED)
+    np.testing.assert_array_equal(res.k_cache, k)
+    want = np.zeros((hkv, t))
+    for i, tr in enumerate(res.trace):
+        n = min(t, (i + 1) * chunk)
+        want[:, :n] += orc.instr_score(qi[i], k[:, :n])
+    np.testing.assert_allclose(res.acc_score, want, atol=1e-10)
