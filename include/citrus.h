@@ -58,7 +58,7 @@
 extern "C" {
 #endif
 
-#define CITRUS_ABI_VERSION 5
+#define CITRUS_ABI_VERSION 6
 #define CITRUS_EVENTS_PER_STEP 8
 
 typedef enum {
@@ -99,6 +99,13 @@ typedef enum {
  * The instruction cache is the same computation in both orderings (hoisted by one step). */
 typedef enum { CITRUS_LM_SCORE_AFTER_APPEND = 0, CITRUS_LM_EVICT_THEN_APPEND = 1 } citrus_lm_ordering;
 
+/* What the selection of the instruction-scored cache ranks.
+ * PER_STEP:    this step's Eq. (1) score (the paper's method).
+ * ACCUMULATED: the sum of the Eq. (1) scores a state has received from the instruction in every step since
+ *              it entered the cache: the accumulative-attention rule of H2O that Section 5.2 ("Baselines")
+ *              combines with the instruction-aware cache ("H2O + Shared Cache").  INSTR / SHARED only. */
+typedef enum { CITRUS_SCORE_PER_STEP = 0, CITRUS_SCORE_ACCUMULATED = 1 } citrus_score_mode;
+
 /* PER_KV_HEAD: one index set per (document, layer, KV head).
  * PER_LAYER:   scores of all KV heads are added first and one index set is used
  *              by the whole layer (the layer-wise eviction of Section 4.1).     */
@@ -123,6 +130,7 @@ typedef struct {
                              initial tokens"); 0 = plain Eq. (2)-(3); < budget (and < budget_lm)  */
   int32_t lm_ordering;    /* citrus_lm_ordering (DUAL, STANDARD); EVICT_THEN_APPEND needs cache_capacity >=
                              budget_lm + chunk_len (DUAL) or budget + chunk_len (STANDARD)             */
+  int32_t score_mode;     /* citrus_score_mode                                   */
   float softmax_scale;    /* 0 -> 1/sqrt(head_dim), the scaling of Eq. (1)       */
 } citrus_config;
 
@@ -243,6 +251,22 @@ int32_t citrus_decode_step(const citrus_config* cfg, citrus_tensor q, citrus_ten
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The two steps of the ACCUMULATED score mode around the selection (Section 5.2, H2O's accumulative
+ * attention score on the instruction-aware cache):
+ *   citrus_score_accumulate  score[b,l,g,j] += acc[b,l,g,j] for j < cache_len: a cache state's sum so far is
+ *                            added to this step's score; candidates from the chunk start at their own score.
+ *   citrus_score_gather      acc_new[b,l,g,r] = score[b,l,g, idx[b,l,g',r]] for r < m: the kept states carry
+ *                            their sums on (g' = g, or 0 for PER_LAYER, as in citrus_kv_compact).
+ * score    dense [B, L, Hkv, n] f32 (in/out for accumulate), 1 <= n <= cache_capacity + chunk_len
+ * acc, acc_new  dense [B, L, Hkv, cfg->cache_capacity] f32, distinct buffers; 0 <= cache_len <= min(n, capacity)
+ * idx      dense int32 with row pitch idx_pitch >= m, values in [0, n); 1 <= m <= cfg->cache_capacity
+ */
+int32_t citrus_score_accumulate(const citrus_config* cfg, float* score, int32_t n, const float* acc,
+                                int32_t cache_len, void* hip_stream);
+int32_t citrus_score_gather(const citrus_config* cfg, const float* score, int32_t n, const int32_t* idx,
+                            int32_t idx_pitch, int32_t m, float* acc_new, void* hip_stream);
+
+/*
  * Selection (Eq. (2)-(3)): the positions of the min(k, n) highest scores.
  * Equal scores: the lower position wins.  Output positions are ascending, so
  * kept states stay in their original order.  n <= k keeps everything
@@ -321,6 +345,8 @@ int32_t citrus_resident_provider(void* user, int32_t chunk_index, void* hip_stre
  *                    buffer (cache_len_lm grows to kept + chunk_len; no eviction
  *                    happens after the last chunk).  idx_history_lm then holds the
  *                    kept positions of the LM cache (not the appended chunk rows).
+ *   INSTR / SHARED with score_mode = ACCUMULATED: score_accumulate between
+ *                    instr_score and topk_select, score_gather next to kv_compact.
  *   STANDARD:        the language-modelling steps of DUAL (in either ordering) on
  *                    the only cache pair with budget `budget`; io.q_instr is not
  *                    read and may be NULL; idx_history holds its selections.
@@ -336,6 +362,10 @@ int32_t citrus_resident_provider(void* user, int32_t chunk_index, void* hip_stre
  *                               current (0/1) on entry / on return.  Passing
  *                               the values a previous call returned, with the
  *                               same buffers, resumes a document bit-exactly.
+ * acc_score[2]    score_mode = ACCUMULATED only (else may be NULL): two dense f32
+ *                 buffers [B, L, Hkv, cache_capacity] holding the accumulated
+ *                 scores of the cache rows; they follow buffer_index like
+ *                 k_cache / v_cache and belong to the state a resume needs
  * idx_history     optional dense int32 [steps, B, L, Hsel, budget]: the
  *                 selection of every step done by this call (step 0 = chunk
  *                 first_chunk); Hsel = Hkv or 1 (PER_LAYER)
@@ -357,6 +387,7 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
                                 const citrus_tensor* k_cache_lm, const citrus_tensor* v_cache_lm,
                                 int32_t* cache_len, int32_t* cache_len_lm,
                                 int32_t* buffer_index, int32_t* buffer_index_lm,
+                                float* const* acc_score,
                                 int32_t* idx_history, int32_t* idx_history_lm, int32_t* chunks_done,
                                 void* const* phase_events,
                                 void* workspace, size_t workspace_bytes, void* hip_stream);

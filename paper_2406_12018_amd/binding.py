@@ -22,6 +22,7 @@ F32, BF16 = 0, 1
 CACHE_INSTR, CACHE_SHARED, CACHE_DUAL, CACHE_STANDARD = 0, 1, 2, 3
 SELECT_PER_KV_HEAD, SELECT_PER_LAYER = 0, 1
 LM_SCORE_AFTER_APPEND, LM_EVICT_THEN_APPEND = 0, 1
+SCORE_PER_STEP, SCORE_ACCUMULATED = 0, 1
 
 EVENTS_PER_STEP = 8
 
@@ -29,7 +30,7 @@ OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE, ERR_PROVIDE
 
 EXPORTS = (
     "citrus_abi_version", "citrus_status_string", "citrus_workspace_bytes", "citrus_chunk_attn",
-    "citrus_instr_score", "citrus_cache_score", "citrus_evict_cache", "citrus_decode_step", "citrus_topk_select", "citrus_kv_compact", "citrus_resident_provider",
+    "citrus_instr_score", "citrus_cache_score", "citrus_evict_cache", "citrus_decode_step", "citrus_score_accumulate", "citrus_score_gather", "citrus_topk_select", "citrus_kv_compact", "citrus_resident_provider",
     "citrus_process_document",
 )
 
@@ -44,7 +45,7 @@ class CitrusError(RuntimeError):
 class CConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "batch", "layers", "q_heads", "kv_heads", "head_dim", "chunk_len", "budget", "budget_lm", "instr_len",
-        "cache_capacity", "dtype", "cache_mode", "select_mode", "start_size", "lm_ordering")] + [("softmax_scale", C.c_float)]
+        "cache_capacity", "dtype", "cache_mode", "select_mode", "start_size", "lm_ordering", "score_mode")] + [("softmax_scale", C.c_float)]
 
 
 class CTensor(C.Structure):
@@ -93,6 +94,10 @@ def _lib():
     lib.citrus_evict_cache.argtypes = [P(CConfig), CTensor, I, CTensor, CTensor, I, I, CTensor, CTensor, V, V, S, V]
     lib.citrus_decode_step.restype = I
     lib.citrus_decode_step.argtypes = [P(CConfig), CTensor, CTensor, CTensor, CTensor, CTensor, I, CTensor, V, S, V]
+    lib.citrus_score_accumulate.restype = I
+    lib.citrus_score_accumulate.argtypes = [P(CConfig), V, I, V, I, V]
+    lib.citrus_score_gather.restype = I
+    lib.citrus_score_gather.argtypes = [P(CConfig), V, I, V, I, I, V, V]
     lib.citrus_topk_select.restype = I
     lib.citrus_topk_select.argtypes = [P(CConfig), V, I, I, V, V, S, V]
     lib.citrus_kv_compact.restype = I
@@ -101,7 +106,7 @@ def _lib():
     lib.citrus_resident_provider.argtypes = [V, I, V, P(CChunkIO)]
     lib.citrus_process_document.restype = I
     lib.citrus_process_document.argtypes = [P(CConfig), V, V, I, I, P(CTensor), P(CTensor), P(CTensor), P(CTensor),
-                                            P(I), P(I), P(I), P(I), V, V, P(I), V, V, S, V]
+                                            P(I), P(I), P(I), P(I), P(V), V, V, P(I), V, V, S, V]
     _LIB = lib
     return lib
 
@@ -124,6 +129,7 @@ class Config:
     softmax_scale: float = 0.0
     start_size: int = 0              # leading document states that are never evicted
     lm_ordering: int = LM_SCORE_AFTER_APPEND
+    score_mode: int = SCORE_PER_STEP
 
     def __post_init__(self):
         if self.cache_capacity == 0:
@@ -139,7 +145,7 @@ class Config:
     def c(self) -> CConfig:
         return CConfig(self.batch, self.layers, self.q_heads, self.kv_heads, self.head_dim, self.chunk_len,
                        self.budget, self.budget_lm, self.instr_len, self.cache_capacity, self.dtype,
-                       self.cache_mode, self.select_mode, self.start_size, self.lm_ordering, self.softmax_scale)
+                       self.cache_mode, self.select_mode, self.start_size, self.lm_ordering, self.score_mode, self.softmax_scale)
 
     @property
     def torch_dtype(self) -> torch.dtype:
@@ -155,7 +161,7 @@ class Config:
                   chunk_len=w.chunk_len, budget=w.budget, instr_len=w.instr_len,
                   dtype=F32 if w.dtype == "f32" else BF16, cache_mode=w.cache_mode, select_mode=w.select_mode,
                   budget_lm=w.budget_lm, start_size=getattr(w, "start_size", 0),
-                  lm_ordering=getattr(w, "lm_ordering", 0))
+                  lm_ordering=getattr(w, "lm_ordering", 0), score_mode=getattr(w, "score_mode", 0))
         kw.update(overrides)
         return Config(**kw)
 
@@ -269,6 +275,25 @@ def citrus_decode_step(cfg: Config, q, k_new, v_new, k_cache, v_cache, cache_len
     return out
 
 
+def citrus_score_accumulate(cfg: Config, score, acc, cache_len: int, stream=None, n: Optional[int] = None):
+    """score[..., j] += acc[..., j] for j < cache_len (in place)."""
+    n = score.shape[-1] if n is None else n
+    cc = cfg.c()
+    st = _lib().citrus_score_accumulate(C.byref(cc), _ptr(score), n, _ptr(acc), cache_len, _stream(stream))
+    _check(st, "citrus_score_accumulate")
+    return score
+
+
+def citrus_score_gather(cfg: Config, score, idx, m: int, acc_new, stream=None, n: Optional[int] = None,
+                        idx_pitch: Optional[int] = None):
+    n = score.shape[-1] if n is None else n
+    idx_pitch = idx.shape[-1] if idx_pitch is None else idx_pitch
+    cc = cfg.c()
+    st = _lib().citrus_score_gather(C.byref(cc), _ptr(score), n, _ptr(idx), idx_pitch, m, _ptr(acc_new), _stream(stream))
+    _check(st, "citrus_score_gather")
+    return acc_new
+
+
 def citrus_topk_select(cfg: Config, score, k: int, idx=None, stream=None, n: Optional[int] = None):
     n = score.shape[-1] if n is None else n
     if idx is None:
@@ -302,6 +327,7 @@ class DocumentState:
     v_cache_lm: Optional[Sequence[torch.Tensor]] = None
     cache_len_lm: int = 0
     buffer_index_lm: int = 0
+    acc_score: Optional[Sequence[torch.Tensor]] = None   # SCORE_ACCUMULATED: sums of the cache rows, ping-pong
 
     @staticmethod
     def allocate(cfg: Config, device="cuda") -> "DocumentState":
@@ -310,6 +336,9 @@ class DocumentState:
         st = DocumentState(mk(), mk())
         if cfg.cache_mode == CACHE_DUAL:
             st.k_cache_lm, st.v_cache_lm = mk(), mk()
+        if cfg.score_mode == SCORE_ACCUMULATED:
+            st.acc_score = [torch.zeros((cfg.batch, cfg.layers, cfg.kv_heads, cfg.cache_capacity), dtype=torch.float32,
+                                        device=device) for _ in range(2)]
         return st
 
     def current(self):
@@ -365,8 +394,11 @@ def citrus_process_document(cfg: Config, state: DocumentState, workspace, *, doc
     cur, cur_lm = C.c_int32(state.buffer_index), C.c_int32(state.buffer_index_lm)
     done = C.c_int32(0)
     cc = cfg.c()
+    acc = None
+    if state.acc_score is not None:
+        acc = (C.c_void_p * 2)(state.acc_score[0].data_ptr(), state.acc_score[1].data_ptr())
     st = lib.citrus_process_document(C.byref(cc), fn, user, first_chunk, max_chunks, kc, vc, kl, vl,
-                                     C.byref(n_c), C.byref(n_c_lm), C.byref(cur), C.byref(cur_lm),
+                                     C.byref(n_c), C.byref(n_c_lm), C.byref(cur), C.byref(cur_lm), acc,
                                      _ptr(idx_history), _ptr(idx_history_lm), C.byref(done), phase_events, _ptr(workspace),
                                      0 if workspace is None else workspace.numel(), _stream(stream))
     del keep

@@ -42,6 +42,10 @@ citrus_status check_config(const citrus_config* c) {
   }
   if (c->cache_mode == CITRUS_CACHE_DUAL && c->start_size >= c->budget_lm) return CITRUS_ERR_SHAPE;
   if (!(c->softmax_scale >= 0.0f) || isinf(c->softmax_scale)) return CITRUS_ERR_SHAPE;
+  if (c->score_mode != CITRUS_SCORE_PER_STEP && c->score_mode != CITRUS_SCORE_ACCUMULATED) return CITRUS_ERR_UNSUPPORTED;
+  if (c->score_mode == CITRUS_SCORE_ACCUMULATED && c->cache_mode != CITRUS_CACHE_INSTR &&
+      c->cache_mode != CITRUS_CACHE_SHARED)
+    return CITRUS_ERR_UNSUPPORTED;
   return CITRUS_OK;
 }
 
@@ -358,6 +362,26 @@ int32_t citrus_decode_step(const citrus_config* cfg, citrus_tensor q, citrus_ten
                                    make_view(rows_from(v_cache, cache_len, cfg->dtype)), st));
 }
 
+int32_t citrus_score_accumulate(const citrus_config* cfg, float* score, int32_t n, const float* acc,
+                                int32_t cache_len, void* hip_stream) {
+  CITRUS_TRY(check_config(cfg));
+  if (score == nullptr || acc == nullptr) return CITRUS_ERR_NULL;
+  if (n < 1 || n > cfg->cache_capacity + cfg->chunk_len) return CITRUS_ERR_SHAPE;
+  if (cache_len < 0 || cache_len > n || cache_len > cfg->cache_capacity) return CITRUS_ERR_SHAPE;
+  return hip_status(launch_score_add(dims_of(cfg), score, acc, n, cache_len, cfg->cache_capacity,
+                                     static_cast<hipStream_t>(hip_stream)));
+}
+
+int32_t citrus_score_gather(const citrus_config* cfg, const float* score, int32_t n, const int32_t* idx,
+                            int32_t idx_pitch, int32_t m, float* acc_new, void* hip_stream) {
+  CITRUS_TRY(check_config(cfg));
+  if (score == nullptr || idx == nullptr || acc_new == nullptr) return CITRUS_ERR_NULL;
+  if (n < 1 || n > cfg->cache_capacity + cfg->chunk_len) return CITRUS_ERR_SHAPE;
+  if (m < 1 || m > cfg->cache_capacity || idx_pitch < m) return CITRUS_ERR_SHAPE;
+  return hip_status(launch_score_gather(dims_of(cfg), score, idx, acc_new, n, m, idx_pitch, sel_heads(cfg),
+                                        cfg->cache_capacity, static_cast<hipStream_t>(hip_stream)));
+}
+
 int32_t citrus_topk_select(const citrus_config* cfg, const float* score, int32_t n, int32_t k, int32_t* idx,
                            void* workspace, size_t workspace_bytes, void* hip_stream) {
   (void)workspace;
@@ -417,7 +441,8 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
                                 int32_t first_chunk, int32_t max_chunks, const citrus_tensor* k_cache,
                                 const citrus_tensor* v_cache, const citrus_tensor* k_cache_lm,
                                 const citrus_tensor* v_cache_lm, int32_t* cache_len, int32_t* cache_len_lm,
-                                int32_t* buffer_index, int32_t* buffer_index_lm, int32_t* idx_history,
+                                int32_t* buffer_index, int32_t* buffer_index_lm, float* const* acc_score,
+                                int32_t* idx_history,
                                 int32_t* idx_history_lm, int32_t* chunks_done, void* const* phase_events,
                                 void* workspace, size_t workspace_bytes, void* hip_stream) {
   CITRUS_TRY(check_config(cfg));
@@ -427,6 +452,9 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
   const bool standard = cfg->cache_mode == CITRUS_CACHE_STANDARD;
   if (dual && (k_cache_lm == nullptr || v_cache_lm == nullptr || cache_len_lm == nullptr || buffer_index_lm == nullptr))
     return CITRUS_ERR_NULL;
+  const bool accumulated = cfg->score_mode == CITRUS_SCORE_ACCUMULATED;
+  if (accumulated && (acc_score == nullptr || acc_score[0] == nullptr || acc_score[1] == nullptr)) return CITRUS_ERR_NULL;
+  if (accumulated && acc_score[0] == acc_score[1]) return CITRUS_ERR_SHAPE;
   if (first_chunk < 0) return CITRUS_ERR_SHAPE;
   for (int i = 0; i < 2; ++i) {
     CITRUS_TRY(check_tensor(k_cache[i], cfg->dtype, false));
@@ -558,10 +586,16 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
 
     int32_t* idx = idx_history ? idx_history + static_cast<size_t>(done) * units_sel * cfg->budget : idx_ws;
     if ((status = do_instr_score(cfg, dm, io.q_instr, ks, lse_instr, score, st)) != CITRUS_OK) break;
+    if (accumulated &&
+        (status = hip_status(launch_score_add(dm, score, acc_score[cur], n, n_c, cfg->cache_capacity, st))) != CITRUS_OK)
+      break;
     mark(done, 5);
     if ((status = do_topk(cfg, score, n, cfg->budget, idx, st)) != CITRUS_OK) break;
     mark(done, 6);
     if ((status = do_compact(cfg, dm, ks, vs, idx, cfg->budget, m, k_cache[cur ^ 1], v_cache[cur ^ 1], st)) != CITRUS_OK)
+      break;
+    if (accumulated && (status = hip_status(launch_score_gather(dm, score, idx, acc_score[cur ^ 1], n, m, cfg->budget,
+                                                               sel_heads(cfg), cfg->cache_capacity, st))) != CITRUS_OK)
       break;
     mark(done, 7);
     cur ^= 1;

@@ -70,6 +70,12 @@ hipError_t launch_topk(const float* score, int units, int heads_to_sum, int n, i
                        hipStream_t st);
 // p[i] = base + i for i < count
 hipError_t launch_iota(int32_t* p, int base, int count, hipStream_t st);
+// score [B*L*Hkv][n] += acc [B*L*Hkv][acc_pitch] on the first n_c candidates
+hipError_t launch_score_add(const Dims& dm, float* score, const float* acc, int n, int n_c, int acc_pitch,
+                            hipStream_t st);
+// acc_new [B*L*Hkv][acc_pitch]: row r < m takes score[idx[r]] (idx as in launch_compact)
+hipError_t launch_score_gather(const Dims& dm, const float* score, const int32_t* idx, float* acc_new, int n, int m,
+                               int idx_pitch, int idx_heads, int acc_pitch, hipStream_t st);
 hipError_t launch_compact(int elem_bytes, const Dims& dm, Segments kseg, Segments vseg, const int32_t* idx,
                           int idx_pitch, int idx_heads, int m, View k_new, View v_new, hipStream_t st);
 

@@ -130,6 +130,28 @@ __global__ void iota_kernel(int32_t* p, int base, int count) {
   if (i < count) p[i] = base + i;
 }
 
+// Accumulated scores: the sum a cache state carries is added to this step's score of the same candidate
+// (chunk candidates start at their first score) ...
+__global__ __launch_bounds__(256) void score_add_kernel(float* score, const float* acc, int n, int n_c, int acc_pitch,
+                                                        int heads) {
+  const int64_t u = static_cast<int64_t>(blockIdx.z) * heads + blockIdx.y;
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j < n_c) score[u * n + j] += acc[u * acc_pitch + j];
+}
+// ... and the kept states take their sums along: acc_new[r] = score[idx[r]].
+__global__ __launch_bounds__(256) void score_gather_kernel(const float* score, const int32_t* idx, float* acc_new, int n,
+                                                           int m, int idx_pitch, int idx_heads, int acc_pitch,
+                                                           int heads) {
+  const int g = blockIdx.y;
+  const int64_t u = static_cast<int64_t>(blockIdx.z) * heads + g;
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r >= m) return;
+  const int gi = idx_heads == 1 ? 0 : g;
+  int j = idx[(static_cast<int64_t>(blockIdx.z) * idx_heads + gi) * idx_pitch + r];
+  j = max(0, min(j, n - 1));  // a bad index must never become an out-of-bounds read
+  acc_new[u * acc_pitch + r] = score[u * n + j];
+}
+
 // Row gather: every thread moves 16 bytes of a K row and 16 bytes of a V row.
 template <int ROW_BYTES>
 __global__ __launch_bounds__(256) void compact_kernel(Dims dm, Segments ks, Segments vs, int elem_bytes,
@@ -188,6 +210,21 @@ hipError_t launch_topk(const float* score, int units, int heads_to_sum, int n, i
 
 hipError_t launch_iota(int32_t* p, int base, int count, hipStream_t st) {
   hipLaunchKernelGGL(iota_kernel, dim3((count + 255) / 256), dim3(256), 0, st, p, base, count);
+  return hipGetLastError();
+}
+
+hipError_t launch_score_add(const Dims& dm, float* score, const float* acc, int n, int n_c, int acc_pitch,
+                            hipStream_t st) {
+  if (n_c <= 0) return hipSuccess;
+  hipLaunchKernelGGL(score_add_kernel, dim3((n_c + 255) / 256, dm.Hkv, dm.B * dm.L), dim3(256), 0, st, score, acc, n,
+                     n_c, acc_pitch, dm.Hkv);
+  return hipGetLastError();
+}
+
+hipError_t launch_score_gather(const Dims& dm, const float* score, const int32_t* idx, float* acc_new, int n, int m,
+                               int idx_pitch, int idx_heads, int acc_pitch, hipStream_t st) {
+  hipLaunchKernelGGL(score_gather_kernel, dim3((m + 255) / 256, dm.Hkv, dm.B * dm.L), dim3(256), 0, st, score, idx,
+                     acc_new, n, m, idx_pitch, idx_heads, acc_pitch, dm.Hkv);
   return hipGetLastError();
 }
 

@@ -137,10 +137,15 @@ class StepwiseRun:
             out = api.citrus_chunk_attn(cfg, q, kc, vc, st.cache_len, k, v, lse=lse)
             rec["lse"] = lse
         score = api.citrus_instr_score(cfg, q_instr, kc, st.cache_len, k, workspace=self.ws)
+        accumulated = cfg.score_mode == api.SCORE_ACCUMULATED
+        if accumulated:  # a cache state's sum so far joins this step's score
+            api.citrus_score_accumulate(cfg, score, st.acc_score[st.buffer_index], st.cache_len)
         idx = api.citrus_topk_select(cfg, score, cfg.budget)
         m = min(cfg.budget, n)
         api.citrus_kv_compact(cfg, kc, vc, st.cache_len, k, v, idx, m, st.k_cache[st.buffer_index ^ 1],
                               st.v_cache[st.buffer_index ^ 1])
+        if accumulated:  # and the kept states carry their sums on
+            api.citrus_score_gather(cfg, score, idx, m, st.acc_score[st.buffer_index ^ 1])
         st.buffer_index ^= 1
         st.cache_len = m
         rec.update(out=out, score=score, idx=idx, m=m)

@@ -24,11 +24,11 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(B.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
-    assert B.abi_version() == 5
+    assert B.abi_version() == 6
 
 
 def test_struct_layouts_match_the_header():
-    assert C.sizeof(B.CConfig) == 16 * 4
+    assert C.sizeof(B.CConfig) == 17 * 4
     assert C.sizeof(B.CTensor) == 5 * 8
     assert C.sizeof(B.CChunkIO) == 5 * 40 + 8
     assert C.sizeof(B.CResidentDoc) == 5 * 40 + 8 + 16
@@ -56,7 +56,9 @@ def test_status_strings():
     ({"cache_mode": B.CACHE_DUAL, "budget_lm": 48, "lm_ordering": B.LM_EVICT_THEN_APPEND, "cache_capacity": 64}, False),
     ({"cache_mode": B.CACHE_STANDARD}, True), ({"cache_mode": B.CACHE_STANDARD, "lm_ordering": B.LM_EVICT_THEN_APPEND}, True),
     ({"cache_mode": B.CACHE_STANDARD, "lm_ordering": B.LM_EVICT_THEN_APPEND, "cache_capacity": 64}, False),
-    ({"cache_mode": 4}, False),
+    ({"cache_mode": 4}, False), ({"score_mode": B.SCORE_ACCUMULATED}, True), ({"score_mode": 2}, False),
+    ({"score_mode": B.SCORE_ACCUMULATED, "cache_mode": B.CACHE_STANDARD}, False),
+    ({"score_mode": B.SCORE_ACCUMULATED, "cache_mode": B.CACHE_DUAL, "budget_lm": 16}, False),
 ])
 def test_workspace_bytes_validates_config(kw, ok):
     assert (B.workspace_bytes(cfg(**kw)) > 0) == ok
@@ -133,6 +135,18 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     assert dec(kn=fake(0x5000)) == B.ERR_SHAPE
     assert dec(qq=null) == B.ERR_NULL
     assert dec(w=None, wb=0) == B.ERR_WORKSPACE
+    # accumulated scores: NULLs, lengths
+    p1, p2, p3 = C.c_void_p(0x2000), C.c_void_p(0x3000), C.c_void_p(0x4000)
+    assert lib.citrus_score_accumulate(C.byref(c), None, 8, p2, 4, None) == B.ERR_NULL
+    assert lib.citrus_score_accumulate(C.byref(c), p1, 8, None, 4, None) == B.ERR_NULL
+    assert lib.citrus_score_accumulate(C.byref(c), p1, 0, p2, 0, None) == B.ERR_SHAPE
+    assert lib.citrus_score_accumulate(C.byref(c), p1, 97, p2, 4, None) == B.ERR_SHAPE
+    assert lib.citrus_score_accumulate(C.byref(c), p1, 8, p2, 9, None) == B.ERR_SHAPE
+    assert lib.citrus_score_accumulate(C.byref(c), p1, 90, p2, 65, None) == B.ERR_SHAPE
+    assert lib.citrus_score_gather(C.byref(c), p1, 8, None, 4, 4, p3, None) == B.ERR_NULL
+    assert lib.citrus_score_gather(C.byref(c), p1, 8, p2, 4, 0, p3, None) == B.ERR_SHAPE
+    assert lib.citrus_score_gather(C.byref(c), p1, 8, p2, 3, 4, p3, None) == B.ERR_SHAPE
+    assert lib.citrus_score_gather(C.byref(c), p1, 8, p2, 80, 65, p3, None) == B.ERR_SHAPE
     # unsupported head_dim
     bad = cfg(head_dim=96).c()
     assert lib.citrus_topk_select(C.byref(bad), C.c_void_p(0x2000), 8, 4, C.c_void_p(0x3000), None, 0, None) == B.ERR_UNSUPPORTED
@@ -156,7 +170,8 @@ def test_process_document_validation_and_provider_protocol():
     fn = C.cast(cb, C.c_void_p)
     run = lambda **o: lib.citrus_process_document(
         o.get("cfg", C.byref(c)), o.get("fn", fn), None, o.get("first", 3), -1, o.get("k", two), two_v, None, None,
-        C.byref(o.get("n_c", n_c)), None, C.byref(cur), None, None, None, C.byref(done), None, o.get("ws", ws),
+        C.byref(o.get("n_c", n_c)), None, C.byref(cur), None, o.get("acc", None), None, None, C.byref(done), None,
+        o.get("ws", ws),
         o.get("ws_bytes", big), None)
     assert run() == B.OK and calls == [3] and done.value == 0
     assert run(fn=None) == B.ERR_NULL
@@ -165,6 +180,12 @@ def test_process_document_validation_and_provider_protocol():
     assert run(first=-1) == B.ERR_SHAPE
     assert run(ws=None) == B.ERR_WORKSPACE
     assert run(ws_bytes=100) == B.ERR_WORKSPACE
+    # accumulated scores need their two buffers
+    ca = cfg(score_mode=B.SCORE_ACCUMULATED).c()
+    assert run(cfg=C.byref(ca)) == B.ERR_NULL
+    same_acc = (C.c_void_p * 2)(0x50000, 0x50000)
+    assert run(cfg=C.byref(ca), acc=same_acc) == B.ERR_SHAPE
+    assert run(cfg=C.byref(ca), acc=(C.c_void_p * 2)(0x50000, 0x60000)) == B.OK
     # a provider that aborts
     cb2 = B.PROVIDER(lambda _u, i, _s, _io: -5)
     assert run(fn=C.cast(cb2, C.c_void_p)) == B.ERR_PROVIDER

@@ -330,11 +330,13 @@ def run_document_stepwise(w: Workload, sample_units=None, check_every=1):
     run = StepwiseRun(api, cfg, DEV)
     dual = w.cache_mode == api.CACHE_DUAL
     paper_lm = dual and w.lm_ordering == api.LM_EVICT_THEN_APPEND
+    accumulated = w.score_mode == api.SCORE_ACCUMULATED
     units = sample_units or [(b, l) for b in range(w.batch) for l in range(w.layers)]
     hs = cfg.sel_heads
     # oracle-side state per unit: document positions held by each cache row
     pos = {u: np.zeros((w.kv_heads, 0), dtype=np.int64) for u in units}
     pos_lm = {u: np.zeros((w.kv_heads, 0), dtype=np.int64) for u in units}
+    acc_ref = {u: np.zeros((w.kv_heads, 0)) for u in units}   # oracle-side accumulated scores of the cache rows
     host = {name: t.cpu() for name, t in doc.items()}
     band_fracs = []
     for i in range(w.n_chunks):
@@ -397,10 +399,14 @@ def run_document_stepwise(w: Workload, sample_units=None, check_every=1):
                     pos_lm[(b, l)] = np.stack([cand_lm[g][idx_lm[g % hs]] for g in range(w.kv_heads)])
             elif check:
                 o_ref, lse_ref, _ = orc.chunk_attn(qd, kcat, vcat, n_c)
+            if check or accumulated:
+                s_ref = orc.instr_score(qi, kcat)
+                if accumulated:   # sums follow the replayed selections, like the positions
+                    s_ref = s_ref + np.concatenate([acc_ref[(b, l)], np.zeros((w.kv_heads, c))], axis=1)
+                    acc_ref[(b, l)] = np.stack([s_ref[g][idx[g % hs]] for g in range(w.kv_heads)])
             if check:
                 assert_close(np64(rec["out"][b, l]), o_ref, w.dtype, f"out step {i} unit {(b, l)}")
                 assert_close(np64(rec["lse"][b, l]), lse_ref, w.dtype, f"lse step {i} unit {(b, l)}")
-                s_ref = orc.instr_score(qi, kcat)
                 assert_close(np64(rec["score"][b, l]), s_ref, w.dtype, f"score step {i} unit {(b, l)}")
                 for g in range(hs):
                     ref_vec = s_ref.sum(0) if hs == 1 else s_ref[g]
@@ -416,6 +422,13 @@ def run_document_stepwise(w: Workload, sample_units=None, check_every=1):
                     p = torch.from_numpy(pos[(b, l)][g])
                     np.testing.assert_array_equal(bits(kc_gpu[b, l, g]), bits(host["k"][b, l, g][p]))
                     np.testing.assert_array_equal(bits(vc_gpu[b, l, g]), bits(host["v"][b, l, g][p]))
+                if accumulated:
+                    # the sums the kept states carry: copies of the GPU's own scores, close to the oracle's
+                    acc_gpu = st.acc_score[st.buffer_index][b, l, :, :st.cache_len]
+                    for g in range(w.kv_heads):
+                        own = rec["score"][b, l, g][torch.from_numpy(idx[g % hs]).to(DEV).long()]
+                        assert torch.equal(acc_gpu[g], own)
+                    assert_close(np64(acc_gpu), acc_ref[(b, l)], w.dtype, f"accumulated score step {i} unit {(b, l)}")
                 if dual:
                     kl_gpu, vl_gpu = st.current_lm()
                     for g in range(w.kv_heads):
@@ -457,6 +470,13 @@ DOC_CASES = {
     "cfg1_dual_paper_order_start4_per_layer": scaled_down(
         peaked(WORKLOADS["cfg1_tiny_f32"]), doc_len=256, layers=2, kv_heads=2, cache_mode=api.CACHE_DUAL, budget_lm=20,
         start_size=4, select_mode=api.SELECT_PER_LAYER, lm_ordering=api.LM_EVICT_THEN_APPEND),
+    "cfg1_accumulated": scaled_down(peaked(WORKLOADS["cfg1_tiny_f32"]), doc_len=300, layers=2, kv_heads=2,
+                                    score_mode=api.SCORE_ACCUMULATED),
+    "cfg1_accumulated_per_layer_start4": scaled_down(peaked(WORKLOADS["cfg1_tiny_f32"]), doc_len=256, layers=2, kv_heads=2,
+                                                     score_mode=api.SCORE_ACCUMULATED, start_size=4,
+                                                     select_mode=api.SELECT_PER_LAYER),
+    "cfg2_small_accumulated": scaled_down(WORKLOADS["cfg2_mistral7b"], layers=2, doc_len=2300,
+                                          score_mode=api.SCORE_ACCUMULATED),
     "cfg2_small": scaled_down(WORKLOADS["cfg2_mistral7b"], layers=2, doc_len=2560),
     "cfg2_small_start4": scaled_down(WORKLOADS["cfg2_mistral7b"], layers=2, doc_len=2560, start_size=4),
     "cfg2_small_peaked": scaled_down(peaked(WORKLOADS["cfg2_mistral7b"]), layers=1, doc_len=2000),
@@ -681,7 +701,8 @@ def run_process_document(w, doc, split_at=None, use_python_provider=False):
 
 @pytest.mark.parametrize("case", ["cfg1", "cfg1_ragged", "cfg1_dual", "cfg1_dual_start4", "cfg1_dual_paper_order",
                                   "cfg1_dual_paper_order_start4_per_layer", "cfg2_small", "cfg2_small_start4",
-                                  "cfg4_small_dual", "cfg4_small_dual_paper_order", "cfg1_standard_paper_order",
+                                  "cfg4_small_dual", "cfg4_small_dual_paper_order", "cfg1_accumulated",
+                                  "cfg1_accumulated_per_layer_start4", "cfg2_small_accumulated", "cfg1_standard_paper_order",
                                   "cfg1_standard_after_append_per_layer_start2", "cfg2_small_standard_paper_order"])
 def test_process_document_equals_stepwise_and_resumes(case):
     w = DOC_CASES.get(case) or STANDARD_CASES[case]
@@ -712,6 +733,9 @@ def test_process_document_equals_stepwise_and_resumes(case):
     if hist_lm is not None:
         for a, b in zip(state.current_lm(), run.state.current_lm()):
             assert torch.equal(a, b)
+    if w.score_mode == api.SCORE_ACCUMULATED:
+        assert torch.equal(state.acc_score[state.buffer_index][..., :state.cache_len],
+                           run.state.acc_score[run.state.buffer_index][..., :run.state.cache_len])
     # resume: two calls give the same bits as one; so does a second full run and a Python provider
     for kw in (dict(split_at=max(1, w.n_chunks // 3)), dict(), dict(use_python_provider=True)):
         state2, out2, hist2, _ = run_process_document(w, doc, **kw)

@@ -70,6 +70,7 @@ class Workload:
     budget_lm: int = 0
     start_size: int = 0        # leading document states that are never evicted (0 = plain selection)
     lm_ordering: int = 0       # DUAL only: 0 = score after append, 1 = evict, then append (Section 4.1's order)
+    score_mode: int = 0        # 0 = this step's score decides, 1 = accumulated scores (H2O's rule)
     sink_scale: float = 4.0
     heavy_prob: float = 0.0
     heavy_scale: float = 2.5
