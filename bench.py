@@ -119,6 +119,17 @@ def cpu_baseline(w, target_seconds: float = 15.0):
                       f"unit, {dt:.1f} s, scaled by batch*layers={w.batch * w.layers}; numpy float64, BLAS threads={threads}"}
 
 
+def calibrate_copy(torch, dev):
+    """A plain elementwise copy of known size (256 MiB read + 256 MiB written), three times: the reference
+    for scaling rocprofv3's HBM counters."""
+    src = torch.ones(128 * 1024 * 1024, dtype=torch.bfloat16, device=dev)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        torch.add(src, 0, out=dst)
+    torch.cuda.synchronize()
+    del src, dst
+
+
 def decode_mode(args, w, api, torch):
     """K decoding steps of one token (all layers) over budget + instr_len retained states."""
     dev = "cuda:0"
@@ -136,6 +147,8 @@ def decode_mode(args, w, api, torch):
              mk((w.batch, w.layers, w.kv_heads, 1, w.head_dim), 1.0)) for _ in range(4)]
     out = torch.empty_like(toks[0][0])
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        calibrate_copy(torch, dev)
     for i in range(args.warmup):
         q, kn, vn = toks[i % 4]
         api.citrus_decode_step(cfg, q, kn, vn, kc, vc, n0 + i, out=out, workspace=ws)
@@ -276,12 +289,7 @@ def main():
         assert done == w.n_chunks
 
     if args.calibrate_copy:
-        src = torch.ones(128 * 1024 * 1024, dtype=torch.bfloat16, device=dev)      # 256 MiB
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            torch.add(src, 0, out=dst)
-        torch.cuda.synchronize()
-        del src, dst
+        calibrate_copy(torch, dev)
 
     for _ in range(args.warmup):
         one_document()
