@@ -58,7 +58,7 @@
 extern "C" {
 #endif
 
-#define CITRUS_ABI_VERSION 6
+#define CITRUS_ABI_VERSION 7
 #define CITRUS_EVENTS_PER_STEP 8
 
 typedef enum {
@@ -162,6 +162,10 @@ int32_t citrus_abi_version(void);
  * cache_len   0 .. cfg->cache_capacity;  chunk_len 1 .. cfg->chunk_len
  * lse         optional, dense [B, L, Hq, chunk_len] f32: log-sum-exp of each
  *             row's scaled logits over the candidates it sees
+ * lse_cache   optional (cache_len >= 1), dense [B, L, Hq, chunk_len] f32: the same
+ *             over the cache states alone, i.e. the normaliser of Eq. (1) as
+ *             printed; citrus_cache_score takes it.  A by-product of the bf16
+ *             d=128 kernel when cache_len is a multiple of 32, else one more pass.
  * lm_score    optional, dense [B, L, Hkv, n] f32: chunk-scored importance,
  *             lm_score[b,l,g,j] = sum over heads h of group g and chunk rows t
  *             of the attention probability p[h,t,j] (0 where masked); Eq. (1)
@@ -172,8 +176,8 @@ int32_t citrus_abi_version(void);
  */
 int32_t citrus_chunk_attn(const citrus_config* cfg, citrus_tensor q, citrus_tensor k_cache, citrus_tensor v_cache,
                           int32_t cache_len, citrus_tensor k_chunk, citrus_tensor v_chunk, int32_t chunk_len,
-                          citrus_tensor out, float* lse, float* lm_score, void* workspace, size_t workspace_bytes,
-                          void* hip_stream);
+                          citrus_tensor out, float* lse, float* lse_cache, float* lm_score, void* workspace,
+                          size_t workspace_bytes, void* hip_stream);
 
 /*
  * Instruction-aware importance (Eq. (1) with the instruction I in the role of
@@ -206,12 +210,16 @@ int32_t citrus_instr_score(const citrus_config* cfg, citrus_tensor q_instr, citr
  *         configuration runs a cache in the EVICT_THEN_APPEND order (the workspace is sized by these);
  *         more rows: CITRUS_ERR_SHAPE
  * k_cache [B, L, Hkv, >= cache_len, d], 1 <= cache_len <= cfg->cache_capacity
+ * lse_cache optional, dense [B, L, Hq, rows] f32: the rows' log-sum-exp over the cache states, as
+ *         citrus_chunk_attn returns it for the same q and cache; then only the column sums are computed
+ *         (one pass over the keys instead of two), no workspace is needed and rows may go up to
+ *         max(chunk_len, instr_len) in any configuration
  * score   dense [B, L, Hkv, cache_len] f32
- * workspace: >= citrus_workspace_bytes(cfg).
+ * workspace: >= citrus_workspace_bytes(cfg) (may be NULL when lse_cache is given).
  */
 int32_t citrus_cache_score(const citrus_config* cfg, citrus_tensor q, int32_t rows, citrus_tensor k_cache,
-                           int32_t cache_len, float* score, void* workspace, size_t workspace_bytes,
-                           void* hip_stream);
+                           int32_t cache_len, const float* lse_cache, float* score, void* workspace,
+                           size_t workspace_bytes, void* hip_stream);
 
 /*
  * One eviction of a cache by a text (Section 4.1 step 2; with the instruction as the text: the additional
@@ -339,6 +347,7 @@ int32_t citrus_resident_provider(void* user, int32_t chunk_index, void* hip_stre
  *                    kv_compact on the instruction pair.
  *   DUAL with lm_ordering = EVICT_THEN_APPEND: chunk_attn over [LM cache ; chunk]
  *                    where the LM cache holds up to budget_lm + chunk_len states;
+ *                    (with its cache-only log-sum-exp as a by-product);
  *                    cache_score of the chunk's queries over the LM cache alone,
  *                    topk_select(budget_lm) among its states, then the kept states
  *                    followed by all states of the chunk are written to the other LM

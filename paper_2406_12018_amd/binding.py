@@ -85,11 +85,11 @@ def _lib():
     lib.citrus_workspace_bytes.restype = S
     lib.citrus_workspace_bytes.argtypes = [P(CConfig)]
     lib.citrus_chunk_attn.restype = I
-    lib.citrus_chunk_attn.argtypes = [P(CConfig), CTensor, CTensor, CTensor, I, CTensor, CTensor, I, CTensor, V, V, V, S, V]
+    lib.citrus_chunk_attn.argtypes = [P(CConfig), CTensor, CTensor, CTensor, I, CTensor, CTensor, I, CTensor, V, V, V, V, S, V]
     lib.citrus_instr_score.restype = I
     lib.citrus_instr_score.argtypes = [P(CConfig), CTensor, CTensor, I, CTensor, I, V, V, S, V]
     lib.citrus_cache_score.restype = I
-    lib.citrus_cache_score.argtypes = [P(CConfig), CTensor, I, CTensor, I, V, V, S, V]
+    lib.citrus_cache_score.argtypes = [P(CConfig), CTensor, I, CTensor, I, V, V, V, S, V]
     lib.citrus_evict_cache.restype = I
     lib.citrus_evict_cache.argtypes = [P(CConfig), CTensor, I, CTensor, CTensor, I, I, CTensor, CTensor, V, V, S, V]
     lib.citrus_decode_step.restype = I
@@ -211,13 +211,13 @@ def alloc_workspace(cfg: Config, device="cuda") -> torch.Tensor:
 
 
 def citrus_chunk_attn(cfg: Config, q, k_cache, v_cache, cache_len: int, k_chunk, v_chunk, out=None, lse=None,
-                      lm_score=None, workspace=None, stream=None, chunk_len: Optional[int] = None):
+                      lm_score=None, workspace=None, stream=None, chunk_len: Optional[int] = None, lse_cache=None):
     chunk_len = q.shape[3] if chunk_len is None else chunk_len
     if out is None:
         out = torch.empty_like(q)
     cc = cfg.c()
     st = _lib().citrus_chunk_attn(C.byref(cc), tensor(q), tensor(k_cache), tensor(v_cache), cache_len,
-                                  tensor(k_chunk), tensor(v_chunk), chunk_len, tensor(out), _ptr(lse),
+                                  tensor(k_chunk), tensor(v_chunk), chunk_len, tensor(out), _ptr(lse), _ptr(lse_cache),
                                   _ptr(lm_score), _ptr(workspace), 0 if workspace is None else workspace.numel(),
                                   _stream(stream))
     _check(st, "citrus_chunk_attn")
@@ -239,13 +239,13 @@ def citrus_instr_score(cfg: Config, q_instr, k_cache, cache_len: int, k_chunk, s
 
 
 def citrus_cache_score(cfg: Config, q, k_cache, cache_len: int, score=None, workspace=None, stream=None,
-                       rows: Optional[int] = None):
+                       rows: Optional[int] = None, lse_cache=None):
     rows = q.shape[3] if rows is None else rows
     if score is None:
         score = torch.empty((cfg.batch, cfg.layers, cfg.kv_heads, cache_len), dtype=torch.float32, device=q.device)
     cc = cfg.c()
-    st = _lib().citrus_cache_score(C.byref(cc), tensor(q), rows, tensor(k_cache), cache_len, _ptr(score),
-                                   _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream))
+    st = _lib().citrus_cache_score(C.byref(cc), tensor(q), rows, tensor(k_cache), cache_len, _ptr(lse_cache),
+                                   _ptr(score), _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream))
     _check(st, "citrus_cache_score")
     return score
 

@@ -435,7 +435,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
 // K tiles are fetched one 64-key tile further ahead than V tiles; one barrier per 64 keys.
 template <int WAVES>
 __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, int rows, const Segments& ks,
-                                               const Segments& vs, int causal, const View& out, float* lse) {
+                                               const Segments& vs, int causal, const View& out, float* lse,
+                                               float* lse_cache) {
   constexpr bool HAS_PV = true;
   constexpr int key_splits = 1;
   float2* const part = nullptr;
@@ -581,6 +582,11 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
   // ---- running softmax state: one query per lane ----
   const float c2 = dm.scale * kLog2e;  // logits are kept in the log2 domain
   float m_run = -INFINITY, l_run = 0.f;
+  // Optional by-product: each row's log-sum-exp over the cache states alone, i.e. the running
+  // (maximum, sum) pair at the moment the last cache half tile has been added.  Needs the cache to end
+  // on a half-tile boundary (the launcher checks); every row sees every cache state.
+  const int snap_h = lse_cache != nullptr ? n_c / 32 - 1 : -1;
+  float m_snap = -INFINITY, l_snap = 0.f;
   f32x16 o_acc[4];
 #pragma unroll
   for (int r = 0; r < 4; ++r)
@@ -748,6 +754,10 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
                                              __builtin_bit_cast(bf16x2, 0x3f803f80u), psum, false);
     }
     l_run += psum;
+    if (hc == snap_h) {  // block-uniform
+      m_snap = m_run;
+      l_snap = l_run;
+    }
     // keep the probabilities in this block: without a use here the optimiser sinks the exponentials
     // to their first use in the next step, behind the MFMAs they are meant to overlap with
     keep_values_here(p_cur, l_run);
@@ -811,12 +821,14 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
   __syncthreads();  // the buffers are free for the next row block
   }
 
+  const float l_snap_tot = l_snap + __shfl_xor(l_snap, 32, 64);
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const int t = row0 + col;
   if (wave_active && t < rows) {
   const int64_t row_id = (static_cast<int64_t>(bl) * dm.Hq + h) * rows + t;
   if (part != nullptr && grp == 0)  // log2 domain; an empty or fully masked range leaves (-inf, 0)
     part[static_cast<int64_t>(sp) * dm.B * dm.L * dm.Hq * rows + row_id] = make_float2(m_run, l_tot);
+  if (lse_cache != nullptr && grp == 0) lse_cache[row_id] = (m_snap + log2f(l_snap_tot)) * kLn2;
   if (lse != nullptr && grp == 0) lse[row_id] = (m_run + log2f(l_tot)) * kLn2;
   if (HAS_PV) {
     const float inv = 1.f / l_tot;
@@ -842,8 +854,8 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
 // split for smaller groups) share every K/V tile, which halves the fetch traffic per MFMA
 // against four waves; one workgroup per CU, two waves per SIMD.
 __global__ __launch_bounds__(512, 1) void attn_pipe_kernel_w8(Dims dm, View q, int rows, Segments ks, Segments vs,
-                                                             int causal, View out, float* lse) {
-  attn_pipe_body<8>(dm, q, rows, ks, vs, causal, out, lse);
+                                                             int causal, View out, float* lse, float* lse_cache) {
+  attn_pipe_body<8>(dm, q, rows, ks, vs, causal, out, lse, lse_cache);
 }
 
 // Summed form of Eq. (1): score[g, j] = sum over the query rows of the KV group of
@@ -1203,8 +1215,13 @@ static bool fits_i32(const View& v, int rows) {
   return v.ss > 0 && v.ss * static_cast<int64_t>(rows > 0 ? rows : 1) < (int64_t{1} << 31);
 }
 
+bool attn_mfma_emits_cache_lse(const Segments& ks, int causal, View out) {
+  return out.ptr != nullptr && causal != 0 && ks.n_c > 0 && ks.n_c % 32 == 0;
+}
+
 hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments ks, Segments vs, int causal, View out,
-                            float* lse, int key_splits, float2* part, hipStream_t st) {
+                            float* lse, float* lse_cache, int key_splits, float2* part, hipStream_t st) {
+  if (lse_cache != nullptr && !attn_mfma_emits_cache_lse(ks, causal, out)) return hipErrorInvalidValue;
   if (!fits_i32(ks.cache, ks.n_c) || !fits_i32(ks.chunk, ks.c) || !fits_i32(vs.cache, vs.n_c) ||
       !fits_i32(vs.chunk, vs.c))
     return hipErrorInvalidValue;
@@ -1217,7 +1234,8 @@ hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments ks, Segme
   const int rb_slots = (causal && key_splits == 1) ? (row_blocks + 1) / 2 : row_blocks;  // paired row blocks
   dim3 grid(rb_slots * (dm.G / ts.heads_per_block) * dm.Hkv * dm.B * dm.L * key_splits);
   if (pipe)
-    hipLaunchKernelGGL(attn_pipe_kernel_w8, grid, dim3(kPipeWaves * 64), 0, st, dm, q, rows, ks, vs, causal, out, lse);
+    hipLaunchKernelGGL(attn_pipe_kernel_w8, grid, dim3(kPipeWaves * 64), 0, st, dm, q, rows, ks, vs, causal, out, lse,
+                       lse_cache);
   else
     hipLaunchKernelGGL((attn_mfma_kernel<false>), grid, dim3(kThreads), 0, st, dm, q, rows, ks, vs, causal, out, lse,
                        key_splits, part);
@@ -1257,7 +1275,7 @@ hipError_t launch_instr_score_mfma(const Dims& dm, View q, int rows, Segments ks
   splits = splits < 1 ? 1 : (splits > kMaxKeySplits ? kMaxKeySplits : splits);
   float2* part = reinterpret_cast<float2*>(workspace);
   View none{nullptr, 0, 0, 0, 0};
-  hipError_t e = launch_attn_mfma(dm, q, rows, ks, ks, /*causal=*/0, none, nullptr, splits, part, st);
+  hipError_t e = launch_attn_mfma(dm, q, rows, ks, ks, /*causal=*/0, none, nullptr, nullptr, splits, part, st);
   if (e != hipSuccess) return e;
   return launch_colsum_mfma(dm, q, rows, ks, /*causal=*/0, nullptr, splits, part, score, st);
 }

@@ -125,7 +125,7 @@ citrus_status check_workspace(const citrus_config* c, const void* ws, size_t byt
 hipError_t run_attn(const citrus_config* c, const Dims& dm, View q, int rows, Segments ks, Segments vs, int causal,
                     View out, float* lse, hipStream_t st) {
   if (mfma_path_supported(c->dtype, dm))
-    return launch_attn_mfma(dm, q, rows, ks, vs, causal, out, lse, 1, nullptr, st);
+    return launch_attn_mfma(dm, q, rows, ks, vs, causal, out, lse, nullptr, 1, nullptr, st);
   return launch_attn_generic(c->dtype, dm, q, rows, ks, vs, causal, out, lse, st);
 }
 
@@ -138,9 +138,26 @@ hipError_t run_colsum(const citrus_config* c, const Dims& dm, View q, int rows, 
 
 // Unchecked bodies shared by the public entry points and the chunk loop.
 
+// lse_cache (optional, needs ks.n_c > 0): each row's log-sum-exp over the cache states alone, the
+// normaliser of Eq. (1) as printed.  A by-product of the MFMA attention kernel when the cache ends on
+// a 32-key boundary; a pass of its own over the cache otherwise.
 citrus_status do_chunk_attn(const citrus_config* c, const Dims& dm, const citrus_tensor& q, Segments ks, Segments vs,
-                            const citrus_tensor& out, float* lse, float* lm_score, hipStream_t st) {
-  CITRUS_TRY(hip_status(run_attn(c, dm, make_view(q), ks.c, ks, vs, /*causal=*/1, make_view(out), lse, st)));
+                            const citrus_tensor& out, float* lse, float* lm_score, float* lse_cache, hipStream_t st) {
+  const bool mfma = mfma_path_supported(c->dtype, dm);
+  if (lse_cache != nullptr && mfma && attn_mfma_emits_cache_lse(ks, 1, make_view(out))) {
+    CITRUS_TRY(hip_status(launch_attn_mfma(dm, make_view(q), ks.c, ks, vs, /*causal=*/1, make_view(out), lse, lse_cache,
+                                           1, nullptr, st)));
+  } else {
+    CITRUS_TRY(hip_status(run_attn(c, dm, make_view(q), ks.c, ks, vs, /*causal=*/1, make_view(out), lse, st)));
+    if (lse_cache != nullptr) {
+      Segments only = ks;  // the cache as the only key segment
+      only.chunk = ks.cache;
+      only.c = ks.n_c;
+      only.n_c = 0;
+      View none{nullptr, 0, 0, 0, 0};
+      CITRUS_TRY(hip_status(run_attn(c, dm, make_view(q), ks.c, only, only, /*causal=*/0, none, lse_cache, st)));
+    }
+  }
   if (lm_score != nullptr)
     CITRUS_TRY(hip_status(run_colsum(c, dm, make_view(q), ks.c, ks, /*causal=*/1, lse, lm_score, st)));
   return CITRUS_OK;
@@ -172,8 +189,11 @@ Segments cache_only(const citrus_tensor& cache, int cache_len) {
 // Eq. (1) as printed: the rows of q score the states of one cache, softmax over those states alone.
 // The cache is handed to the kernels as the only key segment.
 citrus_status do_cache_score(const citrus_config* c, const Dims& dm, const citrus_tensor& q, int rows,
-                             const citrus_tensor& k_cache, int cache_len, float* lse_ws, float* score, hipStream_t st) {
+                             const citrus_tensor& k_cache, int cache_len, const float* lse_given, float* lse_ws,
+                             float* score, hipStream_t st) {
   const Segments ks = cache_only(k_cache, cache_len);
+  if (lse_given != nullptr)  // the normalisers are known: only the column sums are left
+    return hip_status(run_colsum(c, dm, make_view(q), rows, ks, /*causal=*/0, lse_given, score, st));
   if (mfma_path_supported(c->dtype, dm))
     return hip_status(launch_instr_score_mfma(dm, make_view(q), rows, ks, lse_ws, score, st));
   View none{nullptr, 0, 0, 0, 0};
@@ -248,10 +268,11 @@ size_t citrus_workspace_bytes(const citrus_config* cfg) {
 
 int32_t citrus_chunk_attn(const citrus_config* cfg, citrus_tensor q, citrus_tensor k_cache, citrus_tensor v_cache,
                           int32_t cache_len, citrus_tensor k_chunk, citrus_tensor v_chunk, int32_t chunk_len,
-                          citrus_tensor out, float* lse, float* lm_score, void* workspace, size_t workspace_bytes,
-                          void* hip_stream) {
+                          citrus_tensor out, float* lse, float* lse_cache, float* lm_score, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
   CITRUS_TRY(check_config(cfg));
   CITRUS_TRY(check_lengths(cfg, cache_len, chunk_len));
+  if (lse_cache != nullptr && cache_len == 0) return CITRUS_ERR_SHAPE;
   CITRUS_TRY(check_tensor(q, cfg->dtype, false));
   CITRUS_TRY(check_tensor(out, cfg->dtype, false));
   CITRUS_TRY(check_tensor(k_chunk, cfg->dtype, false));
@@ -264,7 +285,7 @@ int32_t citrus_chunk_attn(const citrus_config* cfg, citrus_tensor q, citrus_tens
   }
   const Dims dm = dims_of(cfg);
   return do_chunk_attn(cfg, dm, q, segments(k_cache, cache_len, k_chunk, chunk_len),
-                       segments(v_cache, cache_len, v_chunk, chunk_len), out, lse, lm_score,
+                       segments(v_cache, cache_len, v_chunk, chunk_len), out, lse, lm_score, lse_cache,
                        static_cast<hipStream_t>(hip_stream));
 }
 
@@ -285,17 +306,22 @@ int32_t citrus_instr_score(const citrus_config* cfg, citrus_tensor q_instr, citr
 }
 
 int32_t citrus_cache_score(const citrus_config* cfg, citrus_tensor q, int32_t rows, citrus_tensor k_cache,
-                           int32_t cache_len, float* score, void* workspace, size_t workspace_bytes,
-                           void* hip_stream) {
+                           int32_t cache_len, const float* lse_cache, float* score, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
   CITRUS_TRY(check_config(cfg));
   if (rows < 1 || cache_len < 1 || cache_len > cfg->cache_capacity) return CITRUS_ERR_SHAPE;
   if (score == nullptr) return CITRUS_ERR_NULL;
   CITRUS_TRY(check_tensor(q, cfg->dtype, false));
   CITRUS_TRY(check_tensor(k_cache, cfg->dtype, false));
+  if (lse_cache != nullptr) {  // no workspace needed: the rows' normalisers are given
+    if (rows > cfg->chunk_len && rows > cfg->instr_len) return CITRUS_ERR_SHAPE;
+    return do_cache_score(cfg, dims_of(cfg), q, rows, k_cache, cache_len, lse_cache, nullptr, score,
+                          static_cast<hipStream_t>(hip_stream));
+  }
   CITRUS_TRY(check_workspace(cfg, workspace, workspace_bytes));
   float* lse_ws = cache_score_block(cfg, workspace, rows);
   if (lse_ws == nullptr) return CITRUS_ERR_SHAPE;
-  return do_cache_score(cfg, dims_of(cfg), q, rows, k_cache, cache_len, lse_ws, score,
+  return do_cache_score(cfg, dims_of(cfg), q, rows, k_cache, cache_len, nullptr, lse_ws, score,
                         static_cast<hipStream_t>(hip_stream));
 }
 
@@ -322,7 +348,7 @@ int32_t citrus_evict_cache(const citrus_config* cfg, citrus_tensor q, int32_t ro
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int m = cache_len < k ? cache_len : k;
   // a cache that fits stays whole: the selection is the identity and reads no score
-  if (cache_len > k) CITRUS_TRY(do_cache_score(cfg, dm, q, rows, k_cache, cache_len, lse_ws, score, st));
+  if (cache_len > k) CITRUS_TRY(do_cache_score(cfg, dm, q, rows, k_cache, cache_len, nullptr, lse_ws, score, st));
   CITRUS_TRY(do_topk(cfg, score, cache_len, k, idx, st));
   const Segments ks = cache_only(k_cache, cache_len), vs = cache_only(v_cache, cache_len);
   return do_compact(cfg, dm, ks, vs, idx, k, m, k_new, v_new, st);
@@ -515,9 +541,11 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
       // the order Section 4.1 prints: encode the chunk given the cache (it still holds the whole previous
       // chunk), evict the cache by the chunk's attention to it, then put the chunk in
       const int kept = n_old < t.budget ? n_old : t.budget;
-      CITRUS_TRY(do_chunk_attn(cfg, dm, io.q, kl, vl, io.out, nullptr, nullptr, st));
+      const bool evicts = n_old > t.budget;
+      // the rows' normalisers over the cache alone come out of the attention launch
+      CITRUS_TRY(do_chunk_attn(cfg, dm, io.q, kl, vl, io.out, nullptr, nullptr, evicts ? lse_cache : nullptr, st));
       mark(done, 1);
-      if (n_old > t.budget) CITRUS_TRY(do_cache_score(cfg, dm, io.q, c, t.k[from], n_old, lse_cache, t.score, st));
+      if (evicts) CITRUS_TRY(do_cache_score(cfg, dm, io.q, c, t.k[from], n_old, lse_cache, nullptr, t.score, st));
       mark(done, 2);
       if (n_old > 0) CITRUS_TRY(do_topk(cfg, t.score, n_old, t.budget, t.idx, st));
       mark(done, 3);
@@ -533,7 +561,7 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
       // the chunk attends over [cache ; chunk] and scores all of it itself; eviction in the same step
       const int n_new = n_old + c;
       const int kept = n_new < t.budget ? n_new : t.budget;
-      CITRUS_TRY(do_chunk_attn(cfg, dm, io.q, kl, vl, io.out, lse_chunk, nullptr, st));
+      CITRUS_TRY(do_chunk_attn(cfg, dm, io.q, kl, vl, io.out, lse_chunk, nullptr, nullptr, st));
       mark(done, 1);
       CITRUS_TRY(hip_status(run_colsum(cfg, dm, make_view(io.q), c, kl, /*causal=*/1, lse_chunk, t.score, st)));
       mark(done, 2);
@@ -580,7 +608,7 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
       const ChunkEvicted t{k_cache_lm, v_cache_lm, &n_c_lm, &cur_lm, cfg->budget_lm, score_lm, idx_lm};
       if ((status = chunk_evicted_step(t, io, c)) != CITRUS_OK) break;
     } else {
-      if ((status = do_chunk_attn(cfg, dm, io.q, ks, vs, io.out, nullptr, nullptr, st)) != CITRUS_OK) break;
+      if ((status = do_chunk_attn(cfg, dm, io.q, ks, vs, io.out, nullptr, nullptr, nullptr, st)) != CITRUS_OK) break;
       for (int p = 1; p <= 4; ++p) mark(done, p);
     }
 

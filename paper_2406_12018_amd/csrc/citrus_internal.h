@@ -46,8 +46,11 @@ hipError_t launch_colsum_generic(int dtype, const Dims& dm, View q, int rows, Se
 bool mfma_path_supported(int dtype, const Dims& dm);
 // key_splits > 1: log-sum-exp only, one partial (log2-domain maximum, sum) pair per key range
 // and row in part[split][B*L*Hq*rows]; key_splits == 1: out and/or lse (natural log) as given.
+// lse_cache (optional): per row, the log-sum-exp over the cache states alone, a by-product of the
+// causal kernel with output when attn_mfma_emits_cache_lse() holds (cache ends on a 32-key boundary).
+bool attn_mfma_emits_cache_lse(const Segments& kseg, int causal, View out);
 hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments kseg, Segments vseg, int causal, View out,
-                            float* lse, int key_splits, float2* part, hipStream_t st);
+                            float* lse, float* lse_cache, int key_splits, float2* part, hipStream_t st);
 // normaliser per row from lse (natural log) or, if part != NULL, merged from key_splits partial pairs
 hipError_t launch_colsum_mfma(const Dims& dm, View q, int rows, Segments kseg, int causal, const float* lse,
                               int key_splits, const float2* part, float* score, hipStream_t st);

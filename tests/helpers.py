@@ -89,11 +89,16 @@ class StepwiseRun:
             # Section 4.1's order: encode given the cache, evict the cache by the chunk's attention to it,
             # then append the whole chunk
             kept = min(budget, n_old)
-            out = api.citrus_chunk_attn(cfg, q, kl, vl, n_old, k, v, lse=lse)
+            # when something has to go, the attention launch also returns each row's normaliser over the
+            # cache alone, and the cache score is then a single pass over the keys
+            lse_cache = None
+            if n_old > budget:
+                lse_cache = torch.empty((cfg.batch, cfg.layers, cfg.q_heads, c), dtype=torch.float32, device=q.device)
+            out = api.citrus_chunk_attn(cfg, q, kl, vl, n_old, k, v, lse=lse, lse_cache=lse_cache)
             score = idx = None
             if n_old > 0:
                 if n_old > budget:
-                    score = api.citrus_cache_score(cfg, q, kl, n_old, workspace=self.ws)
+                    score = api.citrus_cache_score(cfg, q, kl, n_old, lse_cache=lse_cache)
                     idx = api.citrus_topk_select(cfg, score, budget)
                 else:  # everything stays: the selection does not read the scores
                     unread = torch.zeros((cfg.batch, cfg.layers, cfg.kv_heads, n_old), dtype=torch.float32, device=q.device)

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(B.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
-    assert B.abi_version() == 6
+    assert B.abi_version() == 7
 
 
 def test_struct_layouts_match_the_header():
@@ -75,19 +75,19 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     ws = C.c_void_p(0x10000)
     big = 1 << 30
     # NULL config
-    assert lib.citrus_chunk_attn(None, fake(), fake(), fake(), 0, fake(), fake(), 8, fake(), None, None, None, 0, None) == B.ERR_NULL
+    assert lib.citrus_chunk_attn(None, fake(), fake(), fake(), 0, fake(), fake(), 8, fake(), None, None, None, None, 0, None) == B.ERR_NULL
     # NULL q
-    assert lib.citrus_chunk_attn(C.byref(c), null, fake(), fake(), 0, fake(), fake(), 8, fake(), None, None, None, 0, None) == B.ERR_NULL
+    assert lib.citrus_chunk_attn(C.byref(c), null, fake(), fake(), 0, fake(), fake(), 8, fake(), None, None, None, None, 0, None) == B.ERR_NULL
     # NULL cache with cache_len > 0
-    assert lib.citrus_chunk_attn(C.byref(c), fake(), null, null, 4, fake(), fake(), 8, fake(), None, None, None, 0, None) == B.ERR_NULL
+    assert lib.citrus_chunk_attn(C.byref(c), fake(), null, null, 4, fake(), fake(), 8, fake(), None, None, None, None, 0, None) == B.ERR_NULL
     # chunk_len out of range, cache_len above capacity
-    assert lib.citrus_chunk_attn(C.byref(c), fake(), fake(), fake(), 0, fake(), fake(), 33, fake(), None, None, None, 0, None) == B.ERR_SHAPE
-    assert lib.citrus_chunk_attn(C.byref(c), fake(), fake(), fake(), 65, fake(), fake(), 8, fake(), None, None, None, 0, None) == B.ERR_SHAPE
+    assert lib.citrus_chunk_attn(C.byref(c), fake(), fake(), fake(), 0, fake(), fake(), 33, fake(), None, None, None, None, 0, None) == B.ERR_SHAPE
+    assert lib.citrus_chunk_attn(C.byref(c), fake(), fake(), fake(), 65, fake(), fake(), 8, fake(), None, None, None, None, 0, None) == B.ERR_SHAPE
     # misaligned pointer / stride
-    assert lib.citrus_chunk_attn(C.byref(c), fake(0x1004), fake(), fake(), 0, fake(), fake(), 8, fake(), None, None, None, 0, None) == B.ERR_SHAPE
-    assert lib.citrus_chunk_attn(C.byref(c), fake(s=66), fake(), fake(), 0, fake(), fake(), 8, fake(), None, None, None, 0, None) == B.ERR_SHAPE
+    assert lib.citrus_chunk_attn(C.byref(c), fake(0x1004), fake(), fake(), 0, fake(), fake(), 8, fake(), None, None, None, None, 0, None) == B.ERR_SHAPE
+    assert lib.citrus_chunk_attn(C.byref(c), fake(s=66), fake(), fake(), 0, fake(), fake(), 8, fake(), None, None, None, None, 0, None) == B.ERR_SHAPE
     # lm_score without lse needs a workspace
-    assert lib.citrus_chunk_attn(C.byref(c), fake(), fake(), fake(), 0, fake(), fake(), 8, fake(), None, C.c_void_p(0x2000), None, 0, None) == B.ERR_WORKSPACE
+    assert lib.citrus_chunk_attn(C.byref(c), fake(), fake(), fake(), 0, fake(), fake(), 8, fake(), None, None, C.c_void_p(0x2000), None, 0, None) == B.ERR_WORKSPACE
     # instr_score: NULL score, missing / short workspace
     assert lib.citrus_instr_score(C.byref(c), fake(), fake(), 0, fake(), 8, None, ws, big, None) == B.ERR_NULL
     assert lib.citrus_instr_score(C.byref(c), fake(), fake(), 0, fake(), 8, C.c_void_p(0x2000), None, 0, None) == B.ERR_WORKSPACE
@@ -108,17 +108,21 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     # cache_score: the rows must fit the workspace (instr_len rows, or chunk_len rows for a configuration
     # that runs a cache in the evict-then-append order)
     sc = C.c_void_p(0x2000)
-    assert lib.citrus_cache_score(C.byref(c), fake(), 9, fake(), 8, sc, ws, big, None) == B.ERR_SHAPE
+    assert lib.citrus_cache_score(C.byref(c), fake(), 9, fake(), 8, None, sc, ws, big, None) == B.ERR_SHAPE
     for mode_kw in (dict(cache_mode=B.CACHE_DUAL, budget_lm=16), dict(cache_mode=B.CACHE_STANDARD)):
         e = cfg(lm_ordering=B.LM_EVICT_THEN_APPEND, **mode_kw).c()
-        assert lib.citrus_cache_score(C.byref(e), null, 8, fake(), 8, sc, ws, big, None) == B.ERR_NULL
-        assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 8, None, ws, big, None) == B.ERR_NULL
-        assert lib.citrus_cache_score(C.byref(e), fake(), 0, fake(), 8, sc, ws, big, None) == B.ERR_SHAPE
-        assert lib.citrus_cache_score(C.byref(e), fake(), 33, fake(), 8, sc, ws, big, None) == B.ERR_SHAPE
-        assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 0, sc, ws, big, None) == B.ERR_SHAPE
-        assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 97, sc, ws, big, None) == B.ERR_SHAPE
-        assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 8, sc, None, 0, None) == B.ERR_WORKSPACE
-        assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 8, sc, ws, 16, None) == B.ERR_WORKSPACE
+        assert lib.citrus_cache_score(C.byref(e), null, 8, fake(), 8, None, sc, ws, big, None) == B.ERR_NULL
+        assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 8, None, None, ws, big, None) == B.ERR_NULL
+        assert lib.citrus_cache_score(C.byref(e), fake(), 0, fake(), 8, None, sc, ws, big, None) == B.ERR_SHAPE
+        assert lib.citrus_cache_score(C.byref(e), fake(), 33, fake(), 8, None, sc, ws, big, None) == B.ERR_SHAPE
+        assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 0, None, sc, ws, big, None) == B.ERR_SHAPE
+        assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 97, None, sc, ws, big, None) == B.ERR_SHAPE
+        assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 8, None, sc, None, 0, None) == B.ERR_WORKSPACE
+        assert lib.citrus_cache_score(C.byref(e), fake(), 8, fake(), 8, None, sc, ws, 16, None) == B.ERR_WORKSPACE
+    # a given normaliser makes the workspace unnecessary; a cache-only normaliser needs a cache
+    assert lib.citrus_cache_score(C.byref(c), null, 8, fake(), 8, C.c_void_p(0x7000), sc, None, 0, None) == B.ERR_NULL
+    assert lib.citrus_chunk_attn(C.byref(c), fake(), fake(), fake(), 0, fake(), fake(), 8, fake(), None, C.c_void_p(0x7000),
+                                 None, None, 0, None) == B.ERR_SHAPE
     # evict_cache: rows as above, k within the budget, destinations distinct from the sources
     ev = lambda cc, rows=8, n=40, k=16, kn=fake(0x9000), vn=fake(0xA000), w=ws, wb=big: lib.citrus_evict_cache(
         C.byref(cc), fake(), rows, fake(0x5000), fake(0x6000), n, k, kn, vn, None, w, wb, None)

@@ -163,6 +163,8 @@ SHAPES = [
     ("bf16", 1, 1, 2, 1, 128, 1, 300, 1, 1.0),
     ("bf16", 1, 2, 8, 2, 128, 45, 83, 37, 0.3),
     ("bf16", 1, 1, 8, 2, 128, 200, 1150, 40, 0.09),
+    ("bf16", 1, 2, 8, 2, 128, 300, 1280, 16, 0.09),
+    ("bf16", 2, 1, 4, 1, 128, 45, 96, 8, 0.5),
 ]
 
 
@@ -216,6 +218,25 @@ def test_cache_score_parity(shape):
         np.testing.assert_allclose(got.sum(-1), rows * (Hq // Hkv), rtol=2e-3 if dtype == "bf16" else 1e-5)
         again = api.citrus_cache_score(cfg, x["q"], x["kc"], n_c, workspace=ws, rows=rows)
         assert torch.equal(score, again)
+    # the normaliser over the cache as a by-product of the chunk's attention (aligned caches: the same
+    # launch; others: a pass of its own), and the single-pass score that takes it
+    lse_c = torch.empty((B, L, Hq, c), dtype=torch.float32, device=DEV)
+    kch, vch = rand((B, L, Hkv, c, d), tdt(dtype), 251, s), rand((B, L, Hkv, c, d), tdt(dtype), 252)
+    out_a = api.citrus_chunk_attn(cfg, x["q"], x["kc"], x["vc"], n_c, kch, vch, lse_cache=lse_c)
+    out_b = api.citrus_chunk_attn(cfg, x["q"], x["kc"], x["vc"], n_c, kch, vch)
+    assert torch.equal(out_a, out_b)
+    one_pass = api.citrus_cache_score(cfg, x["q"], x["kc"], n_c, lse_cache=lse_c)
+    torch.cuda.synchronize()
+    from scipy.special import logsumexp
+    scale = 1.0 / np.sqrt(d)
+    for b in range(B):
+        for l in range(L):
+            ref = orc.instr_score(np64(x["q"][b, l]), np64(x["kc"][b, l, :, :n_c]))
+            assert_close(np64(one_pass[b, l]), ref, dtype, f"single-pass cache score b{b} l{l}")
+            kc64, q64 = np64(x["kc"][b, l, :, :n_c]), np64(x["q"][b, l])
+            lse_ref = np.stack([logsumexp(q64[h] @ kc64[h // (Hq // Hkv)].T * scale, axis=1) for h in range(Hq)])
+            np.testing.assert_allclose(np64(lse_c[b, l]), lse_ref, rtol=1e-2 if dtype == "bf16" else 1e-5,
+                                       atol=2e-2 if dtype == "bf16" else 1e-5)
     # a configuration without such a cache has workspace for instr_len rows only
     plain = make_cfg(dtype, B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, c=c, k=n_c + 3, n_i=n_i)
     ws_plain = api.alloc_workspace(plain)
