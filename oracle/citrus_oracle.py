@@ -31,6 +31,11 @@ What each function follows in the paper:
   paragraph describes): Eq. (1) over the cache states alone, Eq. (2)-(3).
 * ``standard_cse``: the Standard CSE process of Section 4.1 on its own (one
   cache, evicted by the document chunks), ending with that extra eviction.
+* ``rope`` and ``position_shift`` in ``process_document``: the position shift
+  mechanism of Section 5.3 ("Hyperparameters"): the cache always uses the same
+  positional embeddings, i.e. a state's position is its slot in the cache, not
+  its place in the document.  Keys are kept without rotary embedding and are
+  rotated by their slot index whenever they are attended to.
 * ``decode_step``: one step of generating the response from the retained
   states (Section 4.3): the new token's state joins the cache and its query
   attends over all of it, the same softmax attention as in Eq. (1).
@@ -114,6 +119,24 @@ def _causal_valid(c: int, n_c: int, n: int) -> np.ndarray:
     j = np.arange(n)[None, :]
     t = np.arange(c)[:, None]
     return j <= (n_c + t)
+
+
+def rope(x, positions, base: float = 10000.0) -> np.ndarray:
+    """Rotary position embedding in the convention of the Llama / Mistral
+    models the paper runs (pairs (i, i + d/2); angle = position * base^(-2i/d)).
+
+    x [H, S, d]; positions [S] (any integers or floats).  Returns the rotated
+    array: y_i = x_i cos - x_{i+d/2} sin,  y_{i+d/2} = x_{i+d/2} cos + x_i sin.
+    """
+    x = _f64(x)
+    h, s_len, d = x.shape
+    half = d // 2
+    pos = np.asarray(positions, dtype=np.float64).reshape(s_len)
+    inv_freq = base ** (-np.arange(half, dtype=np.float64) * 2.0 / d)
+    ang = pos[:, None] * inv_freq[None, :]               # [S, d/2]
+    cos, sin = np.cos(ang)[None], np.sin(ang)[None]
+    lo, hi = x[..., :half], x[..., half:]
+    return np.concatenate([lo * cos - hi * sin, hi * cos + lo * sin], axis=-1)
 
 
 def chunk_attn(q, k_cat, v_cat, n_c: int, scale: Optional[float] = None):
@@ -262,7 +285,8 @@ def process_document(q, k, v, q_instr: Sequence[np.ndarray], chunk_len: int, bud
                      forced_idx_lm: Optional[Sequence[np.ndarray]] = None,
                      keep_trace: bool = True, start_size: int = 0,
                      lm_ordering: int = LM_SCORE_AFTER_APPEND,
-                     score_mode: int = SCORE_PER_STEP) -> DocumentResult:
+                     score_mode: int = SCORE_PER_STEP,
+                     position_shift: bool = False, rope_base: float = 10000.0) -> DocumentResult:
     """The chunk loop for one (document, layer).
 
     q [Hq, T, d]; k, v [Hkv, T, d]; q_instr: one [Hq, n_i, d] array per chunk
@@ -297,6 +321,11 @@ def process_document(q, k, v, q_instr: Sequence[np.ndarray], chunk_len: int, bud
     scores it has received from the instruction in every step since it entered
     the cache (a new state starts at its first score); the k largest sums stay
     and carry their sums on.  Only the instruction-scored cache uses it.
+    ``position_shift`` (INSTR / SHARED): q, k and q_instr are given WITHOUT
+    rotary embedding and positions are those of the cache (Section 5.3): in
+    every step candidate j of [cache ; chunk] is rotated to position j, chunk
+    query t to n_c + t, instruction query u to n + u (the instruction follows
+    the candidates); the cache itself keeps the unrotated keys.
     """
     q, k, v = _f64(q), _f64(k), _f64(v)
     hq, t_total, d = q.shape
@@ -356,10 +385,18 @@ def process_document(q, k, v, q_instr: Sequence[np.ndarray], chunk_len: int, bud
                 kc_lm, vc_lm = kv_compact(k_cat_lm, v_cat_lm, idx_lm)
                 pos_lm = np.stack([pos_cat_lm[g][idx_lm[g % idx_lm.shape[0]]] for g in range(hkv)])
             tr_lm = dict(n_c_lm=n_c_lm, score_lm=s_lm, idx_lm=idx_lm)
+        elif position_shift:
+            n = n_c + c
+            k_att = rope(k_cat, np.arange(n), rope_base)
+            out, lse, _ = chunk_attn(rope(qs, n_c + np.arange(c), rope_base), k_att, v_cat, n_c, scale)
         else:
             out, lse, _ = chunk_attn(qs, k_cat, v_cat, n_c, scale)
 
-        s_in = instr_score(q_instr[i], k_cat, scale)
+        if position_shift:
+            assert not dual, "position shift is defined here for the single-cache designs"
+            s_in = instr_score(rope(q_instr[i], n + np.arange(np.asarray(q_instr[i]).shape[1]), rope_base), k_att, scale)
+        else:
+            s_in = instr_score(q_instr[i], k_cat, scale)
         if score_mode == SCORE_ACCUMULATED:
             s_in = s_in + np.concatenate([acc, np.zeros((hkv, c))], axis=1)
         idx = (np.asarray(forced_idx[i]) if forced_idx is not None

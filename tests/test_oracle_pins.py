@@ -757,3 +757,101 @@ def test_accumulated_scores_invariants():
         n = min(t, (i + 1) * chunk)
         want[:, :n] += orc.instr_score(qi[i], k[:, :n])
     np.testing.assert_allclose(res.acc_score, want, atol=1e-10)
+
+
+# ----------------------------------------------------------------------------
+# rotary embedding at cache positions (position shift)
+# ----------------------------------------------------------------------------
+
+def test_rope_worked_examples_and_properties():
+    # d = 2: one pair, frequency 1: a plane rotation by `position` radians
+    x = np.array([[[1.0, 0.0], [0.0, 2.0], [3.0, 4.0]]])
+    y = orc.rope(x, [0, math.pi / 2, 1.0])
+    np.testing.assert_allclose(y[0, 0], [1.0, 0.0], atol=1e-15)                     # position 0: untouched
+    np.testing.assert_allclose(y[0, 1], [-2.0, 0.0], atol=1e-12)                    # quarter turn of (0, 2)
+    np.testing.assert_allclose(y[0, 2], [3 * math.cos(1) - 4 * math.sin(1), 4 * math.cos(1) + 3 * math.sin(1)], atol=1e-12)
+    # d = 4, base 100: pairs (0, 2) and (1, 3) with frequencies 1 and 100^(-1/2) = 0.1
+    x = np.array([[[1.0, 1.0, 0.0, 0.0]]])
+    y = orc.rope(x, [5], base=100.0)
+    np.testing.assert_allclose(y[0, 0], [math.cos(5), math.cos(0.5), math.sin(5), math.sin(0.5)], atol=1e-12)
+    # norms are kept, and q.k depends on the distance of the two positions only
+    r = rng(171)
+    q, k = r.normal(size=(2, 7, 16)), r.normal(size=(2, 7, 16))
+    pos = np.array([0, 3, 4, 10, 11, 50, 700])
+    np.testing.assert_allclose(np.linalg.norm(orc.rope(q, pos), axis=-1), np.linalg.norm(q, axis=-1), atol=1e-12)
+    a = np.einsum("hsd,htd->hst", orc.rope(q, pos), orc.rope(k, pos))
+    b = np.einsum("hsd,htd->hst", orc.rope(q, pos + 123), orc.rope(k, pos + 123))
+    np.testing.assert_allclose(a, b, atol=1e-10)
+    # the same rotation written the way the model code writes it (cos/sin tables and a rotate-half), in torch
+    t = torch.from_numpy(q)
+    inv = 1.0 / (10000.0 ** (torch.arange(0, 16, 2, dtype=torch.float64) / 16))
+    ang = torch.from_numpy(pos.astype(np.float64))[:, None] * inv[None, :]
+    emb = torch.cat([ang, ang], dim=-1)
+    rot = torch.cat([-t[..., 8:], t[..., :8]], dim=-1)
+    np.testing.assert_allclose(orc.rope(q, pos), (t * emb.cos() + rot * emb.sin()).numpy(), atol=1e-12)
+
+
+def _rot_by_hand(x, pos, base):
+    d = len(x)
+    y = [0.0] * d
+    for i in range(d // 2):
+        a = pos * base ** (-2.0 * i / d)
+        y[i] = x[i] * math.cos(a) - x[i + d // 2] * math.sin(a)
+        y[i + d // 2] = x[i + d // 2] * math.cos(a) + x[i] * math.sin(a)
+    return y
+
+
+def _position_shift_by_hand(q, k, v, q_instr, chunk, budget, base):
+    """ONE head, plain loops: the cache holds unrotated keys; whenever a candidate is attended to it is rotated
+    to its place in [cache ; chunk], a chunk token to the place of its own state, an instruction token to the
+    places behind all candidates.  Returns (outputs, final cache positions)."""
+    t_total, d = q.shape
+    cache, outs, step = [], np.zeros((t_total, v.shape[1])), 0
+    for lo in range(0, t_total, chunk):
+        hi = min(t_total, lo + chunk)
+        cand = cache + list(range(lo, hi))
+        krot = [_rot_by_hand(k[j], slot, base) for slot, j in enumerate(cand)]
+        for t in range(lo, hi):
+            seen = len(cache) + (t - lo) + 1
+            qr = _rot_by_hand(q[t], len(cache) + (t - lo), base)
+            logit = [sum(qr[x] * krot[a][x] for x in range(d)) / math.sqrt(d) for a in range(seen)]
+            mx = max(logit)
+            w = [math.exp(a - mx) for a in logit]
+            z = sum(w)
+            for x in range(v.shape[1]):
+                outs[t][x] = sum(w[a] * v[cand[a]][x] for a in range(seen)) / z
+        imp = [0.0] * len(cand)
+        for u, qt in enumerate(q_instr[step]):
+            qr = _rot_by_hand(qt, len(cand) + u, base)
+            logit = [sum(qr[x] * krot[a][x] for x in range(d)) / math.sqrt(d) for a in range(len(cand))]
+            mx = max(logit)
+            w = [math.exp(a - mx) for a in logit]
+            z = sum(w)
+            for a in range(len(cand)):
+                imp[a] += w[a] / z
+        keep = sorted(sorted(range(len(cand)), key=lambda a: (-imp[a], a))[:budget])
+        cache = [cand[a] for a in keep]
+        step += 1
+    return outs, cache
+
+
+def test_position_shift_vs_hand_written_loop():
+    hq, hkv, t, d, chunk, budget = 1, 1, 33, 4, 5, 8
+    q, k, v, qi = _doc(172, hq, hkv, t, d, 3, chunk)
+    res = orc.process_document(q, k, v, qi, chunk, budget, position_shift=True, rope_base=50.0)
+    outs, cache = _position_shift_by_hand(q[0], k[0], v[0], [x[0] for x in qi], chunk, budget, 50.0)
+    np.testing.assert_allclose(np.concatenate([tr.out for tr in res.trace], axis=1)[0], outs, atol=1e-12)
+    assert res.positions[0].tolist() == cache
+    np.testing.assert_array_equal(res.k_cache[0], k[0][cache])       # the cache keeps the unrotated keys
+    # positions matter: without the shift the same tensors give another result
+    plain = orc.process_document(q, k, v, qi, chunk, budget)
+    assert not np.allclose(np.concatenate([tr.out for tr in plain.trace], axis=1)[0], outs)
+
+
+def test_position_shift_without_eviction_is_rope_at_document_positions():
+    hq, hkv, t, d, chunk = 4, 2, 29, 8, 6
+    q, k, v, qi = _doc(173, hq, hkv, t, d, 2, chunk)
+    res = orc.process_document(q, k, v, qi, chunk, budget=64, position_shift=True)
+    out = np.concatenate([tr.out for tr in res.trace], axis=1)
+    pos = np.arange(t)
+    np.testing.assert_allclose(out, _sdpa(orc.rope(q, pos), orc.rope(k, pos), v, causal=True, group=2), atol=1e-12)
