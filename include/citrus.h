@@ -58,7 +58,7 @@
 extern "C" {
 #endif
 
-#define CITRUS_ABI_VERSION 7
+#define CITRUS_ABI_VERSION 8
 #define CITRUS_EVENTS_PER_STEP 8
 
 typedef enum {
@@ -131,6 +131,10 @@ typedef struct {
   int32_t lm_ordering;    /* citrus_lm_ordering (DUAL, STANDARD); EVICT_THEN_APPEND needs cache_capacity >=
                              budget_lm + chunk_len (DUAL) or budget + chunk_len (STANDARD)             */
   int32_t score_mode;     /* citrus_score_mode                                   */
+  int32_t position_shift; /* 0 / 1: the position shift of Section 5.3 in the chunk loop (INSTR / SHARED): the
+                             provider hands over q, k and q_instr WITHOUT rotary embedding and every step
+                             rotates them to the positions of the cache (see citrus_rope)              */
+  float rope_base;        /* base of the rotary frequencies; 0 -> 10000                                */
   float softmax_scale;    /* 0 -> 1/sqrt(head_dim), the scaling of Eq. (1)       */
 } citrus_config;
 
@@ -238,6 +242,23 @@ int32_t citrus_evict_cache(const citrus_config* cfg, citrus_tensor q, int32_t ro
                            citrus_tensor v_cache, int32_t cache_len, int32_t k, citrus_tensor k_new,
                            citrus_tensor v_new, int32_t* idx, void* workspace, size_t workspace_bytes,
                            void* hip_stream);
+
+/*
+ * Rotary position embedding at explicit positions (the position shift mechanism of Section 5.3,
+ * "Hyperparameters": the cache always uses the same positional embeddings, so a state's position is its
+ * slot in the cache and not its place in the document).  Convention of the Llama / Mistral models:
+ * pairs (i, i + d/2), angle a = (pos0 + s) * rope_base^(-2 i / d):
+ *   y[b,l,h,s,i]       = x[b,l,h,s,i] cos a - x[b,l,h,s,i+d/2] sin a
+ *   y[b,l,h,s,i+d/2]   = x[b,l,h,s,i+d/2] cos a + x[b,l,h,s,i] sin a        for h < heads, s < rows
+ * x, y  [B, L, heads, >= rows, d]; y may be x itself (in place) but must not overlap it otherwise
+ * heads 1 .. 65535;  rows >= 0;  pos0 >= 0
+ * bf16: f32 arithmetic, result rounded to bf16; f32: angles and products in f64.
+ * With cfg->position_shift the chunk loop applies it, every step, to the candidates [cache ; chunk]
+ * (position = index j), to the chunk's queries (cache_len + t) and to the instruction's queries
+ * (cache_len + chunk_len + u); the caches keep the unrotated keys.
+ */
+int32_t citrus_rope(const citrus_config* cfg, citrus_tensor x, int32_t heads, int32_t rows, int32_t pos0,
+                    citrus_tensor y, void* hip_stream);
 
 /*
  * One decoding step of the response over the retained states (Section 4.3: the k states left by the last
@@ -356,6 +377,11 @@ int32_t citrus_resident_provider(void* user, int32_t chunk_index, void* hip_stre
  *                    kept positions of the LM cache (not the appended chunk rows).
  *   INSTR / SHARED with score_mode = ACCUMULATED: score_accumulate between
  *                    instr_score and topk_select, score_gather next to kv_compact.
+ *   INSTR / SHARED with position_shift: before these, rope of the cache keys
+ *                    (position 0 ..), the chunk keys and queries (cache_len ..)
+ *                    and the instruction queries (cache_len + chunk_len ..) into
+ *                    the workspace; attention and scores read the rotated
+ *                    copies, kv_compact gathers the unrotated keys.
  *   STANDARD:        the language-modelling steps of DUAL (in either ordering) on
  *                    the only cache pair with budget `budget`; io.q_instr is not
  *                    read and may be NULL; idx_history holds its selections.

@@ -30,7 +30,7 @@ OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE, ERR_PROVIDE
 
 EXPORTS = (
     "citrus_abi_version", "citrus_status_string", "citrus_workspace_bytes", "citrus_chunk_attn",
-    "citrus_instr_score", "citrus_cache_score", "citrus_evict_cache", "citrus_decode_step", "citrus_score_accumulate", "citrus_score_gather", "citrus_topk_select", "citrus_kv_compact", "citrus_resident_provider",
+    "citrus_instr_score", "citrus_cache_score", "citrus_evict_cache", "citrus_decode_step", "citrus_rope", "citrus_score_accumulate", "citrus_score_gather", "citrus_topk_select", "citrus_kv_compact", "citrus_resident_provider",
     "citrus_process_document",
 )
 
@@ -45,7 +45,8 @@ class CitrusError(RuntimeError):
 class CConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "batch", "layers", "q_heads", "kv_heads", "head_dim", "chunk_len", "budget", "budget_lm", "instr_len",
-        "cache_capacity", "dtype", "cache_mode", "select_mode", "start_size", "lm_ordering", "score_mode")] + [("softmax_scale", C.c_float)]
+        "cache_capacity", "dtype", "cache_mode", "select_mode", "start_size", "lm_ordering", "score_mode", "position_shift")] + [
+            ("rope_base", C.c_float), ("softmax_scale", C.c_float)]
 
 
 class CTensor(C.Structure):
@@ -94,6 +95,8 @@ def _lib():
     lib.citrus_evict_cache.argtypes = [P(CConfig), CTensor, I, CTensor, CTensor, I, I, CTensor, CTensor, V, V, S, V]
     lib.citrus_decode_step.restype = I
     lib.citrus_decode_step.argtypes = [P(CConfig), CTensor, CTensor, CTensor, CTensor, CTensor, I, CTensor, V, S, V]
+    lib.citrus_rope.restype = I
+    lib.citrus_rope.argtypes = [P(CConfig), CTensor, I, I, I, CTensor, V]
     lib.citrus_score_accumulate.restype = I
     lib.citrus_score_accumulate.argtypes = [P(CConfig), V, I, V, I, V]
     lib.citrus_score_gather.restype = I
@@ -130,6 +133,8 @@ class Config:
     start_size: int = 0              # leading document states that are never evicted
     lm_ordering: int = LM_SCORE_AFTER_APPEND
     score_mode: int = SCORE_PER_STEP
+    position_shift: int = 0          # 1: inputs come without rotary embedding, positions are cache slots
+    rope_base: float = 0.0           # 0 -> 10000
 
     def __post_init__(self):
         if self.cache_capacity == 0:
@@ -145,7 +150,8 @@ class Config:
     def c(self) -> CConfig:
         return CConfig(self.batch, self.layers, self.q_heads, self.kv_heads, self.head_dim, self.chunk_len,
                        self.budget, self.budget_lm, self.instr_len, self.cache_capacity, self.dtype,
-                       self.cache_mode, self.select_mode, self.start_size, self.lm_ordering, self.score_mode, self.softmax_scale)
+                       self.cache_mode, self.select_mode, self.start_size, self.lm_ordering, self.score_mode, self.position_shift, self.rope_base,
+                       self.softmax_scale)
 
     @property
     def torch_dtype(self) -> torch.dtype:
@@ -161,7 +167,8 @@ class Config:
                   chunk_len=w.chunk_len, budget=w.budget, instr_len=w.instr_len,
                   dtype=F32 if w.dtype == "f32" else BF16, cache_mode=w.cache_mode, select_mode=w.select_mode,
                   budget_lm=w.budget_lm, start_size=getattr(w, "start_size", 0),
-                  lm_ordering=getattr(w, "lm_ordering", 0), score_mode=getattr(w, "score_mode", 0))
+                  lm_ordering=getattr(w, "lm_ordering", 0), score_mode=getattr(w, "score_mode", 0),
+                  position_shift=getattr(w, "position_shift", 0), rope_base=getattr(w, "rope_base", 0.0))
         kw.update(overrides)
         return Config(**kw)
 
@@ -273,6 +280,17 @@ def citrus_decode_step(cfg: Config, q, k_new, v_new, k_cache, v_cache, cache_len
                                    0 if workspace is None else workspace.numel(), _stream(stream))
     _check(st, "citrus_decode_step")
     return out
+
+
+def citrus_rope(cfg: Config, x, pos0: int, y=None, stream=None, rows: Optional[int] = None):
+    """Rotary embedding of x [B, L, H, rows, d] at positions pos0, pos0 + 1, ...; y=x rotates in place."""
+    rows = x.shape[3] if rows is None else rows
+    if y is None:
+        y = torch.empty_like(x)
+    cc = cfg.c()
+    st = _lib().citrus_rope(C.byref(cc), tensor(x), x.shape[2], rows, pos0, tensor(y), _stream(stream))
+    _check(st, "citrus_rope")
+    return y
 
 
 def citrus_score_accumulate(cfg: Config, score, acc, cache_len: int, stream=None, n: Optional[int] = None):

@@ -18,6 +18,7 @@
 // reductions are in-lane plus one exchange with lane l ^ 32, and the S^T
 // accumulators are directly the B operand (P^T) of the second product.
 #include "citrus_internal.h"
+#include "rope_math.h"
 
 
 namespace citrus {
@@ -433,10 +434,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
 // half tile h, so that inside ONE wave the matrix pipe, the vector pipe and the LDS reads run at
 // the same time instead of taking turns (the scheduler is told the order with group directives).
 // K tiles are fetched one 64-key tile further ahead than V tiles; one barrier per 64 keys.
-template <int WAVES>
+template <int WAVES, bool ROTATE_Q>
 __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, int rows, const Segments& ks,
                                                const Segments& vs, int causal, const View& out, float* lse,
-                                               float* lse_cache) {
+                                               float* lse_cache, int q_rope_pos0, float rope_log2_base) {
   constexpr bool HAS_PV = true;
   constexpr int key_splits = 1;
   float2* const part = nullptr;
@@ -773,6 +774,29 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
   fetch_k(t_begin);
   fetch_v(t_begin);
   if (t_begin + 1 < t_end) fetch_k(t_begin + 1);
+  // Position shift: the query rows arrive without rotary embedding and are rotated here, in
+  // registers, to position q_rope_pos0 + row, after the first tiles have been requested: the wait for
+  // the query rows then overlaps with the arrival of the tiles instead of preceding their request.  Element 16 kk + 8 grp + j (kk < 4) and its partner
+  // 64 further on sit in the same lane, in q_op[kk] and q_op[kk + 4].
+  if (ROTATE_Q) {
+    const int pos = q_rope_pos0 + t_lane;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      Pack8 lo, hi;
+      lo.v = q_op[kk];
+      hi.v = q_op[kk + 4];
+#pragma unroll
+      for (int wd = 0; wd < 4; ++wd) {
+        const int i0 = 16 * kk + 8 * grp + 2 * wd;
+        float s0, c0, s1, c1;
+        rope_sincos_bf16(pos, i0, D, rope_log2_base, s0, c0);
+        rope_sincos_bf16(pos, i0 + 1, D, rope_log2_base, s1, c1);
+        rope_rotate_words(lo.w[wd], hi.w[wd], c0, s0, c1, s1, lo.w[wd], hi.w[wd]);
+      }
+      q_op[kk] = lo.v;
+      q_op[kk + 4] = hi.v;
+    }
+  }
   barrier_after_lds_fill();  // also: the Q operand loads have landed
   read_k_ops(h_first);
 #pragma unroll
@@ -855,7 +879,15 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
 // against four waves; one workgroup per CU, two waves per SIMD.
 __global__ __launch_bounds__(512, 1) void attn_pipe_kernel_w8(Dims dm, View q, int rows, Segments ks, Segments vs,
                                                              int causal, View out, float* lse, float* lse_cache) {
-  attn_pipe_body<8>(dm, q, rows, ks, vs, causal, out, lse, lse_cache);
+  attn_pipe_body<8, false>(dm, q, rows, ks, vs, causal, out, lse, lse_cache, -1, 0.f);
+}
+// The same kernel for query rows that arrive without rotary embedding (position shift): they are rotated
+// in registers right after they are loaded.  An instance of its own, so that the register allocation of
+// the kernel above is not touched by the extra prologue.
+__global__ __launch_bounds__(512, 1) void attn_pipe_kernel_w8_rotq(Dims dm, View q, int rows, Segments ks, Segments vs,
+                                                                  int causal, View out, float* lse, float* lse_cache,
+                                                                  int q_rope_pos0, float rope_log2_base) {
+  attn_pipe_body<8, true>(dm, q, rows, ks, vs, causal, out, lse, lse_cache, q_rope_pos0, rope_log2_base);
 }
 
 // Summed form of Eq. (1): score[g, j] = sum over the query rows of the KV group of
@@ -1220,8 +1252,10 @@ bool attn_mfma_emits_cache_lse(const Segments& ks, int causal, View out) {
 }
 
 hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments ks, Segments vs, int causal, View out,
-                            float* lse, float* lse_cache, int key_splits, float2* part, hipStream_t st) {
+                            float* lse, float* lse_cache, int key_splits, float2* part, hipStream_t st,
+                            int q_rope_pos0, float rope_base) {
   if (lse_cache != nullptr && !attn_mfma_emits_cache_lse(ks, causal, out)) return hipErrorInvalidValue;
+  if (q_rope_pos0 >= 0 && out.ptr == nullptr) return hipErrorInvalidValue;  // only the kernel with output rotates
   if (!fits_i32(ks.cache, ks.n_c) || !fits_i32(ks.chunk, ks.c) || !fits_i32(vs.cache, vs.n_c) ||
       !fits_i32(vs.chunk, vs.c))
     return hipErrorInvalidValue;
@@ -1233,7 +1267,10 @@ hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments ks, Segme
   const int row_blocks = (rows + rows_per_block - 1) / rows_per_block;
   const int rb_slots = (causal && key_splits == 1) ? (row_blocks + 1) / 2 : row_blocks;  // paired row blocks
   dim3 grid(rb_slots * (dm.G / ts.heads_per_block) * dm.Hkv * dm.B * dm.L * key_splits);
-  if (pipe)
+  if (pipe && q_rope_pos0 >= 0)
+    hipLaunchKernelGGL(attn_pipe_kernel_w8_rotq, grid, dim3(kPipeWaves * 64), 0, st, dm, q, rows, ks, vs, causal, out, lse,
+                       lse_cache, q_rope_pos0, log2f(rope_base));
+  else if (pipe)
     hipLaunchKernelGGL(attn_pipe_kernel_w8, grid, dim3(kPipeWaves * 64), 0, st, dm, q, rows, ks, vs, causal, out, lse,
                        lse_cache);
   else

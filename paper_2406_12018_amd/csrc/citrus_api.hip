@@ -46,6 +46,11 @@ citrus_status check_config(const citrus_config* c) {
   if (c->score_mode == CITRUS_SCORE_ACCUMULATED && c->cache_mode != CITRUS_CACHE_INSTR &&
       c->cache_mode != CITRUS_CACHE_SHARED)
     return CITRUS_ERR_UNSUPPORTED;
+  if (c->position_shift != 0 && c->position_shift != 1) return CITRUS_ERR_UNSUPPORTED;
+  if (c->position_shift && c->cache_mode != CITRUS_CACHE_INSTR && c->cache_mode != CITRUS_CACHE_SHARED)
+    return CITRUS_ERR_UNSUPPORTED;
+  if (!(c->rope_base >= 0.0f) || isinf(c->rope_base) || (c->rope_base > 0.0f && c->rope_base < 1.0f))
+    return CITRUS_ERR_SHAPE;
   return CITRUS_OK;
 }
 
@@ -56,6 +61,8 @@ Dims dims_of(const citrus_config* c) {
   d.scale = c->softmax_scale > 0.0f ? c->softmax_scale : 1.0f / sqrtf(static_cast<float>(c->head_dim));
   return d;
 }
+
+float rope_base_of(const citrus_config* c) { return c->rope_base > 0.0f ? c->rope_base : 10000.0f; }
 
 // 16-byte row alignment: pointer and every stride.
 citrus_status check_tensor(const citrus_tensor& t, int dtype, bool may_be_null) {
@@ -81,7 +88,7 @@ citrus_status check_lengths(const citrus_config* c, int cache_len, int chunk_len
 
 // Workspace layout (all blocks kAlign-aligned).
 struct Workspace {
-  size_t lse_chunk, lse_instr, lse_cache, score, score_lm, idx, idx_lm, iota, decode, total;
+  size_t lse_chunk, lse_instr, lse_cache, score, score_lm, idx, idx_lm, iota, decode, k_rot, q_rot, qi_rot, total;
 };
 
 // A cache evicted by the document's own chunks exists (DUAL's second cache, or the only one of STANDARD)
@@ -110,6 +117,11 @@ Workspace workspace_layout(const citrus_config* c) {
     const Dims dm = dims_of(c);
     w.decode = off;  off += decode_mfma_supported(c->dtype, dm) ? align_up(decode_mfma_workspace_floats(dm) * sizeof(float)) : 0;
   }
+  // position shift: rotated copies of the candidates' keys, the chunk's and the instruction's queries
+  const size_t esz = static_cast<size_t>(elem_bytes(c->dtype)) * c->head_dim;
+  w.k_rot = off;   off += c->position_shift ? align_up(units_kv * n_max * esz) : 0;
+  w.q_rot = off;   off += c->position_shift ? align_up(units_q * c->chunk_len * esz) : 0;
+  w.qi_rot = off;  off += c->position_shift ? align_up(units_q * c->instr_len * esz) : 0;
   w.total = off;
   return w;
 }
@@ -141,12 +153,18 @@ hipError_t run_colsum(const citrus_config* c, const Dims& dm, View q, int rows, 
 // lse_cache (optional, needs ks.n_c > 0): each row's log-sum-exp over the cache states alone, the
 // normaliser of Eq. (1) as printed.  A by-product of the MFMA attention kernel when the cache ends on
 // a 32-key boundary; a pass of its own over the cache otherwise.
+// q_rope_pos0 >= 0 (MFMA path only, see attn_rotates_queries): q is unrotated and the kernel rotates it.
 citrus_status do_chunk_attn(const citrus_config* c, const Dims& dm, const citrus_tensor& q, Segments ks, Segments vs,
-                            const citrus_tensor& out, float* lse, float* lm_score, float* lse_cache, hipStream_t st) {
+                            const citrus_tensor& out, float* lse, float* lm_score, float* lse_cache, hipStream_t st,
+                            int q_rope_pos0 = -1) {
   const bool mfma = mfma_path_supported(c->dtype, dm);
-  if (lse_cache != nullptr && mfma && attn_mfma_emits_cache_lse(ks, 1, make_view(out))) {
-    CITRUS_TRY(hip_status(launch_attn_mfma(dm, make_view(q), ks.c, ks, vs, /*causal=*/1, make_view(out), lse, lse_cache,
-                                           1, nullptr, st)));
+  if (q_rope_pos0 >= 0 && !mfma) return CITRUS_ERR_UNSUPPORTED;
+  const bool fused_lse = lse_cache != nullptr && mfma && attn_mfma_emits_cache_lse(ks, 1, make_view(out));
+  if (fused_lse || q_rope_pos0 >= 0) {
+    CITRUS_TRY(hip_status(launch_attn_mfma(dm, make_view(q), ks.c, ks, vs, /*causal=*/1, make_view(out), lse,
+                                           fused_lse ? lse_cache : nullptr, 1, nullptr, st, q_rope_pos0,
+                                           rope_base_of(c))));
+    if (lse_cache != nullptr && !fused_lse) return CITRUS_ERR_UNSUPPORTED;  // not combined by any caller
   } else {
     CITRUS_TRY(hip_status(run_attn(c, dm, make_view(q), ks.c, ks, vs, /*causal=*/1, make_view(out), lse, st)));
     if (lse_cache != nullptr) {
@@ -215,6 +233,17 @@ citrus_status do_compact(const citrus_config* c, const Dims& dm, Segments ks, Se
                          hipStream_t st) {
   return hip_status(launch_compact(elem_bytes(c->dtype), dm, ks, vs, idx, idx_pitch, sel_heads(c), m,
                                    make_view(k_new), make_view(v_new), st));
+}
+
+// A dense [B, L, heads, rows, d] tensor at `ptr`.
+citrus_tensor dense_tensor(void* ptr, int64_t layers, int64_t heads, int64_t rows, int64_t d) {
+  citrus_tensor t;
+  t.ptr = ptr;
+  t.stride_s = d;
+  t.stride_h = rows * d;
+  t.stride_l = heads * rows * d;
+  t.stride_b = layers * heads * rows * d;
+  return t;
 }
 
 // The same tensor starting at sequence row `row`.
@@ -352,6 +381,16 @@ int32_t citrus_evict_cache(const citrus_config* cfg, citrus_tensor q, int32_t ro
   CITRUS_TRY(do_topk(cfg, score, cache_len, k, idx, st));
   const Segments ks = cache_only(k_cache, cache_len), vs = cache_only(v_cache, cache_len);
   return do_compact(cfg, dm, ks, vs, idx, k, m, k_new, v_new, st);
+}
+
+int32_t citrus_rope(const citrus_config* cfg, citrus_tensor x, int32_t heads, int32_t rows, int32_t pos0,
+                    citrus_tensor y, void* hip_stream) {
+  CITRUS_TRY(check_config(cfg));
+  if (heads < 1 || heads > 65535 || rows < 0 || pos0 < 0) return CITRUS_ERR_SHAPE;
+  CITRUS_TRY(check_tensor(x, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(y, cfg->dtype, false));
+  return hip_status(launch_rope(cfg->dtype, dims_of(cfg), make_view(x), make_view(y), heads, rows, pos0,
+                                rope_base_of(cfg), static_cast<hipStream_t>(hip_stream)));
 }
 
 int32_t citrus_decode_step(const citrus_config* cfg, citrus_tensor q, citrus_tensor k_new, citrus_tensor v_new,
@@ -603,17 +642,47 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
     const Segments ks = segments(k_cache[cur], n_c, io.k, c), vs = segments(v_cache[cur], n_c, io.v, c);
     const int n = n_c + c;
     const int m = n < cfg->budget ? n : cfg->budget;
+    // What attention and scores read.  With the position shift: copies rotated to this step's
+    // positions (candidate j -> j, chunk query t -> n_c + t, instruction query u -> n + u); the
+    // selection still gathers the unrotated keys.
+    Segments ks_att = ks;
+    citrus_tensor q_att = io.q, qi_att = io.q_instr;
+    const int q_rope_pos0 = cfg->position_shift && mfma_path_supported(cfg->dtype, dm) ? n_c : -1;
+    if (cfg->position_shift) {
+      const float base = rope_base_of(cfg);
+      const citrus_tensor k_rot = dense_tensor(ws + wl.k_rot, cfg->layers, cfg->kv_heads, n, cfg->head_dim);
+      q_att = dense_tensor(ws + wl.q_rot, cfg->layers, cfg->q_heads, c, cfg->head_dim);
+      qi_att = dense_tensor(ws + wl.qi_rot, cfg->layers, cfg->q_heads, cfg->instr_len, cfg->head_dim);
+      const citrus_tensor k_rot_chunk = rows_from(k_rot, n_c, cfg->dtype);
+      if (n_c > 0 && (status = hip_status(launch_rope(cfg->dtype, dm, ks.cache, make_view(k_rot), cfg->kv_heads, n_c, 0,
+                                                      base, st))) != CITRUS_OK)
+        break;
+      if ((status = hip_status(launch_rope(cfg->dtype, dm, ks.chunk, make_view(k_rot_chunk), cfg->kv_heads, c, n_c, base,
+                                           st))) != CITRUS_OK)
+        break;
+      // the MFMA attention kernel rotates its query rows itself while they sit in registers
+      if (q_rope_pos0 < 0 && (status = hip_status(launch_rope(cfg->dtype, dm, make_view(io.q), make_view(q_att),
+                                                              cfg->q_heads, c, n_c, base, st))) != CITRUS_OK)
+        break;
+      if (q_rope_pos0 >= 0) q_att = io.q;
+      if ((status = hip_status(launch_rope(cfg->dtype, dm, make_view(io.q_instr), make_view(qi_att), cfg->q_heads,
+                                           cfg->instr_len, n, base, st))) != CITRUS_OK)
+        break;
+      ks_att = segments(k_rot, n_c, k_rot_chunk, c);
+    }
     if (dual) {
       int32_t* idx_lm = idx_history_lm ? idx_history_lm + static_cast<size_t>(done) * units_sel * cfg->budget_lm : idx_lm_ws;
       const ChunkEvicted t{k_cache_lm, v_cache_lm, &n_c_lm, &cur_lm, cfg->budget_lm, score_lm, idx_lm};
       if ((status = chunk_evicted_step(t, io, c)) != CITRUS_OK) break;
     } else {
-      if ((status = do_chunk_attn(cfg, dm, io.q, ks, vs, io.out, nullptr, nullptr, nullptr, st)) != CITRUS_OK) break;
+      if ((status = do_chunk_attn(cfg, dm, q_att, ks_att, vs, io.out, nullptr, nullptr, nullptr, st, q_rope_pos0)) !=
+          CITRUS_OK)
+        break;
       for (int p = 1; p <= 4; ++p) mark(done, p);
     }
 
     int32_t* idx = idx_history ? idx_history + static_cast<size_t>(done) * units_sel * cfg->budget : idx_ws;
-    if ((status = do_instr_score(cfg, dm, io.q_instr, ks, lse_instr, score, st)) != CITRUS_OK) break;
+    if ((status = do_instr_score(cfg, dm, qi_att, ks_att, lse_instr, score, st)) != CITRUS_OK) break;
     if (accumulated &&
         (status = hip_status(launch_score_add(dm, score, acc_score[cur], n, n_c, cfg->cache_capacity, st))) != CITRUS_OK)
       break;

@@ -49,8 +49,11 @@ bool mfma_path_supported(int dtype, const Dims& dm);
 // lse_cache (optional): per row, the log-sum-exp over the cache states alone, a by-product of the
 // causal kernel with output when attn_mfma_emits_cache_lse() holds (cache ends on a 32-key boundary).
 bool attn_mfma_emits_cache_lse(const Segments& kseg, int causal, View out);
+// q_rope_pos0 >= 0 (kernel with output only): the query rows are given without rotary embedding and are
+// rotated to positions q_rope_pos0 + row inside the kernel, with the bits launch_rope would give.
 hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments kseg, Segments vseg, int causal, View out,
-                            float* lse, float* lse_cache, int key_splits, float2* part, hipStream_t st);
+                            float* lse, float* lse_cache, int key_splits, float2* part, hipStream_t st,
+                            int q_rope_pos0 = -1, float rope_base = 0.f);
 // normaliser per row from lse (natural log) or, if part != NULL, merged from key_splits partial pairs
 hipError_t launch_colsum_mfma(const Dims& dm, View q, int rows, Segments kseg, int causal, const float* lse,
                               int key_splits, const float2* part, float* score, hipStream_t st);
@@ -66,6 +69,11 @@ size_t decode_mfma_workspace_floats(const Dims& dm);
 // also written to row kseg.n_c of the cache tensors (which must have room for it).
 hipError_t launch_decode_mfma(const Dims& dm, View q, Segments kseg, Segments vseg, View out, float* workspace,
                               int append_token, hipStream_t st);
+
+// ---- rotary embedding at explicit positions, rope.hip ----
+// y[b,l,h,s,:] = RoPE(x[b,l,h,s,:], pos0 + s) for h < heads, s < rows; y may be x itself.
+hipError_t launch_rope(int dtype, const Dims& dm, View x, View y, int heads, int rows, int pos0, float base,
+                       hipStream_t st);
 
 // ---- selection and compaction, select_compact.hip ----
 // units = B*L*Hsel; score rows are [units*(per_layer?Hkv:1)] x n.

@@ -130,6 +130,17 @@ class StepwiseRun:
             return rec
         kc, vc = st.k_cache[st.buffer_index], st.v_cache[st.buffer_index]
         n = st.cache_len + c
+        # what attention and scores read: with the position shift, copies rotated to this step's positions
+        q_att, qi_att, kc_att, k_att = q, q_instr, kc, k
+        if cfg.position_shift:
+            n_c = st.cache_len
+            k_rot = torch.empty((cfg.batch, cfg.layers, cfg.kv_heads, n, cfg.head_dim), dtype=q.dtype, device=q.device)
+            if n_c > 0:
+                api.citrus_rope(cfg, kc, 0, y=k_rot, rows=n_c)
+            api.citrus_rope(cfg, k, n_c, y=k_rot[:, :, :, n_c:])
+            q_att = api.citrus_rope(cfg, q, n_c)
+            qi_att = api.citrus_rope(cfg, q_instr, n)
+            kc_att, k_att = k_rot, k_rot[:, :, :, n_c:]
         if dual:
             r = self._chunk_evicted_step(q, k, v, st.k_cache_lm, st.v_cache_lm, st.cache_len_lm, st.buffer_index_lm,
                                          cfg.budget_lm)
@@ -139,9 +150,9 @@ class StepwiseRun:
             st.cache_len_lm = r["new_len"]
         else:
             lse = torch.empty((cfg.batch, cfg.layers, cfg.q_heads, c), dtype=torch.float32, device=q.device)
-            out = api.citrus_chunk_attn(cfg, q, kc, vc, st.cache_len, k, v, lse=lse)
+            out = api.citrus_chunk_attn(cfg, q_att, kc_att, vc, st.cache_len, k_att, v, lse=lse)
             rec["lse"] = lse
-        score = api.citrus_instr_score(cfg, q_instr, kc, st.cache_len, k, workspace=self.ws)
+        score = api.citrus_instr_score(cfg, qi_att, kc_att, st.cache_len, k_att, workspace=self.ws)
         accumulated = cfg.score_mode == api.SCORE_ACCUMULATED
         if accumulated:  # a cache state's sum so far joins this step's score
             api.citrus_score_accumulate(cfg, score, st.acc_score[st.buffer_index], st.cache_len)

@@ -24,11 +24,11 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(B.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
-    assert B.abi_version() == 7
+    assert B.abi_version() == 8
 
 
 def test_struct_layouts_match_the_header():
-    assert C.sizeof(B.CConfig) == 17 * 4
+    assert C.sizeof(B.CConfig) == 19 * 4
     assert C.sizeof(B.CTensor) == 5 * 8
     assert C.sizeof(B.CChunkIO) == 5 * 40 + 8
     assert C.sizeof(B.CResidentDoc) == 5 * 40 + 8 + 16
@@ -58,6 +58,8 @@ def test_status_strings():
     ({"cache_mode": B.CACHE_STANDARD, "lm_ordering": B.LM_EVICT_THEN_APPEND, "cache_capacity": 64}, False),
     ({"cache_mode": 4}, False), ({"score_mode": B.SCORE_ACCUMULATED}, True), ({"score_mode": 2}, False),
     ({"score_mode": B.SCORE_ACCUMULATED, "cache_mode": B.CACHE_STANDARD}, False),
+    ({"position_shift": 1}, True), ({"position_shift": 2}, False), ({"position_shift": 1, "rope_base": 0.5}, False),
+    ({"position_shift": 1, "rope_base": 1e6}, True), ({"position_shift": 1, "cache_mode": B.CACHE_STANDARD}, False),
     ({"score_mode": B.SCORE_ACCUMULATED, "cache_mode": B.CACHE_DUAL, "budget_lm": 16}, False),
 ])
 def test_workspace_bytes_validates_config(kw, ok):
@@ -151,6 +153,12 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     assert lib.citrus_score_gather(C.byref(c), p1, 8, p2, 4, 0, p3, None) == B.ERR_SHAPE
     assert lib.citrus_score_gather(C.byref(c), p1, 8, p2, 3, 4, p3, None) == B.ERR_SHAPE
     assert lib.citrus_score_gather(C.byref(c), p1, 8, p2, 80, 65, p3, None) == B.ERR_SHAPE
+    # rope: heads, rows, positions
+    assert lib.citrus_rope(C.byref(c), null, 4, 8, 0, fake(), None) == B.ERR_NULL
+    assert lib.citrus_rope(C.byref(c), fake(), 0, 8, 0, fake(), None) == B.ERR_SHAPE
+    assert lib.citrus_rope(C.byref(c), fake(), 4, -1, 0, fake(), None) == B.ERR_SHAPE
+    assert lib.citrus_rope(C.byref(c), fake(), 4, 8, -1, fake(), None) == B.ERR_SHAPE
+    assert lib.citrus_rope(C.byref(c), fake(), 4, 0, 0, fake(), None) == B.OK      # nothing to do, nothing launched
     # unsupported head_dim
     bad = cfg(head_dim=96).c()
     assert lib.citrus_topk_select(C.byref(bad), C.c_void_p(0x2000), 8, 4, C.c_void_p(0x3000), None, 0, None) == B.ERR_UNSUPPORTED

@@ -376,6 +376,12 @@ def run_document_stepwise(w: Workload, sample_units=None, check_every=1):
             vcat = np.stack([vd[g, cand[g]] for g in range(w.kv_heads)])
             n_c = pos[(b, l)].shape[1]
             assert n_c == rec["n_c"]
+            if w.position_shift:
+                # the tensors are un-rotated; every step rotates them to the positions of the cache
+                base = w.rope_base or 10000.0
+                kcat = orc.rope(kcat, np.arange(n_c + c), base)
+                qd = orc.rope(qd, n_c + np.arange(c), base)
+                qi = orc.rope(qi, n_c + c + np.arange(qi.shape[1]), base)
             idx = rec["idx"][b, l].cpu().numpy()[:, :rec["m"]]
             check = (i % check_every == 0) or i == w.n_chunks - 1
             if dual:
@@ -498,6 +504,12 @@ DOC_CASES = {
                                                      select_mode=api.SELECT_PER_LAYER),
     "cfg2_small_accumulated": scaled_down(WORKLOADS["cfg2_mistral7b"], layers=2, doc_len=2300,
                                           score_mode=api.SCORE_ACCUMULATED),
+    "cfg1_position_shift": scaled_down(peaked(WORKLOADS["cfg1_tiny_f32"]), doc_len=301, layers=2, kv_heads=2,
+                                       position_shift=1),
+    "cfg1_position_shift_accumulated_per_layer": scaled_down(
+        peaked(WORKLOADS["cfg1_tiny_f32"]), doc_len=256, layers=2, kv_heads=2, position_shift=1, rope_base=500.0,
+        score_mode=api.SCORE_ACCUMULATED, select_mode=api.SELECT_PER_LAYER, start_size=2),
+    "cfg2_small_position_shift": scaled_down(WORKLOADS["cfg2_mistral7b"], layers=2, doc_len=2300, position_shift=1),
     "cfg2_small": scaled_down(WORKLOADS["cfg2_mistral7b"], layers=2, doc_len=2560),
     "cfg2_small_start4": scaled_down(WORKLOADS["cfg2_mistral7b"], layers=2, doc_len=2560, start_size=4),
     "cfg2_small_peaked": scaled_down(peaked(WORKLOADS["cfg2_mistral7b"]), layers=1, doc_len=2000),
@@ -605,6 +617,34 @@ def test_standard_cse_document_and_final_instruction_eviction(case):
                 np.testing.assert_array_equal(bits(v_fin[b, l, g, :kept]), bits(host["v"][b, l, g][p]))
     if w.start_size:
         assert (idx_f[..., :w.start_size].cpu() == torch.arange(w.start_size)).all()
+
+
+# ----------------------------------------------------------------------------
+# rotary embedding at explicit positions
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype,B,L,H,rows,d,pos0,base", [
+    ("bf16", 1, 2, 8, 70, 128, 0, 0.0), ("bf16", 2, 1, 3, 33, 128, 777, 1e6), ("bf16", 1, 1, 32, 512, 128, 768, 0.0),
+    ("bf16", 1, 2, 2, 19, 64, 5, 500.0), ("f32", 1, 2, 4, 45, 64, 1300, 0.0), ("f32", 2, 1, 2, 7, 128, 4000, 1e6),
+])
+def test_rope_parity(dtype, B, L, H, rows, d, pos0, base):
+    say(f"rope {dtype} B{B} L{L} H{H} rows{rows} d{d} pos0 {pos0} base {base}")
+    cfg = make_cfg(dtype, B=B, L=L, Hq=H, Hkv=H, d=d, c=32, k=64, n_i=8, rope_base=base)
+    buf = rand((B, L, H, rows + 6, d), tdt(dtype), 501)
+    x = buf[:, :, :, 3:3 + rows]                     # a strided view
+    before = buf.clone()
+    y = api.citrus_rope(cfg, x, pos0)
+    torch.cuda.synchronize()
+    assert torch.equal(buf, before)
+    for b in range(B):
+        for l in range(L):
+            ref = orc.rope(np64(x[b, l]), pos0 + np.arange(rows), base or 10000.0)
+            assert_close(np64(y[b, l]), ref, dtype, f"rope b{b} l{l}")
+    # in place gives the same bits and leaves the rows around the view alone
+    api.citrus_rope(cfg, x, pos0, y=x)
+    torch.cuda.synchronize()
+    assert torch.equal(x, y)
+    assert torch.equal(buf[:, :, :, :3], before[:, :, :, :3]) and torch.equal(buf[:, :, :, 3 + rows:], before[:, :, :, 3 + rows:])
 
 
 # ----------------------------------------------------------------------------
@@ -722,7 +762,8 @@ def run_process_document(w, doc, split_at=None, use_python_provider=False):
 
 @pytest.mark.parametrize("case", ["cfg1", "cfg1_ragged", "cfg1_dual", "cfg1_dual_start4", "cfg1_dual_paper_order",
                                   "cfg1_dual_paper_order_start4_per_layer", "cfg2_small", "cfg2_small_start4",
-                                  "cfg4_small_dual", "cfg4_small_dual_paper_order", "cfg1_accumulated",
+                                  "cfg4_small_dual", "cfg4_small_dual_paper_order", "cfg1_position_shift",
+                                  "cfg1_position_shift_accumulated_per_layer", "cfg2_small_position_shift", "cfg1_accumulated",
                                   "cfg1_accumulated_per_layer_start4", "cfg2_small_accumulated", "cfg1_standard_paper_order",
                                   "cfg1_standard_after_append_per_layer_start2", "cfg2_small_standard_paper_order"])
 def test_process_document_equals_stepwise_and_resumes(case):

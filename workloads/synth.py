@@ -71,6 +71,8 @@ class Workload:
     start_size: int = 0        # leading document states that are never evicted (0 = plain selection)
     lm_ordering: int = 0       # DUAL only: 0 = score after append, 1 = evict, then append (Section 4.1's order)
     score_mode: int = 0        # 0 = this step's score decides, 1 = accumulated scores (H2O's rule)
+    position_shift: int = 0    # 1 = tensors are taken as un-rotated, positions are cache slots (Section 5.3)
+    rope_base: float = 0.0     # 0 -> 10000
     sink_scale: float = 4.0
     heavy_prob: float = 0.0
     heavy_scale: float = 2.5
