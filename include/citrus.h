@@ -413,7 +413,9 @@ int32_t citrus_resident_provider(void* user, int32_t chunk_index, void* hip_stre
  *                 attention, 2 after the chunk-scored importance, 3 after the
  *                 LM selection, 4 after the LM compaction (2..4 coincide with 1
  *                 unless DUAL), 5 after the instruction score, 6 after the
- *                 selection, 7 after the compaction.  For per-phase timing only.
+ *                 selection, 7 after the compaction.  A NULL entry is skipped (every
+ *                 recorded event costs a few microseconds of stream time).  For
+ *                 per-phase timing only.
  * No host/device synchronisation happens inside the loop.
  */
 int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider next, void* user,

@@ -559,7 +559,7 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
   int done = 0;
   citrus_status status = CITRUS_OK;
   auto mark = [&](int step, int phase) {
-    if (phase_events != nullptr)
+    if (phase_events != nullptr && phase_events[step * CITRUS_EVENTS_PER_STEP + phase] != nullptr)
       (void)hipEventRecord(static_cast<hipEvent_t>(phase_events[step * CITRUS_EVENTS_PER_STEP + phase]), st);
   };
 
