@@ -443,6 +443,7 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
   float2* const part = nullptr;
   __shared__ __attribute__((aligned(1024))) char k_s[2 * kTileBytes];  // double-buffered tiles
   __shared__ __attribute__((aligned(1024))) char v_s[HAS_PV ? 2 * kTileBytes : 16];
+  extern __shared__ __attribute__((aligned(1024))) char q_stage[];  // [WAVES][32 rows][256 B], dynamic
 
   const int tid = threadIdx.x, lane = tid % 64, w = tid / 64;
   const int col = lane % 32, grp = lane / 32;
@@ -567,17 +568,10 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
   const int wave_limit_min = causal ? n_c + row0 : n - 1;           // up to it every row sees everything
 
   // ---- Q^T operand, kept in registers: q_op[kk] = Q[row0 + col][16 kk + 8 grp ..+7] ----
+  // (loaded further down, behind the requests for the first tiles: a lane reads 16-byte pieces of its
+  // own row, 64 scattered pieces per instruction, which keep the address path busy for a while)
   bf16x8 q_op[8];
   const int t_lane = max(min(row0 + col, rows - 1), 0);
-  {
-    const uint16_t* qp = unit_ptr(q, b, l, h) + static_cast<int64_t>(t_lane) * q.ss + 8 * grp;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      Pack8 p;
-      p.u = *reinterpret_cast<const uint4*>(qp + 16 * kk);
-      q_op[kk] = p.v;
-    }
-  }
   const int limit_lane = causal ? n_c + t_lane : n - 1;
 
   // ---- running softmax state: one query per lane ----
@@ -774,9 +768,37 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
   fetch_k(t_begin);
   fetch_v(t_begin);
   if (t_begin + 1 < t_end) fetch_k(t_begin + 1);
+  // The wave's 32 query rows come in through LDS as well: whole 256-byte rows, four per load
+  // instruction, into the wave's own 8 KB (same swizzle as a key tile), from where the B operand is
+  // read like a key operand.  Loading them straight into the operand layout would put 64 scattered
+  // 16-byte pieces into every load instruction.
+  {
+    const int q_ss2 = static_cast<int>(q.ss) * 2;
+    const __amdgpu_buffer_rsrc_t q_rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t*>(unit_ptr(q, b, l, h)), 0, ((rows - 1) * static_cast<int>(q.ss) + D) * 2, kBufferFlags);
+    int r_in = lane / 16, pos = lane % 16;
+    hide_loop_invariance(r_in, pos);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int r = 4 * i + r_in;
+      const int f = (2 * (r % 8)) ^ ((r / 8) % 2);
+      const int row = min(row0 + r, rows - 1);  // rows past the end repeat the last one; never stored
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(q_rs, (lds_void_ptr)(q_stage + (32 * wu + 4 * i) * kRowBytes), 16,
+                                               max(row, 0) * q_ss2 + ((pos ^ f) * 16), 0, 0, 0);
+    }
+  }
+  barrier_after_lds_fill();  // also: the query rows have landed
+  {
+    const char* q_t = q_stage + 32 * wu * kRowBytes;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      Pack8 p;
+      p.u = *reinterpret_cast<const uint4*>(q_t + k_off(kk));
+      q_op[kk] = p.v;
+    }
+  }
   // Position shift: the query rows arrive without rotary embedding and are rotated here, in
-  // registers, to position q_rope_pos0 + row, after the first tiles have been requested: the wait for
-  // the query rows then overlaps with the arrival of the tiles instead of preceding their request.  Element 16 kk + 8 grp + j (kk < 4) and its partner
+  // registers, to position q_rope_pos0 + row.  Element 16 kk + 8 grp + j (kk < 4) and its partner
   // 64 further on sit in the same lane, in q_op[kk] and q_op[kk + 4].
   if (ROTATE_Q) {
     const int pos = q_rope_pos0 + t_lane;
@@ -797,7 +819,6 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
       q_op[kk + 4] = hi.v;
     }
   }
-  barrier_after_lds_fill();  // also: the Q operand loads have landed
   read_k_ops(h_first);
 #pragma unroll
   for (int i = 0; i < 16; ++i) s_cur[i] = 0.f;
@@ -854,23 +875,43 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
     part[static_cast<int64_t>(sp) * dm.B * dm.L * dm.Hq * rows + row_id] = make_float2(m_run, l_tot);
   if (lse_cache != nullptr && grp == 0) lse_cache[row_id] = (m_snap + log2f(l_snap_tot)) * kLn2;
   if (lse != nullptr && grp == 0) lse[row_id] = (m_run + log2f(l_tot)) * kLn2;
-  if (HAS_PV) {
+  }  // row valid
+  // The output tile leaves through LDS: a lane holds 4-element pieces of ONE query row (256 bytes
+  // between neighbouring lanes), so direct stores put 64 scattered 8-byte pieces into every store
+  // instruction and keep the compute unit's address path busy for microseconds per row block.  Each
+  // wave parks its 32 x 128 tile in its own 8 KB of the tile buffers (free after the barrier above;
+  // 16-byte segments XOR-swizzled by the row so that the column-wise writes spread over the banks)
+  // and stores it back as whole 256-byte rows.
+  {
+    int colx = col, lanex = lane;
+    hide_loop_invariance(colx, lanex);  // offsets are formed here, per row block, not kept in registers
+    char* o_s = (w < 4 ? k_s : v_s) + (w % 4) * (32 * kRowBytes) + colx * kRowBytes;
+    const int c16 = colx % 16, sub = 8 * grp;  // a lane pair (col, col + 32) shares every 16-byte segment
     const float inv = 1.f / l_tot;
-    uint16_t* op = const_cast<uint16_t*>(unit_ptr(out, b, l, h)) + static_cast<int64_t>(t) * out.ss;
 #pragma unroll
     for (int r = 0; r < 4; ++r)
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
-        // registers 4 i4 .. +3 are rows c' = 8 i4 + 4 grp + 0..3 -> head_dim 16 r + (c' % 16) + 64 (c' / 16)
-        const int c0 = 8 * i4 + 4 * grp;
-        const int d0 = 16 * r + (c0 % 16) + 64 * (c0 / 16);
+        // registers 4 i4 .. +3 are rows c' = 8 i4 + 4 grp + 0..3 -> head_dim 16 r + (c' % 16) + 64 (c' / 16):
+        // 16-byte segment 2 r + (i4 % 2) + 8 (i4 / 2), its half `grp`
+        const int sg = 2 * r + (i4 % 2) + 8 * (i4 / 2);
         uint2 wds;
         wds.x = pack_bf16x2(o_acc[r][4 * i4] * inv, o_acc[r][4 * i4 + 1] * inv);
         wds.y = pack_bf16x2(o_acc[r][4 * i4 + 2] * inv, o_acc[r][4 * i4 + 3] * inv);
-        *reinterpret_cast<uint2*>(op + d0) = wds;
+        *reinterpret_cast<uint2*>(o_s + ((sg ^ c16) * 16) + sub) = wds;
       }
+    const char* o_r = (w < 4 ? k_s : v_s) + (w % 4) * (32 * kRowBytes) + lanex * 16;  // row lanex / 16 of a 4-row group
+    const int r_in = lanex / 16, pos = lanex % 16;
+    uint16_t* ob = const_cast<uint16_t*>(unit_ptr(out, b, l, h));
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int r = 4 * i + r_in;
+      const uint4 piece = *reinterpret_cast<const uint4*>(o_r + 4 * i * kRowBytes);
+      if (wave_active && row0 + r < rows)
+        *reinterpret_cast<uint4*>(ob + static_cast<int64_t>(row0 + r) * out.ss + 8 * (pos ^ (r % 16))) = piece;
+    }
   }
-  }  // row valid
+  __syncthreads();  // the parked tiles have been read back: the next row block may fill the buffers
   }  // pass
 }
 
@@ -1267,11 +1308,20 @@ hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments ks, Segme
   const int row_blocks = (rows + rows_per_block - 1) / rows_per_block;
   const int rb_slots = (causal && key_splits == 1) ? (row_blocks + 1) / 2 : row_blocks;  // paired row blocks
   dim3 grid(rb_slots * (dm.G / ts.heads_per_block) * dm.Hkv * dm.B * dm.L * key_splits);
+  constexpr int kQStageBytes = kPipeWaves * 32 * kRowBytes;  // dynamic LDS next to the 64 KB of static tiles
+  if (pipe) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_pipe_kernel_w8),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kQStageBytes);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_pipe_kernel_w8_rotq),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kQStageBytes);
+    if (e != hipSuccess) return e;
+  }
   if (pipe && q_rope_pos0 >= 0)
-    hipLaunchKernelGGL(attn_pipe_kernel_w8_rotq, grid, dim3(kPipeWaves * 64), 0, st, dm, q, rows, ks, vs, causal, out, lse,
+    hipLaunchKernelGGL(attn_pipe_kernel_w8_rotq, grid, dim3(kPipeWaves * 64), kQStageBytes, st, dm, q, rows, ks, vs, causal, out, lse,
                        lse_cache, q_rope_pos0, log2f(rope_base));
   else if (pipe)
-    hipLaunchKernelGGL(attn_pipe_kernel_w8, grid, dim3(kPipeWaves * 64), 0, st, dm, q, rows, ks, vs, causal, out, lse,
+    hipLaunchKernelGGL(attn_pipe_kernel_w8, grid, dim3(kPipeWaves * 64), kQStageBytes, st, dm, q, rows, ks, vs, causal, out, lse,
                        lse_cache);
   else
     hipLaunchKernelGGL((attn_mfma_kernel<false>), grid, dim3(kThreads), 0, st, dm, q, rows, ks, vs, causal, out, lse,
