@@ -474,7 +474,8 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
   const int g = (logical / (rb_slots * head_groups)) % dm.Hkv;
   const int bl = logical / (rb_slots * head_groups * dm.Hkv);
   const int b = bl / dm.L, l = bl % dm.L;
-  const int h = g * dm.G + hg * ts.heads_per_block + (w % ts.heads_per_block);
+  const int wu = __builtin_amdgcn_readfirstlane(w);  // the wave's index as a scalar: what depends on it stays scalar
+  const int h = g * dm.G + hg * ts.heads_per_block + (wu % ts.heads_per_block);
   const int n_c = ks.n_c;
   const int n = n_c + ks.c;
 
@@ -497,7 +498,6 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
       const_cast<uint16_t*>(unit_ptr(HAS_PV ? vs.cache : ks.cache, b, l, g)), 0, seg_bytes(n_c, v_ss_cache), kBufferFlags);
   const __amdgpu_buffer_rsrc_t v_rs_chunk = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint16_t*>(unit_ptr(HAS_PV ? vs.chunk : ks.chunk, b, l, g)), 0, seg_bytes(ks.c, v_ss_chunk), kBufferFlags);
-  const int wu = __builtin_amdgcn_readfirstlane(w);
   const int fill_row_c = kFillRows * wu + lane / 16;                // tile row this lane fills with instruction 0
   const int fill_seg16_c = ((lane % 16) ^ (2 * (lane / 16))) * 16;  // byte offset of its global segment, before ^ c_i
   // instruction i covers rows r = kFillRows wu + 4 i .. + 3; the lane-independent part of f(row)
@@ -555,7 +555,7 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
 
   for (int pass = 0; pass < passes; ++pass) {
   const int rb = pass == 0 ? rb_first : rb_second;
-  const int row0 = (rb * ts.tiles_per_block + w / ts.heads_per_block) * kRowsPerWave;
+  const int row0 = (rb * ts.tiles_per_block + wu / ts.heads_per_block) * kRowsPerWave;
 
   // last candidate any row of this block / this wave can see
   const int blk_row_last = min(rows, (rb + 1) * rows_per_block) - 1;
@@ -885,7 +885,7 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
   {
     int colx = col, lanex = lane;
     hide_loop_invariance(colx, lanex);  // offsets are formed here, per row block, not kept in registers
-    char* o_s = (w < 4 ? k_s : v_s) + (w % 4) * (32 * kRowBytes) + colx * kRowBytes;
+    char* o_s = (wu < 4 ? k_s : v_s) + (wu % 4) * (32 * kRowBytes) + colx * kRowBytes;
     const int c16 = colx % 16, sub = 8 * grp;  // a lane pair (col, col + 32) shares every 16-byte segment
     const float inv = 1.f / l_tot;
 #pragma unroll
@@ -900,7 +900,7 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
         wds.y = pack_bf16x2(o_acc[r][4 * i4 + 2] * inv, o_acc[r][4 * i4 + 3] * inv);
         *reinterpret_cast<uint2*>(o_s + ((sg ^ c16) * 16) + sub) = wds;
       }
-    const char* o_r = (w < 4 ? k_s : v_s) + (w % 4) * (32 * kRowBytes) + lanex * 16;  // row lanex / 16 of a 4-row group
+    const char* o_r = (wu < 4 ? k_s : v_s) + (wu % 4) * (32 * kRowBytes) + lanex * 16;  // row lanex / 16 of a 4-row group
     const int r_in = lanex / 16, pos = lanex % 16;
     uint16_t* ob = const_cast<uint16_t*>(unit_ptr(out, b, l, h));
 #pragma unroll
