@@ -886,7 +886,9 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
     int colx = col, lanex = lane;
     hide_loop_invariance(colx, lanex);  // offsets are formed here, per row block, not kept in registers
     char* o_s = (wu < 4 ? k_s : v_s) + (wu % 4) * (32 * kRowBytes) + colx * kRowBytes;
-    const int c16 = colx % 16, sub = 8 * grp;  // a lane pair (col, col + 32) shares every 16-byte segment
+    // a lane pair (col, col + 32) shares every 16-byte segment; rows 16..31 keep its halves swapped, so that
+    // the 32 lanes of one write cycle hit 32 different 8-byte slots
+    const int c16 = colx % 16, sub = 8 * (grp ^ (colx / 16));
     const float inv = 1.f / l_tot;
 #pragma unroll
     for (int r = 0; r < 4; ++r)
@@ -906,7 +908,8 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int r = 4 * i + r_in;
-      const uint4 piece = *reinterpret_cast<const uint4*>(o_r + 4 * i * kRowBytes);
+      uint4 piece = *reinterpret_cast<const uint4*>(o_r + 4 * i * kRowBytes);
+      if (i >= 4) piece = make_uint4(piece.z, piece.w, piece.x, piece.y);  // rows 16..31: halves back in order
       if (wave_active && row0 + r < rows)
         *reinterpret_cast<uint4*>(ob + static_cast<int64_t>(row0 + r) * out.ss + 8 * (pos ^ (r % 16))) = piece;
     }
