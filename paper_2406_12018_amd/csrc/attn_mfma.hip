@@ -17,6 +17,8 @@
 // Computing S^T (keys x queries) puts one query per lane, so softmax row
 // reductions are in-lane plus one exchange with lane l ^ 32, and the S^T
 // accumulators are directly the B operand (P^T) of the second product.
+#include <type_traits>
+
 #include "citrus_internal.h"
 #include "rope_math.h"
 
@@ -956,12 +958,17 @@ __global__ __launch_bounds__(kColsumWaves * 64, 2) void colsum_mfma_kernel(Dims 
   const int j_last = j0 + 32 * kColsumKeyTiles - 1;
 
   bf16x8 k_op[kColsumKeyTiles][8];
+  // bases and strides are read once: a per-lane choice between the two structs' fields would compile to a
+  // per-lane load of the chosen field from the argument block
+  const uint16_t* const k_cache_u = unit_ptr(ks.cache, b, l, g) + 8 * grp;
+  const uint16_t* const k_chunk_u = unit_ptr(ks.chunk, b, l, g) + 8 * grp;
+  const int64_t k_ss_cache = ks.cache.ss, k_ss_chunk = ks.chunk.ss;
 #pragma unroll
   for (int kt = 0; kt < kColsumKeyTiles; ++kt) {
     const int j = min(j0 + 32 * kt + col, n - 1);
-    const uint16_t* kp = (j < n_c ? unit_ptr(ks.cache, b, l, g) + static_cast<int64_t>(j) * ks.cache.ss
-                                  : unit_ptr(ks.chunk, b, l, g) + static_cast<int64_t>(j - n_c) * ks.chunk.ss) +
-                         8 * grp;
+    const bool in_cache = j < n_c;
+    const int64_t off = in_cache ? j * k_ss_cache : (j - n_c) * k_ss_chunk;
+    const uint16_t* kp = (in_cache ? k_cache_u : k_chunk_u) + off;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
       Pack8 p;
@@ -1116,10 +1123,14 @@ __global__ __launch_bounds__(WAVES * 64) void instr_fused_kernel(Dims dm, View q
 
   const uint16_t* k_cache_u = unit_ptr(ks.cache, b, l, g) + 8 * grp;
   const uint16_t* k_chunk_u = unit_ptr(ks.chunk, b, l, g) + 8 * grp;
+  // the strides are read here, once: a per-lane choice between the two struct fields inside the loader
+  // would compile to a per-lane LOAD of the chosen field from the argument block, in front of every tile
+  const int64_t k_ss_cache = ks.cache.ss, k_ss_chunk = ks.chunk.ss;
   auto load_keys = [&](int kt, bf16x8 (&k_op)[8]) {
     const int j = min(32 * kt + col, n - 1);
-    const uint16_t* kp = j < n_c ? k_cache_u + static_cast<int64_t>(j) * ks.cache.ss
-                                 : k_chunk_u + static_cast<int64_t>(j - n_c) * ks.chunk.ss;
+    const bool in_cache = j < n_c;
+    const int64_t off = in_cache ? j * k_ss_cache : (j - n_c) * k_ss_chunk;
+    const uint16_t* kp = (in_cache ? k_cache_u : k_chunk_u) + off;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
       Pack8 p;
@@ -1140,25 +1151,43 @@ __global__ __launch_bounds__(WAVES * 64) void instr_fused_kernel(Dims dm, View q
     return s_t;
   };
 
-  bf16x8 k_res[KREG > 0 ? KREG : 1][8];
-  if constexpr (KREG > 0) {  // the launcher guarantees tiles <= KW * KREG
+  // The query rows go through LDS.  They are requested first and waited for BEFORE the bulk of the key
+  // loads is issued: every workgroup of the launch starts at the same moment, and behind 80+ MB of key
+  // requests the query rows of the slowest wave (all of them are needed before the first product) arrive
+  // when the whole burst is nearly through.  Loads return in order and the compiler counts them, so the
+  // first pass then starts on a wave's first key tile while its later ones are still arriving.
+  constexpr int kQLoads = QROWS / (WAVES * 4);  // 16 threads per row, 16 bytes each
+  i32x4 q_in[kQLoads];
 #pragma unroll
-    for (int i = 0; i < KREG; ++i) load_keys(min(kw + KW * i, tiles - 1), k_res[i]);
-  }
-  // the query rows go through LDS (the key loads above are in flight meanwhile)
-  for (int r = tid / 16; r < QROWS; r += WAVES * 4) {  // 16 threads per row, 16 bytes each
-    const int f = min(r, total_rows - 1);               // padding rows repeat the last row; never summed
+  for (int x = 0; x < kQLoads; ++x) {
+    const int f = min(tid / 16 + x * WAVES * 4, total_rows - 1);  // padding rows repeat the last row; never summed
     const int hh = f / rows, t = f % rows;
-    const uint16_t* qp = unit_ptr(q, b, l, g * dm.G + hh) + static_cast<int64_t>(t) * q.ss + 8 * (tid % 16);
-    *reinterpret_cast<uint4*>(&q_s[r * kPitchK + 8 * (tid % 16)]) = *reinterpret_cast<const uint4*>(qp);
+    q_in[x] = *reinterpret_cast<const i32x4*>(unit_ptr(q, b, l, g * dm.G + hh) + static_cast<int64_t>(t) * q.ss +
+                                              8 * (tid % 16));
   }
+  __builtin_amdgcn_sched_barrier(0);  // keep the issue order
+  bf16x8 k_res[KREG > 0 ? KREG : 1][8];
+  if constexpr (KREG > 0) load_keys(min(kw, tiles - 1), k_res[0]);  // the launcher guarantees tiles <= KW * KREG
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int x = 0; x < kQLoads; ++x)
+    *reinterpret_cast<i32x4*>(&q_s[(tid / 16 + x * WAVES * 4) * kPitchK + 8 * (tid % 16)]) = q_in[x];
   __syncthreads();
 
-  auto for_my_tiles = [&](auto&& tile_fn) {
+  // With resident key tiles the first pass requests tile i + 1 when it starts on tile i: a compute unit
+  // can only keep so many requests in flight, so issuing all of a wave's key loads up front would hold
+  // the wave (and with it the barrier above) until most of the keys have arrived.
+  auto for_my_tiles = [&](auto first_pass, auto&& tile_fn) {
     if constexpr (KREG > 0) {
 #pragma unroll
-      for (int i = 0; i < KREG; ++i)
+      for (int i = 0; i < KREG; ++i) {
+        if constexpr (decltype(first_pass)::value) {
+          __builtin_amdgcn_sched_barrier(0);
+          if (i + 1 < KREG) load_keys(min(kw + KW * (i + 1), tiles - 1), k_res[i + 1]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
         if (kw + KW * i < tiles) tile_fn(k_res[i], kw + KW * i);  // wave-uniform
+      }
     } else {
       for (int kt = kw; kt < tiles; kt += KW) {
         bf16x8 k_op[8];
@@ -1175,7 +1204,7 @@ __global__ __launch_bounds__(WAVES * 64) void instr_fused_kernel(Dims dm, View q
     m_run[x] = -INFINITY;
     l_run[x] = 0.f;
   }
-  for_my_tiles([&](const bf16x8 (&k_op)[8], int kt) {
+  for_my_tiles(std::true_type{}, [&](const bf16x8 (&k_op)[8], int kt) {
     const int valid = n - 32 * kt;  // keys of the tile that exist (wave-uniform)
 #pragma unroll
     for (int x = 0; x < QT_PER; ++x) {
@@ -1231,7 +1260,7 @@ __global__ __launch_bounds__(WAVES * 64) void instr_fused_kernel(Dims dm, View q
   float lse2[QT_PER];
 #pragma unroll
   for (int x = 0; x < QT_PER; ++x) lse2[x] = lse_s[32 * (qh * QT_PER + x) + col];
-  for_my_tiles([&](const bf16x8 (&k_op)[8], int kt) {
+  for_my_tiles(std::false_type{}, [&](const bf16x8 (&k_op)[8], int kt) {
     float acc[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = 0.f;
