@@ -947,8 +947,10 @@ constexpr int kColsumQRows = 128;   // query rows per LDS chunk
 __global__ __launch_bounds__(kColsumWaves * 64, 2) void colsum_mfma_kernel(Dims dm, View q, int rows, Segments ks,
                                                                         int causal, const float* lse, int key_splits,
                                                                         const float2* part, float* score) {
-  __shared__ __attribute__((aligned(16))) uint16_t q_s[kColsumQRows * kPitchK];
-  __shared__ float lse_s[kColsumQRows];  // log2-domain normaliser per staged row (+inf for padding rows)
+  // two staging buffers of query rows and their normalisers (log2 domain, +inf for padding rows)
+  extern __shared__ __attribute__((aligned(16))) char colsum_smem[];
+  uint16_t* const q_sb = reinterpret_cast<uint16_t*>(colsum_smem);                        // [2][kColsumQRows][kPitchK]
+  float* const lse_sb = reinterpret_cast<float*>(q_sb + 2 * kColsumQRows * kPitchK);      // [2][kColsumQRows]
   const int tid = threadIdx.x, lane = tid % 64, w = tid / 64;
   const int col = lane % 32, grp = lane / 32;
   const int g = blockIdx.y, bl = blockIdx.z, b = bl / dm.L, l = bl % dm.L;
@@ -985,36 +987,50 @@ __global__ __launch_bounds__(kColsumWaves * 64, 2) void colsum_mfma_kernel(Dims 
 
   const int total_rows = dm.G * rows;  // flattened (head in group, row)
   const int64_t part_stride = static_cast<int64_t>(dm.B) * dm.L * dm.Hq * rows;
-  for (int f0 = 0; f0 < total_rows; f0 += kColsumQRows) {
-    const int f_cnt = min(kColsumQRows, total_rows - f0);
-    __syncthreads();  // previous chunk fully consumed
-    // stage the chunk: 16 threads per row, 16 bytes each
-    for (int r = tid / 16; r < kColsumQRows; r += kColsumWaves * 4) {
-      const int f = min(f0 + r, total_rows - 1);
+  // The rows of chunk c + 1 are requested (into registers) before the products of chunk c start and
+  // written to the other buffer afterwards: one barrier per chunk, no exposed load latency.
+  constexpr int kStageLoads = kColsumQRows / (kColsumWaves * 4);  // 16 threads per row, 16 bytes each
+  i32x4 q_in[kStageLoads];
+  float lse_in = INFINITY;
+  auto request_chunk = [&](int f0) {
+#pragma unroll
+    for (int x = 0; x < kStageLoads; ++x) {
+      const int f = min(f0 + tid / 16 + x * kColsumWaves * 4, total_rows - 1);
       const int hh = f / rows, t = f % rows;
-      const uint16_t* qp = unit_ptr(q, b, l, g * dm.G + hh) + static_cast<int64_t>(t) * q.ss + 8 * (tid % 16);
-      *reinterpret_cast<uint4*>(&q_s[r * kPitchK + 8 * (tid % 16)]) = *reinterpret_cast<const uint4*>(qp);
+      q_in[x] = *reinterpret_cast<const i32x4*>(unit_ptr(q, b, l, g * dm.G + hh) + static_cast<int64_t>(t) * q.ss +
+                                                8 * (tid % 16));
     }
-    if (tid < kColsumQRows) {
-      float v = INFINITY;  // padding rows contribute exp2(-inf) = 0
-      if (tid < f_cnt) {
-        const int f = f0 + tid;
-        const int64_t row_id = (static_cast<int64_t>(bl) * dm.Hq + g * dm.G + f / rows) * rows + f % rows;
-        if (part != nullptr) {  // merge the per-range (maximum, sum) pairs
-          float m = -INFINITY;
-          for (int s = 0; s < key_splits; ++s) m = fmaxf(m, part[s * part_stride + row_id].x);
-          float lsum = 0.f;
-          for (int s = 0; s < key_splits; ++s) {
-            const float2 ps = part[s * part_stride + row_id];
-            lsum += ps.y * exp2f(ps.x - m);
-          }
-          v = m + log2f(lsum);
-        } else {
-          v = lse[row_id] * kLog2e;
+    float v = INFINITY;  // padding rows contribute exp2(-inf) = 0
+    if (tid < kColsumQRows && f0 + tid < total_rows) {
+      const int f = f0 + tid;
+      const int64_t row_id = (static_cast<int64_t>(bl) * dm.Hq + g * dm.G + f / rows) * rows + f % rows;
+      if (part != nullptr) {  // merge the per-range (maximum, sum) pairs
+        float m = -INFINITY;
+        for (int s = 0; s < key_splits; ++s) m = fmaxf(m, part[s * part_stride + row_id].x);
+        float lsum = 0.f;
+        for (int s = 0; s < key_splits; ++s) {
+          const float2 ps = part[s * part_stride + row_id];
+          lsum += ps.y * exp2f(ps.x - m);
         }
+        v = m + log2f(lsum);
+      } else {
+        v = lse[row_id] * kLog2e;
       }
-      lse_s[tid] = v;
     }
+    lse_in = v;
+  };
+  request_chunk(0);
+  int buf = 0;
+  for (int f0 = 0; f0 < total_rows; f0 += kColsumQRows, buf ^= 1) {
+    const int f_cnt = min(kColsumQRows, total_rows - f0);
+    uint16_t* const q_s = q_sb + buf * (kColsumQRows * kPitchK);
+    float* const lse_s = lse_sb + buf * kColsumQRows;
+    // this buffer was last read two chunks ago, and every wave has passed the previous chunk's barrier since
+#pragma unroll
+    for (int x = 0; x < kStageLoads; ++x)
+      *reinterpret_cast<i32x4*>(&q_s[(tid / 16 + x * kColsumWaves * 4) * kPitchK + 8 * (tid % 16)]) = q_in[x];
+    if (tid < kColsumQRows) lse_s[tid] = lse_in;
+    if (f0 + kColsumQRows < total_rows) request_chunk(f0 + kColsumQRows);  // block-uniform
     __syncthreads();
     if (wave_has_keys) {
       for (int qt = 0; qt * 32 < f_cnt; ++qt) {
@@ -1366,7 +1382,15 @@ hipError_t launch_colsum_mfma(const Dims& dm, View q, int rows, Segments ks, int
   const int n = ks.n_c + ks.c;
   constexpr int kKeysPerBlock = 32 * kColsumKeyTiles * kColsumWaves;
   dim3 grid((n + kKeysPerBlock - 1) / kKeysPerBlock, dm.Hkv, dm.B * dm.L);
-  hipLaunchKernelGGL(colsum_mfma_kernel, grid, dim3(kColsumWaves * 64), 0, st, dm, q, rows, ks, causal, lse,
+  constexpr int kLdsBytes = 2 * kColsumQRows * (kPitchK * 2 + 4);  // two buffers of rows and normalisers: 70 KB
+  static bool cleared = false;
+  if (!cleared) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(colsum_mfma_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e != hipSuccess) return e;
+    cleared = true;
+  }
+  hipLaunchKernelGGL(colsum_mfma_kernel, grid, dim3(kColsumWaves * 64), kLdsBytes, st, dm, q, rows, ks, causal, lse,
                      key_splits, part, score);
   return hipGetLastError();
 }
