@@ -115,7 +115,7 @@ def cpu_baseline(w, target_seconds: float = 15.0):
         kc, vc = orc.kv_compact(k_cat, v_cat, idx)
         steps += 1
         dt = time.perf_counter() - t0
-        if dt > target_seconds or steps >= 64:
+        if dt > target_seconds or steps >= 128:
             break
     per_unit_step = dt / steps                       # seconds per (document, layer) chunk step
     tok_s = w.chunk_len / (per_unit_step * w.batch * w.layers)
