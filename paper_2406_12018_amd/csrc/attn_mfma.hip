@@ -790,6 +790,35 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
     }
   }
   barrier_after_lds_fill();  // also: the query rows have landed
+  // Position shift: the query rows arrive without rotary embedding and are rotated here, in the staging
+  // region, to position q_rope_pos0 + row, before the operands are read (only a few registers are live at
+  // this point; rotating the operands in registers pushed the whole kernel over its register budget).
+  // Element i of a row pairs with element i + 64: 16-byte segment sg with segment sg + 8.  A lane takes
+  // one (row, sg) of the wave's 32 x 8 per round; the wave touches only its own rows, so no barrier.
+  if (ROTATE_Q) {
+    char* q_t = q_stage + 32 * wu * kRowBytes;
+#pragma unroll 1
+    for (int round = 0; round < 4; ++round) {
+      const int r = 8 * round + lane / 8, sg = lane % 8;
+      const int f = (2 * (r % 8)) ^ ((r / 8) % 2);
+      uint4* lo_p = reinterpret_cast<uint4*>(q_t + r * kRowBytes + ((sg ^ f) * 16));
+      uint4* hi_p = reinterpret_cast<uint4*>(q_t + r * kRowBytes + (((sg + 8) ^ f) * 16));
+      Pack8 lo, hi;
+      lo.u = *lo_p;
+      hi.u = *hi_p;
+      const int pos = q_rope_pos0 + max(min(row0 + r, rows - 1), 0);
+#pragma unroll
+      for (int wd = 0; wd < 4; ++wd) {
+        const int i0 = 8 * sg + 2 * wd;
+        float s0, c0, s1, c1;
+        rope_sincos_bf16(pos, i0, D, rope_log2_base, s0, c0);
+        rope_sincos_bf16(pos, i0 + 1, D, rope_log2_base, s1, c1);
+        rope_rotate_words(lo.w[wd], hi.w[wd], c0, s0, c1, s1, lo.w[wd], hi.w[wd]);
+      }
+      *lo_p = lo.u;
+      *hi_p = hi.u;
+    }
+  }
   {
     const char* q_t = q_stage + 32 * wu * kRowBytes;
 #pragma unroll
@@ -797,28 +826,6 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
       Pack8 p;
       p.u = *reinterpret_cast<const uint4*>(q_t + k_off(kk));
       q_op[kk] = p.v;
-    }
-  }
-  // Position shift: the query rows arrive without rotary embedding and are rotated here, in
-  // registers, to position q_rope_pos0 + row.  Element 16 kk + 8 grp + j (kk < 4) and its partner
-  // 64 further on sit in the same lane, in q_op[kk] and q_op[kk + 4].
-  if (ROTATE_Q) {
-    const int pos = q_rope_pos0 + t_lane;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      Pack8 lo, hi;
-      lo.v = q_op[kk];
-      hi.v = q_op[kk + 4];
-#pragma unroll
-      for (int wd = 0; wd < 4; ++wd) {
-        const int i0 = 16 * kk + 8 * grp + 2 * wd;
-        float s0, c0, s1, c1;
-        rope_sincos_bf16(pos, i0, D, rope_log2_base, s0, c0);
-        rope_sincos_bf16(pos, i0 + 1, D, rope_log2_base, s1, c1);
-        rope_rotate_words(lo.w[wd], hi.w[wd], c0, s0, c1, s1, lo.w[wd], hi.w[wd]);
-      }
-      q_op[kk] = lo.v;
-      q_op[kk + 4] = hi.v;
     }
   }
   read_k_ops(h_first);
@@ -928,8 +935,8 @@ __global__ __launch_bounds__(512, 1) void attn_pipe_kernel_w8(Dims dm, View q, i
   attn_pipe_body<8, false>(dm, q, rows, ks, vs, causal, out, lse, lse_cache, -1, 0.f);
 }
 // The same kernel for query rows that arrive without rotary embedding (position shift): they are rotated
-// in registers right after they are loaded.  An instance of its own, so that the register allocation of
-// the kernel above is not touched by the extra prologue.
+// in the LDS staging region before the operands are read.  An instance of its own, so that the kernel
+// above does not carry the extra prologue.
 __global__ __launch_bounds__(512, 1) void attn_pipe_kernel_w8_rotq(Dims dm, View q, int rows, Segments ks, Segments vs,
                                                                   int causal, View out, float* lse, float* lse_cache,
                                                                   int q_rope_pos0, float rope_log2_base) {

@@ -660,7 +660,7 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
       if ((status = hip_status(launch_rope(cfg->dtype, dm, ks.chunk, make_view(k_rot_chunk), cfg->kv_heads, c, n_c, base,
                                            st))) != CITRUS_OK)
         break;
-      // the MFMA attention kernel rotates its query rows itself while they sit in registers
+      // the MFMA attention kernel rotates its query rows itself while they are staged in LDS
       if (q_rope_pos0 < 0 && (status = hip_status(launch_rope(cfg->dtype, dm, make_view(io.q), make_view(q_att),
                                                               cfg->q_heads, c, n_c, base, st))) != CITRUS_OK)
         break;

@@ -1,5 +1,5 @@
 // Arithmetic of the rotary embedding shared by the stand-alone kernel (rope.hip) and the chunk-attention
-// kernel, which rotates its query rows while they sit in registers: both produce the same bits.
+// kernel, which rotates its query rows while they are staged in LDS: both produce the same bits.
 #pragma once
 
 #include <hip/hip_runtime.h>
