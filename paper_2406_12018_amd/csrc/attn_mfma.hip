@@ -1364,13 +1364,15 @@ hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments ks, Segme
   const int rb_slots = (causal && key_splits == 1) ? (row_blocks + 1) / 2 : row_blocks;  // paired row blocks
   dim3 grid(rb_slots * (dm.G / ts.heads_per_block) * dm.Hkv * dm.B * dm.L * key_splits);
   constexpr int kQStageBytes = kPipeWaves * 32 * kRowBytes;  // dynamic LDS next to the 64 KB of static tiles
-  if (pipe) {
+  static bool lds_limit_raised = false;  // once per process: the kernels' dynamic-LDS limit
+  if (pipe && !lds_limit_raised) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_pipe_kernel_w8),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kQStageBytes);
     if (e == hipSuccess)
       e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_pipe_kernel_w8_rotq),
                               hipFuncAttributeMaxDynamicSharedMemorySize, kQStageBytes);
     if (e != hipSuccess) return e;
+    lds_limit_raised = true;
   }
   if (pipe && q_rope_pos0 >= 0)
     hipLaunchKernelGGL(attn_pipe_kernel_w8_rotq, grid, dim3(kPipeWaves * 64), kQStageBytes, st, dm, q, rows, ks, vs, causal, out, lse,
