@@ -13,8 +13,12 @@ namespace {
 constexpr int kWave = 64;
 constexpr int kRowsPerBlock = 4;  // one wavefront per query row
 
+// Logit: the type the q.k products are accumulated and the maximum / normaliser subtracted in.  The f32
+// mode promises 1e-5 against an f64 reference: with logits of a few tens an f32 dot product and subtraction
+// alone leave a relative error of that order in the probability, so f32 inputs use f64 there.
 template <typename T> struct Elem;
 template <> struct Elem<float> {
+  typedef double Logit;
   static constexpr int kVec = 4;  // elements per 16-byte load
   __device__ static void load16(const float* p, float* dst) {
     float4 v = *reinterpret_cast<const float4*>(p);
@@ -24,6 +28,7 @@ template <> struct Elem<float> {
   __device__ static void store1(float* p, float v) { *p = v; }
 };
 template <> struct Elem<uint16_t> {  // bf16 as raw bits
+  typedef float Logit;
   static constexpr int kVec = 8;
   __device__ static float cvt(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
   __device__ static void load16(const uint16_t* p, float* dst) {
@@ -53,6 +58,9 @@ template <typename T>
 __device__ inline const T* cand_ptr(const Segments& sg, int b, int l, int g, int j) {
   return j < sg.n_c ? row_ptr<T>(sg.cache, b, l, g, j) : row_ptr<T>(sg.chunk, b, l, g, j - sg.n_c);
 }
+
+__device__ inline float mad(float a, float b, float c) { return fmaf(a, b, c); }
+__device__ inline double mad(double a, double b, double c) { return fma(a, b, c); }
 
 __device__ inline float wave_max(float v) {
 #pragma unroll
@@ -95,22 +103,24 @@ __global__ __launch_bounds__(kWave* kRowsPerBlock) void attn_generic_kernel(Dims
   for (int j0 = 0; j0 <= blk_limit; j0 += kWave) {
     const int j = j0 + lane;
     const bool valid = j <= limit;
-    float s = -INFINITY;
+    typedef typename Elem<T>::Logit Logit;
+    Logit s = -INFINITY;
     if (valid) {
       const T* kp = cand_ptr<T>(ks, b, l, g, j);
-      float dot = 0.f;
+      Logit dot = 0;
 #pragma unroll 4
       for (int e = 0; e < D; e += Elem<T>::kVec) {
         float kv[Elem<T>::kVec];
         Elem<T>::load16(kp + e, kv);
 #pragma unroll
-        for (int x = 0; x < Elem<T>::kVec; ++x) dot = fmaf(q_s[w][e + x], kv[x], dot);
+        for (int x = 0; x < Elem<T>::kVec; ++x) dot = mad(static_cast<Logit>(q_s[w][e + x]), static_cast<Logit>(kv[x]), dot);
       }
-      s = dot * dm.scale;
+      s = dot * static_cast<Logit>(dm.scale);
     }
-    const float m_new = fmaxf(m, wave_max(s));
+    // the running maximum is an f32 value; it only has to be the same number wherever it is subtracted
+    const float m_new = fmaxf(m, wave_max(static_cast<float>(s)));
     // tile 0 always holds candidate 0, which every row sees, so m_new is finite
-    const float p = valid ? expf(s - m_new) : 0.f;
+    const float p = valid ? expf(static_cast<float>(s - static_cast<Logit>(m_new))) : 0.f;
     const float corr = expf(m - m_new);
     lsum = lsum * corr + wave_sum(p);
     m = m_new;
@@ -177,10 +187,11 @@ __global__ __launch_bounds__(kColsumThreads) void colsum_generic_kernel(Dims dm,
       if (threadIdx.x < tn) lse_s[threadIdx.x] = lse_h[t0 + threadIdx.x];
       __syncthreads();
       for (int tt = 0; tt < tn; ++tt) {
-        float dot = 0.f;
+        typedef typename Elem<T>::Logit Logit;
+        Logit dot = 0;
 #pragma unroll
-        for (int e = 0; e < D; ++e) dot = fmaf(q_s[tt][e], kreg[e], dot);
-        const float p = expf(dot * dm.scale - lse_s[tt]);
+        for (int e = 0; e < D; ++e) dot = mad(static_cast<Logit>(q_s[tt][e]), static_cast<Logit>(kreg[e]), dot);
+        const float p = expf(static_cast<float>(dot * static_cast<Logit>(dm.scale) - static_cast<Logit>(lse_s[tt])));
         if (t0 + tt >= t_first) sum += p;
       }
     }

@@ -33,7 +33,7 @@ def draw_shape(case):
     # an empty cache, any length, or a multiple of the 32-key half tile (the fused cache normaliser's case)
     n_c = int(rng.choice([0, int(rng.integers(1, 1500)), 32 * int(rng.integers(1, 44))]))
     n_i = int(rng.integers(1, 140))
-    scale = float(rng.choice([0.09, 0.3, 1.0]))  # flat to peaked attention rows
+    scale = float(rng.choice([0.09, 0.3, 1.0, 3.0]))  # flat to sharply peaked attention rows (logits of a few tens)
     return dtype, d, B, L, Hkv, G, c, n_c, n_i, scale
 
 
