@@ -522,6 +522,19 @@ DOC_CASES = {
                                                lm_ordering=api.LM_EVICT_THEN_APPEND),
     "cfg5_small_g8": scaled_down(WORKLOADS["cfg5_large"], batch=1, layers=1, q_heads=16, kv_heads=2, doc_len=2048,
                                  chunk_len=512, budget=640, instr_len=96),
+    # degenerate sizes: one-token chunks, budget 1, one instruction token, a document shorter than a chunk
+    "degenerate_f32_c1_k1_ni1": scaled_down(WORKLOADS["cfg1_tiny_f32"], doc_len=7, chunk_len=1, budget=1, instr_len=1),
+    "degenerate_bf16_c1_k1_ni1": scaled_down(WORKLOADS["cfg2_mistral7b"], layers=1, doc_len=6, chunk_len=1, budget=1,
+                                             instr_len=1),
+    "degenerate_bf16_c64_k1": scaled_down(WORKLOADS["cfg2_mistral7b"], layers=1, doc_len=300, chunk_len=64, budget=1),
+    "degenerate_bf16_doc_shorter_than_chunk": scaled_down(WORKLOADS["cfg2_mistral7b"], layers=1, doc_len=100),
+    "degenerate_bf16_dual_c1": scaled_down(peaked(WORKLOADS["cfg2_mistral7b"]), layers=1, doc_len=9, chunk_len=1, budget=2,
+                                           budget_lm=3, instr_len=3, cache_mode=api.CACHE_DUAL),
+    "degenerate_bf16_dual_paper_order_c5": scaled_down(peaked(WORKLOADS["cfg2_mistral7b"]), layers=1, doc_len=40,
+                                                       chunk_len=5, budget=4, budget_lm=3, instr_len=3,
+                                                       cache_mode=api.CACHE_DUAL, lm_ordering=api.LM_EVICT_THEN_APPEND),
+    "degenerate_bf16_position_shift_c7": scaled_down(peaked(WORKLOADS["cfg2_mistral7b"]), layers=1, doc_len=50,
+                                                     chunk_len=7, budget=9, instr_len=3, position_shift=1),
 }
 
 
