@@ -895,9 +895,11 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
     int colx = col, lanex = lane;
     hide_loop_invariance(colx, lanex);  // offsets are formed here, per row block, not kept in registers
     char* o_s = (wu < 4 ? k_s : v_s) + (wu % 4) * (32 * kRowBytes) + colx * kRowBytes;
-    // a lane pair (col, col + 32) shares every 16-byte segment; rows 16..31 keep its halves swapped, so that
-    // the 32 lanes of one write cycle hit 32 different 8-byte slots
-    const int c16 = colx % 16, sub = 8 * (grp ^ (colx / 16));
+    // A lane pair (col, col + 32) shares every 16-byte segment.  The LDS has 32 banks of 4 bytes, so segment
+    // positions p and p + 8 of a row meet in the same banks, and 16 lanes go through per cycle: the two 8-byte
+    // halves of a segment are kept swapped where (p / 8) ^ (row / 16) is odd, which gives the 16 lanes of a
+    // cycle 16 different 8-byte slots of the 128 bytes the banks span.
+    const int c16 = colx % 16, half0 = grp ^ (colx / 16);
     const float inv = 1.f / l_tot;
 #pragma unroll
     for (int r = 0; r < 4; ++r)
@@ -909,7 +911,8 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
         uint2 wds;
         wds.x = pack_bf16x2(o_acc[r][4 * i4] * inv, o_acc[r][4 * i4 + 1] * inv);
         wds.y = pack_bf16x2(o_acc[r][4 * i4 + 2] * inv, o_acc[r][4 * i4 + 3] * inv);
-        *reinterpret_cast<uint2*>(o_s + ((sg ^ c16) * 16) + sub) = wds;
+        const int p = sg ^ c16;  // segment position
+        *reinterpret_cast<uint2*>(o_s + p * 16 + 8 * (half0 ^ (p >> 3))) = wds;
       }
     const char* o_r = (wu < 4 ? k_s : v_s) + (wu % 4) * (32 * kRowBytes) + lanex * 16;  // row lanex / 16 of a 4-row group
     const int r_in = lanex / 16, pos = lanex % 16;
@@ -918,7 +921,7 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
     for (int i = 0; i < 8; ++i) {
       const int r = 4 * i + r_in;
       uint4 piece = *reinterpret_cast<const uint4*>(o_r + 4 * i * kRowBytes);
-      if (i >= 4) piece = make_uint4(piece.z, piece.w, piece.x, piece.y);  // rows 16..31: halves back in order
+      if (((pos >> 3) ^ (i >> 2)) & 1) piece = make_uint4(piece.z, piece.w, piece.x, piece.y);  // halves back in order
       if (wave_active && row0 + r < rows)
         *reinterpret_cast<uint4*>(ob + static_cast<int64_t>(row0 + r) * out.ss + 8 * (pos ^ (r % 16))) = piece;
     }
