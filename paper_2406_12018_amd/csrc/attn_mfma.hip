@@ -1324,13 +1324,9 @@ template <int QT_TOTAL, int Q_SPLIT, int WAVES, int KREG>
 hipError_t instr_fused_launch(const Dims& dm, View q, int rows, Segments ks, float* score, hipStream_t st) {
   const size_t lds = instr_fused_lds_bytes<QT_TOTAL, Q_SPLIT, WAVES>(ks.n_c + ks.c);
   auto kern = instr_fused_kernel<QT_TOTAL, Q_SPLIT, WAVES, KREG>;
-  static size_t allowed = 0;  // largest dynamic LDS size the kernel has been cleared for
-  if (lds > allowed) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-    if (e != hipSuccess) return e;
-    allowed = lds;
-  }
+  static LdsLimit limit;
+  const hipError_t e = raise_lds_limit(limit, reinterpret_cast<const void*>(kern), static_cast<int>(lds));
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(dm.B * dm.L * dm.Hkv), dim3(WAVES * 64), lds, st, dm, q, rows, ks, score);
   return hipGetLastError();
 }
@@ -1367,15 +1363,11 @@ hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments ks, Segme
   const int rb_slots = (causal && key_splits == 1) ? (row_blocks + 1) / 2 : row_blocks;  // paired row blocks
   dim3 grid(rb_slots * (dm.G / ts.heads_per_block) * dm.Hkv * dm.B * dm.L * key_splits);
   constexpr int kQStageBytes = kPipeWaves * 32 * kRowBytes;  // dynamic LDS next to the 64 KB of static tiles
-  static bool lds_limit_raised = false;  // once per process: the kernels' dynamic-LDS limit
-  if (pipe && !lds_limit_raised) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_pipe_kernel_w8),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kQStageBytes);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_pipe_kernel_w8_rotq),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, kQStageBytes);
+  if (pipe) {
+    static LdsLimit limit, limit_rotq;
+    hipError_t e = raise_lds_limit(limit, reinterpret_cast<const void*>(attn_pipe_kernel_w8), kQStageBytes);
+    if (e == hipSuccess) e = raise_lds_limit(limit_rotq, reinterpret_cast<const void*>(attn_pipe_kernel_w8_rotq), kQStageBytes);
     if (e != hipSuccess) return e;
-    lds_limit_raised = true;
   }
   if (pipe && q_rope_pos0 >= 0)
     hipLaunchKernelGGL(attn_pipe_kernel_w8_rotq, grid, dim3(kPipeWaves * 64), kQStageBytes, st, dm, q, rows, ks, vs, causal, out, lse,
@@ -1395,13 +1387,9 @@ hipError_t launch_colsum_mfma(const Dims& dm, View q, int rows, Segments ks, int
   constexpr int kKeysPerBlock = 32 * kColsumKeyTiles * kColsumWaves;
   dim3 grid((n + kKeysPerBlock - 1) / kKeysPerBlock, dm.Hkv, dm.B * dm.L);
   constexpr int kLdsBytes = 2 * kColsumQRows * (kPitchK * 2 + 4);  // two buffers of rows and normalisers: 70 KB
-  static bool cleared = false;
-  if (!cleared) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(colsum_mfma_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
-    cleared = true;
-  }
+  static LdsLimit limit;
+  const hipError_t e = raise_lds_limit(limit, reinterpret_cast<const void*>(colsum_mfma_kernel), kLdsBytes);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(colsum_mfma_kernel, grid, dim3(kColsumWaves * 64), kLdsBytes, st, dm, q, rows, ks, causal, lse,
                      key_splits, part, score);
   return hipGetLastError();

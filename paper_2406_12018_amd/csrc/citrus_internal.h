@@ -75,6 +75,23 @@ hipError_t launch_decode_mfma(const Dims& dm, View q, Segments kseg, Segments vs
 hipError_t launch_rope(int dtype, const Dims& dm, View x, View y, int heads, int rows, int pos0, float base,
                        hipStream_t st);
 
+// Kernels that take more than 64 KB of dynamic LDS need their limit raised once per device.  `state` is a
+// static object next to the launch; the current device's slot remembers the largest size granted.
+constexpr int kMaxDevices = 64;
+struct LdsLimit {
+  int granted[kMaxDevices] = {};
+};
+inline hipError_t raise_lds_limit(LdsLimit& state, const void* kernel, int bytes) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const bool tracked = dev >= 0 && dev < kMaxDevices;
+  if (tracked && state.granted[dev] >= bytes) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && tracked) state.granted[dev] = bytes;
+  return e;
+}
+
 // ---- selection and compaction, select_compact.hip ----
 // units = B*L*Hsel; score rows are [units*(per_layer?Hkv:1)] x n.
 hipError_t launch_topk(const float* score, int units, int heads_to_sum, int n, int k, int forced, int32_t* idx,

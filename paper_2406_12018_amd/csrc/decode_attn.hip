@@ -443,8 +443,8 @@ hipError_t launch_decode_mfma(const Dims& dm, View q, Segments ks, Segments vs, 
   part.ml = reinterpret_cast<float2*>(workspace);
   part.o = workspace + 2 * static_cast<size_t>(kMaxSplits) * rows;
   constexpr int kLdsBytes = kWaves * kWaveLdsBytes;  // 128 KB
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_attn_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+  static LdsLimit limit;
+  hipError_t e = raise_lds_limit(limit, reinterpret_cast<const void*>(decode_attn_kernel), kLdsBytes);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(decode_attn_kernel, dim3(units * splits), dim3(64 * kWaves), kLdsBytes, st, dm, q, ks, vs, out,
                      splits, part, append_token);
