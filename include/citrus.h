@@ -58,7 +58,7 @@
 extern "C" {
 #endif
 
-#define CITRUS_ABI_VERSION 8
+#define CITRUS_ABI_VERSION 9
 #define CITRUS_EVENTS_PER_STEP 8
 
 typedef enum {
@@ -416,8 +416,27 @@ int32_t citrus_resident_provider(void* user, int32_t chunk_index, void* hip_stre
  *                 selection, 7 after the compaction.  A NULL entry is skipped (every
  *                 recorded event costs a few microseconds of stream time).  For
  *                 per-phase timing only.
+ * side            optional (NULL: every launch goes to hip_stream in the order a1 .. a4).  A second stream
+ *                 of the same device and two events, all created by the caller.  In the single-cache
+ *                 modes (INSTR, SHARED) a step then runs its instruction score first, and its selection
+ *                 and gather on side->stream NEXT TO its chunk attention on hip_stream: neither reads
+ *                 what the other writes (the attention reads the current buffer of the pair and the
+ *                 chunk, the gather writes the other buffer), and the gather's waves fit beside the
+ *                 attention's on a compute unit.  fork_event orders the side stream behind the
+ *                 instruction score, join_event orders hip_stream behind the gather before the next
+ *                 step; on return everything the call enqueued is ordered before later work on
+ *                 hip_stream.  Results are bit-identical with and without it.  Phase events 6 and 7 are
+ *                 then recorded on the side stream and event 5 (after the instruction score) comes
+ *                 before the attention: the attention launch is bracketed by events 5 and 1.  Other
+ *                 cache modes ignore it.
  * No host/device synchronisation happens inside the loop.
  */
+typedef struct citrus_side_stream {
+  void* stream;     /* hipStream_t */
+  void* fork_event; /* hipEvent_t */
+  void* join_event; /* hipEvent_t */
+} citrus_side_stream;
+
 int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider next, void* user,
                                 int32_t first_chunk, int32_t max_chunks,
                                 const citrus_tensor* k_cache, const citrus_tensor* v_cache,
@@ -427,7 +446,8 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
                                 float* const* acc_score,
                                 int32_t* idx_history, int32_t* idx_history_lm, int32_t* chunks_done,
                                 void* const* phase_events,
-                                void* workspace, size_t workspace_bytes, void* hip_stream);
+                                void* workspace, size_t workspace_bytes, void* hip_stream,
+                                const citrus_side_stream* side);
 
 #ifdef __cplusplus
 }

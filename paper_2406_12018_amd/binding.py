@@ -49,6 +49,10 @@ class CConfig(C.Structure):
             ("rope_base", C.c_float), ("softmax_scale", C.c_float)]
 
 
+class CSideStream(C.Structure):
+    _fields_ = [("stream", C.c_void_p), ("fork_event", C.c_void_p), ("join_event", C.c_void_p)]
+
+
 class CTensor(C.Structure):
     _fields_ = [("ptr", C.c_void_p), ("stride_b", C.c_int64), ("stride_l", C.c_int64), ("stride_h", C.c_int64),
                 ("stride_s", C.c_int64)]
@@ -109,7 +113,7 @@ def _lib():
     lib.citrus_resident_provider.argtypes = [V, I, V, P(CChunkIO)]
     lib.citrus_process_document.restype = I
     lib.citrus_process_document.argtypes = [P(CConfig), V, V, I, I, P(CTensor), P(CTensor), P(CTensor), P(CTensor),
-                                            P(I), P(I), P(I), P(I), P(V), V, V, P(I), V, V, S, V]
+                                            P(I), P(I), P(I), P(I), P(V), V, V, P(I), V, V, S, V, P(CSideStream)]
     _LIB = lib
     return lib
 
@@ -378,15 +382,41 @@ def resident_doc(cfg: Config, q, k, v, q_instr, out, doc_len: Optional[int] = No
                         q.shape[3] if doc_len is None else doc_len, cfg.chunk_len, cfg.dtype)
 
 
+class SideStream:
+    """A second stream and the two events citrus_process_document needs to run a step's selection and
+    gather next to its chunk attention.  The events are plain HIP events without timing."""
+
+    def __init__(self, device=None):
+        self.stream = torch.cuda.Stream(device=device)
+        self._hip = C.CDLL("libamdhip64.so")
+        self._hip.hipEventCreateWithFlags.argtypes = [C.POINTER(C.c_void_p), C.c_uint]
+        self._hip.hipEventDestroy.argtypes = [C.c_void_p]
+        self._events = []
+        with torch.cuda.device(self.stream.device):
+            for _ in range(2):
+                ev = C.c_void_p()
+                rc = self._hip.hipEventCreateWithFlags(C.byref(ev), 0x2)  # hipEventDisableTiming
+                if rc != 0:
+                    raise RuntimeError(f"hipEventCreateWithFlags failed: {rc}")
+                self._events.append(ev)
+        self.c = CSideStream(C.c_void_p(self.stream.cuda_stream), self._events[0], self._events[1])
+
+    def __del__(self):
+        for ev in getattr(self, "_events", []):
+            self._hip.hipEventDestroy(ev)
+
+
 def citrus_process_document(cfg: Config, state: DocumentState, workspace, *, doc: Optional[CResidentDoc] = None,
                             provider: Optional[Callable] = None, first_chunk: int = 0, max_chunks: int = -1,
-                            idx_history=None, idx_history_lm=None, phase_events=None, stream=None) -> int:
+                            idx_history=None, idx_history_lm=None, phase_events=None, stream=None,
+                            side: Optional[SideStream] = None) -> int:
     """Run the chunk loop.  Either ``doc`` (a resident document, served by the
     library's own provider) or ``provider`` (a Python callable
     ``(chunk_index, io: CChunkIO) -> 0 | 1 | negative``) supplies the chunks.
     ``phase_events`` is an optional ctypes array of hipEvent_t handles
-    (EVENTS_PER_STEP per step).  Updates ``state`` in place and returns the
-    number of chunks processed."""
+    (EVENTS_PER_STEP per step).  ``side``: an optional SideStream; the single-cache
+    modes then run selection and gather next to the chunk attention.  Updates
+    ``state`` in place and returns the number of chunks processed."""
     lib = _lib()
     if (doc is None) == (provider is None):
         raise ValueError("give exactly one of doc / provider")
@@ -418,7 +448,8 @@ def citrus_process_document(cfg: Config, state: DocumentState, workspace, *, doc
     st = lib.citrus_process_document(C.byref(cc), fn, user, first_chunk, max_chunks, kc, vc, kl, vl,
                                      C.byref(n_c), C.byref(n_c_lm), C.byref(cur), C.byref(cur_lm), acc,
                                      _ptr(idx_history), _ptr(idx_history_lm), C.byref(done), phase_events, _ptr(workspace),
-                                     0 if workspace is None else workspace.numel(), _stream(stream))
+                                     0 if workspace is None else workspace.numel(), _stream(stream),
+                                     None if side is None else C.byref(side.c))
     del keep
     state.cache_len, state.buffer_index = n_c.value, cur.value
     if dual:

@@ -555,6 +555,12 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
   const int v_off0 = (4 * (q16 / 2) + s16 / 4) * kRowBytes + (v_cl * 16) + 8 * (s16 % 2);
   auto v_off = [&](int e) { return v_off0 ^ (16 * e); };
 
+  // The first step of a row block multiplies p_prev = 0 with the second half of V buffer 1, which nothing has
+  // filled yet in the first row block: zero it once (0 x garbage could be NaN).  Published by the barrier
+  // in front of the first operand reads.
+  *reinterpret_cast<uint4*>(v_s + kTileBytes + 32 * kRowBytes + 16 * tid) = make_uint4(0u, 0u, 0u, 0u);
+  static_assert(WAVES * 64 * 16 == 32 * kRowBytes, "one 16-byte store per thread covers the half tile");
+
   for (int pass = 0; pass < passes; ++pass) {
   const int rb = pass == 0 ? rb_first : rb_second;
   const int row0 = (rb * ts.tiles_per_block + wu / ts.heads_per_block) * kRowsPerWave;
@@ -612,8 +618,8 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
   const int straddle_tile = (n_c % kTileN) ? n_c / kTileN : -1;
   const int ragged_tile = (n % kTileN) ? n / kTileN : -1;
   auto tile_is_simple = [&](int tile) { return tile != straddle_tile && tile != ragged_tile; };
-  auto plan_fill = [&](char* buffers, int tile, __amdgpu_buffer_rsrc_t rs_cache, __amdgpu_buffer_rsrc_t rs_chunk,
-                       int ss_cache, int ss_chunk) {
+  auto plan_fill = [&](char* buffer, int tile, __amdgpu_buffer_rsrc_t rs_cache, __amdgpu_buffer_rsrc_t rs_chunk,
+                       int ss_cache, int ss_chunk) {  // `buffer`: the tile buffer of the right parity
     const int j0 = tile * kTileN;
     const bool in_cache = j0 < n_c;
     const int ss2 = (in_cache ? ss_cache : ss_chunk) * 2;
@@ -621,7 +627,7 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
     hide_loop_invariance(fill_row, fill_seg16);  // formed per fetch: see fill4
     FillPlan fp;
     fp.rs = in_cache ? rs_cache : rs_chunk;
-    fp.lds = buffers + ((tile - t_begin) & 1) * kTileBytes + kFillRows * wu * kRowBytes;
+    fp.lds = buffer + kFillRows * wu * kRowBytes;
     fp.soff = ((in_cache ? j0 : j0 - n_c) + kFillRows * wu) * ss2;
     fp.ss8 = 4 * ss2;
     fp.row_off = fill_row * ss2;
@@ -648,11 +654,21 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
     for (int kk = 0; kk < 8; ++kk) ka[kk].u = *reinterpret_cast<const uint4*>(k_t + k_off(kk));
   };
 
+  // The same with the buffer parity and the half tile as constants: inside the key loop (unrolled over the
+  // two parities) every LDS address is then a per-lane register plus an immediate offset.  No clamp: what is
+  // read past the last tile feeds logits that are never used.
+  auto read_k_ops_at = [&](auto parity, auto half) {
+    const char* k_t = k_s + decltype(parity)::value * kTileBytes + decltype(half)::value * 32 * kRowBytes;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) ka[kk].u = *reinterpret_cast<const uint4*>(k_t + k_off(kk));
+  };
+
   // One step: finish the softmax of half tile h (logits in s_cur) while the logits of h + 1 and the
   // product P(h - 1).V run on the matrix pipe.  Past either end the neighbour is clamped: the
   // logits computed past the end are never used, and p_prev is zero before the first step.
   // With fill_k / fill_v the four fetch instructions of that plan are issued between the MFMAs.
-  auto half_step = [&](int hc, bool fill_k, bool fill_v, const FillPlan& fk, const FillPlan& fv) {
+  // v_t: the V half tile that belongs to half tile hc - 1.
+  auto half_step = [&](int hc, const char* v_t, bool fill_k, bool fill_v, const FillPlan& fk, const FillPlan& fv) {
     const int jb = 32 * hc;
     if (jb + 31 > wave_limit_min) {  // wave-uniform: the causal edge and the ragged end only
       const int lim_rel = limit_lane - jb - 4 * grp;
@@ -687,8 +703,6 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
       }
       m_run = m_new;
     }
-    const int hp = max(hc - 1, h_first);
-    const char* v_t = v_s + (((hp >> 1) - t_begin) & 1) * kTileBytes + (hp & 1) * 32 * kRowBytes;
     const float m_sub = m_run == -INFINITY ? 0.f : m_run;  // a row that has seen nothing yet: exp2(-inf) = 0
     __builtin_amdgcn_sched_barrier(0);
 
@@ -838,22 +852,32 @@ __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, in
 #pragma unroll
   for (int i = 1; i < 16; ++i) mx_cur = fmaxf(mx_cur, s_cur[i]);
   read_k_ops(h_first + 1);
-  for (int jt = t_begin; jt < t_end; ++jt) {
-    half_step(2 * jt, false, false, no_plan, no_plan);
+  // One 64-key tile per call; `parity` is the tile's buffer (t_begin = 0 in this kernel: tile jt lives in
+  // buffer jt % 2), so the loop below alternates two copies of the step whose LDS offsets are constants.
+  static_assert(key_splits == 1, "the tile buffers are addressed by jt % 2");
+  auto tile_step = [&](auto parity, int jt) {
+    constexpr int P = decltype(parity)::value;
+    // P.V of the second half of tile jt - 1 (before the first tile: p_prev = 0 times the zeros written at
+    // kernel start, or times stale finite data in later row blocks)
+    half_step(2 * jt, v_s + (1 - P) * kTileBytes + 32 * kRowBytes, false, false, no_plan, no_plan);
     // Every wave has read the second half of K tile jt and the last of V tile jt - 1: their buffers
     // take K tile jt + 2 and V tile jt + 1, which are first read after the next barrier.
     barrier_after_lds_fill();
-    read_k_ops(2 * jt + 2);  // first half of K tile jt + 1, published by this barrier
+    read_k_ops_at(std::integral_constant<int, 1 - P>{}, std::integral_constant<int, 0>{});  // K tile jt + 1, first half
     // Tiles inside one segment are fetched from within the step, one instruction between two
     // MFMAs (plans of tiles that are not wanted are formed but never used); the others here.
     const bool want_k = jt + 2 < t_end, want_v = jt + 1 < t_end;
     const bool k_inside = want_k && tile_is_simple(jt + 2), v_inside = want_v && tile_is_simple(jt + 1);
     if (want_k && !k_inside) fetch_k(jt + 2);
     if (want_v && !v_inside) fetch_v(jt + 1);
-    const FillPlan fk = plan_fill(k_s, jt + 2, k_rs_cache, k_rs_chunk, k_ss_cache, k_ss_chunk);
-    const FillPlan fv = plan_fill(v_s, jt + 1, v_rs_cache, v_rs_chunk, v_ss_cache, v_ss_chunk);
-    half_step(2 * jt + 1, k_inside, v_inside, fk, fv);
-    read_k_ops(2 * jt + 3);  // second half of K tile jt + 1
+    const FillPlan fk = plan_fill(k_s + P * kTileBytes, jt + 2, k_rs_cache, k_rs_chunk, k_ss_cache, k_ss_chunk);
+    const FillPlan fv = plan_fill(v_s + (1 - P) * kTileBytes, jt + 1, v_rs_cache, v_rs_chunk, v_ss_cache, v_ss_chunk);
+    half_step(2 * jt + 1, v_s + P * kTileBytes, k_inside, v_inside, fk, fv);
+    read_k_ops_at(std::integral_constant<int, 1 - P>{}, std::integral_constant<int, 1>{});  // K tile jt + 1, second half
+  };
+  for (int jt = t_begin; jt < t_end; jt += 2) {
+    tile_step(std::integral_constant<int, 0>{}, jt);
+    if (jt + 1 < t_end) tile_step(std::integral_constant<int, 1>{}, jt + 1);
   }
   {  // the product of the last half tile
     const char* v_t = v_s + ((t_end - 1 - t_begin) & 1) * kTileBytes + 32 * kRowBytes;

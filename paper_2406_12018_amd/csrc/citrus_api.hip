@@ -509,8 +509,11 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
                                 int32_t* buffer_index, int32_t* buffer_index_lm, float* const* acc_score,
                                 int32_t* idx_history,
                                 int32_t* idx_history_lm, int32_t* chunks_done, void* const* phase_events,
-                                void* workspace, size_t workspace_bytes, void* hip_stream) {
+                                void* workspace, size_t workspace_bytes, void* hip_stream,
+                                const citrus_side_stream* side) {
   CITRUS_TRY(check_config(cfg));
+  if (side != nullptr && (side->stream == nullptr || side->fork_event == nullptr || side->join_event == nullptr))
+    return CITRUS_ERR_NULL;
   if (next == nullptr || k_cache == nullptr || v_cache == nullptr || cache_len == nullptr || buffer_index == nullptr)
     return CITRUS_ERR_NULL;
   const bool dual = cfg->cache_mode == CITRUS_CACHE_DUAL;
@@ -558,10 +561,14 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
   int n_c_lm = dual ? *cache_len_lm : 0, cur_lm = dual ? *buffer_index_lm : 0;
   int done = 0;
   citrus_status status = CITRUS_OK;
-  auto mark = [&](int step, int phase) {
+  // selection and gather of the single-cache modes next to the chunk attention, on the caller's second stream
+  const bool overlap = side != nullptr && !dual && !standard;
+  hipStream_t st_side = overlap ? static_cast<hipStream_t>(side->stream) : st;
+  auto mark_on = [&](hipStream_t stream, int step, int phase) {
     if (phase_events != nullptr && phase_events[step * CITRUS_EVENTS_PER_STEP + phase] != nullptr)
-      (void)hipEventRecord(static_cast<hipEvent_t>(phase_events[step * CITRUS_EVENTS_PER_STEP + phase]), st);
+      (void)hipEventRecord(static_cast<hipEvent_t>(phase_events[step * CITRUS_EVENTS_PER_STEP + phase]), stream);
   };
+  auto mark = [&](int step, int phase) { mark_on(st, step, phase); };
 
   // One step of a cache that the document's own chunks evict (Section 4.1): the second cache of DUAL, the
   // only cache of STANDARD.  Marks phases 1..4.
@@ -670,31 +677,50 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
         break;
       ks_att = segments(k_rot, n_c, k_rot_chunk, c);
     }
-    if (dual) {
-      int32_t* idx_lm = idx_history_lm ? idx_history_lm + static_cast<size_t>(done) * units_sel * cfg->budget_lm : idx_lm_ws;
-      const ChunkEvicted t{k_cache_lm, v_cache_lm, &n_c_lm, &cur_lm, cfg->budget_lm, score_lm, idx_lm};
-      if ((status = chunk_evicted_step(t, io, c)) != CITRUS_OK) break;
-    } else {
+    int32_t* idx = idx_history ? idx_history + static_cast<size_t>(done) * units_sel * cfg->budget : idx_ws;
+    // instruction score, selection and gather of the instruction (or only) cache; the last two on `sel_st`
+    auto score_step = [&]() -> citrus_status {
+      CITRUS_TRY(do_instr_score(cfg, dm, qi_att, ks_att, lse_instr, score, st));
+      if (accumulated) CITRUS_TRY(hip_status(launch_score_add(dm, score, acc_score[cur], n, n_c, cfg->cache_capacity, st)));
+      mark(done, 5);
+      return CITRUS_OK;
+    };
+    auto select_gather_step = [&](hipStream_t sel_st) -> citrus_status {
+      CITRUS_TRY(do_topk(cfg, score, n, cfg->budget, idx, sel_st));
+      mark_on(sel_st, done, 6);
+      CITRUS_TRY(do_compact(cfg, dm, ks, vs, idx, cfg->budget, m, k_cache[cur ^ 1], v_cache[cur ^ 1], sel_st));
+      if (accumulated)
+        CITRUS_TRY(hip_status(launch_score_gather(dm, score, idx, acc_score[cur ^ 1], n, m, cfg->budget, sel_heads(cfg),
+                                                  cfg->cache_capacity, sel_st)));
+      mark_on(sel_st, done, 7);
+      return CITRUS_OK;
+    };
+    if (overlap) {
+      if ((status = score_step()) != CITRUS_OK) break;
+      if ((status = hip_status(hipEventRecord(static_cast<hipEvent_t>(side->fork_event), st))) != CITRUS_OK) break;
+      if ((status = hip_status(hipStreamWaitEvent(st_side, static_cast<hipEvent_t>(side->fork_event), 0))) != CITRUS_OK) break;
+      if ((status = select_gather_step(st_side)) != CITRUS_OK) break;
+      if ((status = hip_status(hipEventRecord(static_cast<hipEvent_t>(side->join_event), st_side))) != CITRUS_OK) break;
       if ((status = do_chunk_attn(cfg, dm, q_att, ks_att, vs, io.out, nullptr, nullptr, nullptr, st, q_rope_pos0)) !=
           CITRUS_OK)
         break;
       for (int p = 1; p <= 4; ++p) mark(done, p);
+      // the next step (and whatever the caller enqueues after the call) reads the buffer the gather fills
+      if ((status = hip_status(hipStreamWaitEvent(st, static_cast<hipEvent_t>(side->join_event), 0))) != CITRUS_OK) break;
+    } else {
+      if (dual) {
+        int32_t* idx_lm = idx_history_lm ? idx_history_lm + static_cast<size_t>(done) * units_sel * cfg->budget_lm : idx_lm_ws;
+        const ChunkEvicted t{k_cache_lm, v_cache_lm, &n_c_lm, &cur_lm, cfg->budget_lm, score_lm, idx_lm};
+        if ((status = chunk_evicted_step(t, io, c)) != CITRUS_OK) break;
+      } else {
+        if ((status = do_chunk_attn(cfg, dm, q_att, ks_att, vs, io.out, nullptr, nullptr, nullptr, st, q_rope_pos0)) !=
+            CITRUS_OK)
+          break;
+        for (int p = 1; p <= 4; ++p) mark(done, p);
+      }
+      if ((status = score_step()) != CITRUS_OK) break;
+      if ((status = select_gather_step(st)) != CITRUS_OK) break;
     }
-
-    int32_t* idx = idx_history ? idx_history + static_cast<size_t>(done) * units_sel * cfg->budget : idx_ws;
-    if ((status = do_instr_score(cfg, dm, qi_att, ks_att, lse_instr, score, st)) != CITRUS_OK) break;
-    if (accumulated &&
-        (status = hip_status(launch_score_add(dm, score, acc_score[cur], n, n_c, cfg->cache_capacity, st))) != CITRUS_OK)
-      break;
-    mark(done, 5);
-    if ((status = do_topk(cfg, score, n, cfg->budget, idx, st)) != CITRUS_OK) break;
-    mark(done, 6);
-    if ((status = do_compact(cfg, dm, ks, vs, idx, cfg->budget, m, k_cache[cur ^ 1], v_cache[cur ^ 1], st)) != CITRUS_OK)
-      break;
-    if (accumulated && (status = hip_status(launch_score_gather(dm, score, idx, acc_score[cur ^ 1], n, m, cfg->budget,
-                                                               sel_heads(cfg), cfg->cache_capacity, st))) != CITRUS_OK)
-      break;
-    mark(done, 7);
     cur ^= 1;
     n_c = m;
   }

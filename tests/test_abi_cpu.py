@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert getattr(lib, n) is not None
     header = open(os.path.join(ROOT, "include", "citrus.h")).read()
-    assert B.abi_version() == int(re.search(r"#define\s+CITRUS_ABI_VERSION\s+(\d+)", header).group(1)) == 8
+    assert B.abi_version() == int(re.search(r"#define\s+CITRUS_ABI_VERSION\s+(\d+)", header).group(1)) == 9
 
 
 def test_struct_layouts_match_the_header():
@@ -185,8 +185,13 @@ def test_process_document_validation_and_provider_protocol():
         o.get("cfg", C.byref(c)), o.get("fn", fn), None, o.get("first", 3), -1, o.get("k", two), two_v, None, None,
         C.byref(o.get("n_c", n_c)), None, C.byref(cur), None, o.get("acc", None), None, None, C.byref(done), None,
         o.get("ws", ws),
-        o.get("ws_bytes", big), None)
+        o.get("ws_bytes", big), None, o.get("side", None))
     assert run() == B.OK and calls == [3] and done.value == 0
+    # a side stream needs its stream and both events
+    half_side = B.CSideStream(C.c_void_p(0x70000), C.c_void_p(0x71000), None)
+    assert run(side=C.byref(half_side)) == B.ERR_NULL
+    full_side = B.CSideStream(C.c_void_p(0x70000), C.c_void_p(0x71000), C.c_void_p(0x72000))
+    assert run(side=C.byref(full_side)) == B.OK
     assert run(fn=None) == B.ERR_NULL
     assert run(k=same) == B.ERR_SHAPE
     assert run(n_c=C.c_int32(65)) == B.ERR_SHAPE

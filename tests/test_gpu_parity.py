@@ -736,7 +736,7 @@ def test_decode_step_repeats_bit_identically_and_matches_chunk_attention_of_one_
 # the chunk loop entry point
 # ----------------------------------------------------------------------------
 
-def run_process_document(w, doc, split_at=None, use_python_provider=False):
+def run_process_document(w, doc, split_at=None, use_python_provider=False, use_side_stream=False):
     cfg = api.Config.from_workload(w)
     state = api.DocumentState.allocate(cfg, DEV)
     ws = api.alloc_workspace(cfg, DEV)
@@ -746,7 +746,15 @@ def run_process_document(w, doc, split_at=None, use_python_provider=False):
     if w.cache_mode == api.CACHE_DUAL:
         hist_lm = torch.full((w.n_chunks, w.batch, w.layers, cfg.sel_heads, w.budget_lm), -1, dtype=torch.int32, device=DEV)
     rd = api.resident_doc(cfg, doc["q"], doc["k"], doc["v"], doc["q_instr"], out)
-    if use_python_provider:
+    side = api.SideStream(DEV) if use_side_stream else None
+    if use_side_stream:
+        # selection and gather next to the attention (single-cache modes); twice in a row, so that a second call
+        # starts while the side stream may still hold work of the first
+        done = api.citrus_process_document(cfg, state, ws, doc=rd, idx_history=hist, idx_history_lm=hist_lm, side=side)
+        state.cache_len = state.cache_len_lm = 0
+        state.buffer_index = state.buffer_index_lm = 0
+        done = api.citrus_process_document(cfg, state, ws, doc=rd, idx_history=hist, idx_history_lm=hist_lm, side=side)
+    elif use_python_provider:
         def provider(i, io):
             lo, hi = w.chunk_bounds(i)
             if lo >= w.doc_len:
@@ -811,8 +819,8 @@ def test_process_document_equals_stepwise_and_resumes(case):
     if w.score_mode == api.SCORE_ACCUMULATED:
         assert torch.equal(state.acc_score[state.buffer_index][..., :state.cache_len],
                            run.state.acc_score[run.state.buffer_index][..., :run.state.cache_len])
-    # resume: two calls give the same bits as one; so does a second full run and a Python provider
-    for kw in (dict(split_at=max(1, w.n_chunks // 3)), dict(), dict(use_python_provider=True)):
+    # resume: two calls give the same bits as one; so does a second full run, a Python provider, and a run with a side stream
+    for kw in (dict(split_at=max(1, w.n_chunks // 3)), dict(), dict(use_python_provider=True), dict(use_side_stream=True)):
         state2, out2, hist2, _ = run_process_document(w, doc, **kw)
         assert torch.equal(out2, out) and torch.equal(hist2, hist), kw
         for a, b in zip(state2.current(), state.current()):
