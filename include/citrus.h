@@ -23,12 +23,17 @@
  * ------------------------------------------
  * Memory.  Every pointer is a DEVICE pointer unless its comment says "host".
  *   The caller owns all buffers, including the workspace; the library allocates
- *   and frees no device memory and keeps no mutable global state.
+ *   and frees no device memory.  The only state it keeps between calls is, per
+ *   device, the dynamic-LDS limits it has raised for its kernels (atomics), so
+ *   host threads may call any entry point concurrently.
  * Tensors.  A citrus_tensor is a base pointer plus ELEMENT strides for the
  *   document (b), layer (l), head (h) and sequence (s) axes; the head_dim axis is
  *   contiguous (stride 1).  Rows (one head_dim vector) must start on a 16-byte
  *   boundary, i.e. ptr is 16-byte aligned and every stride is a multiple of
  *   8 (bf16) or 4 (f32) elements.  Element type is citrus_config.dtype.
+ *   The rows of one (b, l, h) unit that a call touches must span less than
+ *   2 GiB ((rows - 1) * stride_s + head_dim elements): the kernels address a
+ *   unit's rows with 32-bit byte offsets.  Larger spans: CITRUS_ERR_SHAPE.
  *   bf16 is the 16-bit brain-float, stored as its raw bits.
  * Heads.  Query head h reads KV head h / G with G = q_heads / kv_heads
  *   (contiguous groups).

@@ -1336,6 +1336,9 @@ __global__ __launch_bounds__(WAVES * 64) void instr_fused_kernel(Dims dm, View q
   }
 }
 
+constexpr size_t kFusedLdsBudget = 150 * 1024;  // of the CU's 160 KB
+constexpr int kFusedKeyTilesInRegs = 5;           // 160 of a wave's 256 registers
+
 template <int QT_TOTAL, int Q_SPLIT, int WAVES>
 size_t instr_fused_lds_bytes(int n) {
   constexpr int QROWS = QT_TOTAL * 32;
@@ -1349,14 +1352,12 @@ hipError_t instr_fused_launch(const Dims& dm, View q, int rows, Segments ks, flo
   const size_t lds = instr_fused_lds_bytes<QT_TOTAL, Q_SPLIT, WAVES>(ks.n_c + ks.c);
   auto kern = instr_fused_kernel<QT_TOTAL, Q_SPLIT, WAVES, KREG>;
   static LdsLimit limit;
-  const hipError_t e = raise_lds_limit(limit, reinterpret_cast<const void*>(kern), static_cast<int>(lds));
+  const hipError_t e = raise_lds_limit(limit, reinterpret_cast<const void*>(kern), static_cast<int>(kFusedLdsBudget));
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(dm.B * dm.L * dm.Hkv), dim3(WAVES * 64), lds, st, dm, q, rows, ks, score);
   return hipGetLastError();
 }
 
-constexpr size_t kFusedLdsBudget = 150 * 1024;  // of the CU's 160 KB
-constexpr int kFusedKeyTilesInRegs = 5;           // 160 of a wave's 256 registers
 
 }  // namespace
 

@@ -64,13 +64,18 @@ Dims dims_of(const citrus_config* c) {
 
 float rope_base_of(const citrus_config* c) { return c->rope_base > 0.0f ? c->rope_base : 10000.0f; }
 
-// 16-byte row alignment: pointer and every stride.
-citrus_status check_tensor(const citrus_tensor& t, int dtype, bool may_be_null) {
+// 16-byte row alignment: pointer and every stride.  `rows`: the sequence rows of a (b, l, h) unit the call may
+// touch; they must span less than 2 GiB, because the kernels address a unit's rows with 32-bit byte offsets.
+citrus_status check_tensor(const citrus_config* c, const citrus_tensor& t, int64_t rows, bool may_be_null) {
   if (t.ptr == nullptr) return may_be_null ? CITRUS_OK : CITRUS_ERR_NULL;
-  const int64_t q = 16 / elem_bytes(dtype);
+  const int esz = elem_bytes(c->dtype);
+  const int64_t q = 16 / esz;
   if (reinterpret_cast<uintptr_t>(t.ptr) % 16 != 0) return CITRUS_ERR_SHAPE;
   if (t.stride_b % q || t.stride_l % q || t.stride_h % q || t.stride_s % q) return CITRUS_ERR_SHAPE;
   if (t.stride_s <= 0) return CITRUS_ERR_SHAPE;
+  constexpr int64_t kUnitSpan = int64_t{1} << 31;
+  if (t.stride_s >= kUnitSpan) return CITRUS_ERR_SHAPE;
+  if (rows > 0 && ((rows - 1) * t.stride_s + c->head_dim) * esz >= kUnitSpan) return CITRUS_ERR_SHAPE;
   return CITRUS_OK;
 }
 
@@ -160,11 +165,13 @@ citrus_status do_chunk_attn(const citrus_config* c, const Dims& dm, const citrus
   const bool mfma = mfma_path_supported(c->dtype, dm);
   if (q_rope_pos0 >= 0 && !mfma) return CITRUS_ERR_UNSUPPORTED;
   const bool fused_lse = lse_cache != nullptr && mfma && attn_mfma_emits_cache_lse(ks, 1, make_view(out));
+  // in-kernel query rotation together with a cache-only normaliser that needs a pass of its own: not
+  // combined by any caller (decided before anything is launched)
+  if (q_rope_pos0 >= 0 && lse_cache != nullptr && !fused_lse) return CITRUS_ERR_UNSUPPORTED;
   if (fused_lse || q_rope_pos0 >= 0) {
     CITRUS_TRY(hip_status(launch_attn_mfma(dm, make_view(q), ks.c, ks, vs, /*causal=*/1, make_view(out), lse,
                                            fused_lse ? lse_cache : nullptr, 1, nullptr, st, q_rope_pos0,
                                            rope_base_of(c))));
-    if (lse_cache != nullptr && !fused_lse) return CITRUS_ERR_UNSUPPORTED;  // not combined by any caller
   } else {
     CITRUS_TRY(hip_status(run_attn(c, dm, make_view(q), ks.c, ks, vs, /*causal=*/1, make_view(out), lse, st)));
     if (lse_cache != nullptr) {
@@ -271,6 +278,35 @@ float* cache_score_block(const citrus_config* c, void* workspace, int rows) {
   return nullptr;
 }
 
+// Argument checks shared by the two forms of the eviction of a cache by a text.
+citrus_status check_evict_args(const citrus_config* cfg, const citrus_tensor& q, int rows, const citrus_tensor& k_cache,
+                               const citrus_tensor& v_cache, int cache_len, int k, const citrus_tensor& k_new,
+                               const citrus_tensor& v_new) {
+  CITRUS_TRY(check_config(cfg));
+  if (rows < 1 || cache_len < 1 || cache_len > cfg->cache_capacity || k < 1 || k > cfg->budget) return CITRUS_ERR_SHAPE;
+  CITRUS_TRY(check_tensor(cfg, q, rows, false));
+  CITRUS_TRY(check_tensor(cfg, k_cache, cache_len, false));
+  CITRUS_TRY(check_tensor(cfg, v_cache, cache_len, false));
+  CITRUS_TRY(check_tensor(cfg, k_new, k, false));
+  CITRUS_TRY(check_tensor(cfg, v_new, k, false));
+  if (k_new.ptr == k_cache.ptr || v_new.ptr == v_cache.ptr) return CITRUS_ERR_SHAPE;
+  return CITRUS_OK;
+}
+
+// Score of the cache by the rows of q, selection, gather.  lse_ws: partial-softmax block for `rows` query rows;
+// score: B*L*Hkv*cache_len floats; idx: B*L*Hsel*k positions.  A cache that fits stays whole: the selection is
+// then the identity and reads no score.
+citrus_status do_evict_cache(const citrus_config* cfg, const citrus_tensor& q, int rows, const citrus_tensor& k_cache,
+                             const citrus_tensor& v_cache, int cache_len, int k, const citrus_tensor& k_new,
+                             const citrus_tensor& v_new, int32_t* idx, float* lse_ws, float* score, hipStream_t st) {
+  const Dims dm = dims_of(cfg);
+  const int m = cache_len < k ? cache_len : k;
+  if (cache_len > k) CITRUS_TRY(do_cache_score(cfg, dm, q, rows, k_cache, cache_len, nullptr, lse_ws, score, st));
+  CITRUS_TRY(do_topk(cfg, score, cache_len, k, idx, st));
+  const Segments ks = cache_only(k_cache, cache_len), vs = cache_only(v_cache, cache_len);
+  return do_compact(cfg, dm, ks, vs, idx, k, m, k_new, v_new, st);
+}
+
 }  // namespace
 
 extern "C" {
@@ -302,12 +338,12 @@ int32_t citrus_chunk_attn(const citrus_config* cfg, citrus_tensor q, citrus_tens
   CITRUS_TRY(check_config(cfg));
   CITRUS_TRY(check_lengths(cfg, cache_len, chunk_len));
   if (lse_cache != nullptr && cache_len == 0) return CITRUS_ERR_SHAPE;
-  CITRUS_TRY(check_tensor(q, cfg->dtype, false));
-  CITRUS_TRY(check_tensor(out, cfg->dtype, false));
-  CITRUS_TRY(check_tensor(k_chunk, cfg->dtype, false));
-  CITRUS_TRY(check_tensor(v_chunk, cfg->dtype, false));
-  CITRUS_TRY(check_tensor(k_cache, cfg->dtype, cache_len == 0));
-  CITRUS_TRY(check_tensor(v_cache, cfg->dtype, cache_len == 0));
+  CITRUS_TRY(check_tensor(cfg, q, chunk_len, false));
+  CITRUS_TRY(check_tensor(cfg, out, chunk_len, false));
+  CITRUS_TRY(check_tensor(cfg, k_chunk, chunk_len, false));
+  CITRUS_TRY(check_tensor(cfg, v_chunk, chunk_len, false));
+  CITRUS_TRY(check_tensor(cfg, k_cache, cache_len, cache_len == 0));
+  CITRUS_TRY(check_tensor(cfg, v_cache, cache_len, cache_len == 0));
   if (lm_score != nullptr && lse == nullptr) {
     CITRUS_TRY(check_workspace(cfg, workspace, workspace_bytes));
     lse = reinterpret_cast<float*>(static_cast<char*>(workspace) + workspace_layout(cfg).lse_chunk);
@@ -324,9 +360,9 @@ int32_t citrus_instr_score(const citrus_config* cfg, citrus_tensor q_instr, citr
   CITRUS_TRY(check_config(cfg));
   CITRUS_TRY(check_lengths(cfg, cache_len, chunk_len));
   if (score == nullptr) return CITRUS_ERR_NULL;
-  CITRUS_TRY(check_tensor(q_instr, cfg->dtype, false));
-  CITRUS_TRY(check_tensor(k_chunk, cfg->dtype, false));
-  CITRUS_TRY(check_tensor(k_cache, cfg->dtype, cache_len == 0));
+  CITRUS_TRY(check_tensor(cfg, q_instr, cfg->instr_len, false));
+  CITRUS_TRY(check_tensor(cfg, k_chunk, chunk_len, false));
+  CITRUS_TRY(check_tensor(cfg, k_cache, cache_len, cache_len == 0));
   CITRUS_TRY(check_workspace(cfg, workspace, workspace_bytes));
   const Dims dm = dims_of(cfg);
   float* lse_ws = reinterpret_cast<float*>(static_cast<char*>(workspace) + workspace_layout(cfg).lse_instr);
@@ -340,8 +376,8 @@ int32_t citrus_cache_score(const citrus_config* cfg, citrus_tensor q, int32_t ro
   CITRUS_TRY(check_config(cfg));
   if (rows < 1 || cache_len < 1 || cache_len > cfg->cache_capacity) return CITRUS_ERR_SHAPE;
   if (score == nullptr) return CITRUS_ERR_NULL;
-  CITRUS_TRY(check_tensor(q, cfg->dtype, false));
-  CITRUS_TRY(check_tensor(k_cache, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(cfg, q, rows, false));
+  CITRUS_TRY(check_tensor(cfg, k_cache, cache_len, false));
   if (lse_cache != nullptr) {  // no workspace needed: the rows' normalisers are given
     if (rows > cfg->chunk_len && rows > cfg->instr_len) return CITRUS_ERR_SHAPE;
     return do_cache_score(cfg, dims_of(cfg), q, rows, k_cache, cache_len, lse_cache, nullptr, score,
@@ -358,37 +394,24 @@ int32_t citrus_evict_cache(const citrus_config* cfg, citrus_tensor q, int32_t ro
                            citrus_tensor v_cache, int32_t cache_len, int32_t k, citrus_tensor k_new,
                            citrus_tensor v_new, int32_t* idx, void* workspace, size_t workspace_bytes,
                            void* hip_stream) {
-  CITRUS_TRY(check_config(cfg));
-  if (rows < 1 || cache_len < 1 || cache_len > cfg->cache_capacity || k < 1 || k > cfg->budget) return CITRUS_ERR_SHAPE;
-  CITRUS_TRY(check_tensor(q, cfg->dtype, false));
-  CITRUS_TRY(check_tensor(k_cache, cfg->dtype, false));
-  CITRUS_TRY(check_tensor(v_cache, cfg->dtype, false));
-  CITRUS_TRY(check_tensor(k_new, cfg->dtype, false));
-  CITRUS_TRY(check_tensor(v_new, cfg->dtype, false));
-  if (k_new.ptr == k_cache.ptr || v_new.ptr == v_cache.ptr) return CITRUS_ERR_SHAPE;
+  CITRUS_TRY(check_evict_args(cfg, q, rows, k_cache, v_cache, cache_len, k, k_new, v_new));
   CITRUS_TRY(check_workspace(cfg, workspace, workspace_bytes));
   float* lse_ws = cache_score_block(cfg, workspace, rows);
   if (lse_ws == nullptr) return CITRUS_ERR_SHAPE;
-  const Dims dm = dims_of(cfg);
   const Workspace wl = workspace_layout(cfg);
   char* ws = static_cast<char*>(workspace);
   float* score = reinterpret_cast<float*>(ws + wl.score);
   if (idx == nullptr) idx = reinterpret_cast<int32_t*>(ws + wl.idx);
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  const int m = cache_len < k ? cache_len : k;
-  // a cache that fits stays whole: the selection is the identity and reads no score
-  if (cache_len > k) CITRUS_TRY(do_cache_score(cfg, dm, q, rows, k_cache, cache_len, nullptr, lse_ws, score, st));
-  CITRUS_TRY(do_topk(cfg, score, cache_len, k, idx, st));
-  const Segments ks = cache_only(k_cache, cache_len), vs = cache_only(v_cache, cache_len);
-  return do_compact(cfg, dm, ks, vs, idx, k, m, k_new, v_new, st);
+  return do_evict_cache(cfg, q, rows, k_cache, v_cache, cache_len, k, k_new, v_new, idx, lse_ws, score,
+                        static_cast<hipStream_t>(hip_stream));
 }
 
 int32_t citrus_rope(const citrus_config* cfg, citrus_tensor x, int32_t heads, int32_t rows, int32_t pos0,
                     citrus_tensor y, void* hip_stream) {
   CITRUS_TRY(check_config(cfg));
   if (heads < 1 || heads > 65535 || rows < 0 || pos0 < 0) return CITRUS_ERR_SHAPE;
-  CITRUS_TRY(check_tensor(x, cfg->dtype, false));
-  CITRUS_TRY(check_tensor(y, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(cfg, x, rows, false));
+  CITRUS_TRY(check_tensor(cfg, y, rows, false));
   return hip_status(launch_rope(cfg->dtype, dims_of(cfg), make_view(x), make_view(y), heads, rows, pos0,
                                 rope_base_of(cfg), static_cast<hipStream_t>(hip_stream)));
 }
@@ -398,12 +421,12 @@ int32_t citrus_decode_step(const citrus_config* cfg, citrus_tensor q, citrus_ten
                            void* workspace, size_t workspace_bytes, void* hip_stream) {
   CITRUS_TRY(check_config(cfg));
   if (cache_len < 0 || cache_len >= cfg->cache_capacity) return CITRUS_ERR_SHAPE;
-  CITRUS_TRY(check_tensor(q, cfg->dtype, false));
-  CITRUS_TRY(check_tensor(k_new, cfg->dtype, false));
-  CITRUS_TRY(check_tensor(v_new, cfg->dtype, false));
-  CITRUS_TRY(check_tensor(k_cache, cfg->dtype, false));
-  CITRUS_TRY(check_tensor(v_cache, cfg->dtype, false));
-  CITRUS_TRY(check_tensor(out, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(cfg, q, 1, false));
+  CITRUS_TRY(check_tensor(cfg, k_new, 1, false));
+  CITRUS_TRY(check_tensor(cfg, v_new, 1, false));
+  CITRUS_TRY(check_tensor(cfg, k_cache, cache_len + 1, false));
+  CITRUS_TRY(check_tensor(cfg, v_cache, cache_len + 1, false));
+  CITRUS_TRY(check_tensor(cfg, out, 1, false));
   if (k_new.ptr == k_cache.ptr || v_new.ptr == v_cache.ptr) return CITRUS_ERR_SHAPE;
   CITRUS_TRY(check_workspace(cfg, workspace, workspace_bytes));
   const Dims dm = dims_of(cfg);
@@ -464,12 +487,12 @@ int32_t citrus_kv_compact(const citrus_config* cfg, citrus_tensor k_cache, citru
   CITRUS_TRY(check_lengths(cfg, cache_len, chunk_len));
   if (idx == nullptr) return CITRUS_ERR_NULL;
   if (m < 1 || m > cfg->cache_capacity || idx_pitch < m) return CITRUS_ERR_SHAPE;
-  CITRUS_TRY(check_tensor(k_chunk, cfg->dtype, false));
-  CITRUS_TRY(check_tensor(v_chunk, cfg->dtype, false));
-  CITRUS_TRY(check_tensor(k_cache, cfg->dtype, cache_len == 0));
-  CITRUS_TRY(check_tensor(v_cache, cfg->dtype, cache_len == 0));
-  CITRUS_TRY(check_tensor(k_new, cfg->dtype, false));
-  CITRUS_TRY(check_tensor(v_new, cfg->dtype, false));
+  CITRUS_TRY(check_tensor(cfg, k_chunk, chunk_len, false));
+  CITRUS_TRY(check_tensor(cfg, v_chunk, chunk_len, false));
+  CITRUS_TRY(check_tensor(cfg, k_cache, cache_len, cache_len == 0));
+  CITRUS_TRY(check_tensor(cfg, v_cache, cache_len, cache_len == 0));
+  CITRUS_TRY(check_tensor(cfg, k_new, m, false));
+  CITRUS_TRY(check_tensor(cfg, v_new, m, false));
   if (k_new.ptr == k_cache.ptr || v_new.ptr == v_cache.ptr || k_new.ptr == k_chunk.ptr || v_new.ptr == v_chunk.ptr)
     return CITRUS_ERR_SHAPE;
   const Dims dm = dims_of(cfg);
@@ -525,11 +548,11 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
   if (accumulated && acc_score[0] == acc_score[1]) return CITRUS_ERR_SHAPE;
   if (first_chunk < 0) return CITRUS_ERR_SHAPE;
   for (int i = 0; i < 2; ++i) {
-    CITRUS_TRY(check_tensor(k_cache[i], cfg->dtype, false));
-    CITRUS_TRY(check_tensor(v_cache[i], cfg->dtype, false));
+    CITRUS_TRY(check_tensor(cfg, k_cache[i], cfg->cache_capacity, false));
+    CITRUS_TRY(check_tensor(cfg, v_cache[i], cfg->cache_capacity, false));
     if (dual) {
-      CITRUS_TRY(check_tensor(k_cache_lm[i], cfg->dtype, false));
-      CITRUS_TRY(check_tensor(v_cache_lm[i], cfg->dtype, false));
+      CITRUS_TRY(check_tensor(cfg, k_cache_lm[i], cfg->cache_capacity, false));
+      CITRUS_TRY(check_tensor(cfg, v_cache_lm[i], cfg->cache_capacity, false));
     }
   }
   if (k_cache[0].ptr == k_cache[1].ptr || v_cache[0].ptr == v_cache[1].ptr) return CITRUS_ERR_SHAPE;
@@ -629,11 +652,11 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
     if (rc != 0) { status = CITRUS_ERR_PROVIDER; break; }
     const int c = io.chunk_len;
     if (c < 1 || c > cfg->chunk_len) { status = CITRUS_ERR_SHAPE; break; }
-    if ((status = check_tensor(io.q, cfg->dtype, false)) != CITRUS_OK) break;
-    if ((status = check_tensor(io.k, cfg->dtype, false)) != CITRUS_OK) break;
-    if ((status = check_tensor(io.v, cfg->dtype, false)) != CITRUS_OK) break;
-    if ((status = check_tensor(io.q_instr, cfg->dtype, /*may_be_null=*/standard)) != CITRUS_OK) break;
-    if ((status = check_tensor(io.out, cfg->dtype, false)) != CITRUS_OK) break;
+    if ((status = check_tensor(cfg, io.q, c, false)) != CITRUS_OK) break;
+    if ((status = check_tensor(cfg, io.k, c, false)) != CITRUS_OK) break;
+    if ((status = check_tensor(cfg, io.v, c, false)) != CITRUS_OK) break;
+    if ((status = check_tensor(cfg, io.q_instr, cfg->instr_len, /*may_be_null=*/standard)) != CITRUS_OK) break;
+    if ((status = check_tensor(cfg, io.out, c, false)) != CITRUS_OK) break;
 
     mark(done, 0);
     if (standard) {
@@ -699,14 +722,23 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
       if ((status = score_step()) != CITRUS_OK) break;
       if ((status = hip_status(hipEventRecord(static_cast<hipEvent_t>(side->fork_event), st))) != CITRUS_OK) break;
       if ((status = hip_status(hipStreamWaitEvent(st_side, static_cast<hipEvent_t>(side->fork_event), 0))) != CITRUS_OK) break;
-      if ((status = select_gather_step(st_side)) != CITRUS_OK) break;
-      if ((status = hip_status(hipEventRecord(static_cast<hipEvent_t>(side->join_event), st_side))) != CITRUS_OK) break;
-      if ((status = do_chunk_attn(cfg, dm, q_att, ks_att, vs, io.out, nullptr, nullptr, nullptr, st, q_rope_pos0)) !=
-          CITRUS_OK)
-        break;
-      for (int p = 1; p <= 4; ++p) mark(done, p);
-      // the next step (and whatever the caller enqueues after the call) reads the buffer the gather fills
-      if ((status = hip_status(hipStreamWaitEvent(st, static_cast<hipEvent_t>(side->join_event), 0))) != CITRUS_OK) break;
+      // From here on the side stream may hold work of this step.  Whatever fails below, hip_stream is ordered
+      // behind that work before the call returns: the next step, and whatever the caller enqueues after the
+      // call, reads the buffer the gather fills.
+      status = select_gather_step(st_side);
+      const hipError_t joined = hipEventRecord(static_cast<hipEvent_t>(side->join_event), st_side);
+      if (status == CITRUS_OK) {
+        status = do_chunk_attn(cfg, dm, q_att, ks_att, vs, io.out, nullptr, nullptr, nullptr, st, q_rope_pos0);
+        for (int p = 1; p <= 4; ++p) mark(done, p);
+      }
+      hipError_t ordered = joined;
+      if (ordered == hipSuccess) ordered = hipStreamWaitEvent(st, static_cast<hipEvent_t>(side->join_event), 0);
+      if (ordered != hipSuccess) {
+        // the event could not order the two streams: drain the side stream on the host (error path only)
+        (void)hipStreamSynchronize(st_side);
+        if (status == CITRUS_OK) status = CITRUS_ERR_DEVICE;
+      }
+      if (status != CITRUS_OK) break;
     } else {
       if (dual) {
         int32_t* idx_lm = idx_history_lm ? idx_history_lm + static_cast<size_t>(done) * units_sel * cfg->budget_lm : idx_lm_ws;

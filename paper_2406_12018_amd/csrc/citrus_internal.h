@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "citrus.h"
 
 namespace citrus {
@@ -76,19 +78,26 @@ hipError_t launch_rope(int dtype, const Dims& dm, View x, View y, int heads, int
                        hipStream_t st);
 
 // Kernels that take more than 64 KB of dynamic LDS need their limit raised once per device.  `state` is a
-// static object next to the launch; the current device's slot remembers the largest size granted.
+// static object next to the launch; the current device's slot remembers the largest size granted.  The
+// slots are atomics (relaxed order is enough: the value only saves a repeated hipFuncSetAttribute, which
+// the runtime serialises itself), so host threads may call the launchers concurrently.  Every launcher
+// asks for ONE size per kernel (its maximum), so two threads can never lower each other's limit.
 constexpr int kMaxDevices = 64;
 struct LdsLimit {
-  int granted[kMaxDevices] = {};
+  std::atomic<int> granted[kMaxDevices] = {};
 };
 inline hipError_t raise_lds_limit(LdsLimit& state, const void* kernel, int bytes) {
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   const bool tracked = dev >= 0 && dev < kMaxDevices;
-  if (tracked && state.granted[dev] >= bytes) return hipSuccess;
+  if (tracked && state.granted[dev].load(std::memory_order_relaxed) >= bytes) return hipSuccess;
   e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-  if (e == hipSuccess && tracked) state.granted[dev] = bytes;
+  if (e == hipSuccess && tracked) {
+    int seen = state.granted[dev].load(std::memory_order_relaxed);
+    while (seen < bytes && !state.granted[dev].compare_exchange_weak(seen, bytes, std::memory_order_relaxed)) {
+    }
+  }
   return e;
 }
 

@@ -230,3 +230,64 @@ def test_resident_provider_slices_the_document():
     assert io.q_instr.ptr == 0x500000 + 2 * 4096 * 2
     assert lib.citrus_resident_provider(C.byref(doc), 3, None, C.byref(io)) == 1
     assert lib.citrus_resident_provider(None, 0, None, C.byref(io)) < 0
+
+
+def test_unit_span_of_two_gib_or_more_is_rejected_before_any_launch():
+    """The kernels address the rows of one (b, l, h) unit with 32-bit byte offsets: every entry point refuses a
+    tensor whose touched rows span 2 GiB or more, on the host."""
+    lib = B._lib()
+    c = cfg(dtype=B.BF16, head_dim=128, chunk_len=512, budget=768, instr_len=64).c()
+    wide = lambda rows: B.CTensor(0x1000, 1 << 40, 1 << 38, 1 << 36, (((1 << 31) // 2 - 128) // (rows - 1)) // 8 * 8 + 8)
+    ok = lambda rows: B.CTensor(0x1000, 1 << 40, 1 << 38, 1 << 36, (((1 << 31) // 2 - 128) // (rows - 1)) // 8 * 8 - 8)
+    attn = lambda q, kc: lib.citrus_chunk_attn(C.byref(c), q, kc, fake(), 0, fake(), fake(), 512, fake(), None, None,
+                                                None, None, 0, None)
+    assert attn(wide(512), fake()) == B.ERR_SHAPE
+    assert attn(B.CTensor(0x1000, 0, 0, 0, 1 << 31), fake()) == B.ERR_SHAPE
+    # the same stride is fine for fewer rows: the bound is on what the call touches (checked up to the next
+    # validation step, which needs no device either: a missing workspace)
+    sc, ws = C.c_void_p(0x2000), C.c_void_p(0x10000)
+    score = lambda qi: lib.citrus_instr_score(C.byref(c), qi, fake(), 0, fake(), 8, sc, None, 0, None)
+    assert score(wide(64)) == B.ERR_SHAPE
+    assert score(ok(64)) == B.ERR_WORKSPACE
+    assert lib.citrus_kv_compact(C.byref(c), fake(), fake(), 4, fake(), fake(), 8, C.c_void_p(0x2000), 768, 768,
+                                 wide(768), fake(0xA000), None) == B.ERR_SHAPE
+    assert lib.citrus_rope(C.byref(c), wide(100), 4, 100, 0, fake(), None) == B.ERR_SHAPE
+
+
+def test_concurrent_host_threads_get_the_same_codes():
+    """Entry points keep no unsynchronised state: many threads validating at once all see the codes a single
+    thread sees."""
+    import threading
+    lib = B._lib()
+    c = cfg().c()
+    null = B.CTensor(None, 0, 0, 0, 0)
+    sc, ws = C.c_void_p(0x2000), C.c_void_p(0x10000)
+
+    def calls():
+        return [
+            lib.citrus_chunk_attn(C.byref(c), null, fake(), fake(), 0, fake(), fake(), 8, fake(), None, None, None, None, 0, None),
+            lib.citrus_chunk_attn(C.byref(c), fake(), fake(), fake(), 65, fake(), fake(), 8, fake(), None, None, None, None, 0, None),
+            lib.citrus_instr_score(C.byref(c), fake(), fake(), 0, fake(), 8, sc, ws, 16, None),
+            lib.citrus_topk_select(C.byref(c), sc, 0, 4, C.c_void_p(0x3000), None, 0, None),
+            lib.citrus_evict_cache(C.byref(c), fake(), 8, fake(0x5000), fake(0x6000), 40, 0, fake(0x9000), fake(0xA000), None, ws, 1 << 30, None),
+            lib.citrus_rope(C.byref(c), fake(), 4, 0, 0, fake(), None),
+            int(lib.citrus_workspace_bytes(C.byref(c)) > 0),
+        ]
+
+    expected = calls()
+    assert expected == [B.ERR_NULL, B.ERR_SHAPE, B.ERR_WORKSPACE, B.ERR_SHAPE, B.ERR_SHAPE, B.OK, 1]
+    results, errors = [], []
+
+    def worker():
+        try:
+            for _ in range(200):
+                results.append(calls())
+        except Exception as e:  # pragma: no cover
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker) for _ in range(8)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors and len(results) == 1600 and all(r == expected for r in results)
