@@ -24,8 +24,9 @@
  * Memory.  Every pointer is a DEVICE pointer unless its comment says "host".
  *   The caller owns all buffers, including the workspace; the library allocates
  *   and frees no device memory.  The only state it keeps between calls is, per
- *   device, the dynamic-LDS limits it has raised for its kernels (atomics), so
- *   host threads may call any entry point concurrently.
+ *   device, the dynamic-LDS limits it has raised for its kernels and the address
+ *   of its static scratch array (see citrus_evict_cache_static); both are
+ *   atomics, so host threads may call any entry point concurrently.
  * Tensors.  A citrus_tensor is a base pointer plus ELEMENT strides for the
  *   document (b), layer (l), head (h) and sequence (s) axes; the head_dim axis is
  *   contiguous (stride 1).  Rows (one head_dim vector) must start on a 16-byte
@@ -63,7 +64,7 @@
 extern "C" {
 #endif
 
-#define CITRUS_ABI_VERSION 9
+#define CITRUS_ABI_VERSION 10
 #define CITRUS_EVENTS_PER_STEP 8
 
 typedef enum {
@@ -247,6 +248,24 @@ int32_t citrus_evict_cache(const citrus_config* cfg, citrus_tensor q, int32_t ro
                            citrus_tensor v_cache, int32_t cache_len, int32_t k, citrus_tensor k_new,
                            citrus_tensor v_new, int32_t* idx, void* workspace, size_t workspace_bytes,
                            void* hip_stream);
+
+/*
+ * citrus_evict_cache for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * bit-identical results; the partial softmax sums, the scores and (with idx == NULL) the kept positions live
+ * in a fixed array of citrus_static_scratch_bytes() bytes (16 MiB) inside the library's device image instead
+ * of a workspace.  Every GPU the library runs on holds its own copy of that array until the process ends.
+ * The call allocates and frees nothing and synchronises nothing.  Its need,
+ *   B*L*Hq*rows*64 + B*L*Hkv*cache_len*4 + B*L*Hsel*k*4 bytes (each term rounded up to 256),
+ * must fit the array, else CITRUS_ERR_WORKSPACE (nothing is launched; use citrus_evict_cache).
+ * The array keeps the previous call's contents and every part a call reads is written by that call first.
+ * All calls on one GPU share the array: two calls that overlap in time on one GPU (different streams or
+ * host threads) race; order them on one stream or with events.
+ */
+size_t citrus_static_scratch_bytes(void);
+int32_t citrus_evict_cache_static(const citrus_config* cfg, citrus_tensor q, int32_t rows, citrus_tensor k_cache,
+                                  citrus_tensor v_cache, int32_t cache_len, int32_t k, citrus_tensor k_new,
+                                  citrus_tensor v_new, int32_t* idx, void* hip_stream);
 
 /*
  * Rotary position embedding at explicit positions (the position shift mechanism of Section 5.3,

@@ -30,7 +30,8 @@ OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE, ERR_PROVIDE
 
 EXPORTS = (
     "citrus_abi_version", "citrus_status_string", "citrus_workspace_bytes", "citrus_chunk_attn",
-    "citrus_instr_score", "citrus_cache_score", "citrus_evict_cache", "citrus_decode_step", "citrus_rope", "citrus_score_accumulate", "citrus_score_gather", "citrus_topk_select", "citrus_kv_compact", "citrus_resident_provider",
+    "citrus_instr_score", "citrus_cache_score", "citrus_evict_cache", "citrus_evict_cache_static",
+    "citrus_static_scratch_bytes", "citrus_decode_step", "citrus_rope", "citrus_score_accumulate", "citrus_score_gather", "citrus_topk_select", "citrus_kv_compact", "citrus_resident_provider",
     "citrus_process_document",
 )
 
@@ -97,6 +98,10 @@ def _lib():
     lib.citrus_cache_score.argtypes = [P(CConfig), CTensor, I, CTensor, I, V, V, V, S, V]
     lib.citrus_evict_cache.restype = I
     lib.citrus_evict_cache.argtypes = [P(CConfig), CTensor, I, CTensor, CTensor, I, I, CTensor, CTensor, V, V, S, V]
+    lib.citrus_evict_cache_static.restype = I
+    lib.citrus_evict_cache_static.argtypes = [P(CConfig), CTensor, I, CTensor, CTensor, I, I, CTensor, CTensor, V, V]
+    lib.citrus_static_scratch_bytes.restype = S
+    lib.citrus_static_scratch_bytes.argtypes = []
     lib.citrus_decode_step.restype = I
     lib.citrus_decode_step.argtypes = [P(CConfig), CTensor, CTensor, CTensor, CTensor, CTensor, I, CTensor, V, S, V]
     lib.citrus_rope.restype = I
@@ -270,6 +275,21 @@ def citrus_evict_cache(cfg: Config, q, k_cache, v_cache, cache_len: int, k: int,
                                    tensor(k_new), tensor(v_new), _ptr(idx), _ptr(workspace),
                                    0 if workspace is None else workspace.numel(), _stream(stream))
     _check(st, "citrus_evict_cache")
+    return min(k, cache_len)
+
+
+def static_scratch_bytes() -> int:
+    return int(_lib().citrus_static_scratch_bytes())
+
+
+def citrus_evict_cache_static(cfg: Config, q, k_cache, v_cache, cache_len: int, k: int, k_new, v_new, idx=None,
+                              stream=None, rows: Optional[int] = None) -> int:
+    """citrus_evict_cache without a workspace: scratch lives in the library's static device array."""
+    rows = q.shape[3] if rows is None else rows
+    cc = cfg.c()
+    st = _lib().citrus_evict_cache_static(C.byref(cc), tensor(q), rows, tensor(k_cache), tensor(v_cache), cache_len, k,
+                                          tensor(k_new), tensor(v_new), _ptr(idx), _stream(stream))
+    _check(st, "citrus_evict_cache_static")
     return min(k, cache_len)
 
 

@@ -307,6 +307,46 @@ citrus_status do_evict_cache(const citrus_config* cfg, const citrus_tensor& q, i
   return do_compact(cfg, dm, ks, vs, idx, k, m, k_new, v_new, st);
 }
 
+// ---- device scratch that lives in the library's own image, for callers that cannot allocate ----
+// One copy per GPU, held from the moment the library's code is loaded on that GPU until the process ends.
+// `scratch` is only a host-side name for the array: its device address differs per GPU and is looked up once
+// per device (hipGetSymbolAddress) and kept; host code passes that address, never the name, to kernels.
+constexpr size_t kStaticScratchBytes = size_t{16} << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+std::atomic<char*> g_scratch_base[kMaxDevices] = {};
+
+citrus_status static_scratch_base(char** base) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return CITRUS_ERR_DEVICE;
+  if (dev < 0 || dev >= kMaxDevices) return CITRUS_ERR_UNSUPPORTED;
+  char* p = g_scratch_base[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    void* sym = nullptr;
+    if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || sym == nullptr) return CITRUS_ERR_DEVICE;
+    p = static_cast<char*>(sym);
+    g_scratch_base[dev].store(p, std::memory_order_release);  // two threads racing here store the same address
+  }
+  *base = p;
+  return CITRUS_OK;
+}
+
+// What citrus_evict_cache_static keeps in the array, sized by the call's own arguments.
+struct StaticEvictLayout {
+  size_t lse, score, idx, total;
+};
+StaticEvictLayout static_evict_layout(const citrus_config* c, int rows, int cache_len, int k) {
+  const size_t units_q = static_cast<size_t>(c->batch) * c->layers * c->q_heads;
+  const size_t units_kv = static_cast<size_t>(c->batch) * c->layers * c->kv_heads;
+  const size_t units_sel = static_cast<size_t>(c->batch) * c->layers * sel_heads(c);
+  StaticEvictLayout s;
+  size_t off = 0;
+  s.lse = off;   off += align_up(units_q * rows * sizeof(float) * 16);  // partial (max, sum) pairs x 8 key ranges
+  s.score = off; off += align_up(units_kv * cache_len * sizeof(float));
+  s.idx = off;   off += align_up(units_sel * k * sizeof(int32_t));
+  s.total = off;
+  return s;
+}
+
 }  // namespace
 
 extern "C" {
@@ -403,6 +443,22 @@ int32_t citrus_evict_cache(const citrus_config* cfg, citrus_tensor q, int32_t ro
   float* score = reinterpret_cast<float*>(ws + wl.score);
   if (idx == nullptr) idx = reinterpret_cast<int32_t*>(ws + wl.idx);
   return do_evict_cache(cfg, q, rows, k_cache, v_cache, cache_len, k, k_new, v_new, idx, lse_ws, score,
+                        static_cast<hipStream_t>(hip_stream));
+}
+
+size_t citrus_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int32_t citrus_evict_cache_static(const citrus_config* cfg, citrus_tensor q, int32_t rows, citrus_tensor k_cache,
+                                  citrus_tensor v_cache, int32_t cache_len, int32_t k, citrus_tensor k_new,
+                                  citrus_tensor v_new, int32_t* idx, void* hip_stream) {
+  CITRUS_TRY(check_evict_args(cfg, q, rows, k_cache, v_cache, cache_len, k, k_new, v_new));
+  const StaticEvictLayout sl = static_evict_layout(cfg, rows, cache_len, k);
+  if (sl.total > kStaticScratchBytes) return CITRUS_ERR_WORKSPACE;  // beyond the fixed array: use citrus_evict_cache
+  char* base = nullptr;
+  CITRUS_TRY(static_scratch_base(&base));
+  if (idx == nullptr) idx = reinterpret_cast<int32_t*>(base + sl.idx);
+  return do_evict_cache(cfg, q, rows, k_cache, v_cache, cache_len, k, k_new, v_new, idx,
+                        reinterpret_cast<float*>(base + sl.lse), reinterpret_cast<float*>(base + sl.score),
                         static_cast<hipStream_t>(hip_stream));
 }
 

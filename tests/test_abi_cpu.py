@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert getattr(lib, n) is not None
     header = open(os.path.join(ROOT, "include", "citrus.h")).read()
-    assert B.abi_version() == int(re.search(r"#define\s+CITRUS_ABI_VERSION\s+(\d+)", header).group(1)) == 9
+    assert B.abi_version() == int(re.search(r"#define\s+CITRUS_ABI_VERSION\s+(\d+)", header).group(1)) == 10
 
 
 def test_struct_layouts_match_the_header():
@@ -254,6 +254,26 @@ def test_unit_span_of_two_gib_or_more_is_rejected_before_any_launch():
     assert lib.citrus_rope(C.byref(c), wide(100), 4, 100, 0, fake(), None) == B.ERR_SHAPE
 
 
+def test_evict_cache_static_validates_like_evict_cache_and_bounds_its_scratch():
+    lib = B._lib()
+    assert B.static_scratch_bytes() == 16 << 20
+    c = cfg().c()
+    null = B.CTensor(None, 0, 0, 0, 0)
+    ev = lambda cc, rows=8, n=40, k=16, kn=fake(0x9000), vn=fake(0xA000), q=fake(): lib.citrus_evict_cache_static(
+        C.byref(cc), q, rows, fake(0x5000), fake(0x6000), n, k, kn, vn, None, None)
+    assert lib.citrus_evict_cache_static(None, fake(), 8, fake(), fake(), 40, 16, fake(), fake(), None, None) == B.ERR_NULL
+    assert ev(c, rows=0) == B.ERR_SHAPE
+    assert ev(c, n=0) == B.ERR_SHAPE and ev(c, n=65) == B.ERR_SHAPE
+    assert ev(c, k=0) == B.ERR_SHAPE and ev(c, k=65) == B.ERR_SHAPE
+    assert ev(c, kn=fake(0x5000)) == B.ERR_SHAPE and ev(c, vn=fake(0x6000)) == B.ERR_SHAPE
+    assert ev(c, kn=null) == B.ERR_NULL and ev(c, q=null) == B.ERR_NULL
+    # a request beyond the fixed array is refused on the host: 64 B per query row alone is 32 MiB here
+    big = cfg(dtype=B.BF16, head_dim=128, batch=4, layers=32, q_heads=32, kv_heads=8, chunk_len=512, budget=768,
+              instr_len=128).c()
+    assert lib.citrus_evict_cache_static(C.byref(big), fake(), 128, fake(0x5000), fake(0x6000), 768, 700, fake(0x9000),
+                                         fake(0xA000), None, None) == B.ERR_WORKSPACE
+
+
 def test_concurrent_host_threads_get_the_same_codes():
     """Entry points keep no unsynchronised state: many threads validating at once all see the codes a single
     thread sees."""
@@ -269,7 +289,7 @@ def test_concurrent_host_threads_get_the_same_codes():
             lib.citrus_chunk_attn(C.byref(c), fake(), fake(), fake(), 65, fake(), fake(), 8, fake(), None, None, None, None, 0, None),
             lib.citrus_instr_score(C.byref(c), fake(), fake(), 0, fake(), 8, sc, ws, 16, None),
             lib.citrus_topk_select(C.byref(c), sc, 0, 4, C.c_void_p(0x3000), None, 0, None),
-            lib.citrus_evict_cache(C.byref(c), fake(), 8, fake(0x5000), fake(0x6000), 40, 0, fake(0x9000), fake(0xA000), None, ws, 1 << 30, None),
+            lib.citrus_evict_cache_static(C.byref(c), fake(), 8, fake(0x5000), fake(0x6000), 40, 0, fake(0x9000), fake(0xA000), None, None),
             lib.citrus_rope(C.byref(c), fake(), 4, 0, 0, fake(), None),
             int(lib.citrus_workspace_bytes(C.byref(c)) > 0),
         ]
