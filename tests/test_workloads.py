@@ -2,7 +2,7 @@
 
 import torch
 
-from workloads import WORKLOADS, gen_tensor, heavy_mask, make_chunk, make_document, peaked, scaled_down
+from workloads import WORKLOADS, gen_tensor, heavy_mask, make_chunk, make_chunk_sliced, make_document, peaked, scaled_down
 
 
 def test_named_workloads_match_their_shapes():
@@ -54,3 +54,15 @@ def test_peaked_variant_leaves_logit_inputs_unscaled():
     d = make_document(w)
     assert abs(d["q"].double().std().item() - 1.0) < 0.02
     assert abs(d["v"].double().std().item() * 8 - 1.0) < 0.02
+
+
+def test_sliced_chunk_generation_gives_the_same_values():
+    w = scaled_down(WORKLOADS["cfg2_mistral7b"], batch=2, layers=3, q_heads=4, kv_heads=2, doc_len=300, chunk_len=64,
+                    instr_len=8)
+    for i in (0, 4):   # a full chunk and the short last one
+        whole = make_chunk(w, i)
+        parts = make_chunk_sliced(w, i, max_elems=4 * 64 * 128 * 2)   # two layers per slice
+        for name in whole:
+            assert torch.equal(whole[name], parts[name])
+        sub = make_chunk_sliced(w, i, b=[1], l=[2, 0], max_elems=1)
+        assert torch.equal(sub["k"][0, 0], whole["k"][1, 2]) and torch.equal(sub["q"][0, 1], whole["q"][1, 0])

@@ -232,6 +232,31 @@ def make_chunk(w: Workload, i: int, device="cpu", b=None, l=None) -> Dict[str, t
     }
 
 
+def make_chunk_sliced(w: Workload, i: int, device="cpu", b=None, l=None, max_elems: int = 1 << 27,
+                      out: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
+    """make_chunk for shapes whose 64-bit temporaries would not fit at once: the same values, generated one
+    (document, group of layers) slice at a time (at most about max_elems elements of q per slice) and written
+    into ``out`` (allocated here if not given)."""
+    b = list(range(w.batch)) if b is None else list(b)
+    l = list(range(w.layers)) if l is None else list(l)
+    lo, hi = w.chunk_bounds(i)
+    c, d, dt = hi - lo, w.head_dim, w.torch_dtype
+    if out is None:
+        out = {"q": torch.empty((len(b), len(l), w.q_heads, c, d), dtype=dt, device=device),
+               "k": torch.empty((len(b), len(l), w.kv_heads, c, d), dtype=dt, device=device),
+               "v": torch.empty((len(b), len(l), w.kv_heads, c, d), dtype=dt, device=device),
+               "q_instr": torch.empty((len(b), len(l), w.q_heads, w.instr_len, d), dtype=dt, device=device)}
+    per_layer = w.q_heads * max(c, w.instr_len) * d
+    lg = max(1, min(len(l), max_elems // per_layer))
+    for bi, bb in enumerate(b):
+        for l0 in range(0, len(l), lg):
+            part = make_chunk(w, i, device, b=[bb], l=l[l0:l0 + lg])
+            for name in ("q", "k", "v", "q_instr"):
+                out[name][bi:bi + 1, l0:l0 + lg, :, :part[name].shape[3]] = part[name]
+            del part
+    return out
+
+
 def make_document(w: Workload, device="cpu", b=None, l=None) -> Dict[str, torch.Tensor]:
     """Whole-document tensors, generated chunk by chunk to bound temporaries:
     q [B,L,Hq,T,d], k/v [B,L,Hkv,T,d], q_instr [n_chunks,B,L,Hq,n_i,d]."""
