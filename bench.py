@@ -124,6 +124,57 @@ def cpu_baseline(w, target_seconds: float = 15.0):
                       f"unit, {dt:.1f} s, scaled by batch*layers={w.batch * w.layers}; numpy float64, BLAS threads={threads}"}
 
 
+def score_bytes_per_launch(w, i: int) -> float:
+    """Algorithmic bytes of chunk i's instruction-score launch: every candidate key and every instruction query
+    read once, the f32 scores written: ((n*Hkv + n_i*Hq)*d*e + 4*n*Hkv) * B * L."""
+    e = 4 if w.dtype == "f32" else 2
+    n = w.cache_len_before(i) + (w.chunk_bounds(i)[1] - w.chunk_bounds(i)[0])
+    return float(w.batch * w.layers) * ((n * w.kv_heads + w.instr_len * w.q_heads) * w.head_dim * e + 4 * n * w.kv_heads)
+
+
+def score_flops_per_launch(w, i: int) -> float:
+    """Flops of Eq. (1) with the instruction as the text: one QK^T over the candidates, 2 * d * n_i * n * Hq * B * L."""
+    n = w.cache_len_before(i) + (w.chunk_bounds(i)[1] - w.chunk_bounds(i)[0])
+    return 2.0 * w.head_dim * w.instr_len * n * w.q_heads * w.batch * w.layers
+
+
+def compact_bytes_per_launch(w, i: int) -> float:
+    """Algorithmic bytes of chunk i's gather: the kept K and V rows read once and written once:
+    4 * m * Hkv * d * e * B * L with m = min(k, n)."""
+    e = 4 if w.dtype == "f32" else 2
+    n = w.cache_len_before(i) + (w.chunk_bounds(i)[1] - w.chunk_bounds(i)[0])
+    return float(w.batch * w.layers) * 4 * min(w.budget, n) * w.kv_heads * w.head_dim * e
+
+
+def measured_peaks(torch, api, dev):
+    """What this machine reaches on the two roofs, measured here and now: a plain 1 GiB device-to-device copy (read +
+    write bytes per second) and a kernel of back-to-back bf16 MFMAs without memory traffic (citrus_probe_mfma)."""
+    src = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).fill_(1.0)
+    dst = torch.empty_like(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    best_copy = 0.0
+    for it in range(4):
+        e0.record()
+        dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        if it > 0:
+            best_copy = max(best_copy, 2.0 * src.numel() * 2 / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    del src, dst
+    sink = torch.empty(1024 * 1024, dtype=torch.float32, device=dev)
+    best_mfma = 0.0
+    for it in range(4):
+        e0.record()
+        count = api.binding.probe_mfma(4000, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        if it > 0:
+            best_mfma = max(best_mfma, count * 32768.0 / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    return {"copy_GBs": round(best_copy, 1), "mfma_only_bf16_TFLOPs": round(best_mfma, 1),
+            "note": "best of 3: 1 GiB device copy (read+write bytes); 16 waves per CU issuing independent 32x32x16 bf16 "
+                    "MFMAs back to back, no memory traffic"}
+
+
 def calibrate_copy(torch, dev):
     """A plain elementwise copy of known size (256 MiB read + 256 MiB written), three times: the reference
     for scaling rocprofv3's HBM counters."""
@@ -323,7 +374,12 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens = w.batch * w.doc_len
     value = tokens / (ms_per_step * 1e-3)
-    one_document(0, phase_events)          # untimed: all eight events of every step
+    # untimed: all eight events of every step, over a few documents (per-phase times and the launch durations
+    # of the instruction score and the gather)
+    PHASE_DOCS = 3
+    phase_sets = [phase_events] + [HipEvents(w.n_chunks * E) for _ in range(PHASE_DOCS - 1)]
+    for pe_set in phase_sets:
+        one_document(0, pe_set)
     torch.cuda.synchronize()
 
     # chunk-attention launch durations from the events recorded inside the timed region
@@ -337,6 +393,19 @@ def main():
     # per-phase device time of the extra document
     names = {1: "chunk_attn", 2: "lm_score", 3: "lm_select", 4: "lm_compact", 5: "instr_score", 6: "select", 7: "compact"}
     phase_ms = {v: 0.0 for v in names.values()}
+    # launch durations of the instruction score (events 4 -> 5; 0 -> 5 with --overlap) and of the gather
+    # (6 -> 7), every chunk of the untimed documents, with the algorithmic bytes of the same launches
+    score_ms, score_by, compact_ms, compact_by, select_ms = [], [], [], [], []
+    if not standard:
+        for pe_set in phase_sets:
+            for i in range(w.n_chunks):
+                score_ms.append(pe_set.elapsed_ms(i * E + (0 if overlap else 4), i * E + 5))
+                score_by.append(score_bytes_per_launch(w, i))
+                select_ms.append(pe_set.elapsed_ms(i * E + 5, i * E + 6))
+                compact_ms.append(pe_set.elapsed_ms(i * E + 6, i * E + 7))
+                compact_by.append(compact_bytes_per_launch(w, i))
+    for pe_set in phase_sets[1:]:
+        pe_set.destroy()
     for i in range(w.n_chunks):
         if overlap:
             # order on the main stream: 0 step start, instruction score, 5, chunk attention, 1; on the side
@@ -357,6 +426,34 @@ def main():
     overridden = args.cache_mode is not None or args.lm_ordering is not None or args.position_shift
     traffic = None if overridden else MEASURED_TRAFFIC_BYTES.get(w.name)
 
+    def hbm_entry(kernel, step, ms, by, note=None):
+        a_ms, a_by = sum(ms) / len(ms), sum(by) / len(by)
+        gbs = a_by / (a_ms * 1e-3) / 1e9
+        e = {"kernel": kernel, "step": step, "bound": "hbm", "algorithmic_bytes_per_launch": a_by,
+             "avg_launch_ms": round(a_ms, 5), "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+             "frac": round(gbs / PEAK_HBM_GBS, 4)}
+        if note:
+            e["note"] = note
+        return e
+
+    roofline_other = []
+    if score_ms:
+        # which roof bounds the instruction score depends on the shape: flops of Eq. (1) per byte it must move
+        sc_flops = sum(score_flops_per_launch(w, i) for i in range(w.n_chunks)) / w.n_chunks
+        ent = hbm_entry("instr_score kernels (instruction score)", "a2", score_ms, score_by,
+                        "launch duration = HIP events around the instruction-score launch(es) of every chunk of "
+                        f"{PHASE_DOCS} untimed documents (includes the event gap of a few microseconds)")
+        a_ms = sum(score_ms) / len(score_ms)
+        ent["algorithmic_flops_per_launch"] = sc_flops
+        ent["achieved_TFLOPs"] = round(sc_flops / (a_ms * 1e-3) / 1e12, 1)
+        ent["frac_of_bf16_mfma_peak"] = round(sc_flops / (a_ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4)
+        roofline_other.append(ent)
+        roofline_other.append(hbm_entry("compact_kernel (K/V gather)", "a4", compact_ms, compact_by,
+                                        "same events, around the gather launch"))
+        roofline_other.append({"kernel": "topk_kernel (selection)", "step": "a3", "bound": "latency",
+                               "avg_launch_ms": round(sum(select_ms) / len(select_ms), 5),
+                               "note": "a chain of barrier-separated LDS passes over a few KB per unit: no roofline fraction"})
+
     result = {
         "metric": "document tokens/sec per layer-stack + % HBM/MFMA peak, Mistral-7B shape",
         "value": round(value, 1), "unit": "document tokens/s per layer-stack",
@@ -373,7 +470,12 @@ def main():
         "roofline": {"kernel": "attn_pipe_kernel_w8 (chunk attention)", "bound": "mfma",
                      "achieved": round(achieved, 2), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": traffic,
+                     "traffic_source": None if traffic is None else
+                     "constant from an offline rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this command "
+                     "(profiles/bench_cfg2_mistral7b_hbm_traffic.md), not measured in this run",
                      "avg_launch_ms": round(avg_ms, 5), "algorithmic_flops_per_launch": avg_fl},
+        "roofline_other": roofline_other,
+        "peaks_measured": measured_peaks(torch, api, dev),
         "phase_ms_per_step": phase_ms,
         "phase_note": "phases: one extra untimed document with all events; roofline: events around every chunk-attention "
                       "launch of the timed region" + ("; select and compact run concurrently with chunk_attn (their times "

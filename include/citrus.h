@@ -473,6 +473,17 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
                                 void* workspace, size_t workspace_bytes, void* hip_stream,
                                 const citrus_side_stream* side);
 
+/*
+ * Measurement aid, not a step of the method: launches a kernel in which every wave (two workgroups of eight
+ * waves per compute unit) issues 16 * iters independent v_mfma_f32_32x32x16_bf16 back to back and touches no
+ * memory until the end; the caller times the launch (events on hip_stream) and divides.  bench.py reports the
+ * rate it reaches next to the published bf16 peak.
+ * iters       1 .. 2^20
+ * sink        device, >= 1024 floats per compute unit (one value per lane is written so that the work is kept)
+ * mfma_count  host, out: MFMA instructions the launch issues; each is 2 * 32 * 32 * 16 = 32768 flop
+ */
+int32_t citrus_probe_mfma(int32_t iters, float* sink, size_t sink_floats, int64_t* mfma_count, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

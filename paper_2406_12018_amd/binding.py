@@ -32,7 +32,7 @@ EXPORTS = (
     "citrus_abi_version", "citrus_status_string", "citrus_workspace_bytes", "citrus_chunk_attn",
     "citrus_instr_score", "citrus_cache_score", "citrus_evict_cache", "citrus_evict_cache_static",
     "citrus_static_scratch_bytes", "citrus_decode_step", "citrus_rope", "citrus_score_accumulate", "citrus_score_gather", "citrus_topk_select", "citrus_kv_compact", "citrus_resident_provider",
-    "citrus_process_document",
+    "citrus_process_document", "citrus_probe_mfma",
 )
 
 
@@ -119,6 +119,8 @@ def _lib():
     lib.citrus_process_document.restype = I
     lib.citrus_process_document.argtypes = [P(CConfig), V, V, I, I, P(CTensor), P(CTensor), P(CTensor), P(CTensor),
                                             P(I), P(I), P(I), P(I), P(V), V, V, P(I), V, V, S, V, P(CSideStream)]
+    lib.citrus_probe_mfma.restype = I
+    lib.citrus_probe_mfma.argtypes = [I, V, S, P(C.c_int64), V]
     _LIB = lib
     return lib
 
@@ -356,6 +358,14 @@ def citrus_kv_compact(cfg: Config, k_cache, v_cache, cache_len: int, k_chunk, v_
                                   _stream(stream))
     _check(st, "citrus_kv_compact")
     return k_new, v_new
+
+
+def probe_mfma(iters: int, sink: torch.Tensor, stream=None) -> int:
+    """Launches the MFMA-only probe kernel; returns the number of MFMA instructions it issues (32768 flop each)."""
+    count = C.c_int64(0)
+    st = _lib().citrus_probe_mfma(iters, _ptr(sink), sink.numel(), C.byref(count), _stream(stream))
+    _check(st, "citrus_probe_mfma")
+    return count.value
 
 
 @dataclass
