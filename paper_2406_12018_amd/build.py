@@ -14,7 +14,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libcitrus.so")
-SOURCES = ["citrus_api.hip", "attn_generic.hip", "attn_mfma.hip", "decode_attn.hip", "rope.hip", "select_compact.hip", "probe.hip"]
+SOURCES = ["citrus_api.hip", "attn_generic.hip", "attn_mfma.hip", "instr_strip.hip", "decode_attn.hip", "rope.hip", "select_compact.hip", "probe.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

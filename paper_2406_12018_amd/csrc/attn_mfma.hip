@@ -1422,14 +1422,19 @@ hipError_t launch_colsum_mfma(const Dims& dm, View q, int rows, Segments ks, int
 
 // Instruction score in two launches: partial log-sum-exp over ranges of key tiles (enough
 // workgroups to fill the chip although there are few instruction rows), then the column sums.
-size_t instr_score_mfma_workspace_floats(const Dims& dm, int rows) {
-  return static_cast<size_t>(2) * kMaxKeySplits * dm.B * dm.L * dm.Hq * rows;
+size_t instr_score_mfma_workspace_floats(const Dims& dm, int rows, int n) {
+  const size_t two_launch = static_cast<size_t>(2) * kMaxKeySplits * dm.B * dm.L * dm.Hq * rows;
+  const size_t strips = instr_strip_workspace_floats(dm, rows, n);
+  return two_launch > strips ? two_launch : strips;
 }
 
 hipError_t launch_instr_score_mfma(const Dims& dm, View q, int rows, Segments ks, float* workspace, float* score,
                                    hipStream_t st) {
   const int n = ks.n_c + ks.c;
-  // few query rows per KV group (the usual case: a short instruction): one fused launch
+  // a short text over a candidate set that a workgroup's registers can hold one row strip of: one product
+  // per (row, key)
+  if (instr_strip_supported(dm, q, rows, ks)) return launch_instr_strip(dm, q, rows, ks, workspace, score, st);
+  // otherwise two passes over the keys; few query rows per KV group: one fused launch
   const int total_rows = dm.G * rows;
   const int tiles32 = (n + 31) / 32;
   if (total_rows <= 128 && instr_fused_lds_bytes<4, 1, 8>(n) <= kFusedLdsBudget)

@@ -111,8 +111,10 @@ Workspace workspace_layout(const citrus_config* c) {
   const bool dual = c->cache_mode == CITRUS_CACHE_DUAL;
   size_t off = 0;
   w.lse_chunk = off; off += align_up(units_q * c->chunk_len * sizeof(float));
-  w.lse_instr = off; off += align_up(units_q * c->instr_len * sizeof(float) * 16);  // partial (max, sum) pairs x 8 ranges
-  w.lse_cache = off; off += evict_then_append(c) ? align_up(units_q * c->chunk_len * sizeof(float) * 16) : 0;  // same, chunk rows
+  // scratch of the instruction score: partial (max, sum) pairs x 8 key ranges, or partial column sums per row strip
+  const Dims dm_ws = dims_of(c);
+  w.lse_instr = off; off += align_up(instr_score_mfma_workspace_floats(dm_ws, c->instr_len, static_cast<int>(n_max)) * sizeof(float));
+  w.lse_cache = off; off += evict_then_append(c) ? align_up(instr_score_mfma_workspace_floats(dm_ws, c->chunk_len, static_cast<int>(n_max)) * sizeof(float)) : 0;  // same, chunk rows
   w.score = off;     off += align_up(units_kv * n_max * sizeof(float));
   w.score_lm = off;  off += dual ? align_up(units_kv * n_max * sizeof(float)) : 0;
   w.idx = off;       off += align_up(units_kv * c->budget * sizeof(int32_t));
@@ -335,12 +337,12 @@ struct StaticEvictLayout {
   size_t lse, score, idx, total;
 };
 StaticEvictLayout static_evict_layout(const citrus_config* c, int rows, int cache_len, int k) {
-  const size_t units_q = static_cast<size_t>(c->batch) * c->layers * c->q_heads;
   const size_t units_kv = static_cast<size_t>(c->batch) * c->layers * c->kv_heads;
   const size_t units_sel = static_cast<size_t>(c->batch) * c->layers * sel_heads(c);
   StaticEvictLayout s;
   size_t off = 0;
-  s.lse = off;   off += align_up(units_q * rows * sizeof(float) * 16);  // partial (max, sum) pairs x 8 key ranges
+  // partial (max, sum) pairs x 8 key ranges, or partial column sums per row strip
+  s.lse = off;   off += align_up(instr_score_mfma_workspace_floats(dims_of(c), rows, cache_len) * sizeof(float));
   s.score = off; off += align_up(units_kv * cache_len * sizeof(float));
   s.idx = off;   off += align_up(units_sel * k * sizeof(int32_t));
   s.total = off;
