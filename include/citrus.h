@@ -123,7 +123,9 @@ typedef struct {
   int32_t layers;         /* L                                               >= 1 */
   int32_t q_heads;        /* Hq, a multiple of kv_heads                          */
   int32_t kv_heads;       /* Hkv                                             >= 1 */
-  int32_t head_dim;       /* d: 64 or 128                                        */
+  int32_t head_dim;       /* d: 64 or 128.  The matrix-core (MFMA) kernels exist for bf16 with d = 128 only;
+                             bf16 with d = 64 and every f32 configuration run on plain vector kernels (one
+                             wavefront per query row), which are meant for tests and small shapes        */
   int32_t chunk_len;      /* l_s: maximum chunk length c                     >= 1 */
   int32_t budget;         /* k: states kept in the (instruction) cache       >= 1 */
   int32_t budget_lm;      /* DUAL: budget of the language-modelling cache; else ignored */

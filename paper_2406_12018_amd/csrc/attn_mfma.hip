@@ -1,11 +1,11 @@
 // bf16 MFMA kernels for head_dim 128 on gfx950 (CDNA4).
 //
-//  attn_mfma_kernel    flash-style chunk attention (Section 4.1 step 1; softmax
+//  attn_pipe_kernel_w8 flash-style chunk attention (Section 4.1 step 1; softmax
 //                      with the 1/sqrt(d_k) scaling of Eq. (1)): online softmax
 //                      over 64-key tiles staged in LDS, S^T = K.Q^T and
-//                      O^T = V^T.P^T on v_mfma_f32_32x32x16_bf16.  Without a
-//                      value/output tensor it only produces the row
-//                      log-sum-exp (first pass of the instruction score).
+//                      O^T = V^T.P^T on v_mfma_f32_32x32x16_bf16.
+//  lse_mfma_kernel     the rows' log-sum-exp alone (first pass of the two-pass
+//                      importance scores).
 //  colsum_mfma_kernel  summed form of Eq. (1): probabilities exp(s - lse)
 //                      added down the query rows of a KV group, per key.
 //
@@ -139,12 +139,12 @@ __host__ __device__ inline TaskShape task_shape(int G, int waves = kWaves) {
   return TaskShape{hpb, waves / hpb};
 }
 
-template <bool HAS_PV>
-__global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q, int rows, Segments ks, Segments vs,
-                                                               int causal, View out, float* lse, int key_splits,
-                                                               float2* part) {
+// Row normalisers only (no values, no output): the log-sum-exp of every query row over the keys it sees,
+// or, with key_splits > 1, one partial (running maximum, sum) pair per key range and row.  First pass of the
+// two-pass importance scores and of a cache-only normaliser that the attention launch could not emit.
+__global__ __launch_bounds__(kThreads, 2) void lse_mfma_kernel(Dims dm, View q, int rows, Segments ks, int causal,
+                                                              float* lse, int key_splits, float2* part) {
   __shared__ __attribute__((aligned(1024))) char k_s[2 * kTileBytes];  // double-buffered tiles
-  __shared__ __attribute__((aligned(1024))) char v_s[HAS_PV ? 2 * kTileBytes : 16];
 
   const int tid = threadIdx.x, lane = tid % 64, w = tid / 64;
   const int col = lane % 32, grp = lane / 32;
@@ -158,7 +158,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
   int logical = blockIdx.x;
   const int total = gridDim.x;
   if (total % kXcds == 0) logical = (blockIdx.x % kXcds) * (total / kXcds) + blockIdx.x / kXcds;
-  // With key_splits > 1 (log-sum-exp only) each workgroup covers one contiguous range of key
+  // With key_splits > 1 each workgroup covers one contiguous range of key
   // tiles and writes a partial (running maximum, sum) pair per row; the consumer merges them.
   const int sp = logical % key_splits;
   logical /= key_splits;
@@ -186,16 +186,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
   // Wave w fills rows 16 w + 4 i .. + 3 with instruction i = 0..3.  Rows that fall outside the
   // candidates re-read the last row (finite values; their logits are masked).
   const int k_ss_cache = static_cast<int>(ks.cache.ss), k_ss_chunk = static_cast<int>(ks.chunk.ss);
-  const int v_ss_cache = static_cast<int>(vs.cache.ss), v_ss_chunk = static_cast<int>(vs.chunk.ss);
   auto seg_bytes = [](int rows_, int ss_) { return rows_ > 0 ? ((rows_ - 1) * ss_ + D) * 2 : 0; };
   const __amdgpu_buffer_rsrc_t k_rs_cache = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint16_t*>(unit_ptr(ks.cache, b, l, g)), 0, seg_bytes(n_c, k_ss_cache), kBufferFlags);
   const __amdgpu_buffer_rsrc_t k_rs_chunk = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint16_t*>(unit_ptr(ks.chunk, b, l, g)), 0, seg_bytes(ks.c, k_ss_chunk), kBufferFlags);
-  const __amdgpu_buffer_rsrc_t v_rs_cache = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint16_t*>(unit_ptr(HAS_PV ? vs.cache : ks.cache, b, l, g)), 0, seg_bytes(n_c, v_ss_cache), kBufferFlags);
-  const __amdgpu_buffer_rsrc_t v_rs_chunk = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint16_t*>(unit_ptr(HAS_PV ? vs.chunk : ks.chunk, b, l, g)), 0, seg_bytes(ks.c, v_ss_chunk), kBufferFlags);
   const int wu = __builtin_amdgcn_readfirstlane(w);
   const int fill_row = 16 * wu + lane / 16;                       // tile row this lane fills with instruction 0
   const int fill_seg16 = ((lane % 16) ^ (2 * (lane / 16))) * 16;  // byte offset of its global segment, before ^ c_i
@@ -223,11 +218,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
       }
     }
   };
-#define CITRUS_FETCH_TILE(j0_, buf_)                                                                        \
-  do {                                                                                                      \
-    fill4(k_s + (buf_) * kTileBytes, k_rs_cache, k_rs_chunk, k_ss_cache, k_ss_chunk, (j0_));                \
-    if (HAS_PV) fill4(v_s + (buf_) * kTileBytes, v_rs_cache, v_rs_chunk, v_ss_cache, v_ss_chunk, (j0_));    \
-  } while (0)
+  auto fetch_tile = [&](int j0_, int buf_) {
+    fill4(k_s + buf_ * kTileBytes, k_rs_cache, k_rs_chunk, k_ss_cache, k_ss_chunk, j0_);
+  };
 
   // per-lane LDS read offsets (bytes inside a tile buffer), swizzle included
   // A operand of S^T: key row `col`, head_dim segment 2 kk + grp
@@ -235,17 +228,6 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
   int k_off[8];
 #pragma unroll
   for (int kk = 0; kk < 8; ++kk) k_off[kk] = col * kRowBytes + (((2 * kk + grp) ^ f_col) * 16);
-  // V^T operand through transpose reads.  The 16-lane group q16 = lane / 16 serves MFMA rows
-  // 16 (q16 % 2) .. +15 for contraction lane group q16 / 2; output row c' of tile r is head_dim
-  // 16 r + (c' % 16) + 64 (c' / 16).  Source lane s16 points at 4 consecutive head_dim values of key
-  // row 4 (q16 / 2) + s16 / 4 (+ 8 rd + 16 half + 32 mt): segment 2 r + 8 (q16 % 2) + (s16 % 4) / 2.
-  const int s16 = lane % 16, q16 = lane / 16;
-  const int v_cl = (8 * (q16 % 2) + (s16 % 4) / 2) ^ (8 * (q16 / 2) + 2 * (s16 / 4));
-  int v_off[8];  // indexed by e = 2 r + rd: f(row) of read rd differs from read 0 by ^ rd
-#pragma unroll
-  for (int e = 0; e < 8; ++e)
-    v_off[e] = (4 * (q16 / 2) + s16 / 4) * kRowBytes + ((e ^ v_cl) * 16) + 8 * (s16 % 2);
-
   for (int pass = 0; pass < passes; ++pass) {
   const int rb = pass == 0 ? rb_first : rb_second;
   const int row0 = (rb * ts.tiles_per_block + w / ts.heads_per_block) * kRowsPerWave;
@@ -279,24 +261,18 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
   // ---- running softmax state: one query per lane ----
   const float c2 = dm.scale * kLog2e;  // logits are kept in the log2 domain
   float m_run = -INFINITY, l_run = 0.f;
-  f32x16 o_acc[4];
-#pragma unroll
-  for (int r = 0; r < 4; ++r)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) o_acc[r][i] = 0.f;
 
   if (t_begin < t_end) {  // block-uniform
-  CITRUS_FETCH_TILE(t_begin * kTileN, 0);
+  fetch_tile(t_begin * kTileN, 0);
   barrier_after_lds_fill();  // also: the Q operand loads have landed
 
   for (int jt = t_begin; jt < t_end; ++jt) {
     const int j0 = jt * kTileN;
     const int buf = (jt - t_begin) & 1;
     const char* k_t = k_s + buf * kTileBytes;
-    const char* v_t = v_s + (HAS_PV ? buf * kTileBytes : 0);
     // The other buffer was last read one iteration ago and every wave has passed the barrier that
     // ended that iteration: the next tile can stream into it while this one is computed.
-    if (jt + 1 < t_end) CITRUS_FETCH_TILE(j0 + kTileN, buf ^ 1);
+    if (jt + 1 < t_end) fetch_tile(j0 + kTileN, buf ^ 1);
 
     if (wave_active && j0 <= wave_limit_max) {
       // S^T = K . Q^T for 64 keys x 32 queries
@@ -332,7 +308,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
       // Running maximum, kept lazily: softmax is invariant to the subtracted value, so m_run only has
       // to stay within kMaxSlack (log2 units) of the true row maximum to keep exp2 in range.  The fast
       // path looks at this lane's own 32 logits only; the exchange with lane l ^ 32, the update of
-      // m_run and the rescale of the accumulators happen only when some row needs them.
+      // m_run and the rescale of the running sum happen only when some row needs them.
       float mx = s_acc[0][0];
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt)
@@ -344,60 +320,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
         // 0 on a row's first visible tile (m_run = -inf); 1 for a row that has seen nothing yet
         const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
         l_run *= alpha;
-        if (HAS_PV) {
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o_acc[r][i] *= alpha;
-        }
         m_run = m_new;
       }
-      uint32_t p_pk[2][8];  // [mt][pair]: bf16 probabilities, pairs of consecutive registers
       float psum = 0.f;
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-        float p[16];
+      for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) p[i] = __builtin_amdgcn_exp2f(fmaf(s_acc[mt][i], c2, -m_run));
-        if (HAS_PV) {
-          // the row sum is taken over the bf16-rounded probabilities, the values P.V actually uses:
-          // one v_dot2 with (1, 1) adds a pair
-#pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            p_pk[mt][i] = pack_bf16x2(p[2 * i], p[2 * i + 1]);
-            psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, p_pk[mt][i]),
-                                                   __builtin_bit_cast(bf16x2, 0x3f803f80u), psum, false);
-          }
-        } else {
-#pragma unroll
-          for (int i = 0; i < 16; ++i) psum += p[i];
-        }
-      }
+        for (int i = 0; i < 16; ++i) psum += __builtin_amdgcn_exp2f(fmaf(s_acc[mt][i], c2, -m_run));
       l_run += psum;
-
-      if (HAS_PV) {
-        // O^T += V^T . P^T ; contraction step (mt, half) covers keys 32 mt + 16 half .. +15 in the slot
-        // order the S^T accumulators already have: slot i of lane group grp is key
-        // 8 (i / 4) + 4 grp + (i % 4) of the step, so slots 0..3 / 4..7 are two transpose reads.
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-#pragma unroll
-          for (int half = 0; half < 2; ++half) {
-            Pack8 a[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-              for (int rd = 0; rd < 2; ++rd)
-                a[r].h[rd] = lds_read_tr16(v_t + (32 * mt + 16 * half + 8 * rd) * kRowBytes + v_off[2 * r + rd]);
-            Pack8 pb;
-#pragma unroll
-            for (int x = 0; x < 4; ++x) pb.w[x] = p_pk[mt][4 * half + x];
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-              o_acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[r].v, pb.v, o_acc[r], 0, 0, 0);
-          }
-        }
-      }
     }
 
     barrier_after_lds_fill();  // publishes the tile that streamed in; everyone is done with this one
@@ -411,22 +341,6 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
   if (part != nullptr && grp == 0)  // log2 domain; an empty or fully masked range leaves (-inf, 0)
     part[static_cast<int64_t>(sp) * dm.B * dm.L * dm.Hq * rows + row_id] = make_float2(m_run, l_tot);
   if (lse != nullptr && grp == 0) lse[row_id] = (m_run + log2f(l_tot)) * kLn2;
-  if (HAS_PV) {
-    const float inv = 1.f / l_tot;
-    uint16_t* op = const_cast<uint16_t*>(unit_ptr(out, b, l, h)) + static_cast<int64_t>(t) * out.ss;
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-#pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        // registers 4 i4 .. +3 are rows c' = 8 i4 + 4 grp + 0..3 -> head_dim 16 r + (c' % 16) + 64 (c' / 16)
-        const int c0 = 8 * i4 + 4 * grp;
-        const int d0 = 16 * r + (c0 % 16) + 64 * (c0 / 16);
-        uint2 wds;
-        wds.x = pack_bf16x2(o_acc[r][4 * i4] * inv, o_acc[r][4 * i4 + 1] * inv);
-        wds.y = pack_bf16x2(o_acc[r][4 * i4 + 2] * inv, o_acc[r][4 * i4 + 3] * inv);
-        *reinterpret_cast<uint2*>(op + d0) = wds;
-      }
-  }
   }  // row valid
   }  // pass
 }
@@ -434,7 +348,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(Dims dm, View q,
 // The same attention, with output, as a software pipeline over half tiles of 32 keys: in step h the
 // MFMAs of S^T(h + 1) = K.Q^T and of O^T += V^T.P^T(h - 1) are issued between the exponentials of
 // half tile h, so that inside ONE wave the matrix pipe, the vector pipe and the LDS reads run at
-// the same time instead of taking turns (the scheduler is told the order with group directives).
+// the same time instead of taking turns (the order is fixed with volatile asm statements, see above).
 // K tiles are fetched one 64-key tile further ahead than V tiles; one barrier per 64 keys.
 template <int WAVES, bool ROTATE_Q>
 __device__ __forceinline__ void attn_pipe_body(const Dims& dm, const View& q, int rows, const Segments& ks,
@@ -1401,8 +1315,7 @@ hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments ks, Segme
     hipLaunchKernelGGL(attn_pipe_kernel_w8, grid, dim3(kPipeWaves * 64), kQStageBytes, st, dm, q, rows, ks, vs, causal, out, lse,
                        lse_cache);
   else
-    hipLaunchKernelGGL((attn_mfma_kernel<false>), grid, dim3(kThreads), 0, st, dm, q, rows, ks, vs, causal, out, lse,
-                       key_splits, part);
+    hipLaunchKernelGGL(lse_mfma_kernel, grid, dim3(kThreads), 0, st, dm, q, rows, ks, causal, lse, key_splits, part);
   return hipGetLastError();
 }
 
