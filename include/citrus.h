@@ -139,9 +139,10 @@ typedef struct {
   int32_t lm_ordering;    /* citrus_lm_ordering (DUAL, STANDARD); EVICT_THEN_APPEND needs cache_capacity >=
                              budget_lm + chunk_len (DUAL) or budget + chunk_len (STANDARD)             */
   int32_t score_mode;     /* citrus_score_mode                                   */
-  int32_t position_shift; /* 0 / 1: the position shift of Section 5.3 in the chunk loop (INSTR / SHARED): the
-                             provider hands over q, k and q_instr WITHOUT rotary embedding and every step
-                             rotates them to the positions of the cache (see citrus_rope)              */
+  int32_t position_shift; /* 0 / 1: the position shift of Section 5.3 in the chunk loop (INSTR / SHARED / DUAL):
+                             the provider hands over q, k and q_instr WITHOUT rotary embedding and every step
+                             rotates them to the positions of the cache (see citrus_rope); with DUAL each of
+                             the two caches has its own slots                                          */
   float rope_base;        /* base of the rotary frequencies; 0 -> 10000                                */
   float softmax_scale;    /* 0 -> 1/sqrt(head_dim), the scaling of Eq. (1)       */
 } citrus_config;
@@ -283,7 +284,7 @@ int32_t citrus_evict_cache_static(const citrus_config* cfg, citrus_tensor q, int
  * bf16: f32 arithmetic, result rounded to bf16; f32: angles and products in f64.
  * With cfg->position_shift the chunk loop applies it, every step, to the candidates [cache ; chunk]
  * (position = index j), to the chunk's queries (cache_len + t) and to the instruction's queries
- * (cache_len + chunk_len + u); the caches keep the unrotated keys.
+ * (cache_len + chunk_len + u), for each cache with that cache's own length; the caches keep the unrotated keys.
  */
 int32_t citrus_rope(const citrus_config* cfg, citrus_tensor x, int32_t heads, int32_t rows, int32_t pos0,
                     citrus_tensor y, void* hip_stream);
@@ -410,6 +411,12 @@ int32_t citrus_resident_provider(void* user, int32_t chunk_index, void* hip_stre
  *                    and the instruction queries (cache_len + chunk_len ..) into
  *                    the workspace; attention and scores read the rotated
  *                    copies, kv_compact gathers the unrotated keys.
+ *   DUAL with position_shift: the same per cache.  The chunk's queries and the
+ *                    candidates [LM cache ; chunk] are rotated to the LM cache's
+ *                    positions (its state j -> j, chunk token t -> cache_len_lm + t)
+ *                    for the attention and the chunk's scores; the candidates
+ *                    [instruction cache ; chunk] and the instruction queries to the
+ *                    instruction cache's (j, cache_len + chunk_len + u).
  *   STANDARD:        the language-modelling steps of DUAL (in either ordering) on
  *                    the only cache pair with budget `budget`; io.q_instr is not
  *                    read and may be NULL; idx_history holds its selections.

@@ -321,11 +321,14 @@ def process_document(q, k, v, q_instr: Sequence[np.ndarray], chunk_len: int, bud
     scores it has received from the instruction in every step since it entered
     the cache (a new state starts at its first score); the k largest sums stay
     and carry their sums on.  Only the instruction-scored cache uses it.
-    ``position_shift`` (INSTR / SHARED): q, k and q_instr are given WITHOUT
-    rotary embedding and positions are those of the cache (Section 5.3): in
-    every step candidate j of [cache ; chunk] is rotated to position j, chunk
-    query t to n_c + t, instruction query u to n + u (the instruction follows
-    the candidates); the cache itself keeps the unrotated keys.
+    ``position_shift``: q, k and q_instr are given WITHOUT rotary embedding
+    and positions are those of the cache (Section 5.3): in every step
+    candidate j of [cache ; chunk] is rotated to position j, chunk query t to
+    n_c + t, instruction query u to n + u (the instruction follows the
+    candidates); the cache itself keeps the unrotated keys.  With DUAL each
+    cache has its own slots: the chunk attends over (and scores) the
+    language-modelling cache at that cache's positions, the instruction scores
+    the instruction cache at its own.
     """
     q, k, v = _f64(q), _f64(k), _f64(v)
     hq, t_total, d = q.shape
@@ -359,13 +362,18 @@ def process_document(q, k, v, q_instr: Sequence[np.ndarray], chunk_len: int, bud
             k_cat_lm = np.concatenate([kc_lm, ks], axis=1)
             v_cat_lm = np.concatenate([vc_lm, vs], axis=1)
             pos_cat_lm = np.concatenate([pos_lm, chunk_pos], axis=1)
-            out, lse, probs = chunk_attn(qs, k_cat_lm, v_cat_lm, n_c_lm, scale)
+            q_att_lm, k_att_lm = qs, k_cat_lm
+            if position_shift:
+                # this cache has its own slots: its state j sits at position j, chunk token t at n_c_lm + t
+                k_att_lm = rope(k_cat_lm, np.arange(n_c_lm + c), rope_base)
+                q_att_lm = rope(qs, n_c_lm + np.arange(c), rope_base)
+            out, lse, probs = chunk_attn(q_att_lm, k_att_lm, v_cat_lm, n_c_lm, scale)
             g_size = hq // hkv
             if lm_ordering == LM_EVICT_THEN_APPEND:
                 # step 2 of Section 4.1: Eq. (1) with s = chunk over the states of the cache alone
                 # (every chunk token sees the whole cache, so there is no mask)
                 if n_c_lm > 0:
-                    s_lm = instr_score(qs, kc_lm, scale)
+                    s_lm = instr_score(q_att_lm, k_att_lm[:, :n_c_lm], scale)
                     idx_lm = (np.asarray(forced_idx_lm[i]) if forced_idx_lm is not None
                               else topk_select(s_lm, budget_lm, select_mode, start_size))
                 else:
@@ -393,7 +401,9 @@ def process_document(q, k, v, q_instr: Sequence[np.ndarray], chunk_len: int, bud
             out, lse, _ = chunk_attn(qs, k_cat, v_cat, n_c, scale)
 
         if position_shift:
-            assert not dual, "position shift is defined here for the single-cache designs"
+            n = n_c + c
+            if dual:   # the instruction cache's own slots
+                k_att = rope(k_cat, np.arange(n), rope_base)
             s_in = instr_score(rope(q_instr[i], n + np.arange(np.asarray(q_instr[i]).shape[1]), rope_base), k_att, scale)
         else:
             s_in = instr_score(q_instr[i], k_cat, scale)

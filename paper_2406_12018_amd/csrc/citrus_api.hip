@@ -47,8 +47,7 @@ citrus_status check_config(const citrus_config* c) {
       c->cache_mode != CITRUS_CACHE_SHARED)
     return CITRUS_ERR_UNSUPPORTED;
   if (c->position_shift != 0 && c->position_shift != 1) return CITRUS_ERR_UNSUPPORTED;
-  if (c->position_shift && c->cache_mode != CITRUS_CACHE_INSTR && c->cache_mode != CITRUS_CACHE_SHARED)
-    return CITRUS_ERR_UNSUPPORTED;
+  if (c->position_shift && c->cache_mode == CITRUS_CACHE_STANDARD) return CITRUS_ERR_UNSUPPORTED;
   if (!(c->rope_base >= 0.0f) || isinf(c->rope_base) || (c->rope_base > 0.0f && c->rope_base < 1.0f))
     return CITRUS_ERR_SHAPE;
   return CITRUS_OK;
@@ -93,7 +92,7 @@ citrus_status check_lengths(const citrus_config* c, int cache_len, int chunk_len
 
 // Workspace layout (all blocks kAlign-aligned).
 struct Workspace {
-  size_t lse_chunk, lse_instr, lse_cache, score, score_lm, idx, idx_lm, iota, decode, k_rot, q_rot, qi_rot, total;
+  size_t lse_chunk, lse_instr, lse_cache, score, score_lm, idx, idx_lm, iota, decode, k_rot, k_rot_lm, q_rot, qi_rot, total;
 };
 
 // A cache evicted by the document's own chunks exists (DUAL's second cache, or the only one of STANDARD)
@@ -127,6 +126,7 @@ Workspace workspace_layout(const citrus_config* c) {
   // position shift: rotated copies of the candidates' keys, the chunk's and the instruction's queries
   const size_t esz = static_cast<size_t>(elem_bytes(c->dtype)) * c->head_dim;
   w.k_rot = off;   off += c->position_shift ? align_up(units_kv * n_max * esz) : 0;
+  w.k_rot_lm = off; off += c->position_shift && dual ? align_up(units_kv * n_max * esz) : 0;  // each cache has its own slots
   w.q_rot = off;   off += c->position_shift ? align_up(units_q * c->chunk_len * esz) : 0;
   w.qi_rot = off;  off += c->position_shift ? align_up(units_q * c->instr_len * esz) : 0;
   w.total = off;
@@ -661,18 +661,37 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
     float* score;
     int32_t* idx;  // where this step's selection goes (pitch = budget)
   };
-  auto chunk_evicted_step = [&](const ChunkEvicted& t, const citrus_chunk_io& io, int c) -> citrus_status {
+  auto chunk_evicted_step = [&](const ChunkEvicted& t, const citrus_chunk_io& io_in, int c) -> citrus_status {
     const int n_old = *t.len, from = *t.cur, to = from ^ 1;
-    const Segments kl = segments(t.k[from], n_old, io.k, c), vl = segments(t.v[from], n_old, io.v, c);
+    const Segments kl = segments(t.k[from], n_old, io_in.k, c), vl = segments(t.v[from], n_old, io_in.v, c);
+    // What the chunk's attention and its scores read.  With the position shift: copies rotated to the
+    // positions of THIS cache (its state j -> j, chunk token t -> n_old + t); the gathers below keep moving
+    // the unrotated keys.
+    citrus_chunk_io io = io_in;
+    Segments kl_att = kl;
+    citrus_tensor k_cache_att = t.k[from];
+    if (cfg->position_shift) {
+      const float base = rope_base_of(cfg);
+      const int n_all = n_old + c;
+      const citrus_tensor k_rot = dense_tensor(ws + wl.k_rot_lm, cfg->layers, cfg->kv_heads, n_all, cfg->head_dim);
+      const citrus_tensor k_rot_chunk = rows_from(k_rot, n_old, cfg->dtype);
+      io.q = dense_tensor(ws + wl.q_rot, cfg->layers, cfg->q_heads, c, cfg->head_dim);
+      if (n_old > 0)
+        CITRUS_TRY(hip_status(launch_rope(cfg->dtype, dm, kl.cache, make_view(k_rot), cfg->kv_heads, n_old, 0, base, st)));
+      CITRUS_TRY(hip_status(launch_rope(cfg->dtype, dm, kl.chunk, make_view(k_rot_chunk), cfg->kv_heads, c, n_old, base, st)));
+      CITRUS_TRY(hip_status(launch_rope(cfg->dtype, dm, make_view(io_in.q), make_view(io.q), cfg->q_heads, c, n_old, base, st)));
+      kl_att = segments(k_rot, n_old, k_rot_chunk, c);
+      k_cache_att = k_rot;
+    }
     if (paper_order) {
       // the order Section 4.1 prints: encode the chunk given the cache (it still holds the whole previous
       // chunk), evict the cache by the chunk's attention to it, then put the chunk in
       const int kept = n_old < t.budget ? n_old : t.budget;
       const bool evicts = n_old > t.budget;
       // the rows' normalisers over the cache alone come out of the attention launch
-      CITRUS_TRY(do_chunk_attn(cfg, dm, io.q, kl, vl, io.out, nullptr, nullptr, evicts ? lse_cache : nullptr, st));
+      CITRUS_TRY(do_chunk_attn(cfg, dm, io.q, kl_att, vl, io.out, nullptr, nullptr, evicts ? lse_cache : nullptr, st));
       mark(done, 1);
-      if (evicts) CITRUS_TRY(do_cache_score(cfg, dm, io.q, c, t.k[from], n_old, lse_cache, nullptr, t.score, st));
+      if (evicts) CITRUS_TRY(do_cache_score(cfg, dm, io.q, c, k_cache_att, n_old, lse_cache, nullptr, t.score, st));
       mark(done, 2);
       if (n_old > 0) CITRUS_TRY(do_topk(cfg, t.score, n_old, t.budget, t.idx, st));
       mark(done, 3);
@@ -688,9 +707,9 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
       // the chunk attends over [cache ; chunk] and scores all of it itself; eviction in the same step
       const int n_new = n_old + c;
       const int kept = n_new < t.budget ? n_new : t.budget;
-      CITRUS_TRY(do_chunk_attn(cfg, dm, io.q, kl, vl, io.out, lse_chunk, nullptr, nullptr, st));
+      CITRUS_TRY(do_chunk_attn(cfg, dm, io.q, kl_att, vl, io.out, lse_chunk, nullptr, nullptr, st));
       mark(done, 1);
-      CITRUS_TRY(hip_status(run_colsum(cfg, dm, make_view(io.q), c, kl, /*causal=*/1, lse_chunk, t.score, st)));
+      CITRUS_TRY(hip_status(run_colsum(cfg, dm, make_view(io.q), c, kl_att, /*causal=*/1, lse_chunk, t.score, st)));
       mark(done, 2);
       CITRUS_TRY(do_topk(cfg, t.score, n_new, t.budget, t.idx, st));
       mark(done, 3);
@@ -735,7 +754,9 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
     // selection still gathers the unrotated keys.
     Segments ks_att = ks;
     citrus_tensor q_att = io.q, qi_att = io.q_instr;
-    const int q_rope_pos0 = cfg->position_shift && mfma_path_supported(cfg->dtype, dm) ? n_c : -1;
+    // (DUAL: the chunk attends over the language-modelling cache, so its queries are rotated to that cache's
+    // positions inside chunk_evicted_step)
+    const int q_rope_pos0 = cfg->position_shift && !dual && mfma_path_supported(cfg->dtype, dm) ? n_c : -1;
     if (cfg->position_shift) {
       const float base = rope_base_of(cfg);
       const citrus_tensor k_rot = dense_tensor(ws + wl.k_rot, cfg->layers, cfg->kv_heads, n, cfg->head_dim);
@@ -749,10 +770,11 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
                                            st))) != CITRUS_OK)
         break;
       // the MFMA attention kernel rotates its query rows itself while they are staged in LDS
-      if (q_rope_pos0 < 0 && (status = hip_status(launch_rope(cfg->dtype, dm, make_view(io.q), make_view(q_att),
-                                                              cfg->q_heads, c, n_c, base, st))) != CITRUS_OK)
+      if (!dual && q_rope_pos0 < 0 &&
+          (status = hip_status(launch_rope(cfg->dtype, dm, make_view(io.q), make_view(q_att), cfg->q_heads, c, n_c, base,
+                                           st))) != CITRUS_OK)
         break;
-      if (q_rope_pos0 >= 0) q_att = io.q;
+      if (dual || q_rope_pos0 >= 0) q_att = io.q;
       if ((status = hip_status(launch_rope(cfg->dtype, dm, make_view(io.q_instr), make_view(qi_att), cfg->q_heads,
                                            cfg->instr_len, n, base, st))) != CITRUS_OK)
         break;

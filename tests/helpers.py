@@ -85,6 +85,16 @@ class StepwiseRun:
         c = q.shape[3]
         kl, vl, kl_new, vl_new = k_pair[cur], v_pair[cur], k_pair[cur ^ 1], v_pair[cur ^ 1]
         lse = torch.empty((cfg.batch, cfg.layers, cfg.q_heads, c), dtype=torch.float32, device=q.device)
+        # what the attention and the chunk's scores read: with the position shift, copies rotated to the slots
+        # of THIS cache; the gathers keep moving the unrotated keys
+        q_att, kl_att, k_att = q, kl, k
+        if cfg.position_shift:
+            k_rot = torch.empty((cfg.batch, cfg.layers, cfg.kv_heads, n_old + c, cfg.head_dim), dtype=q.dtype, device=q.device)
+            if n_old > 0:
+                api.citrus_rope(cfg, kl, 0, y=k_rot, rows=n_old)
+            api.citrus_rope(cfg, k, n_old, y=k_rot[:, :, :, n_old:])
+            q_att = api.citrus_rope(cfg, q, n_old)
+            kl_att, k_att = k_rot, k_rot[:, :, :, n_old:]
         if cfg.lm_ordering == api.LM_EVICT_THEN_APPEND:
             # Section 4.1's order: encode given the cache, evict the cache by the chunk's attention to it,
             # then append the whole chunk
@@ -94,11 +104,11 @@ class StepwiseRun:
             lse_cache = None
             if n_old > budget:
                 lse_cache = torch.empty((cfg.batch, cfg.layers, cfg.q_heads, c), dtype=torch.float32, device=q.device)
-            out = api.citrus_chunk_attn(cfg, q, kl, vl, n_old, k, v, lse=lse, lse_cache=lse_cache)
+            out = api.citrus_chunk_attn(cfg, q_att, kl_att, vl, n_old, k_att, v, lse=lse, lse_cache=lse_cache)
             score = idx = None
             if n_old > 0:
                 if n_old > budget:
-                    score = api.citrus_cache_score(cfg, q, kl, n_old, lse_cache=lse_cache)
+                    score = api.citrus_cache_score(cfg, q_att, kl_att, n_old, lse_cache=lse_cache)
                     idx = api.citrus_topk_select(cfg, score, budget)
                 else:  # everything stays: the selection does not read the scores
                     unread = torch.zeros((cfg.batch, cfg.layers, cfg.kv_heads, n_old), dtype=torch.float32, device=q.device)
@@ -110,7 +120,7 @@ class StepwiseRun:
             return dict(out=out, lse=lse, score=score, idx=idx, kept=kept, new_len=kept + c)
         n_new = n_old + c
         score = torch.empty((cfg.batch, cfg.layers, cfg.kv_heads, n_new), dtype=torch.float32, device=q.device)
-        out = api.citrus_chunk_attn(cfg, q, kl, vl, n_old, k, v, lse=lse, lm_score=score, workspace=self.ws)
+        out = api.citrus_chunk_attn(cfg, q_att, kl_att, vl, n_old, k_att, v, lse=lse, lm_score=score, workspace=self.ws)
         idx = api.citrus_topk_select(cfg, score, budget)
         kept = min(budget, n_new)
         api.citrus_kv_compact(cfg, kl, vl, n_old, k, v, idx, kept, kl_new, vl_new)
@@ -138,7 +148,8 @@ class StepwiseRun:
             if n_c > 0:
                 api.citrus_rope(cfg, kc, 0, y=k_rot, rows=n_c)
             api.citrus_rope(cfg, k, n_c, y=k_rot[:, :, :, n_c:])
-            q_att = api.citrus_rope(cfg, q, n_c)
+            if not dual:   # DUAL: the chunk attends over the other cache, at that cache's positions
+                q_att = api.citrus_rope(cfg, q, n_c)
             qi_att = api.citrus_rope(cfg, q_instr, n)
             kc_att, k_att = k_rot, k_rot[:, :, :, n_c:]
         if dual:

@@ -62,6 +62,8 @@ def test_status_strings():
     ({"position_shift": 1}, True), ({"position_shift": 2}, False), ({"position_shift": 1, "rope_base": 0.5}, False),
     ({"position_shift": 1, "rope_base": 1e6}, True), ({"position_shift": 1, "cache_mode": B.CACHE_STANDARD}, False),
     ({"score_mode": B.SCORE_ACCUMULATED, "cache_mode": B.CACHE_DUAL, "budget_lm": 16}, False),
+    ({"position_shift": 1, "cache_mode": B.CACHE_DUAL, "budget_lm": 16}, True),
+    ({"position_shift": 1, "cache_mode": B.CACHE_DUAL, "budget_lm": 16, "lm_ordering": B.LM_EVICT_THEN_APPEND}, True),
 ])
 def test_workspace_bytes_validates_config(kw, ok):
     assert (B.workspace_bytes(cfg(**kw)) > 0) == ok

@@ -375,11 +375,12 @@ def run_document_stepwise(w: Workload, sample_units=None, check_every=1):
             vcat = np.stack([vd[g, cand[g]] for g in range(w.kv_heads)])
             n_c = pos[(b, l)].shape[1]
             assert n_c == rec["n_c"]
+            base = w.rope_base or 10000.0
             if w.position_shift:
                 # the tensors are un-rotated; every step rotates them to the positions of the cache
-                base = w.rope_base or 10000.0
                 kcat = orc.rope(kcat, np.arange(n_c + c), base)
-                qd = orc.rope(qd, n_c + np.arange(c), base)
+                if not dual:
+                    qd = orc.rope(qd, n_c + np.arange(c), base)
                 qi = orc.rope(qi, n_c + c + np.arange(qi.shape[1]), base)
             idx = rec["idx"][b, l].cpu().numpy()[:, :rec["m"]]
             check = (i % check_every == 0) or i == w.n_chunks - 1
@@ -389,6 +390,9 @@ def run_document_stepwise(w: Workload, sample_units=None, check_every=1):
                 vcat_lm = np.stack([vd[g, cand_lm[g]] for g in range(w.kv_heads)])
                 n_c_lm = pos_lm[(b, l)].shape[1]
                 assert n_c_lm == rec["n_c_lm"]
+                if w.position_shift:   # the language-modelling cache has its own slots
+                    kcat_lm = orc.rope(kcat_lm, np.arange(n_c_lm + c), base)
+                    qd = orc.rope(qd, n_c_lm + np.arange(c), base)
                 if check:
                     o_ref, lse_ref, _ = orc.chunk_attn(qd, kcat_lm, vcat_lm, n_c_lm)
                 if paper_lm:
@@ -509,6 +513,16 @@ DOC_CASES = {
         peaked(WORKLOADS["cfg1_tiny_f32"]), doc_len=256, layers=2, kv_heads=2, position_shift=1, rope_base=500.0,
         score_mode=api.SCORE_ACCUMULATED, select_mode=api.SELECT_PER_LAYER, start_size=2),
     "cfg2_small_position_shift": scaled_down(WORKLOADS["cfg2_mistral7b"], layers=2, doc_len=2300, position_shift=1),
+    "cfg1_dual_position_shift": scaled_down(peaked(WORKLOADS["cfg1_tiny_f32"]), doc_len=301, layers=2, kv_heads=2,
+                                            cache_mode=api.CACHE_DUAL, budget_lm=48, position_shift=1, rope_base=500.0),
+    "cfg1_dual_paper_order_position_shift": scaled_down(peaked(WORKLOADS["cfg1_tiny_f32"]), doc_len=256,
+                                                        cache_mode=api.CACHE_DUAL, budget_lm=40, position_shift=1,
+                                                        lm_ordering=api.LM_EVICT_THEN_APPEND),
+    "cfg4_small_dual_position_shift": scaled_down(peaked(WORKLOADS["cfg4_dual"]), batch=2, layers=1, q_heads=8, kv_heads=2,
+                                                  doc_len=1500, chunk_len=256, budget=320, budget_lm=384, position_shift=1),
+    "cfg4_small_dual_paper_order_position_shift": scaled_down(
+        WORKLOADS["cfg4_dual"], batch=1, layers=2, q_heads=8, kv_heads=2, doc_len=1300, chunk_len=256, budget=320,
+        budget_lm=256, position_shift=1, lm_ordering=api.LM_EVICT_THEN_APPEND),
     "cfg2_small": scaled_down(WORKLOADS["cfg2_mistral7b"], layers=2, doc_len=2560),
     "cfg2_small_start4": scaled_down(WORKLOADS["cfg2_mistral7b"], layers=2, doc_len=2560, start_size=4),
     "cfg2_small_peaked": scaled_down(peaked(WORKLOADS["cfg2_mistral7b"]), layers=1, doc_len=2000),
@@ -782,7 +796,9 @@ def run_process_document(w, doc, split_at=None, use_python_provider=False, use_s
 
 @pytest.mark.parametrize("case", ["cfg1", "cfg1_ragged", "cfg1_dual", "cfg1_dual_start4", "cfg1_dual_paper_order",
                                   "cfg1_dual_paper_order_start4_per_layer", "cfg2_small", "cfg2_small_start4",
-                                  "cfg4_small_dual", "cfg4_small_dual_paper_order", "cfg1_position_shift",
+                                  "cfg4_small_dual", "cfg4_small_dual_paper_order", "cfg1_position_shift", "cfg1_dual_position_shift",
+                                  "cfg1_dual_paper_order_position_shift", "cfg4_small_dual_position_shift",
+                                  "cfg4_small_dual_paper_order_position_shift",
                                   "cfg1_position_shift_accumulated_per_layer", "cfg2_small_position_shift", "cfg1_accumulated",
                                   "cfg1_accumulated_per_layer_start4", "cfg2_small_accumulated", "cfg1_standard_paper_order",
                                   "cfg1_standard_after_append_per_layer_start2", "cfg2_small_standard_paper_order"])

@@ -855,3 +855,70 @@ def test_position_shift_without_eviction_is_rope_at_document_positions():
     out = np.concatenate([tr.out for tr in res.trace], axis=1)
     pos = np.arange(t)
     np.testing.assert_allclose(out, _sdpa(orc.rope(q, pos), orc.rope(k, pos), v, causal=True, group=2), atol=1e-12)
+
+
+def _dual_position_shift_by_hand(q, k, v, q_instr, chunk, budget, budget_lm, base, paper_order):
+    """ONE head, plain loops, two caches with their own slots (Section 4.2 individual cache with the position
+    shift of Section 5.3).  The chunk attends over [LM cache ; chunk] rotated to the LM cache's slots and scores
+    it (its own causal column sums, or, in the printed order, Eq. (1) over the cache states alone before the
+    chunk is appended); the instruction scores [instruction cache ; chunk] rotated to that cache's slots from
+    the places behind its candidates.  Returns (outputs, LM cache positions, instruction cache positions)."""
+    t_total, d = q.shape
+    lm, ic, outs, step = [], [], np.zeros((t_total, v.shape[1])), 0
+    sm = lambda logit: [math.exp(a - max(logit)) / sum(math.exp(b - max(logit)) for b in logit) for a in logit]
+    dot = lambda a, b: sum(a[x] * b[x] for x in range(d)) / math.sqrt(d)
+    for lo in range(0, t_total, chunk):
+        hi = min(t_total, lo + chunk)
+        cand = lm + list(range(lo, hi))
+        krot = [_rot_by_hand(k[j], slot, base) for slot, j in enumerate(cand)]
+        imp_lm = [0.0] * len(cand)
+        imp_cache = [0.0] * len(lm)
+        for t in range(lo, hi):
+            seen = len(lm) + (t - lo) + 1
+            qr = _rot_by_hand(q[t], len(lm) + (t - lo), base)
+            w = sm([dot(qr, krot[a]) for a in range(seen)])
+            for x in range(v.shape[1]):
+                outs[t][x] = sum(w[a] * v[cand[a]][x] for a in range(seen))
+            for a in range(seen):
+                imp_lm[a] += w[a]
+            if lm:   # Eq. (1) as printed: softmax over the cache states alone
+                wc = sm([dot(qr, krot[a]) for a in range(len(lm))])
+                for a in range(len(lm)):
+                    imp_cache[a] += wc[a]
+        if paper_order:
+            keep = sorted(sorted(range(len(lm)), key=lambda a: (-imp_cache[a], a))[:budget_lm])
+            lm = [lm[a] for a in keep] + list(range(lo, hi))
+        else:
+            keep = sorted(sorted(range(len(cand)), key=lambda a: (-imp_lm[a], a))[:budget_lm])
+            lm = [cand[a] for a in keep]
+        cand_i = ic + list(range(lo, hi))
+        krot_i = [_rot_by_hand(k[j], slot, base) for slot, j in enumerate(cand_i)]
+        imp = [0.0] * len(cand_i)
+        for u, qt in enumerate(q_instr[step]):
+            w = sm([dot(_rot_by_hand(qt, len(cand_i) + u, base), krot_i[a]) for a in range(len(cand_i))])
+            for a in range(len(cand_i)):
+                imp[a] += w[a]
+        keep = sorted(sorted(range(len(cand_i)), key=lambda a: (-imp[a], a))[:budget])
+        ic = [cand_i[a] for a in keep]
+        step += 1
+    return outs, lm, ic
+
+
+@pytest.mark.parametrize("paper_order", [False, True])
+def test_dual_position_shift_vs_hand_written_loop(paper_order):
+    hq, hkv, t, d, chunk, budget, budget_lm = 1, 1, 31, 4, 5, 7, 6
+    q, k, v, qi = _doc(181, hq, hkv, t, d, 3, chunk)
+    res = orc.process_document(q, k, v, qi, chunk, budget, cache_mode=orc.CACHE_DUAL, budget_lm=budget_lm,
+                               position_shift=True, rope_base=50.0,
+                               lm_ordering=orc.LM_EVICT_THEN_APPEND if paper_order else orc.LM_SCORE_AFTER_APPEND)
+    outs, lm, ic = _dual_position_shift_by_hand(q[0], k[0], v[0], [x[0] for x in qi], chunk, budget, budget_lm, 50.0,
+                                                paper_order)
+    np.testing.assert_allclose(np.concatenate([tr.out for tr in res.trace], axis=1)[0], outs, atol=1e-12)
+    assert res.positions_lm[0].tolist() == lm and res.positions[0].tolist() == ic
+    np.testing.assert_array_equal(res.k_cache_lm[0], k[0][lm])     # both caches keep the unrotated keys
+    np.testing.assert_array_equal(res.k_cache[0], k[0][ic])
+    # the two caches hold different states at different slots, and the positions matter
+    assert lm != ic
+    plain = orc.process_document(q, k, v, qi, chunk, budget, cache_mode=orc.CACHE_DUAL, budget_lm=budget_lm,
+                                 lm_ordering=orc.LM_EVICT_THEN_APPEND if paper_order else orc.LM_SCORE_AFTER_APPEND)
+    assert not np.allclose(np.concatenate([tr.out for tr in plain.trace], axis=1)[0], outs)
