@@ -452,6 +452,11 @@ def main():
         ent["algorithmic_flops_per_launch"] = sc_flops
         ent["achieved_TFLOPs"] = round(sc_flops / (a_ms * 1e-3) / 1e12, 1)
         ent["frac_of_bf16_mfma_peak"] = round(sc_flops / (a_ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4)
+        ent["frac_of_hbm_peak"] = ent["frac"]
+        # the roof that bounds it: flops per algorithmic byte against the machine balance (312 flop per byte)
+        if sc_flops / ent["algorithmic_bytes_per_launch"] > PEAK_BF16_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+            ent.update(bound="mfma", achieved=ent["achieved_TFLOPs"], peak=PEAK_BF16_MFMA_TFLOPS, unit="TFLOP/s",
+                       frac=ent["frac_of_bf16_mfma_peak"])
         roofline_other.append(ent)
         roofline_other.append(hbm_entry("compact_kernel (K/V gather)", "a4", compact_ms, compact_by,
                                         "same events, around the gather launch"))

@@ -892,7 +892,11 @@ __global__ __launch_bounds__(512, 1) void attn_pipe_kernel_w8_rotq(Dims dm, View
 constexpr int kColsumWaves = 8;
 constexpr int kColsumKeyTiles = 1;  // 32-key tiles per wave: a workgroup covers 256 keys per staged Q chunk
 constexpr int kColsumQRows = 128;   // query rows per LDS chunk
-__global__ __launch_bounds__(kColsumWaves * 64, 2) void colsum_mfma_kernel(Dims dm, View q, int rows, Segments ks,
+// STEPWISE: rows is a multiple of kColsumQRows, so every chunk of staged rows is full and lies inside one
+// head (an instance of its own: both address paths in one kernel cost the registers that two workgroups
+// per compute unit need).
+template <bool STEPWISE>
+__global__ __launch_bounds__(kColsumWaves * 64, 4) void colsum_mfma_kernel(Dims dm, View q, int rows, Segments ks,
                                                                         int causal, const float* lse, int key_splits,
                                                                         const float2* part, float* score) {
   // two staging buffers of query rows and their normalisers (log2 domain, +inf for padding rows)
@@ -937,21 +941,42 @@ __global__ __launch_bounds__(kColsumWaves * 64, 2) void colsum_mfma_kernel(Dims 
   const int64_t part_stride = static_cast<int64_t>(dm.B) * dm.L * dm.Hq * rows;
   // The rows of chunk c + 1 are requested (into registers) before the products of chunk c start and
   // written to the other buffer afterwards: one barrier per chunk, no exposed load latency.
+  // A thread stages 16 bytes of rows tid / 16 + 32 x of a chunk.  STEPWISE: every chunk lies inside one head
+  // and is full, so its first row is a wave-uniform pointer that moves on by adds, and a thread's part of the
+  // address never changes; dividing the flattened row index by `rows` for every load cost more vector
+  // instructions per chunk than three of its four products.
   constexpr int kStageLoads = kColsumQRows / (kColsumWaves * 4);  // 16 threads per row, 16 bytes each
+  constexpr int kStageStep = kColsumWaves * 4;                     // rows between a thread's loads
   i32x4 q_in[kStageLoads];
   float lse_in = INFINITY;
+  const int64_t lse_row0 = (static_cast<int64_t>(bl) * dm.Hq + g * dm.G) * rows;  // the group's heads are consecutive
+  const uint32_t q_thread_off = ((tid / 16) * static_cast<uint32_t>(q.ss) + 8 * (tid % 16)) * 2;  // bytes; a head's rows span < 2 GiB
+  int stage_head = 0, stage_row = 0;  // where the next requested chunk starts (block-uniform)
   auto request_chunk = [&](int f0) {
+    if constexpr (STEPWISE) {
+      const uint16_t* const base = unit_ptr(q, b, l, g * dm.G + stage_head) + static_cast<int64_t>(stage_row) * q.ss;
 #pragma unroll
-    for (int x = 0; x < kStageLoads; ++x) {
-      const int f = min(f0 + tid / 16 + x * kColsumWaves * 4, total_rows - 1);
-      const int hh = f / rows, t = f % rows;
-      q_in[x] = *reinterpret_cast<const i32x4*>(unit_ptr(q, b, l, g * dm.G + hh) + static_cast<int64_t>(t) * q.ss +
-                                                8 * (tid % 16));
+      for (int x = 0; x < kStageLoads; ++x) {  // scalar base per load + one 32-bit per-thread byte offset
+        const char* const base_x = reinterpret_cast<const char*>(base + x * kStageStep * q.ss);
+        q_in[x] = *reinterpret_cast<const i32x4*>(base_x + q_thread_off);
+      }
+      stage_row += kColsumQRows;
+      if (stage_row == rows) {
+        stage_row = 0;
+        ++stage_head;
+      }
+    } else {
+#pragma unroll
+      for (int x = 0; x < kStageLoads; ++x) {
+        const int f = min(f0 + tid / 16 + x * kStageStep, total_rows - 1);
+        const int hh = f / rows, t = f % rows;
+        q_in[x] = *reinterpret_cast<const i32x4*>(unit_ptr(q, b, l, g * dm.G + hh) + static_cast<int64_t>(t) * q.ss +
+                                                  8 * (tid % 16));
+      }
     }
     float v = INFINITY;  // padding rows contribute exp2(-inf) = 0
     if (tid < kColsumQRows && f0 + tid < total_rows) {
-      const int f = f0 + tid;
-      const int64_t row_id = (static_cast<int64_t>(bl) * dm.Hq + g * dm.G + f / rows) * rows + f % rows;
+      const int64_t row_id = lse_row0 + f0 + tid;
       if (part != nullptr) {  // merge the per-range (maximum, sum) pairs
         float m = -INFINITY;
         for (int s = 0; s < key_splits; ++s) m = fmaxf(m, part[s * part_stride + row_id].x);
@@ -969,6 +994,7 @@ __global__ __launch_bounds__(kColsumWaves * 64, 2) void colsum_mfma_kernel(Dims 
   };
   request_chunk(0);
   int buf = 0;
+  int chunk_row = 0;  // STEPWISE: row of its head at which the chunk being multiplied starts
   for (int f0 = 0; f0 < total_rows; f0 += kColsumQRows, buf ^= 1) {
     const int f_cnt = min(kColsumQRows, total_rows - f0);
     uint16_t* const q_s = q_sb + buf * (kColsumQRows * kPitchK);
@@ -976,14 +1002,15 @@ __global__ __launch_bounds__(kColsumWaves * 64, 2) void colsum_mfma_kernel(Dims 
     // this buffer was last read two chunks ago, and every wave has passed the previous chunk's barrier since
 #pragma unroll
     for (int x = 0; x < kStageLoads; ++x)
-      *reinterpret_cast<i32x4*>(&q_s[(tid / 16 + x * kColsumWaves * 4) * kPitchK + 8 * (tid % 16)]) = q_in[x];
+      *reinterpret_cast<i32x4*>(&q_s[(tid / 16 + x * kStageStep) * kPitchK + 8 * (tid % 16)]) = q_in[x];
     if (tid < kColsumQRows) lse_s[tid] = lse_in;
     if (f0 + kColsumQRows < total_rows) request_chunk(f0 + kColsumQRows);  // block-uniform
     __syncthreads();
     if (wave_has_keys) {
       for (int qt = 0; qt * 32 < f_cnt; ++qt) {
+        const int tile_row = STEPWISE ? chunk_row + 32 * qt : (f0 + 32 * qt) % rows;  // wave-uniform
         if (causal) {  // wave-uniform: skip query tiles none of whose rows sees any key of this wave
-          const int t_first = (f0 + 32 * qt) % rows;
+          const int t_first = tile_row;
           const int t_last = t_first + 31 >= rows ? rows - 1 : t_first + 31;  // a tile that wraps reaches a head's end
           if (n_c + t_last < j0) continue;
         }
@@ -996,11 +1023,11 @@ __global__ __launch_bounds__(kColsumWaves * 64, 2) void colsum_mfma_kernel(Dims 
         // past the last candidate, or (causal) a chunk key later than the tile's first row.  The
         // flattened rows of one 32-row tile span at most two heads; t_lo is the smallest chunk row.
         const int f_first = f0 + 32 * qt;
-        int t_lo = f_first % rows;                                  // wave-uniform
+        int t_lo = tile_row;
         if (t_lo + 31 >= rows) t_lo = 0;                            // tile wraps into the next head
         const bool need_mask = (j_last >= n) || (causal && j_last > n_c + t_lo);
         int limit = n - 1;
-        if (need_mask && causal) limit = n_c + (f_first + col) % rows;
+        if (need_mask && causal) limit = n_c + (STEPWISE ? tile_row + col : (f_first + col) % rows);
 #pragma unroll
         for (int kt = 0; kt < kColsumKeyTiles; ++kt) {
           f32x16 s_t;
@@ -1022,6 +1049,10 @@ __global__ __launch_bounds__(kColsumWaves * 64, 2) void colsum_mfma_kernel(Dims 
           }
         }
       }
+    }
+    if (STEPWISE) {
+      chunk_row += kColsumQRows;
+      if (chunk_row == rows) chunk_row = 0;
     }
   }
   if (!wave_has_keys) return;
@@ -1325,11 +1356,13 @@ hipError_t launch_colsum_mfma(const Dims& dm, View q, int rows, Segments ks, int
   constexpr int kKeysPerBlock = 32 * kColsumKeyTiles * kColsumWaves;
   dim3 grid((n + kKeysPerBlock - 1) / kKeysPerBlock, dm.Hkv, dm.B * dm.L);
   constexpr int kLdsBytes = 2 * kColsumQRows * (kPitchK * 2 + 4);  // two buffers of rows and normalisers: 70 KB
-  static LdsLimit limit;
-  const hipError_t e = raise_lds_limit(limit, reinterpret_cast<const void*>(colsum_mfma_kernel), kLdsBytes);
+  static LdsLimit limit_stepwise, limit_any;
+  const bool stepwise = rows % kColsumQRows == 0;
+  const auto kern = stepwise ? colsum_mfma_kernel<true> : colsum_mfma_kernel<false>;
+  const hipError_t e = raise_lds_limit(stepwise ? limit_stepwise : limit_any, reinterpret_cast<const void*>(kern), kLdsBytes);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(colsum_mfma_kernel, grid, dim3(kColsumWaves * 64), kLdsBytes, st, dm, q, rows, ks, causal, lse,
-                     key_splits, part, score);
+  hipLaunchKernelGGL(kern, grid, dim3(kColsumWaves * 64), kLdsBytes, st, dm, q, rows, ks, causal, lse, key_splits, part,
+                     score);
   return hipGetLastError();
 }
 
