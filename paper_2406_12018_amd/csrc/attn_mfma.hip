@@ -884,6 +884,27 @@ __global__ __launch_bounds__(512, 1) void attn_pipe_kernel_w8_rotq(Dims dm, View
   attn_pipe_body<8, true>(dm, q, rows, ks, vs, causal, out, lse, lse_cache, q_rope_pos0, rope_log2_base);
 }
 
+// Brings the per-range (maximum, sum) pairs of a row, part[s * rows_total + row], to one normaliser,
+// left in part[row] as (log-sum-exp in the log2 domain, 1): a pair that the column-sum kernel reads like
+// any single range.  Done once per row here rather than by every workgroup of the column-sum launch
+// (one per 256 keys), each of which walked the ranges with dependent loads in front of every chunk.
+__global__ __launch_bounds__(256) void merge_partials_kernel(float2* part, int key_splits, int64_t rows_total) {
+  const int64_t row = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (row >= rows_total) return;
+  float2 ps[kMaxKeySplits];
+#pragma unroll
+  for (int s = 0; s < kMaxKeySplits; ++s)  // independent loads; an absent range counts as (-inf, 0)
+    ps[s] = s < key_splits ? part[s * rows_total + row] : make_float2(-INFINITY, 0.f);
+  float m = -INFINITY;
+#pragma unroll
+  for (int s = 0; s < kMaxKeySplits; ++s) m = fmaxf(m, ps[s].x);
+  float lsum = 0.f;
+#pragma unroll
+  for (int s = 0; s < kMaxKeySplits; ++s)
+    if (s < key_splits) lsum += ps[s].y * exp2f(ps[s].x - m);
+  part[row] = make_float2(m + log2f(lsum), 1.f);
+}
+
 // Summed form of Eq. (1): score[g, j] = sum over the query rows of the KV group of
 // exp(s - lse).  One wave per 32 candidate keys, which stay in registers as the A operand; the
 // group's query rows (all its heads, flattened) are staged through LDS in chunks of 128 rows and
@@ -1396,7 +1417,14 @@ hipError_t launch_instr_score_mfma(const Dims& dm, View q, int rows, Segments ks
   View none{nullptr, 0, 0, 0, 0};
   hipError_t e = launch_attn_mfma(dm, q, rows, ks, ks, /*causal=*/0, none, nullptr, nullptr, splits, part, st);
   if (e != hipSuccess) return e;
-  return launch_colsum_mfma(dm, q, rows, ks, /*causal=*/0, nullptr, splits, part, score, st);
+  if (splits > 1) {  // one normaliser per row, in place of the first range's pairs
+    const int64_t rows_total = static_cast<int64_t>(dm.B) * dm.L * dm.Hq * rows;
+    hipLaunchKernelGGL(merge_partials_kernel, dim3(static_cast<unsigned>((rows_total + 255) / 256)), dim3(256), 0, st, part,
+                       splits, rows_total);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return launch_colsum_mfma(dm, q, rows, ks, /*causal=*/0, nullptr, 1, part, score, st);
 }
 
 }  // namespace citrus
