@@ -165,6 +165,12 @@ SHAPES = [
     ("bf16", 1, 1, 8, 2, 128, 200, 1150, 40, 0.09),
     ("bf16", 1, 2, 8, 2, 128, 300, 1280, 16, 0.09),
     ("bf16", 2, 1, 4, 1, 128, 45, 96, 8, 0.5),
+    # chunk and instruction lengths that are multiples of the column-sum kernel's 128-row staging chunk (its
+    # pointer-stepping instance), with group sizes 1, 2 and 8, ragged caches, and instruction groups wide enough
+    # for the two-launch scorer with several key ranges merged per row
+    ("bf16", 1, 2, 8, 1, 128, 128, 333, 128, 0.3),
+    ("bf16", 2, 1, 2, 2, 128, 256, 77, 256, 0.5),
+    ("bf16", 1, 1, 4, 2, 128, 384, 1500, 384, 0.09),
 ]
 
 
