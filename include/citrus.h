@@ -24,9 +24,10 @@
  * Memory.  Every pointer is a DEVICE pointer unless its comment says "host".
  *   The caller owns all buffers, including the workspace; the library allocates
  *   and frees no device memory.  The only state it keeps between calls is, per
- *   device, the dynamic-LDS limits it has raised for its kernels and the address
- *   of its static scratch array (see citrus_evict_cache_static); both are
- *   atomics, so host threads may call any entry point concurrently.
+ *   device, the dynamic-LDS limits it has raised for its kernels, the device's
+ *   number of compute units and the address of its static scratch array (see
+ *   citrus_evict_cache_static); all are atomics, so host threads may call any
+ *   entry point concurrently.
  * Tensors.  A citrus_tensor is a base pointer plus ELEMENT strides for the
  *   document (b), layer (l), head (h) and sequence (s) axes; the head_dim axis is
  *   contiguous (stride 1).  Rows (one head_dim vector) must start on a 16-byte
