@@ -479,7 +479,8 @@ def main():
                    f"ring of {ring} pre-staged chunk buffers holding chunks 0..{ring - 1} of the recipe, replayed for the whole "
                    "document (dense timing; not the document's own values)",
                    "streams": "selection + gather next to the chunk attention on a second stream" if overlap else "one"},
-        "roofline": {"kernel": "attn_pipe_kernel_w8 (chunk attention)", "bound": "mfma",
+        "roofline": {"kernel": ("attn_pipe_kernel_w8_rotq + the rope launches of the step (the events bracket both)"
+                                if w.position_shift else "attn_pipe_kernel_w8 (chunk attention)"), "bound": "mfma",
                      "achieved": round(achieved, 2), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": traffic,
                      "traffic_source": None if traffic is None else
