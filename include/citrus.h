@@ -261,8 +261,8 @@ int32_t citrus_evict_cache(const citrus_config* cfg, citrus_tensor q, int32_t ro
  * of a workspace.  Every GPU the library runs on holds its own copy of that array until the process ends.
  * The call allocates and frees nothing and synchronises nothing.  Its need,
  *   max(B*L*Hq*rows*64, S) + B*L*Hkv*cache_len*4 + B*L*Hsel*k*4 bytes (each term rounded up to 256), with
- *   S = B*L*Hkv*ceil(G*rows/32)*cache_len*8 for small launches (G*rows <= 512, cache_len <= 2560 and
- *   B*L*Hkv*ceil(G*rows/64) <= 608; the partial sums of the row strips) and 0 otherwise,
+ *   S = B*L*Hkv*ceil(G*r/32)*min(cache_len, 2560)*8, the partial sums of the row strips of a small launch:
+ *   r = the largest row count <= rows with G*r <= 512 and B*L*Hkv*ceil(G*r/64) <= 608 (S = 0 if there is none),
  * must fit the array, else CITRUS_ERR_WORKSPACE (nothing is launched; use citrus_evict_cache).
  * The array keeps the previous call's contents and every part a call reads is written by that call first.
  * All calls on one GPU share the array: two calls that overlap in time on one GPU (different streams or

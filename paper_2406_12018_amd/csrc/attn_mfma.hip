@@ -1395,12 +1395,13 @@ size_t instr_score_mfma_workspace_floats(const Dims& dm, int rows, int n) {
   return two_launch > strips ? two_launch : strips;
 }
 
-hipError_t launch_instr_score_mfma(const Dims& dm, View q, int rows, Segments ks, float* workspace, float* score,
-                                   hipStream_t st) {
+hipError_t launch_instr_score_mfma(const Dims& dm, View q, int rows, Segments ks, float* workspace,
+                                   size_t workspace_floats, float* score, hipStream_t st) {
   const int n = ks.n_c + ks.c;
   // a short text over a candidate set that a workgroup's registers can hold one row strip of: one product
   // per (row, key)
-  if (instr_strip_supported(dm, q, rows, ks)) return launch_instr_strip(dm, q, rows, ks, workspace, score, st);
+  if (instr_strip_supported(dm, q, rows, ks, workspace_floats))
+    return launch_instr_strip(dm, q, rows, ks, workspace, workspace_floats, score, st);
   // otherwise two passes over the keys; few query rows per KV group: one fused launch
   const int total_rows = dm.G * rows;
   const int tiles32 = (n + 31) / 32;
@@ -1413,12 +1414,13 @@ hipError_t launch_instr_score_mfma(const Dims& dm, View q, int rows, Segments ks
   const int tiles = (n + kTileN - 1) / kTileN;
   int splits = (tiles + 3) / 4;  // about four key tiles per workgroup
   splits = splits < 1 ? 1 : (splits > kMaxKeySplits ? kMaxKeySplits : splits);
+  const int64_t rows_total = static_cast<int64_t>(dm.B) * dm.L * dm.Hq * rows;
+  if (static_cast<size_t>(2) * splits * rows_total > workspace_floats) return hipErrorInvalidValue;
   float2* part = reinterpret_cast<float2*>(workspace);
   View none{nullptr, 0, 0, 0, 0};
   hipError_t e = launch_attn_mfma(dm, q, rows, ks, ks, /*causal=*/0, none, nullptr, nullptr, splits, part, st);
   if (e != hipSuccess) return e;
   if (splits > 1) {  // one normaliser per row, in place of the first range's pairs
-    const int64_t rows_total = static_cast<int64_t>(dm.B) * dm.L * dm.Hq * rows;
     hipLaunchKernelGGL(merge_partials_kernel, dim3(static_cast<unsigned>((rows_total + 255) / 256)), dim3(256), 0, st, part,
                        splits, rows_total);
     e = hipGetLastError();

@@ -90,6 +90,12 @@ citrus_status check_lengths(const citrus_config* c, int cache_len, int chunk_len
   return CITRUS_OK;
 }
 
+// A block of float scratch and what it holds: the scorer picks its kernel by what fits.
+struct Scratch {
+  float* ptr;
+  size_t floats;
+};
+
 // Workspace layout (all blocks kAlign-aligned).
 struct Workspace {
   size_t lse_chunk, lse_instr, lse_cache, score, score_lm, idx, idx_lm, iota, decode, k_rot, k_rot_lm, q_rot, qi_rot, total;
@@ -102,6 +108,13 @@ bool evict_then_append(const citrus_config* c) {
          c->lm_ordering == CITRUS_LM_EVICT_THEN_APPEND;
 }
 
+// floats of the partial-softmax block that serves up to `rows` query rows per head over up to cache_capacity +
+// chunk_len candidates
+size_t score_scratch_floats(const citrus_config* c, int rows) {
+  const size_t n_max = static_cast<size_t>(c->cache_capacity) + c->chunk_len;
+  return instr_score_mfma_workspace_floats(dims_of(c), rows, static_cast<int>(n_max));
+}
+
 Workspace workspace_layout(const citrus_config* c) {
   Workspace w;
   const size_t units_q = static_cast<size_t>(c->batch) * c->layers * c->q_heads;
@@ -111,9 +124,8 @@ Workspace workspace_layout(const citrus_config* c) {
   size_t off = 0;
   w.lse_chunk = off; off += align_up(units_q * c->chunk_len * sizeof(float));
   // scratch of the instruction score: partial (max, sum) pairs x 8 key ranges, or partial column sums per row strip
-  const Dims dm_ws = dims_of(c);
-  w.lse_instr = off; off += align_up(instr_score_mfma_workspace_floats(dm_ws, c->instr_len, static_cast<int>(n_max)) * sizeof(float));
-  w.lse_cache = off; off += evict_then_append(c) ? align_up(instr_score_mfma_workspace_floats(dm_ws, c->chunk_len, static_cast<int>(n_max)) * sizeof(float)) : 0;  // same, chunk rows
+  w.lse_instr = off; off += align_up(score_scratch_floats(c, c->instr_len) * sizeof(float));
+  w.lse_cache = off; off += evict_then_append(c) ? align_up(score_scratch_floats(c, c->chunk_len) * sizeof(float)) : 0;  // same, chunk rows
   w.score = off;     off += align_up(units_kv * n_max * sizeof(float));
   w.score_lm = off;  off += dual ? align_up(units_kv * n_max * sizeof(float)) : 0;
   w.idx = off;       off += align_up(units_kv * c->budget * sizeof(int32_t));
@@ -191,9 +203,10 @@ citrus_status do_chunk_attn(const citrus_config* c, const Dims& dm, const citrus
 }
 
 citrus_status do_instr_score(const citrus_config* c, const Dims& dm, const citrus_tensor& q_instr, Segments ks,
-                             float* lse_ws, float* score, hipStream_t st) {
+                             Scratch scratch, float* score, hipStream_t st) {
+  float* const lse_ws = scratch.ptr;
   if (mfma_path_supported(c->dtype, dm))
-    return hip_status(launch_instr_score_mfma(dm, make_view(q_instr), c->instr_len, ks, lse_ws, score, st));
+    return hip_status(launch_instr_score_mfma(dm, make_view(q_instr), c->instr_len, ks, lse_ws, scratch.floats, score, st));
   View none{nullptr, 0, 0, 0, 0};
   // pass 1: row normalisers (log-sum-exp over all n candidates, no mask)
   CITRUS_TRY(hip_status(run_attn(c, dm, make_view(q_instr), c->instr_len, ks, ks, /*causal=*/0, none, lse_ws, st)));
@@ -216,13 +229,14 @@ Segments cache_only(const citrus_tensor& cache, int cache_len) {
 // Eq. (1) as printed: the rows of q score the states of one cache, softmax over those states alone.
 // The cache is handed to the kernels as the only key segment.
 citrus_status do_cache_score(const citrus_config* c, const Dims& dm, const citrus_tensor& q, int rows,
-                             const citrus_tensor& k_cache, int cache_len, const float* lse_given, float* lse_ws,
+                             const citrus_tensor& k_cache, int cache_len, const float* lse_given, Scratch scratch,
                              float* score, hipStream_t st) {
+  float* const lse_ws = scratch.ptr;
   const Segments ks = cache_only(k_cache, cache_len);
   if (lse_given != nullptr)  // the normalisers are known: only the column sums are left
     return hip_status(run_colsum(c, dm, make_view(q), rows, ks, /*causal=*/0, lse_given, score, st));
   if (mfma_path_supported(c->dtype, dm))
-    return hip_status(launch_instr_score_mfma(dm, make_view(q), rows, ks, lse_ws, score, st));
+    return hip_status(launch_instr_score_mfma(dm, make_view(q), rows, ks, lse_ws, scratch.floats, score, st));
   View none{nullptr, 0, 0, 0, 0};
   CITRUS_TRY(hip_status(run_attn(c, dm, make_view(q), rows, ks, ks, /*causal=*/0, none, lse_ws, st)));
   CITRUS_TRY(hip_status(run_colsum(c, dm, make_view(q), rows, ks, /*causal=*/0, lse_ws, score, st)));
@@ -271,13 +285,14 @@ Segments segments(const citrus_tensor& cache, int cache_len, const citrus_tensor
   return s;
 }
 
-// Partial-softmax block of the workspace that fits `rows` query rows, or NULL.
-float* cache_score_block(const citrus_config* c, void* workspace, int rows) {
+// Partial-softmax block of the workspace that fits `rows` query rows, or a NULL block.
+Scratch cache_score_block(const citrus_config* c, void* workspace, int rows) {
   const Workspace wl = workspace_layout(c);
   char* ws = static_cast<char*>(workspace);
-  if (rows <= c->instr_len) return reinterpret_cast<float*>(ws + wl.lse_instr);
-  if (evict_then_append(c) && rows <= c->chunk_len) return reinterpret_cast<float*>(ws + wl.lse_cache);
-  return nullptr;
+  if (rows <= c->instr_len) return Scratch{reinterpret_cast<float*>(ws + wl.lse_instr), score_scratch_floats(c, c->instr_len)};
+  if (evict_then_append(c) && rows <= c->chunk_len)
+    return Scratch{reinterpret_cast<float*>(ws + wl.lse_cache), score_scratch_floats(c, c->chunk_len)};
+  return Scratch{nullptr, 0};
 }
 
 // Argument checks shared by the two forms of the eviction of a cache by a text.
@@ -295,15 +310,15 @@ citrus_status check_evict_args(const citrus_config* cfg, const citrus_tensor& q,
   return CITRUS_OK;
 }
 
-// Score of the cache by the rows of q, selection, gather.  lse_ws: partial-softmax block for `rows` query rows;
+// Score of the cache by the rows of q, selection, gather.  scratch: partial-softmax block for `rows` query rows;
 // score: B*L*Hkv*cache_len floats; idx: B*L*Hsel*k positions.  A cache that fits stays whole: the selection is
 // then the identity and reads no score.
 citrus_status do_evict_cache(const citrus_config* cfg, const citrus_tensor& q, int rows, const citrus_tensor& k_cache,
                              const citrus_tensor& v_cache, int cache_len, int k, const citrus_tensor& k_new,
-                             const citrus_tensor& v_new, int32_t* idx, float* lse_ws, float* score, hipStream_t st) {
+                             const citrus_tensor& v_new, int32_t* idx, Scratch scratch, float* score, hipStream_t st) {
   const Dims dm = dims_of(cfg);
   const int m = cache_len < k ? cache_len : k;
-  if (cache_len > k) CITRUS_TRY(do_cache_score(cfg, dm, q, rows, k_cache, cache_len, nullptr, lse_ws, score, st));
+  if (cache_len > k) CITRUS_TRY(do_cache_score(cfg, dm, q, rows, k_cache, cache_len, nullptr, scratch, score, st));
   CITRUS_TRY(do_topk(cfg, score, cache_len, k, idx, st));
   const Segments ks = cache_only(k_cache, cache_len), vs = cache_only(v_cache, cache_len);
   return do_compact(cfg, dm, ks, vs, idx, k, m, k_new, v_new, st);
@@ -407,8 +422,9 @@ int32_t citrus_instr_score(const citrus_config* cfg, citrus_tensor q_instr, citr
   CITRUS_TRY(check_tensor(cfg, k_cache, cache_len, cache_len == 0));
   CITRUS_TRY(check_workspace(cfg, workspace, workspace_bytes));
   const Dims dm = dims_of(cfg);
-  float* lse_ws = reinterpret_cast<float*>(static_cast<char*>(workspace) + workspace_layout(cfg).lse_instr);
-  return do_instr_score(cfg, dm, q_instr, segments(k_cache, cache_len, k_chunk, chunk_len), lse_ws, score,
+  const Scratch scratch{reinterpret_cast<float*>(static_cast<char*>(workspace) + workspace_layout(cfg).lse_instr),
+                        score_scratch_floats(cfg, cfg->instr_len)};
+  return do_instr_score(cfg, dm, q_instr, segments(k_cache, cache_len, k_chunk, chunk_len), scratch, score,
                         static_cast<hipStream_t>(hip_stream));
 }
 
@@ -422,13 +438,13 @@ int32_t citrus_cache_score(const citrus_config* cfg, citrus_tensor q, int32_t ro
   CITRUS_TRY(check_tensor(cfg, k_cache, cache_len, false));
   if (lse_cache != nullptr) {  // no workspace needed: the rows' normalisers are given
     if (rows > cfg->chunk_len && rows > cfg->instr_len) return CITRUS_ERR_SHAPE;
-    return do_cache_score(cfg, dims_of(cfg), q, rows, k_cache, cache_len, lse_cache, nullptr, score,
+    return do_cache_score(cfg, dims_of(cfg), q, rows, k_cache, cache_len, lse_cache, Scratch{nullptr, 0}, score,
                           static_cast<hipStream_t>(hip_stream));
   }
   CITRUS_TRY(check_workspace(cfg, workspace, workspace_bytes));
-  float* lse_ws = cache_score_block(cfg, workspace, rows);
-  if (lse_ws == nullptr) return CITRUS_ERR_SHAPE;
-  return do_cache_score(cfg, dims_of(cfg), q, rows, k_cache, cache_len, nullptr, lse_ws, score,
+  const Scratch scratch = cache_score_block(cfg, workspace, rows);
+  if (scratch.ptr == nullptr) return CITRUS_ERR_SHAPE;
+  return do_cache_score(cfg, dims_of(cfg), q, rows, k_cache, cache_len, nullptr, scratch, score,
                         static_cast<hipStream_t>(hip_stream));
 }
 
@@ -438,13 +454,13 @@ int32_t citrus_evict_cache(const citrus_config* cfg, citrus_tensor q, int32_t ro
                            void* hip_stream) {
   CITRUS_TRY(check_evict_args(cfg, q, rows, k_cache, v_cache, cache_len, k, k_new, v_new));
   CITRUS_TRY(check_workspace(cfg, workspace, workspace_bytes));
-  float* lse_ws = cache_score_block(cfg, workspace, rows);
-  if (lse_ws == nullptr) return CITRUS_ERR_SHAPE;
+  const Scratch scratch = cache_score_block(cfg, workspace, rows);
+  if (scratch.ptr == nullptr) return CITRUS_ERR_SHAPE;
   const Workspace wl = workspace_layout(cfg);
   char* ws = static_cast<char*>(workspace);
   float* score = reinterpret_cast<float*>(ws + wl.score);
   if (idx == nullptr) idx = reinterpret_cast<int32_t*>(ws + wl.idx);
-  return do_evict_cache(cfg, q, rows, k_cache, v_cache, cache_len, k, k_new, v_new, idx, lse_ws, score,
+  return do_evict_cache(cfg, q, rows, k_cache, v_cache, cache_len, k, k_new, v_new, idx, scratch, score,
                         static_cast<hipStream_t>(hip_stream));
 }
 
@@ -459,9 +475,10 @@ int32_t citrus_evict_cache_static(const citrus_config* cfg, citrus_tensor q, int
   char* base = nullptr;
   CITRUS_TRY(static_scratch_base(&base));
   if (idx == nullptr) idx = reinterpret_cast<int32_t*>(base + sl.idx);
-  return do_evict_cache(cfg, q, rows, k_cache, v_cache, cache_len, k, k_new, v_new, idx,
-                        reinterpret_cast<float*>(base + sl.lse), reinterpret_cast<float*>(base + sl.score),
-                        static_cast<hipStream_t>(hip_stream));
+  const Scratch scratch{reinterpret_cast<float*>(base + sl.lse),
+                        instr_score_mfma_workspace_floats(dims_of(cfg), rows, cache_len)};
+  return do_evict_cache(cfg, q, rows, k_cache, v_cache, cache_len, k, k_new, v_new, idx, scratch,
+                        reinterpret_cast<float*>(base + sl.score), static_cast<hipStream_t>(hip_stream));
 }
 
 int32_t citrus_rope(const citrus_config* cfg, citrus_tensor x, int32_t heads, int32_t rows, int32_t pos0,
@@ -628,7 +645,7 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
   const Workspace wl = workspace_layout(cfg);
   char* ws = static_cast<char*>(workspace);
   float* lse_chunk = reinterpret_cast<float*>(ws + wl.lse_chunk);
-  float* lse_instr = reinterpret_cast<float*>(ws + wl.lse_instr);
+  const Scratch lse_instr{reinterpret_cast<float*>(ws + wl.lse_instr), score_scratch_floats(cfg, cfg->instr_len)};
   float* lse_cache = reinterpret_cast<float*>(ws + wl.lse_cache);
   int32_t* iota_ws = reinterpret_cast<int32_t*>(ws + wl.iota);
   float* score = reinterpret_cast<float*>(ws + wl.score);
@@ -691,7 +708,7 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
       // the rows' normalisers over the cache alone come out of the attention launch
       CITRUS_TRY(do_chunk_attn(cfg, dm, io.q, kl_att, vl, io.out, nullptr, nullptr, evicts ? lse_cache : nullptr, st));
       mark(done, 1);
-      if (evicts) CITRUS_TRY(do_cache_score(cfg, dm, io.q, c, k_cache_att, n_old, lse_cache, nullptr, t.score, st));
+      if (evicts) CITRUS_TRY(do_cache_score(cfg, dm, io.q, c, k_cache_att, n_old, lse_cache, Scratch{nullptr, 0}, t.score, st));
       mark(done, 2);
       if (n_old > 0) CITRUS_TRY(do_topk(cfg, t.score, n_old, t.budget, t.idx, st));
       mark(done, 3);

@@ -59,16 +59,22 @@ hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments kseg, Seg
 // normaliser per row from lse (natural log) or, if part != NULL, merged from key_splits partial pairs
 hipError_t launch_colsum_mfma(const Dims& dm, View q, int rows, Segments kseg, int causal, const float* lse,
                               int key_splits, const float2* part, float* score, hipStream_t st);
-// floats of scratch that launch_instr_score_mfma may use for `rows` query rows per head over up to n keys
+// Floats of scratch that cover every launch_instr_score_mfma call with at most `rows` query rows per head over
+// at most n keys (the launcher picks its kernel by the call's own shape, and the kernels' needs do not grow
+// together: a block sized for the largest shape alone could be too small for a smaller one).
 size_t instr_score_mfma_workspace_floats(const Dims& dm, int rows, int n);
-hipError_t launch_instr_score_mfma(const Dims& dm, View q, int rows, Segments kseg, float* workspace, float* score,
-                                   hipStream_t st);
+// `workspace_floats`: what the block behind `workspace` holds; a kernel whose scratch does not fit is not
+// chosen, and hipErrorInvalidValue comes back if none fits.
+hipError_t launch_instr_score_mfma(const Dims& dm, View q, int rows, Segments kseg, float* workspace,
+                                   size_t workspace_floats, float* score, hipStream_t st);
 
 // ---- instruction score with one q.k product per (row, key): row strips kept on chip, instr_strip.hip ----
-bool instr_strip_supported(const Dims& dm, const View& q, int rows, const Segments& kseg);
-size_t instr_strip_workspace_floats(const Dims& dm, int rows, int n);  // partial column sums of the strips
-hipError_t launch_instr_strip(const Dims& dm, View q, int rows, Segments kseg, float* workspace, float* score,
-                              hipStream_t st);
+// taken for this shape, given a scratch block of workspace_floats floats?
+bool instr_strip_supported(const Dims& dm, const View& q, int rows, const Segments& kseg, size_t workspace_floats);
+// largest scratch any supported launch with at most `rows` rows and at most n keys writes (0: none is supported)
+size_t instr_strip_workspace_floats(const Dims& dm, int rows, int n);
+hipError_t launch_instr_strip(const Dims& dm, View q, int rows, Segments kseg, float* workspace, size_t workspace_floats,
+                              float* score, hipStream_t st);
 
 // ---- bf16 MFMA decoding step (head_dim 128), decode_attn.hip ----
 bool decode_mfma_supported(int dtype, const Dims& dm);

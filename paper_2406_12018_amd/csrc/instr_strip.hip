@@ -477,13 +477,22 @@ static int compute_units() {
   return cus;
 }
 
-bool instr_strip_supported(const Dims& dm, const View& q, int rows, const Segments& ks) {
+// Floats of partial column sums a launch writes: two columns per strip; counted for the finer strip height,
+// which bounds both.
+static size_t strip_partial_floats(const Dims& dm, int rows, int n) {
+  const size_t units = static_cast<size_t>(dm.B) * dm.L * dm.Hkv;
+  const size_t strips = (static_cast<size_t>(dm.G) * rows + 31) / 32;
+  return units * strips * 2 * n;
+}
+
+bool instr_strip_supported(const Dims& dm, const View& q, int rows, const Segments& ks, size_t workspace_floats) {
   const int n = ks.n_c + ks.c;
   if (n < 1 || n > kStripMaxKeysLong || rows < 1 || dm.G * rows > kStripMaxRows) return false;
   // worth it while the workgroups (one per KV head and strip) fit the chip twice; see the top of this file
   const int strip_rows = (n <= kStripMaxKeysShort && dm.G * rows > 32) ? 64 : 32;
   const int64_t groups = static_cast<int64_t>(dm.B) * dm.L * dm.Hkv * ((dm.G * rows + strip_rows - 1) / strip_rows);
   if (groups > 2 * compute_units() || groups > kStripMaxGroups) return false;
+  if (strip_partial_floats(dm, rows, n) > workspace_floats) return false;  // the caller's block was sized for less
   // per-lane byte offsets into the group's instruction rows and into a key segment are 32-bit
   constexpr int64_t kSpan = int64_t{1} << 31;
   if (q.sh < 0 || q.ss <= 0 || ((dm.G - 1) * q.sh + (rows - 1) * q.ss + D) * 2 >= kSpan) return false;
@@ -492,19 +501,25 @@ bool instr_strip_supported(const Dims& dm, const View& q, int rows, const Segmen
 }
 
 size_t instr_strip_workspace_floats(const Dims& dm, int rows, int n) {
-  if (dm.G * rows > kStripMaxRows || n > kStripMaxKeysLong) return 0;  // such shapes take the two-pass kernels
-  // so do launches with more workgroups than any chip takes twice (a bound that needs no device query:
-  // the size of a workspace must not depend on where it is asked for)
+  // The largest shape (r <= rows, m <= n) the launcher may hand to this kernel: G r <= kStripMaxRows, and no more
+  // workgroups than any chip takes twice even with the taller strips (a bound that needs no device query: the
+  // size of a workspace must not depend on where it is asked for); m <= kStripMaxKeysLong.  The need grows with
+  // both, so the largest admissible pair bounds every smaller call.
   const size_t units = static_cast<size_t>(dm.B) * dm.L * dm.Hkv;
-  if (units * ((static_cast<size_t>(dm.G) * rows + 63) / 64) > kStripMaxGroups) return 0;
-  const size_t strips = (static_cast<size_t>(dm.G) * rows + 31) / 32;   // the finer of the two strip sizes
-  return units * strips * 2 * n;  // two partial columns per strip
+  if (units < 1 || units > kStripMaxGroups || dm.G < 1 || dm.G > kStripMaxRows || rows < 1 || n < 1) return 0;
+  const size_t tall_strips = kStripMaxGroups / units;                       // 64-row strips per KV head, at most
+  size_t r = static_cast<size_t>(kStripMaxRows) / dm.G;                     // G r <= kStripMaxRows
+  if (64 * tall_strips / dm.G < r) r = 64 * tall_strips / dm.G;            // ceil(G r / 64) <= tall_strips
+  if (static_cast<size_t>(rows) < r) r = rows;
+  if (r < 1) return 0;
+  const int m = n < kStripMaxKeysLong ? n : kStripMaxKeysLong;
+  return strip_partial_floats(dm, static_cast<int>(r), m);
 }
 
-hipError_t launch_instr_strip(const Dims& dm, View q, int rows, Segments ks, float* workspace, float* score,
-                              hipStream_t st) {
+hipError_t launch_instr_strip(const Dims& dm, View q, int rows, Segments ks, float* workspace, size_t workspace_floats,
+                              float* score, hipStream_t st) {
   const int n = ks.n_c + ks.c;
-  if (!instr_strip_supported(dm, q, rows, ks)) return hipErrorInvalidValue;
+  if (!instr_strip_supported(dm, q, rows, ks, workspace_floats)) return hipErrorInvalidValue;
   if (n <= kStripMaxKeysShort && dm.G * rows > 32) return strip_launch<2, 5>(dm, q, rows, ks, workspace, score, st);
   if (n <= kStripMaxKeysShort) return strip_launch<1, 5>(dm, q, rows, ks, workspace, score, st);
   return strip_launch<1, 10>(dm, q, rows, ks, workspace, score, st);

@@ -69,6 +69,23 @@ def test_workspace_bytes_validates_config(kw, ok):
     assert (B.workspace_bytes(cfg(**kw)) > 0) == ok
 
 
+def test_workspace_never_shrinks_when_the_configuration_grows():
+    """A call may use any cache length up to the capacity and the entry points that take `rows` any row count
+    up to the configured one, and the scorer picks its kernel by the call's own shape: a workspace sized for a
+    larger configuration must cover every smaller call.  (A size that followed only the largest shape once
+    dropped the single-product scorer's partial sums at 2561 candidates and left the 2560-candidate call
+    writing past its block.)"""
+    base = dict(batch=1, layers=1, q_heads=8, kv_heads=1, head_dim=128, chunk_len=64, budget=64, instr_len=64, dtype=B.BF16)
+    sizes = [B.workspace_bytes(cfg(**base, cache_capacity=cap)) for cap in range(64, 3200, 13)]
+    assert all(b >= a for a, b in zip(sizes, sizes[1:]))
+    by_rows = [B.workspace_bytes(cfg(**{**base, "instr_len": r}, cache_capacity=2496)) for r in range(1, 700, 7)]
+    assert all(b >= a for a, b in zip(by_rows, by_rows[1:]))
+    # the block of the 2560-candidate call: 16 strips x 2 partial columns x 2560 floats
+    need = 16 * 2 * 2560 * 4
+    assert B.workspace_bytes(cfg(**base, cache_capacity=2496)) >= need
+    assert B.workspace_bytes(cfg(**base, cache_capacity=2499)) >= need
+
+
 def fake(ptr=0x1000, s=64):
     return B.CTensor(ptr, s * 1024, s * 512, s * 128, s)
 

@@ -171,6 +171,14 @@ SHAPES = [
     ("bf16", 1, 2, 8, 1, 128, 128, 333, 128, 0.3),
     ("bf16", 2, 1, 2, 2, 128, 256, 77, 256, 0.5),
     ("bf16", 1, 1, 4, 2, 128, 384, 1500, 384, 0.09),
+    # the edges of the single-product scorer's range: 2560 candidates and 512 instruction rows per KV group are
+    # the last shapes it takes, one more of either goes to the two-pass kernels; 1280 / 1281 candidates switch
+    # its strip height
+    ("bf16", 1, 1, 8, 1, 128, 64, 2496, 64, 0.3),
+    ("bf16", 1, 1, 8, 1, 128, 64, 2497, 64, 0.3),
+    ("bf16", 1, 1, 1, 1, 128, 32, 1000, 513, 0.3),
+    ("bf16", 1, 2, 4, 2, 128, 64, 1216, 48, 0.3),
+    ("bf16", 1, 2, 4, 2, 128, 64, 1217, 48, 0.3),
 ]
 
 
