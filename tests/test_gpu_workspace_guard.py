@@ -1,0 +1,95 @@
+"""Nothing may be written outside the workspace: every entry point that takes one is called with a block of
+exactly citrus_workspace_bytes() bytes cut out of a larger buffer, over call shapes on both sides of every
+boundary at which the library changes kernels (the scorers choose by the CALL's candidate and row counts, the
+block is sized by the CONFIGURATION's maxima), and the bytes in front of and behind the block must keep their
+pattern.  Score mass is checked on the way, so a kernel that quietly lost its scratch would show as well.
+Needs an MI355X."""
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2406_12018_amd as api
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+GUARD = 1 << 16
+PATTERN = 0xA5
+
+
+def rand(shape, dt, seed, scale=0.3):
+    g = torch.Generator().manual_seed(int(seed))
+    return (torch.randn(shape, generator=g) * scale).to(dt).to(DEV)
+
+
+class Guarded:
+    def __init__(self, cfg):
+        self.n = api.workspace_bytes(cfg)
+        self.buf = torch.full((self.n + 2 * GUARD,), PATTERN, dtype=torch.uint8, device=DEV)
+        self.ws = self.buf[GUARD:GUARD + self.n]
+
+    def check(self, what):
+        torch.cuda.synchronize()
+        front = bool((self.buf[:GUARD] == PATTERN).all())
+        back = bool((self.buf[GUARD + self.n:] == PATTERN).all())
+        assert front and back, f"{what}: bytes outside the workspace were overwritten (front ok {front}, back ok {back})"
+
+
+CASES = {
+    # name: (config, cache lengths to call with, row counts for the calls that take `rows`)
+    "g8_one_unit_up_to_2600": (dict(B=1, L=1, Hq=8, Hkv=1, c=64, n_i=64, cap=2600, dtype="bf16"),
+                               [0, 1, 31, 32, 1215, 1216, 1217, 2495, 2496, 2497, 2536], [1, 33, 64]),
+    "g4_512_rows_two_layers": (dict(B=1, L=2, Hq=8, Hkv=2, c=64, n_i=128, cap=2500, dtype="bf16"),
+                               [0, 64, 1216, 1217, 2400, 2436], [1, 64, 128]),
+    "many_units_past_the_small_launch_bound": (dict(B=2, L=40, Hq=8, Hkv=8, c=32, n_i=32, cap=1300, dtype="bf16"),
+                                               [0, 700, 1248, 1268], [32]),
+    "wide_groups_two_launch": (dict(B=1, L=2, Hq=16, Hkv=1, c=128, n_i=40, cap=900, dtype="bf16"),
+                               [0, 100, 640, 772], [1, 40]),
+    "dual_paper_order_chunk_rows": (dict(B=1, L=2, Hq=8, Hkv=2, c=128, n_i=16, cap=1500, dtype="bf16", dual=True),
+                                    [64, 1152, 1153, 1372], [1, 16, 17, 64, 128]),
+    "f32_small": (dict(B=2, L=1, Hq=4, Hkv=2, c=32, n_i=8, cap=200, dtype="f32", d=64), [0, 5, 64, 168], [1, 8]),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_workspace_is_never_overrun(name):
+    spec, cache_lens, row_counts = CASES[name]
+    d = spec.get("d", 128)
+    dt = torch.bfloat16 if spec["dtype"] == "bf16" else torch.float32
+    B, L, Hq, Hkv, c, n_i, cap = (spec[k] for k in ("B", "L", "Hq", "Hkv", "c", "n_i", "cap"))
+    G = Hq // Hkv
+    extra = dict(cache_mode=api.CACHE_DUAL, budget_lm=cap - c, lm_ordering=api.LM_EVICT_THEN_APPEND) if spec.get("dual") else {}
+    cfg = api.Config(batch=B, layers=L, q_heads=Hq, kv_heads=Hkv, head_dim=d, chunk_len=c, budget=cap - c, instr_len=n_i,
+                     dtype=api.BF16 if spec["dtype"] == "bf16" else api.F32, cache_capacity=cap, **extra)
+    g = Guarded(cfg)
+    q, qi = rand((B, L, Hq, c, d), dt, 1), rand((B, L, Hq, n_i, d), dt, 2)
+    kc, vc = rand((B, L, Hkv, cap, d), dt, 3), rand((B, L, Hkv, cap, d), dt, 4, 1.0)
+    k, v = rand((B, L, Hkv, c, d), dt, 5), rand((B, L, Hkv, c, d), dt, 6, 1.0)
+    kn, vn = torch.empty_like(kc), torch.empty_like(vc)
+    dq, dk, dv = rand((B, L, Hq, 1, d), dt, 7), rand((B, L, Hkv, 1, d), dt, 8), rand((B, L, Hkv, 1, d), dt, 9, 1.0)
+    tol = 5e-3 if spec["dtype"] == "bf16" else 1e-5
+    for n_c in cache_lens:
+        assert n_c + c <= cap
+        print(f"{name}: cache {n_c}", flush=True)
+        n = n_c + c
+        lm = torch.empty((B, L, Hkv, n), dtype=torch.float32, device=DEV)
+        api.citrus_chunk_attn(cfg, q, kc if n_c else None, vc if n_c else None, n_c, k, v, lm_score=lm, workspace=g.ws)
+        g.check(f"chunk_attn n_c={n_c}")
+        np.testing.assert_allclose(lm.sum(-1).cpu().numpy(), c * G, rtol=tol)
+        sc = api.citrus_instr_score(cfg, qi, kc, n_c, k, workspace=g.ws)
+        g.check(f"instr_score n_c={n_c}")
+        np.testing.assert_allclose(sc.sum(-1).cpu().numpy(), n_i * G, rtol=tol)
+        if n_c == 0:
+            continue
+        for rows in row_counts:
+            text = qi if rows <= n_i else q  # rows above the instruction length come from the chunk's queries
+            cs = api.citrus_cache_score(cfg, text, kc, n_c, workspace=g.ws, rows=rows)
+            g.check(f"cache_score n_c={n_c} rows={rows}")
+            np.testing.assert_allclose(cs.sum(-1).cpu().numpy(), rows * G, rtol=tol)
+            kept = api.citrus_evict_cache(cfg, text, kc, vc, n_c, min(8, cap - c), kn, vn, workspace=g.ws, rows=rows)
+            g.check(f"evict_cache n_c={n_c} rows={rows}")
+            assert kept == min(8, n_c)
+        if n_c + 1 <= cap:
+            kc2, vc2 = kc.clone(), vc.clone()
+            api.citrus_decode_step(cfg, dq, dk, dv, kc2, vc2, n_c, workspace=g.ws)
+            g.check(f"decode_step n_c={n_c}")
