@@ -93,3 +93,81 @@ def test_workspace_is_never_overrun(name):
             kc2, vc2 = kc.clone(), vc.clone()
             api.citrus_decode_step(cfg, dq, dk, dv, kc2, vc2, n_c, workspace=g.ws)
             g.check(f"decode_step n_c={n_c}")
+
+
+# ----------------------------------------------------------------------------
+# the chunk loop: workspace, outputs, both cache pairs, accumulated sums and the index history between guards
+# ----------------------------------------------------------------------------
+
+from test_gpu_parity import DOC_CASES  # noqa: E402  (the document configurations of the parity tests)
+from workloads import make_document  # noqa: E402
+
+GUARD_ELEMS = 4096
+
+
+class GuardedTensor:
+    """A tensor cut out of the middle of a larger buffer whose ends hold a pattern."""
+
+    def __init__(self, shape, dtype, pattern):
+        n = int(np.prod(shape))
+        self.flat = torch.full((n + 2 * GUARD_ELEMS,), pattern, dtype=dtype, device=DEV)
+        self.flat[GUARD_ELEMS:GUARD_ELEMS + n] = 0
+        self.t = self.flat[GUARD_ELEMS:GUARD_ELEMS + n].view(shape)
+        self.n, self.pattern = n, pattern
+
+    def intact(self):
+        return bool((self.flat[:GUARD_ELEMS] == self.pattern).all()) and bool((self.flat[GUARD_ELEMS + self.n:] == self.pattern).all())
+
+
+GUARDED_DOCS = ["cfg1_ragged", "cfg1_per_layer", "cfg1_dual", "cfg1_chunk_gt_budget", "cfg1_dual_paper_order", "cfg2_small",
+                "cfg3_small_shared_mha", "cfg4_small_dual", "cfg4_small_dual_paper_order", "cfg5_small_g8",
+                "cfg2_small_accumulated", "cfg2_small_position_shift", "cfg4_small_dual_position_shift",
+                "cfg4_small_dual_paper_order_position_shift", "cfg2_small_standard_paper_order", "degenerate_bf16_c64_k1",
+                "degenerate_bf16_doc_shorter_than_chunk", "degenerate_bf16_dual_paper_order_c5"]
+
+
+@pytest.mark.parametrize("name", [n for n in GUARDED_DOCS if n in DOC_CASES])
+def test_document_loop_writes_only_what_it_owns(name):
+    w = DOC_CASES[name]
+    cfg = api.Config.from_workload(w)
+    doc = make_document(w, DEV)
+    guards = {}
+
+    def g(key, shape, dtype, pattern):
+        guards[key] = GuardedTensor(shape, dtype, pattern)
+        return guards[key].t
+
+    fpat = 3.0
+    cshape = (cfg.batch, cfg.layers, cfg.kv_heads, cfg.cache_capacity, cfg.head_dim)
+    state = api.DocumentState([g("k0", cshape, cfg.torch_dtype, fpat), g("k1", cshape, cfg.torch_dtype, fpat)],
+                              [g("v0", cshape, cfg.torch_dtype, fpat), g("v1", cshape, cfg.torch_dtype, fpat)])
+    if cfg.cache_mode == api.CACHE_DUAL:
+        state.k_cache_lm = [g("kl0", cshape, cfg.torch_dtype, fpat), g("kl1", cshape, cfg.torch_dtype, fpat)]
+        state.v_cache_lm = [g("vl0", cshape, cfg.torch_dtype, fpat), g("vl1", cshape, cfg.torch_dtype, fpat)]
+    if cfg.score_mode == api.SCORE_ACCUMULATED:
+        ashape = (cfg.batch, cfg.layers, cfg.kv_heads, cfg.cache_capacity)
+        state.acc_score = [g("a0", ashape, torch.float32, fpat), g("a1", ashape, torch.float32, fpat)]
+    out = g("out", tuple(doc["q"].shape), cfg.torch_dtype, fpat)
+    hist = g("hist", (w.n_chunks, w.batch, w.layers, cfg.sel_heads, w.budget), torch.int32, -77)
+    hist_lm = None
+    if cfg.cache_mode == api.CACHE_DUAL:
+        hist_lm = g("hist_lm", (w.n_chunks, w.batch, w.layers, cfg.sel_heads, w.budget_lm), torch.int32, -77)
+    gw = Guarded(cfg)
+    rd = api.resident_doc(cfg, doc["q"], doc["k"], doc["v"], doc["q_instr"], out)
+    done = api.citrus_process_document(cfg, state, gw.ws, doc=rd, idx_history=hist, idx_history_lm=hist_lm)
+    assert done == w.n_chunks
+    gw.check(f"{name}: workspace")
+    for key, gt in guards.items():
+        assert gt.intact(), f"{name}: bytes next to `{key}` were overwritten"
+
+    # the same document with ordinary allocations gives the same bits
+    state2 = api.DocumentState.allocate(cfg, DEV)
+    out2 = torch.zeros_like(doc["q"])
+    ws2 = api.alloc_workspace(cfg, DEV)
+    rd2 = api.resident_doc(cfg, doc["q"], doc["k"], doc["v"], doc["q_instr"], out2)
+    api.citrus_process_document(cfg, state2, ws2, doc=rd2)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+    assert state.cache_len == state2.cache_len and state.buffer_index == state2.buffer_index
+    ka, kb = state.current()[0], state2.current()[0]
+    assert torch.equal(ka, kb)
