@@ -212,6 +212,40 @@ def test_instr_score_parity(shape):
     assert torch.equal(score, again)
 
 
+# Launches with more (document, layer, KV head) units than the single-product scorer takes: the two-pass kernels,
+# which the small shapes above no longer reach.  One case per kernel the launcher can pick, on ragged row and
+# candidate counts; three sampled (document, layer) pairs against the oracle, every unit by its mass and by a
+# second run.
+MANY_UNITS = [
+    # B, L, Hq, Hkv, c, n_c, n_i   -> kernel
+    (2, 40, 8, 8, 19, 45, 37),       # 37 rows per KV head: four waves, one round
+    (2, 40, 32, 8, 33, 700, 50),     # 200 rows, 733 candidates: key tiles stay in registers between the passes
+    (2, 40, 32, 8, 77, 1500, 50),    # 200 rows, 1577 candidates: sixteen waves, keys read twice
+    (2, 40, 32, 8, 40, 900, 70),     # 280 rows: two launches, key ranges merged per row
+    (3, 30, 16, 8, 64, 2497, 64),    # 128 rows, 2561 candidates: one past the single-product scorer's range
+]
+
+
+@pytest.mark.parametrize("shape", MANY_UNITS, ids=lambda s: "-".join(str(x) for x in s))
+def test_instr_score_two_pass_kernels(shape):
+    B, L, Hq, Hkv, c, n_c, n_i = shape
+    say(f"instr_score, many units {shape}")
+    d, t, s = 128, torch.bfloat16, 0.3
+    cfg = make_cfg("bf16", B=B, L=L, Hq=Hq, Hkv=Hkv, d=d, c=c, k=n_c + 3, n_i=n_i)
+    ws = api.alloc_workspace(cfg)
+    qi = rand((B, L, Hq, n_i, d), t, 11, s)
+    kc, k = rand((B, L, Hkv, n_c + 3, d), t, 12, s), rand((B, L, Hkv, c, d), t, 13, s)
+    score = api.citrus_instr_score(cfg, qi, kc, n_c, k, workspace=ws)
+    again = api.citrus_instr_score(cfg, qi, kc, n_c, k, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(score, again)
+    got = np64(score)
+    np.testing.assert_allclose(got.sum(-1), n_i * (Hq // Hkv), rtol=2e-3)
+    for b, l in ((0, 0), (B - 1, L // 2), (B // 2, L - 1)):
+        kcat = np.concatenate([np64(kc[b, l, :, :n_c]), np64(k[b, l])], axis=1)
+        assert_close(got[b, l], orc.instr_score(np64(qi[b, l]), kcat), "bf16", f"score b{b} l{l}")
+
+
 @pytest.mark.parametrize("shape", [s for s in SHAPES if s[7] > 0], ids=lambda s: "-".join(str(x) for x in s[:9]))
 def test_cache_score_parity(shape):
     """Eq. (1) as printed, with the chunk's queries: softmax over the cache states alone, no mask."""
