@@ -86,7 +86,8 @@ def test_kv_compact_identity():
 
 @pytest.mark.parametrize("n,k,levels", [(96, 64, None), (1280, 768, None), (1280, 768, 7), (6144, 4096, None),
                                         (2048, 1024, 2), (300, 300, None), (5, 64, None), (1, 1, None),
-                                        (1000, 1, None), (1000, 999, 3), (257, 128, None)])
+                                        (1000, 1, None), (1000, 999, 3), (257, 128, None), (40096, 5000, None),
+                                        (40096, 40095, 5), (100000, 3, 2)])
 @pytest.mark.parametrize("per_layer", [False, True])
 def test_topk_select_exact(n, k, levels, per_layer):
     B, L, Hkv = 2, 2, 4
@@ -179,6 +180,9 @@ SHAPES = [
     ("bf16", 1, 1, 1, 1, 128, 32, 1000, 513, 0.3),
     ("bf16", 1, 2, 4, 2, 128, 64, 1216, 48, 0.3),
     ("bf16", 1, 2, 4, 2, 128, 64, 1217, 48, 0.3),
+    # a cache far longer than any configuration's: 627 key tiles per row block, scores that no longer fit a
+    # workgroup's LDS (two-launch scorer with eight key ranges)
+    ("bf16", 1, 1, 8, 2, 128, 96, 40000, 24, 0.09),
 ]
 
 
