@@ -739,6 +739,8 @@ DECODE_SHAPES = [
     ("bf16", 1, 1, 64, 2, 128, 300, 0.3),
     ("bf16", 3, 2, 4, 1, 128, 4500, 0.09),
     ("bf16", 4, 8, 16, 8, 128, 100, 0.3),
+    ("bf16", 1, 1, 8, 2, 128, 40000, 0.09),   # two units, keys split over eight workgroups each
+    ("bf16", 2, 40, 8, 8, 128, 1203, 0.3),    # 640 units: more than the chip takes at once, no split
     ("bf16", 1, 2, 4, 2, 64, 77, 0.5),
     ("f32", 2, 1, 4, 2, 64, 45, 1.0),
     ("f32", 1, 1, 2, 2, 128, 130, 0.5),
