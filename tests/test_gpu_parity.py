@@ -857,8 +857,11 @@ def run_process_document(w, doc, split_at=None, use_python_provider=False, use_s
                                   "cfg1_accumulated_per_layer_start4", "cfg2_small_accumulated", "cfg1_standard_paper_order",
                                   "cfg1_standard_after_append_per_layer_start2", "cfg2_small_standard_paper_order"])
 def test_process_document_equals_stepwise_and_resumes(case):
-    w = DOC_CASES.get(case) or STANDARD_CASES[case]
     say(f"process_document {case}")
+    check_process_document_equals_stepwise(DOC_CASES.get(case) or STANDARD_CASES[case])
+
+
+def check_process_document_equals_stepwise(w):
     cfg = api.Config.from_workload(w)
     doc = make_document(w, DEV)
     # stepwise reference run on the GPU (itself checked against the oracle above)
