@@ -693,10 +693,10 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
       const citrus_tensor k_rot = dense_tensor(ws + wl.k_rot_lm, cfg->layers, cfg->kv_heads, n_all, cfg->head_dim);
       const citrus_tensor k_rot_chunk = rows_from(k_rot, n_old, cfg->dtype);
       io.q = dense_tensor(ws + wl.q_rot, cfg->layers, cfg->q_heads, c, cfg->head_dim);
-      if (n_old > 0)
-        CITRUS_TRY(hip_status(launch_rope(cfg->dtype, dm, kl.cache, make_view(k_rot), cfg->kv_heads, n_old, 0, base, st)));
-      CITRUS_TRY(hip_status(launch_rope(cfg->dtype, dm, kl.chunk, make_view(k_rot_chunk), cfg->kv_heads, c, n_old, base, st)));
-      CITRUS_TRY(hip_status(launch_rope(cfg->dtype, dm, make_view(io_in.q), make_view(io.q), cfg->q_heads, c, n_old, base, st)));
+      const RopeJob jobs[3] = {{kl.cache, make_view(k_rot), cfg->kv_heads, n_old, 0},  // skipped while the cache is empty
+                               {kl.chunk, make_view(k_rot_chunk), cfg->kv_heads, c, n_old},
+                               {make_view(io_in.q), make_view(io.q), cfg->q_heads, c, n_old}};
+      CITRUS_TRY(hip_status(launch_rope_batch(cfg->dtype, dm, jobs, 3, base, st)));
       kl_att = segments(k_rot, n_old, k_rot_chunk, c);
       k_cache_att = k_rot;
     }
@@ -780,21 +780,15 @@ int32_t citrus_process_document(const citrus_config* cfg, citrus_chunk_provider 
       q_att = dense_tensor(ws + wl.q_rot, cfg->layers, cfg->q_heads, c, cfg->head_dim);
       qi_att = dense_tensor(ws + wl.qi_rot, cfg->layers, cfg->q_heads, cfg->instr_len, cfg->head_dim);
       const citrus_tensor k_rot_chunk = rows_from(k_rot, n_c, cfg->dtype);
-      if (n_c > 0 && (status = hip_status(launch_rope(cfg->dtype, dm, ks.cache, make_view(k_rot), cfg->kv_heads, n_c, 0,
-                                                      base, st))) != CITRUS_OK)
-        break;
-      if ((status = hip_status(launch_rope(cfg->dtype, dm, ks.chunk, make_view(k_rot_chunk), cfg->kv_heads, c, n_c, base,
-                                           st))) != CITRUS_OK)
-        break;
-      // the MFMA attention kernel rotates its query rows itself while they are staged in LDS
-      if (!dual && q_rope_pos0 < 0 &&
-          (status = hip_status(launch_rope(cfg->dtype, dm, make_view(io.q), make_view(q_att), cfg->q_heads, c, n_c, base,
-                                           st))) != CITRUS_OK)
-        break;
-      if (dual || q_rope_pos0 >= 0) q_att = io.q;
-      if ((status = hip_status(launch_rope(cfg->dtype, dm, make_view(io.q_instr), make_view(qi_att), cfg->q_heads,
-                                           cfg->instr_len, n, base, st))) != CITRUS_OK)
-        break;
+      // one launch for the step's rotations; the MFMA attention kernel rotates its query rows itself while they
+      // are staged in LDS, and with two caches the chunk's queries belong to the other cache's thread
+      const bool rotate_q_here = !dual && q_rope_pos0 < 0;
+      const RopeJob jobs[4] = {{ks.cache, make_view(k_rot), cfg->kv_heads, n_c, 0},  // skipped while the cache is empty
+                               {ks.chunk, make_view(k_rot_chunk), cfg->kv_heads, c, n_c},
+                               {make_view(io.q_instr), make_view(qi_att), cfg->q_heads, cfg->instr_len, n},
+                               {make_view(io.q), make_view(q_att), cfg->q_heads, rotate_q_here ? c : 0, n_c}};
+      if ((status = hip_status(launch_rope_batch(cfg->dtype, dm, jobs, 4, base, st))) != CITRUS_OK) break;
+      if (!rotate_q_here) q_att = io.q;
       ks_att = segments(k_rot, n_c, k_rot_chunk, c);
     }
     int32_t* idx = idx_history ? idx_history + static_cast<size_t>(done) * units_sel * cfg->budget : idx_ws;

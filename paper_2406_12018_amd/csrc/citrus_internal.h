@@ -89,6 +89,14 @@ hipError_t launch_decode_mfma(const Dims& dm, View q, Segments kseg, Segments vs
 // y[b,l,h,s,:] = RoPE(x[b,l,h,s,:], pos0 + s) for h < heads, s < rows; y may be x itself.
 hipError_t launch_rope(int dtype, const Dims& dm, View x, View y, int heads, int rows, int pos0, float base,
                        hipStream_t st);
+// Up to kMaxRopeJobs rotations in one launch (bf16; f32 takes one launch each): the keys and queries of a step.
+// A job with rows <= 0 is skipped.
+constexpr int kMaxRopeJobs = 4;
+struct RopeJob {
+  View x, y;
+  int heads, rows, pos0;
+};
+hipError_t launch_rope_batch(int dtype, const Dims& dm, const RopeJob* jobs, int count, float base, hipStream_t st);
 
 // Kernels that take more than 64 KB of dynamic LDS need their limit raised once per device.  `state` is a
 // static object next to the launch; the current device's slot remembers the largest size granted.  The
