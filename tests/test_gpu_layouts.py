@@ -1,6 +1,7 @@
 """The C ABI takes element strides: every entry point gives the same bits on token-major tensors
-(storage [B, L, S, H, d], passed as a [B, L, H, S, d] view with stride_h = d) as on head-major ones,
-whose results the other GPU tests check against the oracle.  Needs an MI355X."""
+(storage [B, L, S, H, d], passed as a [B, L, H, S, d] view with stride_h = d) and on views with unused
+elements around every axis (all NaN: never read, never written) as on head-major ones, whose results the
+other GPU tests check against the oracle.  Needs an MI355X."""
 
 import pytest
 import torch
@@ -19,6 +20,32 @@ def rand(shape, dt, seed, scale=1.0):
 def token_major(t):
     """Same values, storage order [B, L, S, H, d]."""
     return t.permute(0, 1, 3, 2, 4).contiguous().permute(0, 1, 3, 2, 4)
+
+
+class Padded:
+    """Same values inside a larger allocation: every axis has unused elements in front of and behind the view
+    (rows stay 16-byte aligned), all of them NaN.  A kernel that read them would poison its results; one that
+    wrote them is caught by untouched()."""
+
+    def __init__(self):
+        self.made = []
+
+    def __call__(self, t):
+        B, L, H, S, d = t.shape
+        big = torch.full((B + 1, L + 2, H + 3, S + 5, d + 24), float("nan"), dtype=t.dtype, device=t.device)
+        view = big[1:, 1:L + 1, 2:H + 2, 3:S + 3, 8:8 + d]
+        view.copy_(t)
+        self.made.append((big, view))
+        return view
+
+    def untouched(self):
+        for big, view in self.made:
+            mask = torch.ones(big.shape, dtype=torch.bool, device=big.device)
+            B, L, H, S, d = view.shape
+            mask[1:, 1:L + 1, 2:H + 2, 3:S + 3, 8:8 + d] = False
+            if not bool(torch.isnan(big[mask]).all()):
+                return False
+        return True
 
 
 @pytest.mark.parametrize("dtype,d,Hq,Hkv,c,n_c,n_i", [("bf16", 128, 8, 2, 200, 320, 40), ("bf16", 128, 4, 4, 65, 0, 7),
@@ -40,7 +67,8 @@ def test_token_major_equals_head_major(dtype, d, Hq, Hkv, c, n_c, n_i):
     m = min(n_c + c, 37)
     idx = torch.arange(0, 2 * m, 2, dtype=torch.int32, device=DEV).clamp(max=n_c + c - 1).repeat(B, L, Hkv, 1).contiguous()
     results = []
-    for layout in (lambda t: t, token_major):
+    padded = Padded()
+    for layout in (lambda t: t, token_major, padded):
         Q, QI, KC, VC, K, V = layout(q), layout(qi), layout(kc.clone()), layout(vc.clone()), layout(k), layout(v)
         lse = torch.empty((B, L, Hq, c), dtype=torch.float32, device=DEV)
         lm = torch.empty((B, L, Hkv, n_c + c), dtype=torch.float32, device=DEV)
@@ -63,3 +91,5 @@ def test_token_major_equals_head_major(dtype, d, Hq, Hkv, c, n_c, n_i):
     for name, a in results[0].items():
         if a is not None:
             assert torch.equal(a, results[1][name]), name
+            assert torch.equal(a, results[2][name]), f"{name} (padded strides)"
+    assert padded.untouched(), "elements outside a padded view were written"
