@@ -99,6 +99,7 @@ def test_workspace_is_never_overrun(name):
 # the chunk loop: workspace, outputs, both cache pairs, accumulated sums and the index history between guards
 # ----------------------------------------------------------------------------
 
+from test_gpu_layouts import Padded  # noqa: E402
 from test_gpu_parity import DOC_CASES  # noqa: E402  (the document configurations of the parity tests)
 from workloads import make_document  # noqa: E402
 
@@ -159,6 +160,17 @@ def test_document_loop_writes_only_what_it_owns(name):
     gw.check(f"{name}: workspace")
     for key, gt in guards.items():
         assert gt.intact(), f"{name}: bytes next to `{key}` were overwritten"
+
+    # the same document read through views with NaN elements around every axis (the ragged last chunk ends where
+    # the document ends: one row further is NaN) gives the same bits
+    padded = Padded()
+    state3 = api.DocumentState.allocate(cfg, DEV)
+    out3 = torch.zeros_like(doc["q"])
+    rd3 = api.resident_doc(cfg, padded(doc["q"]), padded(doc["k"]), padded(doc["v"]), doc["q_instr"], out3)
+    api.citrus_process_document(cfg, state3, api.alloc_workspace(cfg, DEV), doc=rd3)
+    torch.cuda.synchronize()
+    assert torch.equal(out3, out), f"{name}: elements outside the document's views were read"
+    assert padded.untouched()
 
     # the same document with ordinary allocations gives the same bits
     state2 = api.DocumentState.allocate(cfg, DEV)
