@@ -121,8 +121,9 @@ typedef enum { CITRUS_SELECT_PER_KV_HEAD = 0, CITRUS_SELECT_PER_LAYER = 1 } citr
 /* Plain data, passed by pointer, read during the call only. */
 typedef struct {
   int32_t batch;          /* B  documents                                    >= 1 */
-  int32_t layers;         /* L                                               >= 1 */
-  int32_t q_heads;        /* Hq, a multiple of kv_heads                          */
+  int32_t layers;         /* L                                               >= 1;  B*L <= 65535 */
+  int32_t q_heads;        /* Hq, a multiple of kv_heads, <= 65535; and B*L*Hq*ceil(max(chunk_len, instr_len)/32)
+                             < 2^28 (the largest launch: 8 workgroups per 32 rows of a head); else CITRUS_ERR_SHAPE */
   int32_t kv_heads;       /* Hkv                                             >= 1 */
   int32_t head_dim;       /* d: 64 or 128.  The matrix-core (MFMA) kernels exist for bf16 with d = 128 only;
                              bf16 with d = 64 and every f32 configuration run on plain vector kernels (one

@@ -38,7 +38,6 @@ constexpr int kThreads = kWaves * 64;
 constexpr int kRowsPerWave = 32;        // one 32-query column tile per wave
 constexpr int kTileN = 64;              // keys per LDS tile
 constexpr int kXcds = 8;
-constexpr int kMaxKeySplits = 8;
 constexpr int kBufferFlags = 0x00020000;  // raw buffer resource word 3 on CDNA: 32-bit data format, no swizzle
 constexpr int kPitchK = D + 8;          // padded LDS row pitch in bf16 (272 B) of the column-sum kernel's Q chunk
 constexpr int kRowBytes = 2 * D;        // K/V tile rows in LDS are unpadded (256 B) and XOR-swizzled

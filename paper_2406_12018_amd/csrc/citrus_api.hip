@@ -22,6 +22,13 @@ citrus_status check_config(const citrus_config* c) {
   if (c->q_heads % c->kv_heads != 0) return CITRUS_ERR_SHAPE;
   if (c->chunk_len < 1 || c->budget < 1 || c->instr_len < 1) return CITRUS_ERR_SHAPE;
   if (static_cast<int64_t>(c->batch) * c->layers > 65535 || c->q_heads > 65535) return CITRUS_ERR_SHAPE;
+  {
+    // the largest launch has one workgroup per (document, layer, query head, 32-row tile, range of key tiles):
+    // its count, like every unit count formed in 32 bits below, has to stay under 2^31
+    const int64_t rows_max = c->chunk_len > c->instr_len ? c->chunk_len : c->instr_len;
+    const int64_t blocks = static_cast<int64_t>(c->batch) * c->layers * c->q_heads * ((rows_max + 31) / 32) * kMaxKeySplits;
+    if (blocks >= (int64_t{1} << 31)) return CITRUS_ERR_SHAPE;
+  }
   if (c->cache_mode != CITRUS_CACHE_INSTR && c->cache_mode != CITRUS_CACHE_SHARED &&
       c->cache_mode != CITRUS_CACHE_DUAL && c->cache_mode != CITRUS_CACHE_STANDARD)
     return CITRUS_ERR_UNSUPPORTED;

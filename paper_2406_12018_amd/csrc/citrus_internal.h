@@ -59,6 +59,8 @@ hipError_t launch_attn_mfma(const Dims& dm, View q, int rows, Segments kseg, Seg
 // normaliser per row from lse (natural log) or, if part != NULL, merged from key_splits partial pairs
 hipError_t launch_colsum_mfma(const Dims& dm, View q, int rows, Segments kseg, int causal, const float* lse,
                               int key_splits, const float2* part, float* score, hipStream_t st);
+// Most ranges of key tiles a two-launch score splits the keys of a row into (one workgroup per range).
+constexpr int kMaxKeySplits = 8;
 // Floats of scratch that cover every launch_instr_score_mfma call with at most `rows` query rows per head over
 // at most n keys (the launcher picks its kernel by the call's own shape, and the kernels' needs do not grow
 // together: a block sized for the largest shape alone could be too small for a smaller one).

@@ -52,6 +52,9 @@ def test_status_strings():
     ({"cache_mode": B.CACHE_DUAL}, False), ({"cache_mode": B.CACHE_DUAL, "budget_lm": 16}, True),
     ({"cache_capacity": 8}, False), ({"softmax_scale": -1.0}, False), ({"select_mode": 5}, False),
     ({"batch": 70000}, False), ({"lm_ordering": 2}, False),
+    # the largest launch (8 workgroups per 32 rows of every head) has to stay a 31-bit grid
+    ({"batch": 64, "layers": 1000, "q_heads": 4096, "kv_heads": 512, "chunk_len": 64}, False),
+    ({"batch": 64, "layers": 1000, "q_heads": 2048, "kv_heads": 512, "chunk_len": 64}, True),
     ({"cache_mode": B.CACHE_DUAL, "budget_lm": 16, "lm_ordering": B.LM_EVICT_THEN_APPEND}, True),
     # the evict-then-append cache keeps a whole chunk beside the budget
     ({"cache_mode": B.CACHE_DUAL, "budget_lm": 48, "lm_ordering": B.LM_EVICT_THEN_APPEND, "cache_capacity": 64}, False),
