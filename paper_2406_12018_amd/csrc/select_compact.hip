@@ -125,6 +125,121 @@ __global__ __launch_bounds__(kSelThreads) void topk_kernel(const float* score, i
   }
 }
 
+// The same selection for a unit whose keys fit the workgroup's registers (n <= ITEMS * kSelThreads): the scores
+// are read once (candidate i * kSelThreads + tid is item i of thread tid), the four radix passes run on the
+// registers with three barriers each (two histograms take turns, so clearing one needs no barrier of its own),
+// and the ordered emission takes two barriers in all: per 256-candidate row and wave, the number of
+// threshold-equal and then of kept candidates goes to LDS, and a candidate's rank is the sum of the counts in
+// front of it.  Exactly the result of topk_kernel.
+template <int ITEMS>
+__global__ __launch_bounds__(kSelThreads) void topk_regs_kernel(const float* score, int heads_to_sum, int n, int k,
+                                                               int forced, int32_t* idx) {
+  __shared__ int hist[2][256];
+  __shared__ uint32_t s_prefix;
+  __shared__ int s_need;
+  __shared__ int wave_tot[kSelWaves];
+  __shared__ int row_cnt[2][ITEMS][kSelWaves];
+  const int unit = blockIdx.x, tid = threadIdx.x, lane = tid % 64, w = tid / 64;
+  const float* base = score + static_cast<int64_t>(unit) * heads_to_sum * n;
+  int32_t* out = idx + static_cast<int64_t>(unit) * k;
+
+  if (n <= k) {  // nothing to evict: keep every candidate
+    for (int j = tid; j < n; j += kSelThreads) out[j] = j;
+    return;
+  }
+
+  uint32_t key[ITEMS];
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    const int j = i * kSelThreads + tid;
+    key[i] = j < n ? unit_key(base, heads_to_sum, n, forced, j) : 0u;
+  }
+  hist[0][tid] = 0;  // kSelThreads == 256 bins
+  __syncthreads();
+
+  uint32_t prefix = 0;  // bits of T fixed so far (high bits)
+  int need = k;         // rank of T among the keys that match the prefix
+#pragma unroll
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    int* h = hist[pass & 1];
+    hist[(pass + 1) & 1][tid] = 0;  // the next pass's histogram; its last readers passed two barriers ago
+    const uint32_t hi_mask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i)
+      if (i * kSelThreads + tid < n && (key[i] & hi_mask) == prefix) atomicAdd(&h[(key[i] >> shift) & 0xff], 1);
+    __syncthreads();
+    // thread t owns bin t: keys in higher bins = suffix sum (wave shuffles + one LDS hop)
+    const int own = h[tid];
+    int incl = own;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int v = __shfl_down(incl, o, 64);
+      if (lane + o < 64) incl += v;
+    }
+    if (lane == 0) wave_tot[w] = incl;
+    __syncthreads();
+    int above = incl - own;
+    for (int x = w + 1; x < kSelWaves; ++x) above += wave_tot[x];
+    if (above < need && need <= above + own) {  // exactly one bin
+      s_prefix = prefix | (static_cast<uint32_t>(tid) << shift);
+      s_need = need - above;
+    }
+    __syncthreads();
+    prefix = s_prefix;
+    need = s_need;
+  }
+  const uint32_t thr = prefix;  // key of the k-th best candidate; `need` of the candidates with that key are kept
+
+  const uint64_t below = (1ull << lane) - 1ull;
+  // candidates of the same row and wave in front of this one (threshold-equal first, then kept): 0 .. 63, a byte each
+  uint32_t rank_in_row[(ITEMS + 3) / 4] = {};
+  auto set_rank = [&](int i, int r) { rank_in_row[i / 4] = (rank_in_row[i / 4] & ~(0xffu << (8 * (i % 4)))) | (static_cast<uint32_t>(r) << (8 * (i % 4))); };
+  auto get_rank = [&](int i) { return static_cast<int>((rank_in_row[i / 4] >> (8 * (i % 4))) & 0xffu); };
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    if (i * kSelThreads >= n) break;  // block-uniform
+    const bool eq = i * kSelThreads + tid < n && key[i] == thr;
+    const uint64_t ballot = __ballot(eq);
+    set_rank(i, __popcll(ballot & below));
+    if (lane == 0) row_cnt[0][i][w] = __popcll(ballot);
+  }
+  __syncthreads();
+  uint32_t keep_bits = 0;
+  int eq_before = 0;
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    if (i * kSelThreads >= n) break;
+    int eq_rank = eq_before + get_rank(i);
+#pragma unroll
+    for (int x = 0; x < kSelWaves; ++x) {
+      const int c = row_cnt[0][i][x];
+      if (x < w) eq_rank += c;
+      eq_before += c;
+    }
+    const bool in = i * kSelThreads + tid < n;
+    const bool keep = in && (key[i] > thr || (key[i] == thr && eq_rank < need));
+    const uint64_t ballot = __ballot(keep);
+    set_rank(i, __popcll(ballot & below));
+    if (lane == 0) row_cnt[1][i][w] = __popcll(ballot);
+    keep_bits |= keep ? (1u << i) : 0u;
+  }
+  __syncthreads();
+  int kept_before = 0;
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    if (i * kSelThreads >= n) break;
+    int pos = kept_before + get_rank(i);
+#pragma unroll
+    for (int x = 0; x < kSelWaves; ++x) {
+      const int c = row_cnt[1][i][x];
+      if (x < w) pos += c;
+      kept_before += c;
+    }
+    if (keep_bits & (1u << i)) out[pos] = i * kSelThreads + tid;
+  }
+}
+
 __global__ void iota_kernel(int32_t* p, int base, int count) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < count) p[i] = base + i;
@@ -204,7 +319,13 @@ hipError_t compact_launch(int elem_bytes, const Dims& dm, Segments ks, Segments 
 
 hipError_t launch_topk(const float* score, int units, int heads_to_sum, int n, int k, int forced, int32_t* idx,
                        hipStream_t st) {
-  hipLaunchKernelGGL(topk_kernel, dim3(units), dim3(kSelThreads), 0, st, score, heads_to_sum, n, k, min(forced, k), idx);
+  forced = min(forced, k);
+  if (n <= 8 * kSelThreads)
+    hipLaunchKernelGGL(topk_regs_kernel<8>, dim3(units), dim3(kSelThreads), 0, st, score, heads_to_sum, n, k, forced, idx);
+  else if (n <= 24 * kSelThreads)
+    hipLaunchKernelGGL(topk_regs_kernel<24>, dim3(units), dim3(kSelThreads), 0, st, score, heads_to_sum, n, k, forced, idx);
+  else
+    hipLaunchKernelGGL(topk_kernel, dim3(units), dim3(kSelThreads), 0, st, score, heads_to_sum, n, k, forced, idx);
   return hipGetLastError();
 }
 

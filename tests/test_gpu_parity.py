@@ -87,7 +87,12 @@ def test_kv_compact_identity():
 @pytest.mark.parametrize("n,k,levels", [(96, 64, None), (1280, 768, None), (1280, 768, 7), (6144, 4096, None),
                                         (2048, 1024, 2), (300, 300, None), (5, 64, None), (1, 1, None),
                                         (1000, 1, None), (1000, 999, 3), (257, 128, None), (40096, 5000, None),
-                                        (40096, 40095, 5), (100000, 3, 2)])
+                                        (40096, 40095, 5), (100000, 3, 2),
+                                        # both sides of the sizes at which the kernel that keeps a unit's keys in
+                                        # registers (8, then 24 per thread) hands over to the next one; few levels:
+                                        # the threshold's ties span every 256-candidate row and wave
+                                        (2048, 1500, 3), (2049, 1500, 3), (2049, 7, None), (6144, 3000, 2), (6145, 3000, 2),
+                                        (6145, 6144, None), (1793, 1792, 4), (255, 3, 2), (513, 512, None)])
 @pytest.mark.parametrize("per_layer", [False, True])
 def test_topk_select_exact(n, k, levels, per_layer):
     B, L, Hkv = 2, 2, 4
