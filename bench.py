@@ -464,6 +464,13 @@ def main():
                                "avg_launch_ms": round(sum(select_ms) / len(select_ms), 5),
                                "note": "a chain of barrier-separated LDS passes over a few KB per unit: no roofline fraction"})
 
+    # the same fractions against what this machine reaches in this run (a device copy, an MFMA-only loop)
+    peaks = measured_peaks(torch, api, dev)
+    for ent in roofline_other:
+        if "achieved" in ent:
+            reached = peaks["mfma_only_bf16_TFLOPs"] if ent["unit"] == "TFLOP/s" else peaks["copy_GBs"]
+            ent["frac_of_measured_peak"] = round(ent["achieved"] / reached, 4) if reached > 0 else None
+
     result = {
         "metric": "document tokens/sec per layer-stack + % HBM/MFMA peak, Mistral-7B shape",
         "value": round(value, 1), "unit": "document tokens/s per layer-stack",
@@ -482,13 +489,16 @@ def main():
         "roofline": {"kernel": ("attn_pipe_kernel_w8_rotq + the rope launches of the step (the events bracket both)"
                                 if w.position_shift else "attn_pipe_kernel_w8 (chunk attention)"), "bound": "mfma",
                      "achieved": round(achieved, 2), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": traffic,
+                     "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 4),
+                     "frac_of_measured_peak": (round(achieved / peaks["mfma_only_bf16_TFLOPs"], 4)
+                                               if peaks["mfma_only_bf16_TFLOPs"] > 0 else None),
+                     "traffic": traffic,
                      "traffic_source": None if traffic is None else
                      "constant from an offline rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this command "
                      "(profiles/bench_cfg2_mistral7b_hbm_traffic.md), not measured in this run",
                      "avg_launch_ms": round(avg_ms, 5), "algorithmic_flops_per_launch": avg_fl},
         "roofline_other": roofline_other,
-        "peaks_measured": measured_peaks(torch, api, dev),
+        "peaks_measured": peaks,
         "phase_ms_per_step": phase_ms,
         "phase_note": "phases: one extra untimed document with all events; roofline: events around every chunk-attention "
                       "launch of the timed region" + ("; select and compact run concurrently with chunk_attn (their times "

@@ -54,3 +54,9 @@ def test_bench_line_fields():
     assert abs(a4["achieved"] - a4["algorithmic_bytes_per_launch"] / (a4["avg_launch_ms"] * 1e-3) / 1e9) <= 1e-2 * a4["achieved"]
     pk = j["peaks_measured"]
     assert 1000.0 < pk["copy_GBs"] < 8000.0 and 500.0 < pk["mfma_only_bf16_TFLOPs"] < 2500.0
+    # every fraction is also given against what the same run measured as reachable
+    assert abs(ro["frac_of_measured_peak"] - ro["achieved"] / pk["mfma_only_bf16_TFLOPs"]) < 1e-3
+    assert abs(a4["frac_of_measured_peak"] - a4["achieved"] / pk["copy_GBs"]) < 1e-3
+    a2 = steps["a2"]
+    reached = pk["mfma_only_bf16_TFLOPs"] if a2["unit"] == "TFLOP/s" else pk["copy_GBs"]
+    assert abs(a2["frac_of_measured_peak"] - a2["achieved"] / reached) < 1e-3
