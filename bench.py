@@ -261,6 +261,9 @@ def main():
     ap.add_argument("--overlap", action="store_true",
                     help="single-cache modes: run selection and gather next to the chunk attention on a second stream "
                          "(2 %% more tokens/s; the attention launch itself then shares the chip and takes 9 %% longer)")
+    ap.add_argument("--graph", action="store_true",
+                    help="record one document's launches into a HIP graph and time its replays (resident documents, "
+                         "one stream); the chunk-attention launch duration then comes from untimed eager documents")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise copy of known size (256 MiB read + 256 MiB written) three "
                          "times before the warm-up, as the reference for scaling rocprofv3 HBM counters")
@@ -367,12 +370,27 @@ def main():
     if args.calibrate_copy:
         calibrate_copy(torch, dev)
 
+    graph = None
+    if args.graph:
+        if ring != 0 or overlap:
+            print("bench.py: --graph takes a resident document on one stream (no --ring, no --overlap)", file=sys.stderr)
+            sys.exit(2)
+        # the library allocates nothing and never synchronises, so a document's launches can be recorded as they
+        # are; one eager document first (it raises the kernels' dynamic-LDS limits, which a capture must not do)
+        capture_stream = torch.cuda.Stream()
+        with torch.cuda.stream(capture_stream):
+            one_document()
+        capture_stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=capture_stream):
+            one_document()
+
     for _ in range(args.warmup):
-        one_document()
+        graph.replay() if graph else one_document()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
-        one_document(s * w.n_chunks * E)
+        graph.replay() if graph else one_document(s * w.n_chunks * E)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
 
@@ -389,11 +407,16 @@ def main():
 
     # chunk-attention launch durations from the events recorded inside the timed region
     attn_ms, attn_fl = [], []
-    for s in range(args.steps):
+    for s in range(0 if graph else args.steps):
         for i in range(w.n_chunks):
             base = (s * w.n_chunks + i) * E
             attn_ms.append(events.elapsed_ms(base + attn_begin, base + 1))
             attn_fl.append(attn_flops_per_launch(w, i, w.budget_lm if dual else w.budget, paper_order))
+    if graph:  # no events inside the replayed graph: the untimed eager documents bracket the same launch (0 -> 1)
+        for pe_set in phase_sets:
+            for i in range(w.n_chunks):
+                attn_ms.append(pe_set.elapsed_ms(i * E, i * E + 1))
+                attn_fl.append(attn_flops_per_launch(w, i, w.budget_lm if dual else w.budget, paper_order))
     events.destroy()
     # per-phase device time of the extra document
     names = {1: "chunk_attn", 2: "lm_score", 3: "lm_select", 4: "lm_compact", 5: "instr_score", 6: "select", 7: "compact"}
@@ -485,7 +508,8 @@ def main():
                    "inputs": "resident document" if ring == 0 else
                    f"ring of {ring} pre-staged chunk buffers holding chunks 0..{ring - 1} of the recipe, replayed for the whole "
                    "document (dense timing; not the document's own values)",
-                   "streams": "selection + gather next to the chunk attention on a second stream" if overlap else "one"},
+                   "streams": "selection + gather next to the chunk attention on a second stream" if overlap else "one",
+                   "launch": "one HIP graph per document, replayed" if graph else "eager"},
         "roofline": {"kernel": ("attn_pipe_kernel_w8_rotq + the rope launches of the step (the events bracket both)"
                                 if w.position_shift else "attn_pipe_kernel_w8 (chunk attention)"), "bound": "mfma",
                      "achieved": round(achieved, 2), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
@@ -501,7 +525,8 @@ def main():
         "peaks_measured": peaks,
         "phase_ms_per_step": phase_ms,
         "phase_note": "phases: one extra untimed document with all events; roofline: events around every chunk-attention "
-                      "launch of the timed region" + ("; select and compact run concurrently with chunk_attn (their times "
+                      + ("launch of the untimed eager documents (the timed region replays a graph without events)" if graph
+                         else "launch of the timed region") + ("; select and compact run concurrently with chunk_attn (their times "
                                                       "are not additive)" if overlap else ""),
     }
     if not args.no_cpu_baseline and not overridden:
