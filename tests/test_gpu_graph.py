@@ -82,3 +82,48 @@ def test_document_loop_replays_from_a_graph(case):
         for i, (a, b) in enumerate(zip(got, want)):
             assert torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a,
                                b.view(torch.int16) if b.dtype == torch.bfloat16 else b), (case, replay, i)
+
+
+def test_final_eviction_and_decoding_replay_from_a_graph():
+    """What follows a document in a serving loop, recorded as one graph: the instruction evicts the cache once more
+    through the entry point that allocates nothing (the one meant for callers under capture), then four tokens are
+    decoded over the retained states."""
+    B, L, Hq, Hkv, d, n, k, rows, steps = 1, 4, 32, 8, 128, 832, 768, 64, 4
+    cfg = api.Config(batch=B, layers=L, q_heads=Hq, kv_heads=Hkv, head_dim=d, chunk_len=64, budget=k, instr_len=rows,
+                     dtype=api.BF16, cache_capacity=n)
+    g = torch.Generator(device="cpu").manual_seed(77)
+    mk = lambda *shape, scale=1.0: (torch.randn(shape, generator=g) * scale).bfloat16().to(DEV)
+    q_i = mk(B, L, Hq, rows, d, scale=1.5)
+    kc, vc = mk(B, L, Hkv, n, d, scale=1.5 * d ** -0.5), mk(B, L, Hkv, n, d)
+    q_t, k_t, v_t = mk(steps, B, L, Hq, 1, d), mk(steps, B, L, Hkv, 1, d, scale=d ** -0.5), mk(steps, B, L, Hkv, 1, d)
+    ws = api.alloc_workspace(cfg, DEV)
+    k_new, v_new = torch.zeros((B, L, Hkv, n, d), dtype=torch.bfloat16, device=DEV), torch.zeros((B, L, Hkv, n, d), dtype=torch.bfloat16, device=DEV)
+    idx = torch.full((B, L, Hkv, k), -1, dtype=torch.int32, device=DEV)
+    outs = torch.zeros((steps, B, L, Hq, 1, d), dtype=torch.bfloat16, device=DEV)
+
+    def run():
+        assert api.citrus_evict_cache_static(cfg, q_i, kc, vc, n, k, k_new, v_new, idx=idx) == k
+        for t in range(steps):
+            api.citrus_decode_step(cfg, q_t[t], k_t[t], v_t[t], k_new, v_new, k + t, out=outs[t], workspace=ws)
+
+    run()  # eager: looks up the static array's address and raises the dynamic-LDS limits
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (k_new, v_new, idx, outs)]
+    assert (idx[..., 1:] > idx[..., :-1]).all() and outs.float().abs().sum() > 0
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        run()
+    stream.synchronize()
+    with torch.cuda.graph(graph, stream=stream):
+        run()
+    for replay in range(3):
+        for t in (k_new, v_new, outs):
+            t.zero_()
+        idx.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(zip((k_new, v_new, idx, outs), want)):
+            assert torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a,
+                               b.view(torch.int16) if b.dtype == torch.bfloat16 else b), (replay, i)
