@@ -260,7 +260,7 @@ def main():
                          "automatically when the resident document would not fit")
     ap.add_argument("--overlap", action="store_true",
                     help="single-cache modes: run selection and gather next to the chunk attention on a second stream "
-                         "(2 %% more tokens/s; the attention launch itself then shares the chip and takes 9 %% longer)")
+                         "(2-3 %% more tokens/s; the attention launch itself then shares the chip and takes 9 %% longer)")
     ap.add_argument("--graph", action="store_true",
                     help="record one document's launches into a HIP graph and time its replays (resident documents, "
                          "one stream); the chunk-attention launch duration then comes from untimed eager documents")

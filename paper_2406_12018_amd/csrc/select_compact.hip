@@ -125,36 +125,38 @@ __global__ __launch_bounds__(kSelThreads) void topk_kernel(const float* score, i
   }
 }
 
-// The same selection for a unit whose keys fit the workgroup's registers (n <= ITEMS * kSelThreads): the scores
-// are read once (candidate i * kSelThreads + tid is item i of thread tid), the four radix passes run on the
-// registers with three barriers each (two histograms take turns, so clearing one needs no barrier of its own),
-// and the ordered emission takes two barriers in all: per 256-candidate row and wave, the number of
-// threshold-equal and then of kept candidates goes to LDS, and a candidate's rank is the sum of the counts in
-// front of it.  Exactly the result of topk_kernel.
-template <int ITEMS>
-__global__ __launch_bounds__(kSelThreads) void topk_regs_kernel(const float* score, int heads_to_sum, int n, int k,
-                                                               int forced, int32_t* idx) {
-  __shared__ int hist[2][256];
+// The same selection for a unit whose keys fit the workgroup's registers (n <= ITEMS * THREADS): the scores
+// are read once (candidate i * THREADS + tid is item i of thread tid), the four radix passes run on the
+// registers with three barriers each (two histograms take turns, so clearing one needs no barrier of its own;
+// the first 256 threads own the bins), and the ordered emission takes two barriers in all: per row of THREADS
+// candidates and wave, the number of threshold-equal and then of kept candidates goes to LDS, and a
+// candidate's rank is the sum of the counts in front of it.  Exactly the result of topk_kernel.
+template <int ITEMS, int THREADS>
+__device__ __forceinline__ void topk_regs_body(const float* score, int heads_to_sum, int n, int k, int forced,
+                                               int32_t* idx) {
+  constexpr int WAVES = THREADS / 64, kBins = 256, kBinWaves = kBins / 64;
+  static_assert(THREADS >= kBins && ITEMS <= 32, "thread t < 256 owns bin t; one bit per item");
+  __shared__ int hist[2][kBins];
   __shared__ uint32_t s_prefix;
   __shared__ int s_need;
-  __shared__ int wave_tot[kSelWaves];
-  __shared__ int row_cnt[2][ITEMS][kSelWaves];
+  __shared__ int wave_tot[kBinWaves];
+  __shared__ int row_cnt[2][ITEMS][WAVES];
   const int unit = blockIdx.x, tid = threadIdx.x, lane = tid % 64, w = tid / 64;
   const float* base = score + static_cast<int64_t>(unit) * heads_to_sum * n;
   int32_t* out = idx + static_cast<int64_t>(unit) * k;
 
   if (n <= k) {  // nothing to evict: keep every candidate
-    for (int j = tid; j < n; j += kSelThreads) out[j] = j;
+    for (int j = tid; j < n; j += THREADS) out[j] = j;
     return;
   }
 
   uint32_t key[ITEMS];
 #pragma unroll
   for (int i = 0; i < ITEMS; ++i) {
-    const int j = i * kSelThreads + tid;
+    const int j = i * THREADS + tid;
     key[i] = j < n ? unit_key(base, heads_to_sum, n, forced, j) : 0u;
   }
-  hist[0][tid] = 0;  // kSelThreads == 256 bins
+  if (tid < kBins) hist[0][tid] = 0;
   __syncthreads();
 
   uint32_t prefix = 0;  // bits of T fixed so far (high bits)
@@ -163,27 +165,32 @@ __global__ __launch_bounds__(kSelThreads) void topk_regs_kernel(const float* sco
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
     int* h = hist[pass & 1];
-    hist[(pass + 1) & 1][tid] = 0;  // the next pass's histogram; its last readers passed two barriers ago
+    if (tid < kBins) hist[(pass + 1) & 1][tid] = 0;  // the next pass's histogram; its last readers passed two barriers ago
     const uint32_t hi_mask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i)
-      if (i * kSelThreads + tid < n && (key[i] & hi_mask) == prefix) atomicAdd(&h[(key[i] >> shift) & 0xff], 1);
+      if (i * THREADS + tid < n && (key[i] & hi_mask) == prefix) atomicAdd(&h[(key[i] >> shift) & 0xff], 1);
     __syncthreads();
-    // thread t owns bin t: keys in higher bins = suffix sum (wave shuffles + one LDS hop)
-    const int own = h[tid];
-    int incl = own;
+    // thread t < 256 owns bin t: keys in higher bins = suffix sum (wave shuffles + one LDS hop)
+    int own = 0, incl = 0;
+    if (w < kBinWaves) {  // wave-uniform
+      own = h[tid];
+      incl = own;
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const int v = __shfl_down(incl, o, 64);
-      if (lane + o < 64) incl += v;
+      for (int o = 1; o < 64; o <<= 1) {
+        const int v = __shfl_down(incl, o, 64);
+        if (lane + o < 64) incl += v;
+      }
+      if (lane == 0) wave_tot[w] = incl;
     }
-    if (lane == 0) wave_tot[w] = incl;
     __syncthreads();
-    int above = incl - own;
-    for (int x = w + 1; x < kSelWaves; ++x) above += wave_tot[x];
-    if (above < need && need <= above + own) {  // exactly one bin
-      s_prefix = prefix | (static_cast<uint32_t>(tid) << shift);
-      s_need = need - above;
+    if (w < kBinWaves) {
+      int above = incl - own;
+      for (int x = w + 1; x < kBinWaves; ++x) above += wave_tot[x];
+      if (above < need && need <= above + own) {  // exactly one bin
+        s_prefix = prefix | (static_cast<uint32_t>(tid) << shift);
+        s_need = need - above;
+      }
     }
     __syncthreads();
     prefix = s_prefix;
@@ -191,17 +198,21 @@ __global__ __launch_bounds__(kSelThreads) void topk_regs_kernel(const float* sco
   }
   const uint32_t thr = prefix;  // key of the k-th best candidate; `need` of the candidates with that key are kept
 
-  const uint64_t below = (1ull << lane) - 1ull;
+  // set bits of a ballot below this lane (v_mbcnt: no per-lane mask to keep in registers)
+  auto lanes_below = [](uint64_t ballot) {
+    return static_cast<int>(__builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(ballot >> 32),
+                                                      __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(ballot), 0u)));
+  };
   // candidates of the same row and wave in front of this one (threshold-equal first, then kept): 0 .. 63, a byte each
   uint32_t rank_in_row[(ITEMS + 3) / 4] = {};
   auto set_rank = [&](int i, int r) { rank_in_row[i / 4] = (rank_in_row[i / 4] & ~(0xffu << (8 * (i % 4)))) | (static_cast<uint32_t>(r) << (8 * (i % 4))); };
   auto get_rank = [&](int i) { return static_cast<int>((rank_in_row[i / 4] >> (8 * (i % 4))) & 0xffu); };
 #pragma unroll
   for (int i = 0; i < ITEMS; ++i) {
-    if (i * kSelThreads >= n) break;  // block-uniform
-    const bool eq = i * kSelThreads + tid < n && key[i] == thr;
+    if (i * THREADS >= n) break;  // block-uniform
+    const bool eq = i * THREADS + tid < n && key[i] == thr;
     const uint64_t ballot = __ballot(eq);
-    set_rank(i, __popcll(ballot & below));
+    set_rank(i, lanes_below(ballot));
     if (lane == 0) row_cnt[0][i][w] = __popcll(ballot);
   }
   __syncthreads();
@@ -209,35 +220,54 @@ __global__ __launch_bounds__(kSelThreads) void topk_regs_kernel(const float* sco
   int eq_before = 0;
 #pragma unroll
   for (int i = 0; i < ITEMS; ++i) {
-    if (i * kSelThreads >= n) break;
+    if (i * THREADS >= n) break;
     int eq_rank = eq_before + get_rank(i);
 #pragma unroll
-    for (int x = 0; x < kSelWaves; ++x) {
+    for (int x = 0; x < WAVES; ++x) {
       const int c = row_cnt[0][i][x];
       if (x < w) eq_rank += c;
       eq_before += c;
     }
-    const bool in = i * kSelThreads + tid < n;
+    const bool in = i * THREADS + tid < n;
     const bool keep = in && (key[i] > thr || (key[i] == thr && eq_rank < need));
     const uint64_t ballot = __ballot(keep);
-    set_rank(i, __popcll(ballot & below));
+    set_rank(i, lanes_below(ballot));
     if (lane == 0) row_cnt[1][i][w] = __popcll(ballot);
     keep_bits |= keep ? (1u << i) : 0u;
+    __builtin_amdgcn_sched_barrier(0);  // one row's counts in registers at a time (see the register budget below)
   }
   __syncthreads();
   int kept_before = 0;
 #pragma unroll
   for (int i = 0; i < ITEMS; ++i) {
-    if (i * kSelThreads >= n) break;
+    if (i * THREADS >= n) break;
     int pos = kept_before + get_rank(i);
 #pragma unroll
-    for (int x = 0; x < kSelWaves; ++x) {
+    for (int x = 0; x < WAVES; ++x) {
       const int c = row_cnt[1][i][x];
       if (x < w) pos += c;
       kept_before += c;
     }
-    if (keep_bits & (1u << i)) out[pos] = i * kSelThreads + tid;
+    if (keep_bits & (1u << i)) out[pos] = i * THREADS + tid;
+    __builtin_amdgcn_sched_barrier(0);
   }
+}
+
+// Six keys per thread (up to 1536 candidates: the Mistral-7B shape's 1280) fit 32 registers with one wave per
+// SIMD: next to two waves of the chunk-attention kernel (240 registers each) a SIMD has 32 left, and with them
+// these workgroups run beside an attention launch (the second-stream form of the chunk loop) instead of waiting
+// for a compute unit of their own.  Eight keys need 34.
+__global__ __launch_bounds__(kSelThreads) void topk_regs6_kernel(const float* score, int heads_to_sum, int n, int k,
+                                                                int forced, int32_t* idx) {
+  topk_regs_body<6, kSelThreads>(score, heads_to_sum, n, k, forced, idx);
+}
+__global__ __launch_bounds__(kSelThreads) void topk_regs8_kernel(const float* score, int heads_to_sum, int n, int k,
+                                                                int forced, int32_t* idx) {
+  topk_regs_body<8, kSelThreads>(score, heads_to_sum, n, k, forced, idx);
+}
+__global__ __launch_bounds__(kSelThreads) void topk_regs24_kernel(const float* score, int heads_to_sum, int n, int k,
+                                                                 int forced, int32_t* idx) {
+  topk_regs_body<24, kSelThreads>(score, heads_to_sum, n, k, forced, idx);
 }
 
 __global__ void iota_kernel(int32_t* p, int base, int count) {
@@ -320,10 +350,12 @@ hipError_t compact_launch(int elem_bytes, const Dims& dm, Segments ks, Segments 
 hipError_t launch_topk(const float* score, int units, int heads_to_sum, int n, int k, int forced, int32_t* idx,
                        hipStream_t st) {
   forced = min(forced, k);
-  if (n <= 8 * kSelThreads)
-    hipLaunchKernelGGL(topk_regs_kernel<8>, dim3(units), dim3(kSelThreads), 0, st, score, heads_to_sum, n, k, forced, idx);
+  if (n <= 6 * kSelThreads)
+    hipLaunchKernelGGL(topk_regs6_kernel, dim3(units), dim3(kSelThreads), 0, st, score, heads_to_sum, n, k, forced, idx);
+  else if (n <= 8 * kSelThreads)
+    hipLaunchKernelGGL(topk_regs8_kernel, dim3(units), dim3(kSelThreads), 0, st, score, heads_to_sum, n, k, forced, idx);
   else if (n <= 24 * kSelThreads)
-    hipLaunchKernelGGL(topk_regs_kernel<24>, dim3(units), dim3(kSelThreads), 0, st, score, heads_to_sum, n, k, forced, idx);
+    hipLaunchKernelGGL(topk_regs24_kernel, dim3(units), dim3(kSelThreads), 0, st, score, heads_to_sum, n, k, forced, idx);
   else
     hipLaunchKernelGGL(topk_kernel, dim3(units), dim3(kSelThreads), 0, st, score, heads_to_sum, n, k, forced, idx);
   return hipGetLastError();
