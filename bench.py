@@ -483,7 +483,7 @@ def main():
         roofline_other.append(ent)
         roofline_other.append(hbm_entry("compact_kernel (K/V gather)", "a4", compact_ms, compact_by,
                                         "same events, around the gather launch"))
-        roofline_other.append({"kernel": "topk_regs_kernel / topk_kernel (selection)", "step": "a3", "bound": "latency",
+        roofline_other.append({"kernel": "topk_regs{6,8,24}_kernel / topk_kernel (selection)", "step": "a3", "bound": "latency",
                                "avg_launch_ms": round(sum(select_ms) / len(select_ms), 5),
                                "note": "a chain of barrier-separated LDS passes over a few KB per unit: no roofline fraction"})
 
