@@ -262,8 +262,8 @@ def main():
                     help="single-cache modes: run selection and gather next to the chunk attention on a second stream "
                          "(2-3 %% more tokens/s; the attention launch itself then shares the chip and takes 9 %% longer)")
     ap.add_argument("--graph", action="store_true",
-                    help="record one document's launches into a HIP graph and time its replays (resident documents, "
-                         "one stream); the chunk-attention launch duration then comes from untimed eager documents")
+                    help="record one document's launches into a HIP graph and time its replays (resident documents); "
+                         "the chunk-attention launch duration then comes from untimed eager documents")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise copy of known size (256 MiB read + 256 MiB written) three "
                          "times before the warm-up, as the reference for scaling rocprofv3 HBM counters")
@@ -372,8 +372,8 @@ def main():
 
     graph = None
     if args.graph:
-        if ring != 0 or overlap:
-            print("bench.py: --graph takes a resident document on one stream (no --ring, no --overlap)", file=sys.stderr)
+        if ring != 0:
+            print("bench.py: --graph takes a resident document (no --ring)", file=sys.stderr)
             sys.exit(2)
         # the library allocates nothing and never synchronises, so a document's launches can be recorded as they
         # are; one eager document first (it raises the kernels' dynamic-LDS limits, which a capture must not do)
@@ -415,7 +415,7 @@ def main():
     if graph:  # no events inside the replayed graph: the untimed eager documents bracket the same launch (0 -> 1)
         for pe_set in phase_sets:
             for i in range(w.n_chunks):
-                attn_ms.append(pe_set.elapsed_ms(i * E, i * E + 1))
+                attn_ms.append(pe_set.elapsed_ms(i * E + attn_begin, i * E + 1))
                 attn_fl.append(attn_flops_per_launch(w, i, w.budget_lm if dual else w.budget, paper_order))
     events.destroy()
     # per-phase device time of the extra document

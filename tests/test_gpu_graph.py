@@ -20,6 +20,9 @@ CASES = {
     "position_shift": dict(position_shift=1),
     "accumulated_per_layer": dict(score_mode=api.SCORE_ACCUMULATED, select_mode=api.SELECT_PER_LAYER),
     "standard": dict(cache_mode=api.CACHE_STANDARD),
+    # selection and gather beside the attention launch: the second stream joins the capture at every step's fork
+    # event and leaves it at the join event
+    "single_cache_second_stream": dict(),
 }
 
 
@@ -48,9 +51,11 @@ def test_document_loop_replays_from_a_graph(case):
     hist = torch.full((w.n_chunks, w.batch, w.layers, cfg.sel_heads, w.budget), -1, dtype=torch.int32, device=DEV)
     rd = api.resident_doc(cfg, doc["q"], doc["k"], doc["v"], doc["q_instr"], out)
 
+    side = api.SideStream(DEV) if case.endswith("second_stream") else None
+
     def run():
         reset(state)
-        done = api.citrus_process_document(cfg, state, ws, doc=rd, idx_history=hist)
+        done = api.citrus_process_document(cfg, state, ws, doc=rd, idx_history=hist, side=side)
         assert done == w.n_chunks
 
     run()  # eager; also raises the kernels' dynamic-LDS limits, which a capture must not do
