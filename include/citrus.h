@@ -46,6 +46,12 @@
  * Streams.  hip_stream is a hipStream_t (NULL = the default stream).  Calls
  *   only enqueue work and return; results are valid once the stream has been
  *   synchronised by the caller.  No call synchronises the device.
+ * Capture.  A call enqueues kernel launches only (plus, with a side stream, one
+ *   event record / wait pair per step), so it may be made while hip_stream is
+ *   being captured into a HIP graph, citrus_process_document with the resident
+ *   provider included.  The first call that reaches a kernel on a device raises
+ *   that kernel's dynamic-LDS limit (and citrus_evict_cache_static looks up its
+ *   array): make one eager call of the same shape on the device before capturing.
  * Errors.  Every entry point returns a citrus_status.  Arguments are validated
  *   on the host before anything is launched; on a validation error nothing is
  *   launched and outputs are untouched.  A failed launch maps to
