@@ -529,39 +529,6 @@ def main():
                          else "launch of the timed region") + ("; select and compact run concurrently with chunk_attn (their times "
                                                       "are not additive)" if overlap else ""),
     }
-    if graph is None and not overlap and ring == 0 and not dual and not standard:
-        # The same documents with the step's selection and gather on a second stream, recorded into one HIP graph
-        # per document (what `--overlap --graph` times): reported next to `value`, which stays the eager
-        # one-stream loop that the chunk-attention events of `roofline` belong to.
-        try:
-            side2 = api.SideStream(dev)
-            cap = torch.cuda.Stream()
-
-            def one_overlapped():
-                state.cache_len = state.cache_len_lm = 0
-                state.buffer_index = state.buffer_index_lm = 0
-                assert api.citrus_process_document(cfg, state, ws, doc=rd, side=side2) == w.n_chunks
-
-            with torch.cuda.stream(cap):
-                one_overlapped()
-            cap.synchronize()
-            g2 = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g2, stream=cap):
-                one_overlapped()
-            for _ in range(args.warmup):
-                g2.replay()
-            torch.cuda.synchronize()
-            t2 = time.perf_counter()
-            for _ in range(args.steps):
-                g2.replay()
-            torch.cuda.synchronize()
-            ms2 = (time.perf_counter() - t2) * 1e3 / args.steps
-            result["other_launch_modes"] = {"second_stream_and_graph": {
-                "ms_per_step": round(ms2, 4), "value": round(tokens / (ms2 * 1e-3), 1),
-                "note": "selection and gather beside the chunk attention on a second stream, one HIP graph per document "
-                        "replayed; same kernels, same bits (tests/test_gpu_graph.py)"}}
-        except Exception as e:  # informational only: never fail the line for it
-            result["other_launch_modes"] = {"second_stream_and_graph": None, "error": repr(e)[:200]}
     if not args.no_cpu_baseline and not overridden:
         # (the baseline times the default step sequence; it is not reported for overridden designs)
         result["cpu_baseline"] = cpu_baseline(w)

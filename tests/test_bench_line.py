@@ -54,11 +54,6 @@ def test_bench_line_fields():
     assert abs(a4["achieved"] - a4["algorithmic_bytes_per_launch"] / (a4["avg_launch_ms"] * 1e-3) / 1e9) <= 1e-2 * a4["achieved"]
     pk = j["peaks_measured"]
     assert 1000.0 < pk["copy_GBs"] < 8000.0 and 500.0 < pk["mfma_only_bf16_TFLOPs"] < 2500.0
-    # the same loop with the second stream inside one graph per document, reported beside the default value
-    other = j["other_launch_modes"]["second_stream_and_graph"]
-    assert other is not None, j["other_launch_modes"]
-    assert other["ms_per_step"] > 0 and abs(other["value"] - j["config"]["batch"] * j["config"]["doc_len"] /
-                                            (other["ms_per_step"] * 1e-3)) <= 1e-3 * other["value"]
     # every fraction is also given against what the same run measured as reachable
     assert abs(ro["frac_of_measured_peak"] - ro["achieved"] / pk["mfma_only_bf16_TFLOPs"]) < 1e-3
     assert abs(a4["frac_of_measured_peak"] - a4["achieved"] / pk["copy_GBs"]) < 1e-3
